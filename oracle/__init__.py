@@ -1,0 +1,216 @@
+"""ctypes binding of the CPU oracle (``gcn_oracle.cpp``).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by ``__graft_entry__.smoke()`` and by the
+``cpu_baseline`` leg of ``bench.py``.  The product package never imports this module and this
+module never imports the product package.
+
+All floating-point tensors are float64 numpy arrays (C-contiguous, ld == number of columns).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "liboracle_gcn.so")
+_lib = None
+
+Q_NONE, Q_F32, Q_BF16 = 0, 1, 2
+
+
+def build(force: bool = False) -> str:
+    src = os.path.join(_HERE, "gcn_oracle.cpp")
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(src):
+        cmd = ["g++", "-O2", "-std=c++17", "-fopenmp", "-shared", "-fPIC", "-o", _SO, src]
+        subprocess.run(cmd, check=True)
+    return _SO
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_SO):
+            build()
+        lib = ctypes.CDLL(_SO)
+        p, i64, i32, u32, u64 = (ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32,
+                                 ctypes.c_uint64)
+        lib.oracle_num_threads.restype = i32
+        lib.oracle_set_num_threads.argtypes = [i32]
+        lib.oracle_build_csr.argtypes = [p, p, u64, u32, i32, i32, p, p]
+        lib.oracle_build_csr.restype = i64
+        lib.oracle_normalize.argtypes = [p, p, u32, p, p, p, p]
+        lib.oracle_normalize.restype = None
+        lib.oracle_transpose.argtypes = [p, p, p, u32, p, p, p]
+        lib.oracle_transpose.restype = None
+        lib.oracle_spmm.argtypes = [p, p, p, p, i64, p, i64, i64, i64, i64, i64, i32]
+        lib.oracle_spmm.restype = None
+        lib.oracle_update_fwd.argtypes = [p, i64, p, i64, p, i64, i64, i64, i64, i32, i32]
+        lib.oracle_update_fwd.restype = None
+        lib.oracle_relu_grad.argtypes = [p, i64, p, i64, p, i64, i64, i64, i32]
+        lib.oracle_relu_grad.restype = None
+        lib.oracle_update_dgrad.argtypes = [p, i64, p, i64, p, i64, i64, i64, i64, i32]
+        lib.oracle_update_dgrad.restype = None
+        lib.oracle_update_wgrad.argtypes = [p, i64, p, i64, p, i64, i64, i64, i64]
+        lib.oracle_update_wgrad.restype = None
+        lib.oracle_softmax_xent.argtypes = [p, i64, p, i64, i64, p, i64]
+        lib.oracle_softmax_xent.restype = ctypes.c_double
+        lib.oracle_gcn_step.argtypes = [p, p, p, p, p, p, i64, i32, p, p, p, p, p, p, p, p, i32, i32]
+        lib.oracle_gcn_step.restype = ctypes.c_double
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return _load().oracle_num_threads()
+
+
+def set_num_threads(n: int) -> None:
+    _load().oracle_set_num_threads(n)
+
+
+def _p(a):
+    return None if a is None else ctypes.c_void_p(a.ctypes.data)
+
+
+def _f64(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    assert a.ndim == 2
+    return a
+
+
+class Graph:
+    """Sorted CSR of A_tilde with its normalisation (and, if asked, the transpose)."""
+
+    def __init__(self, rowptr, col, n):
+        self.n = int(n)
+        self.rowptr = rowptr
+        self.col = col
+        self.nnz = int(rowptr[-1])
+        self.deg = self.dinv = self.val = self.val_f32 = None
+        self.t_rowptr = self.t_col = self.t_val = None
+
+
+def build_csr(src, dst, n, symmetrize=True, self_loops=True) -> Graph:
+    src = np.ascontiguousarray(src, dtype=np.uint32)
+    dst = np.ascontiguousarray(dst, dtype=np.uint32)
+    e = len(src)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    col = np.empty((2 if symmetrize else 1) * e + n, dtype=np.uint32)
+    nnz = _load().oracle_build_csr(_p(src), _p(dst), e, n, int(symmetrize), int(self_loops),
+                                   _p(rowptr), _p(col))
+    if nnz < 0:
+        raise ValueError("edge endpoint out of range")
+    return Graph(rowptr, col[:nnz].copy(), n)
+
+
+def normalize(g: Graph) -> Graph:
+    g.deg = np.empty(g.n, dtype=np.uint32)
+    g.dinv = np.empty(g.n, dtype=np.float64)
+    g.val = np.empty(g.nnz, dtype=np.float64)
+    g.val_f32 = np.empty(g.nnz, dtype=np.float32)
+    _load().oracle_normalize(_p(g.rowptr), _p(g.col), g.n, _p(g.deg), _p(g.dinv), _p(g.val),
+                             _p(g.val_f32))
+    return g
+
+
+def transpose(g: Graph) -> Graph:
+    g.t_rowptr = np.empty(g.n + 1, dtype=np.int64)
+    g.t_col = np.empty(g.nnz, dtype=np.uint32)
+    g.t_val = np.empty(g.nnz, dtype=np.float64)
+    _load().oracle_transpose(_p(g.rowptr), _p(g.col), _p(g.val), g.n, _p(g.t_rowptr),
+                             _p(g.t_col), _p(g.t_val))
+    return g
+
+
+def spmm(g: Graph, H, c0=0, c1=None, r0=0, r1=None, transposed=False, q=Q_NONE, out=None):
+    """Z[r0:r1, c0:c1] = (A_hat or A_hat^T)[r0:r1, :] @ H[:, c0:c1]; other entries untouched."""
+    H = _f64(H)
+    c1 = H.shape[1] if c1 is None else c1
+    r1 = g.n if r1 is None else r1
+    Z = np.zeros_like(H) if out is None else out
+    if transposed:
+        if g.t_rowptr is None:
+            transpose(g)
+        rp, cl, vl = g.t_rowptr, g.t_col, g.t_val
+    else:
+        rp, cl, vl = g.rowptr, g.col, g.val
+    _load().oracle_spmm(_p(rp), _p(cl), _p(vl), _p(H), H.shape[1], _p(Z), Z.shape[1], c0, c1, r0,
+                        r1, q)
+    return Z
+
+
+def update_fwd(Z, W, relu: bool, q=Q_NONE):
+    Z, W = _f64(Z), _f64(W)
+    n, k = Z.shape
+    m = W.shape[1]
+    out = np.empty((n, m), dtype=np.float64)
+    _load().oracle_update_fwd(_p(Z), k, _p(W), m, _p(out), m, n, k, m, int(relu), q)
+    return out
+
+
+def relu_grad(G, Href, q=Q_NONE):
+    G = _f64(G)
+    Href = None if Href is None else _f64(Href)
+    n, m = G.shape
+    out = np.empty((n, m), dtype=np.float64)
+    _load().oracle_relu_grad(_p(G), m, _p(Href), m, _p(out), m, n, m, q)
+    return out
+
+
+def update_dgrad(dP, W, q=Q_NONE):
+    dP, W = _f64(dP), _f64(W)
+    n, m = dP.shape
+    k = W.shape[0]
+    out = np.empty((n, k), dtype=np.float64)
+    _load().oracle_update_dgrad(_p(dP), m, _p(W), m, _p(out), k, n, k, m, q)
+    return out
+
+
+def update_wgrad(Z, dP):
+    Z, dP = _f64(Z), _f64(dP)
+    n, k = Z.shape
+    m = dP.shape[1]
+    out = np.empty((k, m), dtype=np.float64)
+    _load().oracle_update_wgrad(_p(Z), k, _p(dP), m, _p(out), m, n, k, m)
+    return out
+
+
+def softmax_xent(logits, labels, want_grad=True):
+    logits = _f64(logits)
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    n, c = logits.shape
+    d = np.empty((n, c), dtype=np.float64) if want_grad else None
+    loss = _load().oracle_softmax_xent(_p(logits), c, _p(labels), n, c, _p(d), c)
+    return loss, d
+
+
+def gcn_step(g: Graph, X, Ws, labels, want_dx=False, linear=False, q=Q_NONE, backward=True):
+    """One forward(+backward) pass of an L-layer GCN.  Returns a dict with loss, logits,
+    Z (list), H (list, H[0] = X), dW (list) and dX."""
+    X = _f64(X)
+    Ws = [_f64(w) for w in Ws]
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    L = len(Ws)
+    n = g.n
+    dims = np.array([X.shape[1]] + [w.shape[1] for w in Ws], dtype=np.int64)
+    for l, w in enumerate(Ws):
+        assert w.shape[0] == dims[l]
+    if g.t_rowptr is None:
+        transpose(g)
+    Zs = [np.empty((n, int(dims[l])), dtype=np.float64) for l in range(L)]
+    Hs = [X] + [np.empty((n, int(dims[l + 1])), dtype=np.float64) for l in range(L)]
+    dWs = [np.empty_like(w) for w in Ws] if backward else None
+    dX = np.empty_like(X) if (want_dx and backward) else None
+    PtrArr = ctypes.c_void_p * L
+    PtrArr1 = ctypes.c_void_p * (L + 1)
+    w_arr = PtrArr(*[w.ctypes.data for w in Ws])
+    z_arr = PtrArr(*[z.ctypes.data for z in Zs])
+    h_arr = PtrArr1(*[h.ctypes.data for h in Hs])
+    dw_arr = PtrArr(*[d.ctypes.data for d in dWs]) if backward else None
+    loss = _load().oracle_gcn_step(_p(g.rowptr), _p(g.col), _p(g.val), _p(g.t_rowptr),
+                                   _p(g.t_col), _p(g.t_val), n, L, _p(dims), _p(X), w_arr, _p(labels),
+                                   z_arr, h_arr, dw_arr, _p(dX), int(linear), q)
+    return {"loss": loss, "logits": Hs[L], "Z": Zs, "H": Hs, "dW": dWs, "dX": dX}

@@ -1,0 +1,405 @@
+"""Pins for the CPU oracle: everything here checks the oracle against something that is NOT
+the oracle's own formula -- hand-worked fixtures, dense brute force built independently with
+numpy, closed forms, invariants and finite differences.  No GPU needed."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import graphgen as gg
+import oracle
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ------------------------------------------------------------------------------------------
+# independent dense constructions (numpy only)
+# ------------------------------------------------------------------------------------------
+def dense_atilde(src, dst, n, symmetrize=True, self_loops=True):
+    a = np.zeros((n, n), dtype=bool)
+    for u, v in zip(src, dst):
+        if u == v:
+            continue
+        a[u, v] = True
+        if symmetrize:
+            a[v, u] = True
+    if self_loops:
+        a[np.arange(n), np.arange(n)] = True
+    return a
+
+
+def dense_ahat(at):
+    d = at.sum(axis=1).astype(np.float64)
+    with np.errstate(divide="ignore"):
+        s = np.where(d > 0, 1.0 / np.sqrt(d), 0.0)
+    return s[:, None] * at.astype(np.float64) * s[None, :]
+
+
+def csr_to_dense(g, vals=None):
+    m = np.zeros((g.n, g.n), dtype=np.float64)
+    for u in range(g.n):
+        for e in range(g.rowptr[u], g.rowptr[u + 1]):
+            m[u, g.col[e]] += 1.0 if vals is None else vals[e]
+    return m
+
+
+HAND_GRAPHS = {
+    "path5": ([0, 1, 2, 3], [1, 2, 3, 4], 5),
+    "star6": ([0, 0, 0, 0, 0], [1, 2, 3, 4, 5], 6),
+    "k4": ([0, 0, 0, 1, 1, 2], [1, 2, 3, 2, 3, 3], 4),
+    "two_components": ([0, 1, 3, 4], [1, 2, 4, 5], 7),  # node 6 isolated
+    "dups_and_selfedges": ([0, 0, 1, 2, 2, 3, 1, 0], [1, 1, 0, 2, 3, 3, 2, 0], 4),
+    "reverse_listed": ([4, 3, 2, 1], [3, 2, 1, 0], 5),
+}
+
+
+@pytest.mark.parametrize("name", sorted(HAND_GRAPHS))
+@pytest.mark.parametrize("sym", [True, False])
+@pytest.mark.parametrize("loops", [True, False])
+def test_csr_matches_dense_boolean(name, sym, loops):
+    src, dst, n = HAND_GRAPHS[name]
+    g = oracle.build_csr(src, dst, n, symmetrize=sym, self_loops=loops)
+    ref = dense_atilde(src, dst, n, sym, loops)
+    assert g.nnz == int(ref.sum())
+    assert np.array_equal(csr_to_dense(g) > 0, ref)
+    assert np.array_equal(g.rowptr, np.concatenate([[0], np.cumsum(ref.sum(axis=1))]))
+    for u in range(n):
+        cols = g.col[g.rowptr[u]:g.rowptr[u + 1]]
+        assert np.all(np.diff(cols.astype(np.int64)) > 0)  # strictly ascending => no duplicates
+        assert np.array_equal(cols, np.nonzero(ref[u])[0])
+
+
+def test_csr_random_64_nodes_vs_dense():
+    rng = np.random.default_rng(7)
+    for trial in range(20):
+        n = int(rng.integers(2, 65))
+        e = int(rng.integers(0, 4 * n))
+        src = rng.integers(0, n, e)
+        dst = rng.integers(0, n, e)
+        g = oracle.normalize(oracle.build_csr(src, dst, n))
+        at = dense_atilde(src, dst, n)
+        assert np.array_equal(csr_to_dense(g) > 0, at)
+        assert np.array_equal(g.deg, at.sum(axis=1))
+        np.testing.assert_allclose(csr_to_dense(g, g.val), dense_ahat(at), rtol=1e-15, atol=0)
+
+
+def test_csr_rejects_out_of_range():
+    with pytest.raises(ValueError):
+        oracle.build_csr([0, 5], [1, 2], 4)
+
+
+def test_csr_invariants_er_and_rmat():
+    for src, dst, n in [gg.config_graph("c1"), gg.config_graph("c2", scale_override=14)]:
+        g = oracle.normalize(oracle.build_csr(src, dst, n))
+        assert g.rowptr[0] == 0 and g.rowptr[-1] == g.nnz and np.all(np.diff(g.rowptr) >= 1)
+        rows = np.repeat(np.arange(n, dtype=np.int64), np.diff(g.rowptr))
+        keys = rows * n + g.col
+        assert np.all(np.diff(keys) > 0)  # sorted by (row, col), no duplicates
+        # every row holds its own index
+        has_diag = np.zeros(n, dtype=bool)
+        has_diag[rows[g.col == rows]] = True
+        assert has_diag.all()
+        # (u, v) stored <=> (v, u) stored
+        assert np.array_equal(np.sort(keys), np.sort(g.col.astype(np.int64) * n + rows))
+        assert int(g.deg.sum()) == g.nnz
+        # expected pair set, built independently with numpy sets
+        m = src != dst
+        a = np.concatenate([src[m].astype(np.int64) * n + dst[m], dst[m].astype(np.int64) * n + src[m],
+                            np.arange(n, dtype=np.int64) * (n + 1)])
+        assert np.array_equal(np.unique(a), keys)
+
+
+def test_er_mean_degree():
+    src, dst, n = gg.config_graph("c1")
+    assert abs(2 * len(src) / n - 10.0) < 0.3
+
+
+# ------------------------------------------------------------------------------------------
+# A_hat values
+# ------------------------------------------------------------------------------------------
+def test_golden_path3_ahat():
+    ref = np.loadtxt(os.path.join(GOLD, "path3_ahat.txt"))
+    g = oracle.normalize(oracle.build_csr([0, 1], [1, 2], 3))
+    np.testing.assert_allclose(csr_to_dense(g, g.val), ref, rtol=1e-15)
+    np.testing.assert_allclose(csr_to_dense(g, g.val_f32.astype(np.float64)), ref, rtol=2e-7)
+
+
+@pytest.mark.parametrize("n,k", [(16, 2), (50, 4), (1000, 10)])
+def test_regular_graph_values_and_row_sums(n, k):
+    src, dst = gg.ring_lattice_edges(n, k)
+    g = oracle.normalize(oracle.build_csr(src, dst, n))
+    assert np.all(g.deg == k + 1)
+    np.testing.assert_allclose(g.val, 1.0 / (k + 1), rtol=1e-15)
+    z = oracle.spmm(g, np.ones((n, 3)))
+    np.testing.assert_allclose(z, 1.0, rtol=1e-14)
+
+
+def test_eigenvector_identity_any_graph():
+    # A_hat d^(1/2) = d^(1/2):  sum_v At_uv d_u^-1/2 d_v^-1/2 d_v^1/2 = d_u^-1/2 * d_u
+    for src, dst, n in [gg.config_graph("c1"), gg.config_graph("c2", scale_override=15)]:
+        g = oracle.normalize(oracle.build_csr(src, dst, n))
+        r = np.sqrt(g.deg.astype(np.float64))[:, None]
+        np.testing.assert_allclose(oracle.spmm(g, r), r, rtol=1e-12)
+
+
+def test_complete_graph_is_column_mean():
+    n = 12
+    iu = np.triu_indices(n, 1)
+    g = oracle.normalize(oracle.build_csr(iu[0], iu[1], n))
+    h = np.random.default_rng(0).normal(size=(n, 5))
+    np.testing.assert_allclose(oracle.spmm(g, h), np.tile(h.mean(axis=0), (n, 1)), rtol=1e-13)
+
+
+def test_edgeless_graph_is_identity():
+    n = 9
+    g = oracle.normalize(oracle.build_csr([], [], n))
+    assert g.nnz == n and np.all(g.val == 1.0) and np.all(g.deg == 1)
+    h = np.random.default_rng(1).normal(size=(n, 4))
+    assert np.array_equal(oracle.spmm(g, h), h)
+
+
+def test_val_f32_symmetric_and_close():
+    src, dst, n = gg.config_graph("c1")
+    g = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n)))
+    assert np.array_equal(g.t_rowptr, g.rowptr) and np.array_equal(g.t_col, g.col)
+    assert np.array_equal(g.t_val, g.val)  # A_hat^T == A_hat bit for bit on symmetrised input
+    np.testing.assert_allclose(g.val_f32, g.val, rtol=1.5e-7)
+    dense = csr_to_dense(g, g.val_f32.astype(np.float64))
+    assert np.array_equal(dense, dense.T)
+
+
+# ------------------------------------------------------------------------------------------
+# products
+# ------------------------------------------------------------------------------------------
+def test_spmm_vs_dense_with_slices_and_row_ranges():
+    rng = np.random.default_rng(3)
+    n = 61
+    src = rng.integers(0, n, 300)
+    dst = rng.integers(0, n, 300)
+    g = oracle.normalize(oracle.build_csr(src, dst, n))
+    ah = dense_ahat(dense_atilde(src, dst, n))
+    h = rng.normal(size=(n, 24))
+    np.testing.assert_allclose(oracle.spmm(g, h), ah @ h, rtol=1e-12, atol=1e-14)
+    z = oracle.spmm(g, h, c0=5, c1=17, r0=10, r1=33)
+    ref = np.zeros_like(h)
+    ref[10:33, 5:17] = (ah @ h)[10:33, 5:17]
+    np.testing.assert_allclose(z, ref, rtol=1e-12, atol=1e-14)
+
+
+def test_transpose_on_directed_input_adjoint_and_dense():
+    rng = np.random.default_rng(4)
+    n = 40
+    src = rng.integers(0, n, 200)
+    dst = rng.integers(0, n, 200)
+    g = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n, symmetrize=False)))
+    ah = dense_ahat(dense_atilde(src, dst, n, symmetrize=False))
+    assert not np.array_equal(ah, ah.T)
+    x = rng.normal(size=(n, 6))
+    y = rng.normal(size=(n, 6))
+    np.testing.assert_allclose(oracle.spmm(g, y, transposed=True), ah.T @ y, rtol=1e-12, atol=1e-14)
+    lhs = np.sum(oracle.spmm(g, x) * y)
+    rhs = np.sum(x * oracle.spmm(g, y, transposed=True))
+    assert abs(lhs - rhs) <= 1e-12 * max(1.0, abs(lhs))
+    # columns of the transpose ascend too
+    for u in range(n):
+        assert np.all(np.diff(g.t_col[g.t_rowptr[u]:g.t_rowptr[u + 1]].astype(np.int64)) > 0)
+
+
+def test_column_sum_identity():
+    src, dst, n = gg.config_graph("c2", scale_override=12)
+    g = oracle.normalize(oracle.build_csr(src, dst, n))
+    h = gg.normal(1, 2, n, 8).astype(np.float64)
+    colsum_ahat = np.bincount(g.col, weights=g.val, minlength=n)  # 1^T A_hat
+    np.testing.assert_allclose(oracle.spmm(g, h).sum(axis=0), colsum_ahat @ h, rtol=1e-10)
+
+
+def test_updates_vs_numpy_matmul():
+    rng = np.random.default_rng(5)
+    z = rng.normal(size=(37, 11))
+    w = rng.normal(size=(11, 7))
+    dp = rng.normal(size=(37, 7))
+    p = z @ w
+    np.testing.assert_allclose(oracle.update_fwd(z, w, relu=False), p, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(oracle.update_fwd(z, w, relu=True), np.maximum(p, 0), rtol=1e-12,
+                               atol=1e-14)
+    np.testing.assert_allclose(oracle.update_dgrad(dp, w), dp @ w.T, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(oracle.update_wgrad(z, dp), z.T @ dp, rtol=1e-12, atol=1e-13)
+    outer = sum(np.outer(z[v], dp[v]) for v in range(37))
+    np.testing.assert_allclose(oracle.update_wgrad(z, dp), outer, rtol=1e-12, atol=1e-13)
+    href = rng.normal(size=(37, 7))
+    href[3, 2] = 0.0
+    np.testing.assert_array_equal(oracle.relu_grad(dp, href), dp * (href > 0))
+
+
+def test_wgrad_spans_several_row_blocks():
+    rng = np.random.default_rng(6)
+    z = rng.normal(size=(9000, 3))
+    dp = rng.normal(size=(9000, 2))
+    np.testing.assert_allclose(oracle.update_wgrad(z, dp), z.T @ dp, rtol=1e-11, atol=1e-12)
+
+
+def test_golden_star4_layer():
+    ref = np.loadtxt(os.path.join(GOLD, "star4_layer.txt"))
+    g = oracle.normalize(oracle.build_csr([0, 0, 0], [1, 2, 3], 4))
+    h = np.array([[1.0], [2.0], [3.0], [-10.0]])
+    w = np.array([[1.0, -1.0]])
+    z = oracle.spmm(g, h)
+    np.testing.assert_allclose(oracle.update_fwd(z, w, relu=False), ref, rtol=1e-15)
+    np.testing.assert_allclose(oracle.update_fwd(z, w, relu=True), np.maximum(ref, 0), rtol=1e-15)
+
+
+def test_edgeless_graph_layer_is_mlp_layer():
+    n = 10
+    rng = np.random.default_rng(8)
+    g = oracle.normalize(oracle.build_csr([], [], n))
+    x = rng.normal(size=(n, 6))
+    w = rng.normal(size=(6, 4))
+    out = oracle.update_fwd(oracle.spmm(g, x), w, relu=True)
+    np.testing.assert_allclose(out, np.maximum(x @ w, 0), rtol=1e-13, atol=1e-15)
+
+
+# ------------------------------------------------------------------------------------------
+# loss
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("c", [8, 16, 172, 47])
+def test_loss_at_zero_weights_is_ln_c(c):
+    n = 50
+    y = gg.labels(1, 9, n, c)
+    loss, d = oracle.softmax_xent(np.zeros((n, c)), y)
+    assert abs(loss - math.log(c)) < 1e-14
+    np.testing.assert_allclose(d.sum(axis=1), 0.0, atol=1e-16)
+    freq = np.bincount(y, minlength=c) / n
+    np.testing.assert_allclose(d.sum(axis=0), 1.0 / c - freq, atol=1e-15)
+
+
+def test_loss_vs_scipy_and_shift_invariance():
+    from scipy.special import log_softmax
+
+    rng = np.random.default_rng(9)
+    x = rng.normal(size=(33, 7)) * 5
+    y = rng.integers(0, 7, 33).astype(np.int32)
+    loss, d = oracle.softmax_xent(x, y)
+    ls = log_softmax(x, axis=1)
+    assert abs(loss + ls[np.arange(33), y].mean()) < 1e-13
+    oh = np.eye(7)[y]
+    np.testing.assert_allclose(d, (np.exp(ls) - oh) / 33, atol=1e-15)
+    loss2, _ = oracle.softmax_xent(x + 1000.0, y)  # max subtraction keeps it finite
+    assert abs(loss - loss2) < 1e-9
+
+
+# ------------------------------------------------------------------------------------------
+# whole forward + backward
+# ------------------------------------------------------------------------------------------
+def _tiny_problem(seed, n=12, dims=(4, 3, 3, 2)):
+    rng = np.random.default_rng(seed)
+    e = 2 * n
+    src = rng.integers(0, n, e)
+    dst = rng.integers(0, n, e)
+    g = oracle.normalize(oracle.build_csr(src, dst, n))
+    x = rng.normal(size=(n, dims[0]))
+    ws = [rng.normal(size=(dims[i], dims[i + 1])) for i in range(len(dims) - 1)]
+    y = rng.integers(0, dims[-1], n).astype(np.int32)
+    return g, src, dst, x, ws, y
+
+
+def test_linear_activation_closed_form():
+    g, src, dst, x, ws, y = _tiny_problem(11)
+    ah = dense_ahat(dense_atilde(src, dst, g.n))
+    out = oracle.gcn_step(g, x, ws, y, linear=True, backward=False)
+    ref = np.linalg.matrix_power(ah, 3) @ x @ ws[0] @ ws[1] @ ws[2]
+    np.testing.assert_allclose(out["logits"], ref, rtol=1e-11, atol=1e-13)
+
+
+def test_forward_vs_dense_definition():
+    g, src, dst, x, ws, y = _tiny_problem(12)
+    ah = dense_ahat(dense_atilde(src, dst, g.n))
+    h = x
+    for l, w in enumerate(ws):
+        h = ah @ h @ w
+        if l < len(ws) - 1:
+            h = np.maximum(h, 0)
+    out = oracle.gcn_step(g, x, ws, y, backward=False)
+    np.testing.assert_allclose(out["logits"], h, rtol=1e-11, atol=1e-13)
+
+
+@pytest.mark.parametrize("seed", [21, 22, 23])
+def test_gradients_vs_central_finite_differences(seed):
+    g, src, dst, x, ws, y = _tiny_problem(seed)
+    base = oracle.gcn_step(g, x, ws, y, want_dx=True)
+    # stay off the ReLU kinks: every pre-activation must be clear of 0 by more than the step
+    for l in (1, 2):
+        pre = base["Z"][l - 1] @ ws[l - 1]
+        if np.min(np.abs(pre)) < 1e-3:
+            pytest.skip("sample too close to a ReLU kink")
+    hstep = 1e-5
+
+    def loss_at(xx, wws):
+        return oracle.gcn_step(g, xx, wws, y, backward=False)["loss"]
+
+    for l, w in enumerate(ws):
+        num = np.zeros_like(w)
+        for idx in np.ndindex(*w.shape):
+            wp = [a.copy() for a in ws]
+            wm = [a.copy() for a in ws]
+            wp[l][idx] += hstep
+            wm[l][idx] -= hstep
+            num[idx] = (loss_at(x, wp) - loss_at(x, wm)) / (2 * hstep)
+        np.testing.assert_allclose(base["dW"][l], num, rtol=2e-6, atol=1e-9)
+    num = np.zeros_like(x)
+    for idx in np.ndindex(*x.shape):
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += hstep
+        xm[idx] -= hstep
+        num[idx] = (loss_at(xp, ws) - loss_at(xm, ws)) / (2 * hstep)
+    np.testing.assert_allclose(base["dX"], num, rtol=2e-6, atol=1e-9)
+
+
+def test_gradients_fd_on_directed_graph_pins_transpose_in_backward():
+    rng = np.random.default_rng(31)
+    n = 10
+    src = rng.integers(0, n, 25)
+    dst = rng.integers(0, n, 25)
+    g = oracle.normalize(oracle.build_csr(src, dst, n, symmetrize=False))
+    x = rng.normal(size=(n, 3))
+    ws = [rng.normal(size=(3, 3)), rng.normal(size=(3, 2))]
+    y = rng.integers(0, 2, n).astype(np.int32)
+    base = oracle.gcn_step(g, x, ws, y, want_dx=True, linear=True)
+    hstep = 1e-5
+    num = np.zeros_like(x)
+    for idx in np.ndindex(*x.shape):
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += hstep
+        xm[idx] -= hstep
+        num[idx] = (oracle.gcn_step(g, xp, ws, y, linear=True, backward=False)["loss"]
+                    - oracle.gcn_step(g, xm, ws, y, linear=True, backward=False)["loss"]) / (2 * hstep)
+    np.testing.assert_allclose(base["dX"], num, rtol=2e-6, atol=1e-9)
+
+
+def test_step_matches_composition_of_calls():
+    g, src, dst, x, ws, y = _tiny_problem(41, n=30, dims=(5, 6, 4))
+    out = oracle.gcn_step(g, x, ws, y, want_dx=True)
+    z0 = oracle.spmm(g, x)
+    h1 = oracle.update_fwd(z0, ws[0], relu=True)
+    z1 = oracle.spmm(g, h1)
+    logits = oracle.update_fwd(z1, ws[1], relu=False)
+    loss, dp1 = oracle.softmax_xent(logits, y)
+    assert loss == out["loss"]
+    np.testing.assert_array_equal(out["logits"], logits)
+    np.testing.assert_array_equal(out["dW"][1], oracle.update_wgrad(z1, dp1))
+    dh1 = oracle.spmm(g, oracle.update_dgrad(dp1, ws[1]), transposed=True)
+    dp0 = oracle.relu_grad(dh1, h1)
+    np.testing.assert_array_equal(out["dW"][0], oracle.update_wgrad(z0, dp0))
+    np.testing.assert_array_equal(out["dX"],
+                                  oracle.spmm(g, oracle.update_dgrad(dp0, ws[0]), transposed=True))
+
+
+def test_bf16_quantiser_rounds_to_nearest_even():
+    # 1 + 2^-8 is a tie between 1 and 1 + 2^-7 -> even mantissa (1.0); 1 + 3*2^-8 ties up.
+    z = np.array([[1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, -0.3]])
+    w = np.eye(4)
+    out = oracle.update_fwd(z, w, relu=False, q=oracle.Q_BF16)
+    assert out[0, 0] == 1.0 and out[0, 1] == 1.0 + 2.0 ** -6 and out[0, 2] == 1.0 + 2.0 ** -7
+    assert out[0, 3] == np.float32(-0.30078125)
+    out32 = oracle.update_fwd(z, w, relu=False, q=oracle.Q_F32)
+    assert np.array_equal(out32, z.astype(np.float32).astype(np.float64))
