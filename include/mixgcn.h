@@ -1,0 +1,181 @@
+/*
+ * mixgcn.h -- C ABI of the MI355X (gfx950) GCN layer path.
+ *
+ * One GPU's share of full-graph GCN training under the paper's mixture of parallelism
+ * (Algorithm 2): neighbor aggregation  Z = A_hat H  over all nodes on a slice of feature
+ * columns, node update  H' = sigma(Z W), and their backward passes, with the sparse and dense
+ * halves overlapped on row chunks (Sec. 3.2.2, fine-grain pipeline).
+ *
+ * Conventions
+ *  - Matrices are node x feature, row-major, with leading dimensions in ELEMENTS.  (The paper
+ *    writes feature x node matrices; Eq. 3 with W here = the paper's W^T is H' = sigma(A_hat H W).)
+ *  - Every pointer is a DEVICE pointer unless its comment says host.  The caller owns all
+ *    tensors and streams; the library owns only mixgcn_graph / mixgcn_pipeline objects.
+ *  - `stream` arguments are hipStream_t passed as void* (NULL = the default stream).  All work
+ *    is asynchronous on that stream except where stated.
+ *  - Base pointers must be 16-byte aligned and ld * sizeof(element) a multiple of 16.
+ *  - Every call returns 0 on success or a negative MIXGCN_E* code; mixgcn_last_error() gives a
+ *    thread-local message.  Bad arguments are rejected before anything is launched.
+ *  - dtype: MIXGCN_F32 = fp32 storage and arithmetic; MIXGCN_BF16 = bf16 storage of feature
+ *    tensors with fp32 accumulation (weights, A_hat values, logits and dW stay fp32).
+ */
+#ifndef MIXGCN_H
+#define MIXGCN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MIXGCN_VERSION 100
+
+enum {
+    MIXGCN_OK = 0,
+    MIXGCN_EINVAL = -1,       /* bad argument (null, range, alignment, ld < columns ...) */
+    MIXGCN_ENOMEM = -2,       /* device or host allocation failed */
+    MIXGCN_EHIP = -3,         /* a HIP runtime call failed; message has hipGetErrorString */
+    MIXGCN_ESTATE = -4,       /* call order violated (e.g. aggregate before normalize) */
+    MIXGCN_EUNSUPPORTED = -5  /* valid request that this build does not implement */
+};
+
+/* mixgcn_build_csr flags */
+enum {
+    MIXGCN_SYMMETRIZE = 1,      /* also insert (v,u) for every input (u,v) */
+    MIXGCN_ADD_SELF_LOOPS = 2,  /* A_tilde = A + I: one diagonal entry in every row */
+    MIXGCN_BUILD_TRANSPOSE = 4, /* also keep the CSR of the transpose (needed for backward when
+                                   SYMMETRIZE is not set; with SYMMETRIZE the matrix is its own
+                                   transpose and nothing extra is stored) */
+    MIXGCN_INPUT_ON_HOST = 8    /* src/dst are host pointers (copied synchronously) */
+};
+
+enum { MIXGCN_NORM_SYM = 0 }; /* A_hat = D^-1/2 A_tilde D^-1/2 */
+enum { MIXGCN_F32 = 0, MIXGCN_BF16 = 1 };
+
+/* mixgcn_update ops */
+enum {
+    MIXGCN_OP_FWD = 0,      /* C[n x m] = A[n x k] B[k x m]                                  */
+    MIXGCN_OP_FWD_RELU = 1, /* C = max(A B, 0)                                               */
+    MIXGCN_OP_DGRAD = 2,    /* C[n x k] = (A (.) 1[R > 0])[n x m]  B[k x m]^T                */
+    MIXGCN_OP_WGRAD = 3     /* C[k x m] = beta C + A[n x k]^T (B (.) 1[R > 0])[n x m]        */
+};
+
+typedef struct mixgcn_graph mixgcn_graph;
+typedef struct mixgcn_pipeline mixgcn_pipeline;
+
+/* Read-only view of a graph's device arrays (valid until mixgcn_graph_free). */
+typedef struct mixgcn_graph_view {
+    uint32_t n_nodes;
+    uint32_t flags;        /* the build flags */
+    int64_t nnz;           /* stored entries of A_tilde, self-loops included */
+    const int64_t* rowptr; /* [n_nodes + 1] */
+    const uint32_t* col;   /* [nnz], ascending within a row */
+    const float* val;      /* [nnz] A_hat values, NULL before mixgcn_normalize */
+    const uint32_t* deg;   /* [n_nodes] D_tilde_uu, NULL before mixgcn_normalize */
+    const float* dinv;     /* [n_nodes] D_tilde_uu^-1/2, NULL before mixgcn_normalize */
+    const int64_t* t_rowptr; /* transpose CSR; equal to rowptr/col/val pointers when the   */
+    const uint32_t* t_col;   /* graph was symmetrised; NULL if no transpose is available   */
+    const float* t_val;
+} mixgcn_graph_view;
+
+/* One GCN layer for mixgcn_layer_fwd / mixgcn_layer_bwd. */
+typedef struct mixgcn_layer_desc {
+    int32_t f_in;     /* d^(l): width of H and Z */
+    int32_t f_out;    /* d^(l+1): width of H' */
+    int64_t ld_h;     /* leading dimension of H (input features) and of dH */
+    int64_t ld_z;     /* leading dimension of Z and dZ */
+    int64_t ld_out;   /* leading dimension of Hout and G */
+    int64_t ld_w;     /* leading dimension of W and dW (fp32, f_in x f_out) */
+    int32_t dtype;    /* MIXGCN_F32 or MIXGCN_BF16 (storage of H, Z, Hout, G, dH) */
+    int32_t relu;     /* 1: Hout = relu(Z W); 0: Hout = Z W (last layer) */
+    int32_t n_chunks; /* row chunks of the fine-grain pipeline; 1 = no overlap */
+    int32_t reserved;
+} mixgcn_layer_desc;
+
+/*
+ * Sec. 2.1: A_tilde = A + I for a binary adjacency A.  Builds the sorted CSR of A_tilde from a
+ * directed edge list: (optionally) symmetrise, drop u == v, drop duplicates, (optionally) add
+ * the diagonal, order by (row, column).
+ *   src, dst  : [n_edges] node ids (device, or host with MIXGCN_INPUT_ON_HOST); not modified.
+ *   out       : receives a new graph, released with mixgcn_graph_free.
+ * Synchronises `stream` (nnz must be known to size the arrays).  An endpoint >= n_nodes gives
+ * MIXGCN_EINVAL and no graph.
+ */
+int mixgcn_build_csr(const uint32_t* src, const uint32_t* dst, uint64_t n_edges, uint32_t n_nodes,
+                     uint32_t flags, void* stream, mixgcn_graph** out);
+
+/*
+ * Sec. 2.1: D_tilde_uu = sum_v A_tilde_uv and A_hat = D_tilde^-1/2 A_tilde D_tilde^-1/2.
+ * Fills deg (row sums, exact integers), dinv = (float)(1/sqrt((double)deg)) and
+ * val[e] = dinv[row(e)] * dinv[col[e]] (one fp32 multiply, so val is symmetric bit for bit),
+ * for the transpose as well if it is stored.  Asynchronous on `stream`.
+ */
+int mixgcn_normalize(mixgcn_graph* g, int mode, void* stream);
+
+/*
+ * Algorithm 2, aggregation phase (and its adjoint for the backward pass):
+ *   Z[r, c] = sum_{e in row r of M} val[e] * H[col[e], c],
+ *   r in [row_begin, row_end), c in [col_begin, col_end),  M = A_hat (transpose = 0) or
+ *   A_hat^T (transpose = 1).
+ * [col_begin, col_end) is the worker's feature slice [floor(d i/m), floor(d (i+1)/m));
+ * [row_begin, row_end) is a pipeline chunk.  H and Z are indexed with absolute columns; entries
+ * of Z outside the ranges are not touched.  H and Z must not overlap.  col_begin and col_end
+ * must be multiples of 4 (fp32) or 8 (bf16) unless col_end equals the row width given by ld.
+ */
+int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void* H, int64_t ldh,
+                     void* Z, int64_t ldz, int32_t col_begin, int32_t col_end, int64_t row_begin,
+                     int64_t row_end, void* stream);
+
+/*
+ * Algorithm 2, update phase, and the two products of its backward pass (see MIXGCN_OP_*).
+ *   A, B, C    : operands as listed per op; n_rows = n, k = d^(l), m = d^(l+1).
+ *   relu_ref   : R, the stored layer output H' whose sign gives the ReLU derivative
+ *                (1[R > 0], 0 at 0); NULL = no mask.  Only DGRAD and WGRAD read it.
+ *   beta       : WGRAD only, 0 or 1.
+ * B (the weight matrix W[k x m], fp32) is always row-major k x m.  For WGRAD C is fp32.
+ */
+int mixgcn_update(int op, int dtype, const void* A, int64_t lda, const void* B, int64_t ldb,
+                  void* C, int64_t ldc, int64_t n_rows, int32_t k, int32_t m,
+                  const void* relu_ref, int64_t ldr, float beta, void* stream);
+
+/*
+ * One layer forward, Eq. 3 in the order of Algorithm 2:  Z = A_hat H;  Hout = sigma(Z W),
+ * run as d->n_chunks row chunks with the aggregation of chunk k overlapping the update of
+ * chunk k-1 on the pipeline's two streams (Sec. 3.2.2).  Z is kept for the backward pass.
+ * On return the work is enqueued; the pipeline's primary stream is ordered after all of it.
+ */
+int mixgcn_layer_fwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, const void* H,
+                     const float* W, void* Z, void* Hout, mixgcn_pipeline* p);
+
+/*
+ * One layer backward.  With dP = G (.) 1[Hout > 0] (d->relu) or dP = G:
+ *   dW = Z^T dP;   dZ = dP W^T;   dH = A_hat^T dZ.
+ * G may be overwritten.  dZ is written over Z.  dH == NULL skips dZ and dH (first layer when no
+ * input gradient is wanted).  dW is fp32 [f_in x f_out] with leading dimension d->ld_w.
+ */
+int mixgcn_layer_bwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, void* Z, const void* Hout,
+                     const float* W, void* G, float* dW, void* dH, mixgcn_pipeline* p);
+
+/*
+ * Loss glue (Algorithm 2, loss line): mean softmax cross-entropy over n nodes and its gradient
+ * dlogits = (softmax - onehot) / n (may alias logits).  loss: one device double.
+ */
+int mixgcn_softmax_xent(const float* logits, int64_t ldl, const int32_t* labels, int64_t n,
+                        int32_t n_classes, float* dlogits, int64_t ldd, double* loss,
+                        void* stream);
+
+/* Helpers. */
+int mixgcn_graph_info(const mixgcn_graph* g, mixgcn_graph_view* out);
+int mixgcn_graph_free(mixgcn_graph* g);
+/* Two streams for the chunk pipeline: `primary` runs the aggregation, `secondary` the update. */
+int mixgcn_pipeline_create(void* primary_stream, void* secondary_stream, mixgcn_pipeline** out);
+int mixgcn_pipeline_destroy(mixgcn_pipeline* p);
+const char* mixgcn_strerror(int code);
+const char* mixgcn_last_error(void);
+int mixgcn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MIXGCN_H */

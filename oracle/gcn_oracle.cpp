@@ -121,7 +121,9 @@ void oracle_normalize(const int64_t* rowptr, const uint32_t* col, uint32_t n_nod
     for (uint32_t u = 0; u < n_nodes; ++u)
         for (int64_t e = rowptr[u]; e < rowptr[u + 1]; ++e) {
             uint32_t v = col[e];
-            val[e] = 1.0 / std::sqrt((double)deg[u] * (double)deg[v]);
+            /* A zero row sum can only occur without the diagonal (the paper always adds I);
+             * D^(-1/2) is then undefined and the entry is taken as 0. */
+            val[e] = (deg[u] && deg[v]) ? 1.0 / std::sqrt((double)deg[u] * (double)deg[v]) : 0.0;
             if (val_f32) val_f32[e] = (float)dinv[u] * (float)dinv[v];
         }
 }

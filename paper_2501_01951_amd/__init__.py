@@ -1,0 +1,11 @@
+"""MI355X-native GCN layer path (aggregation SpMM + update GEMMs, forward and backward).
+
+Thin Python binding over the C ABI of ``libmixgcn.so`` (see ``include/mixgcn.h``).  Nothing
+is computed in Python: the wrappers only marshal pointers, sizes and streams.  torch is used
+for device memory and streams.  There is no CPU fallback: a missing library is an error.
+"""
+from .binding import (  # noqa: F401
+    BF16, F32, OP_DGRAD, OP_FWD, OP_FWD_RELU, OP_WGRAD, SYMMETRIZE, ADD_SELF_LOOPS,
+    BUILD_TRANSPOSE, INPUT_ON_HOST, Graph, LayerDesc, MixGCNError, Pipeline, aggregate, build_csr,
+    layer_bwd, layer_fwd, lib_path, load_library, normalize, softmax_xent, update, version,
+)

@@ -1,0 +1,273 @@
+"""ctypes binding of libmixgcn.so: argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmixgcn.so")
+_lib = None
+
+F32, BF16 = 0, 1
+OP_FWD, OP_FWD_RELU, OP_DGRAD, OP_WGRAD = 0, 1, 2, 3
+SYMMETRIZE, ADD_SELF_LOOPS, BUILD_TRANSPOSE, INPUT_ON_HOST = 1, 2, 4, 8
+
+
+class MixGCNError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        lib = load_library()
+        msg = lib.mixgcn_last_error().decode()
+        kind = lib.mixgcn_strerror(code).decode()
+        super().__init__(f"{where}: {kind} ({code}): {msg}")
+        self.code = code
+
+
+class _GraphView(ctypes.Structure):
+    _fields_ = [
+        ("n_nodes", ctypes.c_uint32), ("flags", ctypes.c_uint32), ("nnz", ctypes.c_int64),
+        ("rowptr", ctypes.c_void_p), ("col", ctypes.c_void_p), ("val", ctypes.c_void_p),
+        ("deg", ctypes.c_void_p), ("dinv", ctypes.c_void_p), ("t_rowptr", ctypes.c_void_p),
+        ("t_col", ctypes.c_void_p), ("t_val", ctypes.c_void_p),
+    ]
+
+
+class LayerDesc(ctypes.Structure):
+    _fields_ = [
+        ("f_in", ctypes.c_int32), ("f_out", ctypes.c_int32), ("ld_h", ctypes.c_int64),
+        ("ld_z", ctypes.c_int64), ("ld_out", ctypes.c_int64), ("ld_w", ctypes.c_int64),
+        ("dtype", ctypes.c_int32), ("relu", ctypes.c_int32), ("n_chunks", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
+    ]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libmixgcn.so; builds it first only if it has never been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+
+        _build.build()
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64, u32, u64, f32 = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64,
+                                   ctypes.c_uint32, ctypes.c_uint64, ctypes.c_float)
+    lib.mixgcn_version.restype = ctypes.c_int
+    lib.mixgcn_last_error.restype = ctypes.c_char_p
+    lib.mixgcn_strerror.restype = ctypes.c_char_p
+    lib.mixgcn_strerror.argtypes = [ctypes.c_int]
+    lib.mixgcn_build_csr.argtypes = [vp, vp, u64, u32, u32, vp, ctypes.POINTER(vp)]
+    lib.mixgcn_normalize.argtypes = [vp, ctypes.c_int, vp]
+    lib.mixgcn_aggregate.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, i64, vp, i64, i32, i32,
+                                     i64, i64, vp]
+    lib.mixgcn_update.argtypes = [ctypes.c_int, ctypes.c_int, vp, i64, vp, i64, vp, i64, i64, i32,
+                                  i32, vp, i64, f32, vp]
+    lib.mixgcn_layer_fwd.argtypes = [vp, ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp]
+    lib.mixgcn_layer_bwd.argtypes = [vp, ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp]
+    lib.mixgcn_softmax_xent.argtypes = [vp, i64, vp, i64, i32, vp, i64, vp, vp]
+    lib.mixgcn_graph_info.argtypes = [vp, ctypes.POINTER(_GraphView)]
+    lib.mixgcn_graph_free.argtypes = [vp]
+    lib.mixgcn_pipeline_create.argtypes = [vp, vp, ctypes.POINTER(vp)]
+    lib.mixgcn_pipeline_destroy.argtypes = [vp]
+    for name in ("build_csr", "normalize", "aggregate", "update", "layer_fwd", "layer_bwd",
+                 "softmax_xent", "graph_info", "graph_free", "pipeline_create", "pipeline_destroy"):
+        getattr(lib, "mixgcn_" + name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def version() -> int:
+    return load_library().mixgcn_version()
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise MixGCNError(rc, where)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _ld(t) -> int:
+    assert t.dim() == 2 and t.stride(1) == 1, "row-major 2-D tensor expected"
+    return t.stride(0)
+
+
+def _dtype_of(t) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+class _DevArray:
+    """Exposes a library-owned device array through __cuda_array_interface__."""
+
+    def __init__(self, ptr, count, typestr):
+        self.__cuda_array_interface__ = {"shape": (count,), "typestr": typestr,
+                                         "data": (int(ptr), False), "version": 2}
+
+
+_TYPESTR = {torch.int64: "<i8", torch.int32: "<i4", torch.float32: "<f4"}
+
+
+def _view_array(ptr, count, dtype, device):
+    """Copy of a library-owned device array as a torch tensor (for tests and inspection)."""
+    if not count:
+        return torch.empty(0, dtype=dtype, device=device)
+    return torch.as_tensor(_DevArray(ptr, count, _TYPESTR[dtype]), device=device).clone()
+
+
+class Graph:
+    """Owner of a mixgcn_graph handle."""
+
+    def __init__(self, handle, device):
+        self._h = handle
+        self.device = device
+
+    def info(self) -> _GraphView:
+        v = _GraphView()
+        _check(load_library().mixgcn_graph_info(self._h, ctypes.byref(v)), "graph_info")
+        return v
+
+    @property
+    def n(self) -> int:
+        return self.info().n_nodes
+
+    @property
+    def nnz(self) -> int:
+        return self.info().nnz
+
+    def arrays(self, transpose: bool = False):
+        """Copies of rowptr, col, val (and deg, dinv) as torch tensors."""
+        torch.cuda.synchronize()
+        v = self.info()
+        rp, cl, vl = (v.t_rowptr, v.t_col, v.t_val) if transpose else (v.rowptr, v.col, v.val)
+        out = {
+            "rowptr": _view_array(rp, v.n_nodes + 1, torch.int64, self.device),
+            "col": _view_array(cl, v.nnz, torch.int32, self.device),
+        }
+        if vl:
+            out["val"] = _view_array(vl, v.nnz, torch.float32, self.device)
+        if v.deg:
+            out["deg"] = _view_array(v.deg, v.n_nodes, torch.int32, self.device)
+            out["dinv"] = _view_array(v.dinv, v.n_nodes, torch.float32, self.device)
+        torch.cuda.synchronize()
+        return out
+
+    def free(self):
+        if self._h:
+            load_library().mixgcn_graph_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+class Pipeline:
+    """Two streams for the row-chunk pipeline (primary: aggregation, secondary: update)."""
+
+    def __init__(self, primary=None, secondary=None):
+        self.primary = primary if primary is not None else torch.cuda.current_stream()
+        self.secondary = secondary if secondary is not None else torch.cuda.Stream()
+        h = ctypes.c_void_p()
+        _check(load_library().mixgcn_pipeline_create(ctypes.c_void_p(self.primary.cuda_stream),
+                                                     ctypes.c_void_p(self.secondary.cuda_stream),
+                                                     ctypes.byref(h)), "pipeline_create")
+        self._h = h
+
+    def free(self):
+        if self._h:
+            load_library().mixgcn_pipeline_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def build_csr(src, dst, n_nodes: int, flags: int = SYMMETRIZE | ADD_SELF_LOOPS, stream=None) -> Graph:
+    """src, dst: int32/uint32 torch tensors (cuda, or cpu with INPUT_ON_HOST)."""
+    assert src.numel() == dst.numel() and src.element_size() == 4 and dst.element_size() == 4
+    src, dst = src.contiguous(), dst.contiguous()
+    on_host = not src.is_cuda
+    if on_host:
+        flags |= INPUT_ON_HOST
+    dev = torch.device("cuda", torch.cuda.current_device()) if on_host else src.device
+    h = ctypes.c_void_p()
+    rc = load_library().mixgcn_build_csr(_ptr(src) if src.numel() else None,
+                                         _ptr(dst) if dst.numel() else None, src.numel(), n_nodes,
+                                         flags, _stream(stream), ctypes.byref(h))
+    _check(rc, "build_csr")
+    return Graph(h, dev)
+
+
+def normalize(g: Graph, mode: int = 0, stream=None) -> None:
+    _check(load_library().mixgcn_normalize(g._h, mode, _stream(stream)), "normalize")
+
+
+def aggregate(g: Graph, H, Z, col_begin=0, col_end=None, row_begin=0, row_end=None,
+              transpose=False, stream=None) -> None:
+    col_end = H.shape[1] if col_end is None else col_end
+    row_end = g.n if row_end is None else row_end
+    _check(load_library().mixgcn_aggregate(g._h, int(transpose), _dtype_of(H), _ptr(H), _ld(H),
+                                           _ptr(Z), _ld(Z), col_begin, col_end, row_begin, row_end,
+                                           _stream(stream)), "aggregate")
+
+
+def update(op: int, A, B, C, n_rows: int, k: int, m: int, relu_ref=None, beta: float = 0.0,
+           stream=None) -> None:
+    dt = _dtype_of(A)
+    _check(load_library().mixgcn_update(op, dt, _ptr(A), _ld(A), _ptr(B), _ld(B), _ptr(C), _ld(C),
+                                        n_rows, k, m, _ptr(relu_ref),
+                                        _ld(relu_ref) if relu_ref is not None else 0, beta,
+                                        _stream(stream)), "update")
+
+
+def _desc(H_like_in, Z, Hout_like, W, relu: bool, n_chunks: int) -> LayerDesc:
+    d = LayerDesc()
+    d.f_in, d.f_out = W.shape[0], W.shape[1]
+    d.ld_h, d.ld_z, d.ld_out, d.ld_w = _ld(H_like_in), _ld(Z), _ld(Hout_like), _ld(W)
+    d.dtype = _dtype_of(Z)
+    d.relu = int(relu)
+    d.n_chunks = n_chunks
+    return d
+
+
+def layer_fwd(g: Graph, H, W, Z, Hout, pipe: Pipeline, relu: bool = True, n_chunks: int = 1) -> None:
+    d = _desc(H, Z, Hout, W, relu, n_chunks)
+    _check(load_library().mixgcn_layer_fwd(g._h, ctypes.byref(d), _ptr(H), _ptr(W), _ptr(Z),
+                                           _ptr(Hout), pipe._h), "layer_fwd")
+
+
+def layer_bwd(g: Graph, Z, Hout, W, G, dW, dH, pipe: Pipeline, relu: bool = True,
+              n_chunks: int = 1) -> None:
+    d = _desc(dH if dH is not None else Z, Z, G, W, relu, n_chunks)
+    _check(load_library().mixgcn_layer_bwd(g._h, ctypes.byref(d), _ptr(Z), _ptr(Hout), _ptr(W),
+                                           _ptr(G), _ptr(dW), _ptr(dH), pipe._h), "layer_bwd")
+
+
+def softmax_xent(logits, labels, dlogits, loss, stream=None) -> None:
+    n, c = logits.shape
+    _check(load_library().mixgcn_softmax_xent(_ptr(logits), _ld(logits), _ptr(labels), n, c,
+                                              _ptr(dlogits), _ld(dlogits), _ptr(loss),
+                                              _stream(stream)), "softmax_xent")

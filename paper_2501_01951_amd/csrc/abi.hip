@@ -1,0 +1,412 @@
+// C ABI entry points: argument validation, object lifetime, and the two-stream row-chunk
+// pipeline that overlaps the aggregation of chunk k with the update of chunk k-1
+// (paper Sec. 3.2.2, fine-grain pipeline between the sparse and the dense half of a layer).
+#include <cstring>
+#include <mutex>
+#include <new>
+
+#include "internal.h"
+
+namespace mixgcn {
+
+static thread_local std::string g_last_error;
+
+void set_error(const std::string& msg) { g_last_error = msg; }
+int fail(int code, const std::string& msg)
+{
+    g_last_error = msg;
+    return code;
+}
+
+// Grow-only device scratch for entry points that carry no handle (split-K partials of the
+// weight gradient, block partials of the loss).  One buffer per purpose and device.
+namespace {
+struct Scratch {
+    void* p = nullptr;
+    size_t bytes = 0;
+};
+constexpr int kMaxDevices = 16;
+constexpr int kScratchKinds = 2;
+Scratch g_scratch[kMaxDevices][kScratchKinds];
+std::mutex g_scratch_mu;
+}  // namespace
+
+int get_scratch(int which, size_t bytes, void** out)
+{
+    int dev = 0;
+    MIXGCN_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices || which < 0 || which >= kScratchKinds)
+        return fail(MIXGCN_EINVAL, "scratch: bad device or kind");
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    Scratch& sc = g_scratch[dev][which];
+    if (bytes > sc.bytes) {
+        MIXGCN_HIP_TRY(hipDeviceSynchronize());  // earlier kernels may still use the old buffer
+        if (sc.p) (void)hipFree(sc.p);
+        sc.p = nullptr;
+        sc.bytes = 0;
+        const size_t want = bytes + bytes / 4 + 256;
+        MIXGCN_HIP_TRY(hipMalloc(&sc.p, want));
+        sc.bytes = want;
+    }
+    *out = sc.p;
+    return MIXGCN_OK;
+}
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int elem_size(int dtype) { return dtype == MIXGCN_BF16 ? 2 : 4; }
+
+int check_matrix(const char* what, const void* p, int64_t ld, int64_t cols, int esize)
+{
+    if (!p) return fail(MIXGCN_EINVAL, std::string(what) + ": null pointer");
+    if (!aligned16(p)) return fail(MIXGCN_EINVAL, std::string(what) + ": not 16-byte aligned");
+    if (ld < cols) return fail(MIXGCN_EINVAL, std::string(what) + ": ld < columns");
+    if ((ld * esize) % 16 != 0)
+        return fail(MIXGCN_EINVAL, std::string(what) + ": ld * sizeof(element) not a multiple of 16");
+    return MIXGCN_OK;
+}
+
+}  // namespace
+}  // namespace mixgcn
+
+using namespace mixgcn;
+
+extern "C" {
+
+int mixgcn_version(void) { return MIXGCN_VERSION; }
+
+const char* mixgcn_last_error(void) { return g_last_error.c_str(); }
+
+const char* mixgcn_strerror(int code)
+{
+    switch (code) {
+    case MIXGCN_OK: return "ok";
+    case MIXGCN_EINVAL: return "invalid argument";
+    case MIXGCN_ENOMEM: return "out of memory";
+    case MIXGCN_EHIP: return "HIP runtime error";
+    case MIXGCN_ESTATE: return "call order violated";
+    case MIXGCN_EUNSUPPORTED: return "not supported by this build";
+    default: return "unknown error";
+    }
+}
+
+int mixgcn_build_csr(const uint32_t* src, const uint32_t* dst, uint64_t n_edges, uint32_t n_nodes,
+                     uint32_t flags, void* stream, mixgcn_graph** out)
+{
+    if (!out) return fail(MIXGCN_EINVAL, "build_csr: out is null");
+    *out = nullptr;
+    if (n_nodes == 0) return fail(MIXGCN_EINVAL, "build_csr: n_nodes == 0");
+    if (n_nodes > 0x7FFFFFFFu) return fail(MIXGCN_EINVAL, "build_csr: n_nodes > 2^31 - 1");
+    if (n_edges > 0 && (!src || !dst)) return fail(MIXGCN_EINVAL, "build_csr: null edge list");
+    if (n_edges > (1ull << 40)) return fail(MIXGCN_EINVAL, "build_csr: n_edges too large");
+    if (flags & ~(uint32_t)(MIXGCN_SYMMETRIZE | MIXGCN_ADD_SELF_LOOPS | MIXGCN_BUILD_TRANSPOSE |
+                            MIXGCN_INPUT_ON_HOST))
+        return fail(MIXGCN_EINVAL, "build_csr: unknown flag");
+    hipStream_t s = (hipStream_t)stream;
+    const bool sym = flags & MIXGCN_SYMMETRIZE, loops = flags & MIXGCN_ADD_SELF_LOOPS;
+
+    uint32_t* d_src = nullptr;
+    uint32_t* d_dst = nullptr;
+    const uint32_t* use_src = src;
+    const uint32_t* use_dst = dst;
+    int rc = MIXGCN_OK;
+    mixgcn_graph* g = new (std::nothrow) mixgcn_graph();
+    if (!g) return fail(MIXGCN_ENOMEM, "build_csr: host allocation failed");
+    do {
+        if (hipGetDevice(&g->device) != hipSuccess) { rc = fail(MIXGCN_EHIP, "hipGetDevice"); break; }
+        if ((flags & MIXGCN_INPUT_ON_HOST) && n_edges > 0) {
+            if (hipMalloc((void**)&d_src, n_edges * 4) != hipSuccess ||
+                hipMalloc((void**)&d_dst, n_edges * 4) != hipSuccess) {
+                rc = fail(MIXGCN_ENOMEM, "build_csr: staging the host edge list");
+                break;
+            }
+            if (hipMemcpy(d_src, src, n_edges * 4, hipMemcpyHostToDevice) != hipSuccess ||
+                hipMemcpy(d_dst, dst, n_edges * 4, hipMemcpyHostToDevice) != hipSuccess) {
+                rc = fail(MIXGCN_EHIP, "build_csr: copying the host edge list");
+                break;
+            }
+            use_src = d_src;
+            use_dst = d_dst;
+        }
+        g->n = n_nodes;
+        g->flags = flags;
+        rc = csr_from_edges(use_src, use_dst, n_edges, n_nodes, sym, loops, false, &g->fwd, s);
+        if (rc != MIXGCN_OK) break;
+        if ((flags & MIXGCN_BUILD_TRANSPOSE) && !sym) {
+            rc = csr_from_edges(use_src, use_dst, n_edges, n_nodes, false, loops, true, &g->tr, s);
+            if (rc != MIXGCN_OK) break;
+            g->has_transpose = true;
+        }
+    } while (0);
+    if (d_src) (void)hipFree(d_src);
+    if (d_dst) (void)hipFree(d_dst);
+    if (rc != MIXGCN_OK) {
+        mixgcn_graph_free(g);
+        return rc;
+    }
+    *out = g;
+    return MIXGCN_OK;
+}
+
+int mixgcn_graph_free(mixgcn_graph* g)
+{
+    if (!g) return MIXGCN_OK;
+    csr_free(&g->fwd);
+    csr_free(&g->tr);
+    if (g->deg) (void)hipFree(g->deg);
+    if (g->dinv) (void)hipFree(g->dinv);
+    if (g->partials) (void)hipFree(g->partials);
+    delete g;
+    return MIXGCN_OK;
+}
+
+int mixgcn_normalize(mixgcn_graph* g, int mode, void* stream)
+{
+    if (!g) return fail(MIXGCN_EINVAL, "normalize: graph is null");
+    if (mode != MIXGCN_NORM_SYM) return fail(MIXGCN_EINVAL, "normalize: unknown mode");
+    return normalize_sym(g, (hipStream_t)stream);
+}
+
+int mixgcn_graph_info(const mixgcn_graph* g, mixgcn_graph_view* out)
+{
+    if (!g || !out) return fail(MIXGCN_EINVAL, "graph_info: null argument");
+    std::memset(out, 0, sizeof(*out));
+    out->n_nodes = g->n;
+    out->flags = g->flags;
+    out->nnz = g->fwd.nnz;
+    out->rowptr = g->fwd.rowptr;
+    out->col = g->fwd.col;
+    out->val = g->normalized ? g->fwd.val : nullptr;
+    out->deg = g->normalized ? g->deg : nullptr;
+    out->dinv = g->normalized ? g->dinv : nullptr;
+    const mixgcn::Csr* t = nullptr;
+    if (g->flags & MIXGCN_SYMMETRIZE) t = &g->fwd;
+    else if (g->has_transpose) t = &g->tr;
+    if (t) {
+        out->t_rowptr = t->rowptr;
+        out->t_col = t->col;
+        out->t_val = g->normalized ? t->val : nullptr;
+    }
+    return MIXGCN_OK;
+}
+
+int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void* H, int64_t ldh,
+                     void* Z, int64_t ldz, int32_t col_begin, int32_t col_end, int64_t row_begin,
+                     int64_t row_end, void* stream)
+{
+    if (!g) return fail(MIXGCN_EINVAL, "aggregate: graph is null");
+    if (!g->normalized) return fail(MIXGCN_ESTATE, "aggregate: call mixgcn_normalize first");
+    if (dtype != MIXGCN_F32 && dtype != MIXGCN_BF16) return fail(MIXGCN_EINVAL, "aggregate: dtype");
+    const int es = elem_size(dtype), vec = 16 / es;
+    if (col_begin < 0 || col_end < col_begin) return fail(MIXGCN_EINVAL, "aggregate: column range");
+    if (row_begin < 0 || row_end < row_begin || row_end > (int64_t)g->n)
+        return fail(MIXGCN_EINVAL, "aggregate: row range");
+    MIXGCN_TRY(check_matrix("aggregate: H", H, ldh, col_end, es));
+    MIXGCN_TRY(check_matrix("aggregate: Z", Z, ldz, col_end, es));
+    if (col_begin % vec != 0) return fail(MIXGCN_EINVAL, "aggregate: col_begin not vector aligned");
+    if (col_end % vec != 0) {
+        // the last vector reaches into the row padding, which must exist in both matrices
+        const int64_t up = (col_end + vec - 1) / vec * vec;
+        if (up > ldh || up > ldz)
+            return fail(MIXGCN_EINVAL, "aggregate: col_end not vector aligned and no row padding");
+    }
+    {
+        const char* h0 = (const char*)H;
+        const char* h1 = h0 + (size_t)g->n * ldh * es;
+        const char* z0 = (const char*)Z;
+        const char* z1 = z0 + (size_t)g->n * ldz * es;
+        if (h0 < z1 && z0 < h1) return fail(MIXGCN_EINVAL, "aggregate: H and Z overlap");
+    }
+    const mixgcn::Csr* m = &g->fwd;
+    if (transpose && !(g->flags & MIXGCN_SYMMETRIZE)) {
+        if (!g->has_transpose)
+            return fail(MIXGCN_ESTATE, "aggregate: transpose needs MIXGCN_BUILD_TRANSPOSE");
+        m = &g->tr;
+    }
+    if (row_end == row_begin || col_end == col_begin) return MIXGCN_OK;
+    return launch_aggregate(g, *m, dtype, H, ldh, Z, ldz, col_begin, col_end, row_begin, row_end,
+                            (hipStream_t)stream);
+}
+
+int mixgcn_update(int op, int dtype, const void* A, int64_t lda, const void* B, int64_t ldb,
+                  void* C, int64_t ldc, int64_t n_rows, int32_t k, int32_t m,
+                  const void* relu_ref, int64_t ldr, float beta, void* stream)
+{
+    if (op < MIXGCN_OP_FWD || op > MIXGCN_OP_WGRAD) return fail(MIXGCN_EINVAL, "update: op");
+    if (dtype != MIXGCN_F32 && dtype != MIXGCN_BF16) return fail(MIXGCN_EINVAL, "update: dtype");
+    if (n_rows < 0 || k <= 0 || m <= 0) return fail(MIXGCN_EINVAL, "update: sizes");
+    if (beta != 0.f && beta != 1.f) return fail(MIXGCN_EINVAL, "update: beta must be 0 or 1");
+    const int es = elem_size(dtype);
+    switch (op) {
+    case MIXGCN_OP_FWD:
+    case MIXGCN_OP_FWD_RELU:
+        MIXGCN_TRY(check_matrix("update: A", A, lda, k, es));
+        MIXGCN_TRY(check_matrix("update: B", B, ldb, m, 4));
+        MIXGCN_TRY(check_matrix("update: C", C, ldc, m, es));
+        break;
+    case MIXGCN_OP_DGRAD:
+        MIXGCN_TRY(check_matrix("update: A", A, lda, m, es));
+        MIXGCN_TRY(check_matrix("update: B", B, ldb, m, 4));
+        MIXGCN_TRY(check_matrix("update: C", C, ldc, k, es));
+        if (relu_ref) MIXGCN_TRY(check_matrix("update: relu_ref", relu_ref, ldr, m, es));
+        break;
+    default:
+        MIXGCN_TRY(check_matrix("update: A", A, lda, k, es));
+        MIXGCN_TRY(check_matrix("update: B", B, ldb, m, es));
+        MIXGCN_TRY(check_matrix("update: C", C, ldc, m, 4));
+        if (relu_ref) MIXGCN_TRY(check_matrix("update: relu_ref", relu_ref, ldr, m, es));
+        break;
+    }
+    return launch_update(op, dtype, A, lda, (const float*)B, ldb, C, ldc, n_rows, k, m, relu_ref,
+                         ldr, beta, (hipStream_t)stream);
+}
+
+int mixgcn_softmax_xent(const float* logits, int64_t ldl, const int32_t* labels, int64_t n,
+                        int32_t n_classes, float* dlogits, int64_t ldd, double* loss,
+                        void* stream)
+{
+    if (!logits || !labels || !dlogits || !loss) return fail(MIXGCN_EINVAL, "softmax_xent: null");
+    if (n <= 0 || n_classes <= 0 || ldl < n_classes || ldd < n_classes)
+        return fail(MIXGCN_EINVAL, "softmax_xent: sizes");
+    return launch_softmax_xent(logits, ldl, labels, n, n_classes, dlogits, ldd, loss,
+                               (hipStream_t)stream);
+}
+
+int mixgcn_pipeline_create(void* primary_stream, void* secondary_stream, mixgcn_pipeline** out)
+{
+    if (!out) return fail(MIXGCN_EINVAL, "pipeline_create: out is null");
+    *out = nullptr;
+    mixgcn_pipeline* p = new (std::nothrow) mixgcn_pipeline();
+    if (!p) return fail(MIXGCN_ENOMEM, "pipeline_create: host allocation failed");
+    p->primary = (hipStream_t)primary_stream;
+    p->secondary = (hipStream_t)secondary_stream;
+    if (hipEventCreateWithFlags(&p->ev_start, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&p->ev_done, hipEventDisableTiming) != hipSuccess) {
+        mixgcn_pipeline_destroy(p);
+        return fail(MIXGCN_EHIP, "pipeline_create: hipEventCreate");
+    }
+    *out = p;
+    return MIXGCN_OK;
+}
+
+int mixgcn_pipeline_destroy(mixgcn_pipeline* p)
+{
+    if (!p) return MIXGCN_OK;
+    for (hipEvent_t e : p->events) (void)hipEventDestroy(e);
+    if (p->ev_start) (void)hipEventDestroy(p->ev_start);
+    if (p->ev_done) (void)hipEventDestroy(p->ev_done);
+    if (p->wt) (void)hipFree(p->wt);
+    delete p;
+    return MIXGCN_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+int ensure_events(mixgcn_pipeline* p, size_t count)
+{
+    while (p->events.size() < count) {
+        hipEvent_t e;
+        MIXGCN_HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        p->events.push_back(e);
+    }
+    return MIXGCN_OK;
+}
+
+// Chunk boundaries: multiples of 128 rows (the update kernels' row tile), last chunk ragged.
+int64_t chunk_bound(int64_t n, int n_chunks, int i)
+{
+    if (i >= n_chunks) return n;
+    int64_t b = (n * i / n_chunks + 127) / 128 * 128;
+    return b < n ? b : n;
+}
+
+int check_layer(const char* who, const mixgcn_graph* g, const mixgcn_layer_desc* d,
+                const mixgcn_pipeline* p)
+{
+    if (!g || !d || !p) return fail(MIXGCN_EINVAL, std::string(who) + ": null argument");
+    if (!g->normalized) return fail(MIXGCN_ESTATE, std::string(who) + ": graph not normalized");
+    if (d->f_in <= 0 || d->f_out <= 0 || d->n_chunks <= 0 || d->n_chunks > 65536)
+        return fail(MIXGCN_EINVAL, std::string(who) + ": bad layer sizes");
+    if (d->dtype != MIXGCN_F32 && d->dtype != MIXGCN_BF16)
+        return fail(MIXGCN_EINVAL, std::string(who) + ": dtype");
+    return MIXGCN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mixgcn_layer_fwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, const void* H,
+                     const float* W, void* Z, void* Hout, mixgcn_pipeline* p)
+{
+    MIXGCN_TRY(check_layer("layer_fwd", g, d, p));
+    if (!H || !W || !Z || !Hout) return fail(MIXGCN_EINVAL, "layer_fwd: null tensor");
+    const int64_t n = g->n;
+    const int es = elem_size(d->dtype);
+    const int op = d->relu ? MIXGCN_OP_FWD_RELU : MIXGCN_OP_FWD;
+    const int nc = d->n_chunks;
+    if (nc == 1 || p->secondary == p->primary) {
+        MIXGCN_TRY(mixgcn_aggregate(g, 0, d->dtype, H, d->ld_h, Z, d->ld_z, 0, d->f_in, 0, n,
+                                    p->primary));
+        return mixgcn_update(op, d->dtype, Z, d->ld_z, W, d->ld_w, Hout, d->ld_out, n, d->f_in,
+                             d->f_out, nullptr, 0, 0.f, p->primary);
+    }
+    MIXGCN_TRY(ensure_events(p, (size_t)nc));
+    // the dense stream may not start before everything queued on the sparse stream so far
+    MIXGCN_HIP_TRY(hipEventRecord(p->ev_start, p->primary));
+    MIXGCN_HIP_TRY(hipStreamWaitEvent(p->secondary, p->ev_start, 0));
+    for (int c = 0; c < nc; ++c) {
+        const int64_t r0 = chunk_bound(n, nc, c), r1 = chunk_bound(n, nc, c + 1);
+        if (r1 <= r0) continue;
+        MIXGCN_TRY(mixgcn_aggregate(g, 0, d->dtype, H, d->ld_h, Z, d->ld_z, 0, d->f_in, r0, r1,
+                                    p->primary));
+        MIXGCN_HIP_TRY(hipEventRecord(p->events[(size_t)c], p->primary));
+        MIXGCN_HIP_TRY(hipStreamWaitEvent(p->secondary, p->events[(size_t)c], 0));
+        const char* zc = (const char*)Z + (size_t)r0 * d->ld_z * es;
+        char* oc = (char*)Hout + (size_t)r0 * d->ld_out * es;
+        MIXGCN_TRY(mixgcn_update(op, d->dtype, zc, d->ld_z, W, d->ld_w, oc, d->ld_out, r1 - r0,
+                                 d->f_in, d->f_out, nullptr, 0, 0.f, p->secondary));
+    }
+    MIXGCN_HIP_TRY(hipEventRecord(p->ev_done, p->secondary));
+    MIXGCN_HIP_TRY(hipStreamWaitEvent(p->primary, p->ev_done, 0));
+    return MIXGCN_OK;
+}
+
+int mixgcn_layer_bwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, void* Z, const void* Hout,
+                     const float* W, void* G, float* dW, void* dH, mixgcn_pipeline* p)
+{
+    MIXGCN_TRY(check_layer("layer_bwd", g, d, p));
+    if (!Z || !W || !G || !dW) return fail(MIXGCN_EINVAL, "layer_bwd: null tensor");
+    if (d->relu && !Hout) return fail(MIXGCN_EINVAL, "layer_bwd: relu layer needs Hout");
+    const int64_t n = g->n;
+    const void* R = d->relu ? Hout : nullptr;
+    const bool two = p->secondary != p->primary && d->n_chunks > 1;
+    hipStream_t dense = two ? p->secondary : p->primary;
+    if (two) {
+        MIXGCN_HIP_TRY(hipEventRecord(p->ev_start, p->primary));
+        MIXGCN_HIP_TRY(hipStreamWaitEvent(p->secondary, p->ev_start, 0));
+    }
+    // dW = Z^T dP must read Z before dZ overwrites it
+    MIXGCN_TRY(mixgcn_update(MIXGCN_OP_WGRAD, d->dtype, Z, d->ld_z, G, d->ld_out, dW, d->ld_w, n,
+                             d->f_in, d->f_out, R, d->ld_out, 0.f, dense));
+    if (dH) {
+        MIXGCN_TRY(mixgcn_update(MIXGCN_OP_DGRAD, d->dtype, G, d->ld_out, W, d->ld_w, Z, d->ld_z, n,
+                                 d->f_in, d->f_out, R, d->ld_out, 0.f, dense));
+        if (two) {
+            MIXGCN_HIP_TRY(hipEventRecord(p->ev_done, p->secondary));
+            MIXGCN_HIP_TRY(hipStreamWaitEvent(p->primary, p->ev_done, 0));
+        }
+        MIXGCN_TRY(mixgcn_aggregate(g, 1, d->dtype, Z, d->ld_z, dH, d->ld_h, 0, d->f_in, 0, n,
+                                    p->primary));
+    } else if (two) {
+        MIXGCN_HIP_TRY(hipEventRecord(p->ev_done, p->secondary));
+        MIXGCN_HIP_TRY(hipStreamWaitEvent(p->primary, p->ev_done, 0));
+    }
+    return MIXGCN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,374 @@
+// Node update H' = sigma(Z W) (paper Algorithm 2, update phase) and the two dense products of
+// its backward pass, dZ = dP W^T and dW = Z^T dP, on the fp32 matrix cores
+// (v_mfma_f32_32x32x2_f32).  Row-block kernels: the node dimension is the long one, the feature
+// dimensions are at most a few hundred, so a workgroup owns 128 node rows (forward / dgrad) or
+// a slab of node rows (wgrad, split over the reduction and combined in fp64 by a second kernel).
+#include "device_utils.h"
+#include "internal.h"
+
+namespace mixgcn {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 16;          // reduction depth staged per step
+constexpr int kLdsPad = 4;      // row stride of the staged tiles = tile width + 4 floats
+
+// Tile shape: WM x WN waves (4 in total), each owning TM x TN accumulator tiles of 32 x 32.
+template <int WM_, int WN_, int TM_, int TN_>
+struct Shape {
+    static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_;
+    static constexpr int BM = WM * TM * 32;  // extent along the A-operand free dimension
+    static constexpr int BN = WN * TN * 32;  // extent along the B-operand free dimension
+    static_assert(WM * WN == 4, "four waves per block");
+};
+using Shape128x128 = Shape<2, 2, 2, 2>;
+using Shape128x32 = Shape<4, 1, 1, 1>;
+
+// acc += As[kk][a-rows] (x) Bs[kk][b-cols] over the BK staged reduction steps.
+// MFMA 32x32x2 operand layout: lane l supplies A[i = l % 32][k = l / 32] and B[k = l / 32][j = l % 32].
+template <class S>
+__device__ inline void mma_step(const float* As, const float* Bs, int wm, int wn, int lane,
+                                floatx16 (&acc)[S::TM][S::TN])
+{
+    constexpr int LDA = S::BM + kLdsPad, LDB = S::BN + kLdsPad;
+    const int li = lane & 31, lk = lane >> 5;
+#pragma unroll
+    for (int k2 = 0; k2 < BK; k2 += 2) {
+        float a[S::TM], b[S::TN];
+#pragma unroll
+        for (int tm = 0; tm < S::TM; ++tm)
+            a[tm] = As[(k2 + lk) * LDA + (wm * S::TM + tm) * 32 + li];
+#pragma unroll
+        for (int tn = 0; tn < S::TN; ++tn)
+            b[tn] = Bs[(k2 + lk) * LDB + (wn * S::TN + tn) * 32 + li];
+#pragma unroll
+        for (int tm = 0; tm < S::TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < S::TN; ++tn)
+                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+    }
+}
+
+// Loads a float4 of a row-major matrix with zero fill outside [0, rows) x [0, cols) and an
+// optional ReLU-derivative mask taken from R (same indexing): x * 1[R > 0].
+__device__ inline float4 load4_masked(const float* __restrict__ M, int64_t ld, int64_t r, int c,
+                                      int64_t rows, int cols, const float* __restrict__ R,
+                                      int64_t ldr)
+{
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (r < rows && c < cols) {
+        v = *reinterpret_cast<const float4*>(M + r * ld + c);
+        if (R) {
+            const float4 m = *reinterpret_cast<const float4*>(R + r * ldr + c);
+            v.x = m.x > 0.f ? v.x : 0.f;
+            v.y = m.y > 0.f ? v.y : 0.f;
+            v.z = m.z > 0.f ? v.z : 0.f;
+            v.w = m.w > 0.f ? v.w : 0.f;
+        }
+        if (c + 1 >= cols) v.y = 0.f;
+        if (c + 2 >= cols) v.z = 0.f;
+        if (c + 3 >= cols) v.w = 0.f;
+    }
+    return v;
+}
+
+// ---- row-block kernel: C[n x MD] = op(A)[n x KD] * Bop[KD x MD] -------------------------------
+//   B_TRANS = false: Bop[kk][j] = B[kk * ldb + j]   (forward:  Z W)
+//   B_TRANS = true : Bop[kk][j] = B[j * ldb + kk]   (dgrad:   dP W^T with W stored k x m)
+// A is staged transposed (reduction-major) so that the MFMA operand reads are unit-stride.
+template <class S, bool B_TRANS, bool RELU>
+__global__ __launch_bounds__(kBlock) void rowblock_gemm_kernel(
+    const float* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb,
+    float* __restrict__ C, int64_t ldc, int64_t n, int KD, int MD, const float* __restrict__ R,
+    int64_t ldr, int n_col_tiles)
+{
+    constexpr int LDA = S::BM + kLdsPad, LDB = S::BN + kLdsPad;
+    __shared__ float As[BK * LDA];
+    __shared__ float Bs[BK * LDB];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / S::WN, wn = wave % S::WN;
+    const int64_t row0 = (int64_t)(blockIdx.x / n_col_tiles) * S::BM;
+    const int col0 = (int)(blockIdx.x % n_col_tiles) * S::BN;
+
+    floatx16 acc[S::TM][S::TN];
+#pragma unroll
+    for (int tm = 0; tm < S::TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < S::TN; ++tn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
+
+    // staging maps: "strided" = 4 consecutive reduction indices of one row/col per thread
+    constexpr int A_PASSES = S::BM / 64;                       // 64 rows per pass
+    constexpr int BT_PASSES = S::BN / 64 > 0 ? S::BN / 64 : 1; // B_TRANS: 64 cols per pass
+    constexpr int BN_F4 = S::BN / 4;                           // float4 per staged B row
+    constexpr int B_ROWS_PER_PASS = kBlock / BN_F4;
+    constexpr int B_PASSES = (BK + B_ROWS_PER_PASS - 1) / B_ROWS_PER_PASS;
+    float4 ra[A_PASSES];
+    float4 rb[B_TRANS ? BT_PASSES : B_PASSES];
+
+    auto load_tiles = [&](int k0) {
+#pragma unroll
+        for (int p = 0; p < A_PASSES; ++p) {
+            const int i = p * 64 + tid / 4;
+            ra[p] = load4_masked(A, lda, row0 + i, k0 + 4 * (tid & 3), n, KD, R, ldr);
+        }
+        if (B_TRANS) {
+#pragma unroll
+            for (int p = 0; p < BT_PASSES; ++p) {
+                const int j = p * 64 + tid / 4;
+                rb[p] = (j < S::BN) ? load4_masked(B, ldb, col0 + j, k0 + 4 * (tid & 3), MD, KD,
+                                                   nullptr, 0)
+                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < B_PASSES; ++p) {
+                const int kk = p * B_ROWS_PER_PASS + tid / BN_F4;
+                rb[p] = (kk < BK) ? load4_masked(B, ldb, k0 + kk, col0 + 4 * (tid % BN_F4), KD, MD,
+                                                 nullptr, 0)
+                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+    };
+    auto store_tiles = [&]() {
+#pragma unroll
+        for (int p = 0; p < A_PASSES; ++p) {
+            const int i = p * 64 + tid / 4, kq = 4 * (tid & 3);
+            As[(kq + 0) * LDA + i] = ra[p].x;
+            As[(kq + 1) * LDA + i] = ra[p].y;
+            As[(kq + 2) * LDA + i] = ra[p].z;
+            As[(kq + 3) * LDA + i] = ra[p].w;
+        }
+        if (B_TRANS) {
+#pragma unroll
+            for (int p = 0; p < BT_PASSES; ++p) {
+                const int j = p * 64 + tid / 4, kq = 4 * (tid & 3);
+                if (j < S::BN) {
+                    Bs[(kq + 0) * LDB + j] = rb[p].x;
+                    Bs[(kq + 1) * LDB + j] = rb[p].y;
+                    Bs[(kq + 2) * LDB + j] = rb[p].z;
+                    Bs[(kq + 3) * LDB + j] = rb[p].w;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < B_PASSES; ++p) {
+                const int kk = p * B_ROWS_PER_PASS + tid / BN_F4;
+                if (kk < BK)
+                    *reinterpret_cast<float4*>(&Bs[kk * LDB + 4 * (tid % BN_F4)]) = rb[p];
+            }
+        }
+    };
+
+    load_tiles(0);
+    for (int k0 = 0; k0 < KD; k0 += BK) {
+        store_tiles();
+        __syncthreads();
+        if (k0 + BK < KD) load_tiles(k0 + BK);
+        mma_step<S>(As, Bs, wm, wn, lane, acc);
+        __syncthreads();
+    }
+
+    // D layout of the 32x32 MFMA: lane l, register v -> row 8*(v/4) + 4*(l/32) + v%4, col l%32
+    const int li = lane & 31, lk = lane >> 5;
+#pragma unroll
+    for (int tm = 0; tm < S::TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < S::TN; ++tn) {
+            const int c = col0 + (wn * S::TN + tn) * 32 + li;
+            if (c >= MD) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t r = row0 + (wm * S::TM + tm) * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
+                if (r < n) {
+                    float x = acc[tm][tn][v];
+                    if (RELU) x = x > 0.f ? x : 0.f;
+                    C[r * ldc + c] = x;
+                }
+            }
+        }
+}
+
+// ---- slab kernel: P[slab][KD x MD] = A[rows of slab][KD]^T * (B (.) 1[R > 0])[rows][MD] --------
+// Both operands are staged exactly as they lie in memory (node-major), which already is the
+// reduction-major layout the MFMA operand reads want.
+template <class S>
+__global__ __launch_bounds__(kBlock) void wgrad_slab_kernel(
+    const float* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb,
+    const float* __restrict__ R, int64_t ldr, float* __restrict__ P, int64_t n, int KD, int MD,
+    int64_t rows_per_slab, int n_i_tiles, int n_j_tiles)
+{
+    constexpr int LDA = S::BM + kLdsPad, LDB = S::BN + kLdsPad;
+    __shared__ float As[BK * LDA];
+    __shared__ float Bs[BK * LDB];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / S::WN, wn = wave % S::WN;
+    const int tiles = n_i_tiles * n_j_tiles;
+    const int64_t slab = blockIdx.x / tiles;
+    const int t = (int)(blockIdx.x % tiles);
+    const int i0 = (t / n_j_tiles) * S::BM, j0 = (t % n_j_tiles) * S::BN;
+    const int64_t r_begin = slab * rows_per_slab;
+    const int64_t r_end = (r_begin + rows_per_slab) < n ? (r_begin + rows_per_slab) : n;
+
+    floatx16 acc[S::TM][S::TN];
+#pragma unroll
+    for (int tm = 0; tm < S::TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < S::TN; ++tn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
+
+    constexpr int AM_F4 = S::BM / 4, BN_F4 = S::BN / 4;
+    constexpr int A_RPP = kBlock / AM_F4, B_RPP = kBlock / BN_F4;
+    constexpr int A_PASSES = (BK + A_RPP - 1) / A_RPP, B_PASSES = (BK + B_RPP - 1) / B_RPP;
+    float4 ra[A_PASSES], rb[B_PASSES];
+
+    auto load_tiles = [&](int64_t r0) {
+#pragma unroll
+        for (int p = 0; p < A_PASSES; ++p) {
+            const int kk = p * A_RPP + tid / AM_F4;
+            ra[p] = (kk < BK) ? load4_masked(A, lda, r0 + kk, i0 + 4 * (tid % AM_F4), r_end, KD,
+                                             nullptr, 0)
+                              : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int p = 0; p < B_PASSES; ++p) {
+            const int kk = p * B_RPP + tid / BN_F4;
+            rb[p] = (kk < BK) ? load4_masked(B, ldb, r0 + kk, j0 + 4 * (tid % BN_F4), r_end, MD, R,
+                                             ldr)
+                              : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    auto store_tiles = [&]() {
+#pragma unroll
+        for (int p = 0; p < A_PASSES; ++p) {
+            const int kk = p * A_RPP + tid / AM_F4;
+            if (kk < BK) *reinterpret_cast<float4*>(&As[kk * LDA + 4 * (tid % AM_F4)]) = ra[p];
+        }
+#pragma unroll
+        for (int p = 0; p < B_PASSES; ++p) {
+            const int kk = p * B_RPP + tid / BN_F4;
+            if (kk < BK) *reinterpret_cast<float4*>(&Bs[kk * LDB + 4 * (tid % BN_F4)]) = rb[p];
+        }
+    };
+
+    if (r_begin < r_end) {
+        load_tiles(r_begin);
+        for (int64_t r0 = r_begin; r0 < r_end; r0 += BK) {
+            store_tiles();
+            __syncthreads();
+            if (r0 + BK < r_end) load_tiles(r0 + BK);
+            mma_step<S>(As, Bs, wm, wn, lane, acc);
+            __syncthreads();
+        }
+    }
+    float* out = P + (size_t)slab * KD * MD;
+    const int li = lane & 31, lk = lane >> 5;
+#pragma unroll
+    for (int tm = 0; tm < S::TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < S::TN; ++tn) {
+            const int j = j0 + (wn * S::TN + tn) * 32 + li;
+            if (j >= MD) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = i0 + (wm * S::TM + tm) * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
+                if (i < KD) out[(size_t)i * MD + j] = acc[tm][tn][v];
+            }
+        }
+}
+
+// dW = beta * dW + sum over slabs (added in slab order, in fp64).
+__global__ __launch_bounds__(kBlock) void wgrad_reduce_kernel(const float* __restrict__ P,
+                                                              int64_t n_slabs, int64_t cells,
+                                                              int MD, float* __restrict__ dW,
+                                                              int64_t ldw, float beta)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= cells) return;
+    double s = 0.0;
+    for (int64_t b = 0; b < n_slabs; ++b) s += (double)P[(size_t)b * cells + i];
+    float* o = dW + (i / MD) * ldw + (i % MD);
+    *o = (float)(beta != 0.f ? (double)beta * (double)*o + s : s);
+}
+
+template <class S, bool B_TRANS>
+int launch_rowblock(bool relu, const float* A, int64_t lda, const float* B, int64_t ldb, float* C,
+                    int64_t ldc, int64_t n, int KD, int MD, const float* R, int64_t ldr,
+                    hipStream_t s)
+{
+    const int nct = (int)ceil_div(MD, S::BN);
+    const int64_t grid = ceil_div(n, S::BM) * nct;
+    if (grid <= 0) return MIXGCN_OK;
+    if (grid > 0x7FFFFFFF) return fail(MIXGCN_EINVAL, "update: too many row tiles");
+    if (relu)
+        hipLaunchKernelGGL((rowblock_gemm_kernel<S, B_TRANS, true>), dim3((unsigned)grid),
+                           dim3(kBlock), 0, s, A, lda, B, ldb, C, ldc, n, KD, MD, R, ldr, nct);
+    else
+        hipLaunchKernelGGL((rowblock_gemm_kernel<S, B_TRANS, false>), dim3((unsigned)grid),
+                           dim3(kBlock), 0, s, A, lda, B, ldb, C, ldc, n, KD, MD, R, ldr, nct);
+    return MIXGCN_OK;
+}
+
+}  // namespace
+
+int launch_update(int op, int dtype, const void* A_, int64_t lda, const float* B, int64_t ldb,
+                  void* C_, int64_t ldc, int64_t n, int32_t k, int32_t m, const void* R_,
+                  int64_t ldr, float beta, hipStream_t s)
+{
+    if (dtype != MIXGCN_F32) return fail(MIXGCN_EUNSUPPORTED, "update: bf16 storage not built yet");
+    const float* A = (const float*)A_;
+    float* C = (float*)C_;
+    const float* R = (const float*)R_;
+    if (op == MIXGCN_OP_FWD || op == MIXGCN_OP_FWD_RELU) {
+        const bool relu = op == MIXGCN_OP_FWD_RELU;
+        if (m > 64)
+            MIXGCN_TRY((launch_rowblock<Shape128x128, false>(relu, A, lda, B, ldb, C, ldc, n, k, m,
+                                                            nullptr, 0, s)));
+        else
+            MIXGCN_TRY((launch_rowblock<Shape128x32, false>(relu, A, lda, B, ldb, C, ldc, n, k, m,
+                                                           nullptr, 0, s)));
+    } else if (op == MIXGCN_OP_DGRAD) {
+        // C[n x k] = (A (.) mask)[n x m] * W^T, W = B stored k x m: reduction over m
+        if (k > 64)
+            MIXGCN_TRY((launch_rowblock<Shape128x128, true>(false, A, lda, B, ldb, C, ldc, n, m, k,
+                                                           R, ldr, s)));
+        else
+            MIXGCN_TRY((launch_rowblock<Shape128x32, true>(false, A, lda, B, ldb, C, ldc, n, m, k, R,
+                                                          ldr, s)));
+    } else if (op == MIXGCN_OP_WGRAD) {
+        // C[k x m] = beta C + A[n x k]^T (B (.) mask)[n x m]; here `B` of the ABI is passed as B
+        const bool wide = m > 64;
+        const int bm = 128, bn = wide ? 128 : 32;
+        const int nit = (int)ceil_div(k, bm), njt = (int)ceil_div(m, bn);
+        const int tiles = nit * njt;
+        int64_t n_slabs = ceil_div(n, 1024);
+        const int64_t cap = tiles >= 2048 ? 1 : 2048 / tiles;
+        if (n_slabs > cap) n_slabs = cap;
+        if (n_slabs < 1) n_slabs = 1;
+        int64_t rows_per_slab = ceil_div(ceil_div(n, n_slabs), BK) * BK;
+        if (rows_per_slab < BK) rows_per_slab = BK;
+        n_slabs = n > 0 ? ceil_div(n, rows_per_slab) : 1;
+        const int64_t cells = (int64_t)k * m;
+        void* scratch = nullptr;
+        MIXGCN_TRY(get_scratch(0, (size_t)n_slabs * cells * sizeof(float), &scratch));
+        float* P = (float*)scratch;
+        const unsigned grid = (unsigned)(n_slabs * tiles);
+        if (wide)
+            hipLaunchKernelGGL((wgrad_slab_kernel<Shape128x128>), dim3(grid), dim3(kBlock), 0, s, A,
+                               lda, B, ldb, R, ldr, P, n, k, m, rows_per_slab, nit, njt);
+        else
+            hipLaunchKernelGGL((wgrad_slab_kernel<Shape128x32>), dim3(grid), dim3(kBlock), 0, s, A,
+                               lda, B, ldb, R, ldr, P, n, k, m, rows_per_slab, nit, njt);
+        hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)ceil_div(cells, kBlock)),
+                           dim3(kBlock), 0, s, P, n_slabs, cells, m, C, ldc, beta);
+    } else {
+        return fail(MIXGCN_EINVAL, "update: unknown op");
+    }
+    MIXGCN_HIP_TRY(hipGetLastError());
+    return MIXGCN_OK;
+}
+
+}  // namespace mixgcn

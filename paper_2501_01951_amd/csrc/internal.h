@@ -1,0 +1,114 @@
+// Internal declarations shared by the HIP sources of libmixgcn (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "mixgcn.h"
+
+namespace mixgcn {
+
+// ---- error plumbing ---------------------------------------------------------------------------
+void set_error(const std::string& msg);
+int fail(int code, const std::string& msg);
+
+#define MIXGCN_HIP_TRY(expr)                                                                  \
+    do {                                                                                      \
+        hipError_t _e = (expr);                                                               \
+        if (_e != hipSuccess)                                                                 \
+            return ::mixgcn::fail(_e == hipErrorOutOfMemory ? MIXGCN_ENOMEM : MIXGCN_EHIP,    \
+                                  std::string(#expr) + ": " + hipGetErrorString(_e));         \
+    } while (0)
+
+#define MIXGCN_TRY(expr)         \
+    do {                         \
+        int _rc = (expr);        \
+        if (_rc != MIXGCN_OK) return _rc; \
+    } while (0)
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- graph ------------------------------------------------------------------------------------
+// Number of stored entries that one lane group of the aggregation kernel walks.
+constexpr int kGroupNnz = 256;
+
+struct Csr {
+    int64_t nnz = 0;
+    int64_t nnz_padded = 0;          // allocation length of colf / val (multiple of kGroupNnz)
+    int64_t n_groups = 0;            // ceil(nnz / kGroupNnz)
+    int64_t* rowptr = nullptr;       // [n + 1]
+    uint32_t* col = nullptr;         // [nnz]
+    uint32_t* colf = nullptr;        // [nnz_padded] col | (last entry of its row ? 1u << 31 : 0)
+    float* val = nullptr;            // [nnz_padded]
+    uint32_t* grp_row = nullptr;     // [n_groups + 1] row that holds entry g * kGroupNnz
+    std::vector<int64_t> h_rowptr;   // host copy of rowptr
+    bool has_empty_rows = false;
+};
+
+}  // namespace mixgcn
+
+struct mixgcn_graph {
+    uint32_t n = 0;
+    uint32_t flags = 0;
+    int device = 0;
+    bool normalized = false;
+    bool has_transpose = false;  // a separate transpose CSR is stored in `tr`
+    mixgcn::Csr fwd;
+    mixgcn::Csr tr;
+    uint32_t* deg = nullptr;
+    float* dinv = nullptr;
+    // scratch of the aggregation kernels (row pieces that cross lane-group boundaries);
+    // grown on demand, so aggregate calls on one graph must be ordered on one stream.
+    mutable float* partials = nullptr;
+    mutable size_t partials_bytes = 0;
+};
+
+struct mixgcn_pipeline {
+    hipStream_t primary = nullptr;
+    hipStream_t secondary = nullptr;
+    std::vector<hipEvent_t> events;
+    hipEvent_t ev_start = nullptr;
+    hipEvent_t ev_done = nullptr;
+    float* wt = nullptr;  // transposed-weight / split-K scratch
+    size_t wt_bytes = 0;
+};
+
+namespace mixgcn {
+
+// ---- device primitives (scan.hip, sort.hip) ---------------------------------------------------
+// Exclusive prefix sum of n uint32 counts into uint64 offsets; total (optional, device) gets
+// the sum.  tmp must hold scan_tmp_bytes(n).
+size_t scan_tmp_bytes(int64_t n);
+int exclusive_scan_u32_to_u64(const uint32_t* in, uint64_t* out, int64_t n, uint64_t* total,
+                              void* tmp, hipStream_t s);
+
+// Stable LSD radix sort of 64-bit keys on bits [0, n_bits).  Result ends in *sorted (either
+// keys or alt).  tmp must hold sort_tmp_bytes(n).
+size_t sort_tmp_bytes(int64_t n);
+int radix_sort_u64(uint64_t* keys, uint64_t* alt, int64_t n, int n_bits, uint64_t** sorted,
+                   void* tmp, hipStream_t s);
+
+// ---- scratch shared by entry points without a handle --------------------------------------------
+int get_scratch(int which, size_t bytes, void** out);
+
+// ---- kernels behind the entry points ----------------------------------------------------------
+int csr_from_edges(const uint32_t* d_src, const uint32_t* d_dst, uint64_t n_edges, uint32_t n,
+                   bool symmetrize, bool self_loops, bool transposed, Csr* out, hipStream_t s);
+void csr_free(Csr* c);
+int normalize_sym(mixgcn_graph* g, hipStream_t s);
+
+int launch_aggregate(const mixgcn_graph* g, const Csr& m, int dtype, const void* H, int64_t ldh,
+                     void* Z, int64_t ldz, int32_t c0, int32_t c1, int64_t r0, int64_t r1,
+                     hipStream_t s);
+
+int launch_update(int op, int dtype, const void* A, int64_t lda, const float* B, int64_t ldb,
+                  void* C, int64_t ldc, int64_t n, int32_t k, int32_t m, const void* R,
+                  int64_t ldr, float beta, hipStream_t s);
+
+int launch_softmax_xent(const float* logits, int64_t ldl, const int32_t* labels, int64_t n,
+                        int32_t c, float* dlogits, int64_t ldd, double* loss, hipStream_t s);
+
+}  // namespace mixgcn

@@ -1,0 +1,91 @@
+// Loss glue (paper Algorithm 2, loss line): mean softmax cross-entropy over all nodes and its
+// gradient (softmax - onehot) / n.  One wavefront per node row; block partial sums of the loss
+// are combined in a fixed order by a second kernel, so the result is deterministic.
+#include "device_utils.h"
+#include "internal.h"
+
+namespace mixgcn {
+namespace {
+
+constexpr int kRowsPerBlock = 256;
+
+__device__ inline float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+__global__ __launch_bounds__(kBlock) void xent_rows_kernel(const float* logits,
+                                                           int64_t ldl,
+                                                           const int32_t* __restrict__ labels,
+                                                           int64_t n, int c, float* dlogits,
+                                                           int64_t ldd, double* __restrict__ part)
+{
+    __shared__ double wsum[kBlock / kWave];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t r_begin = (int64_t)blockIdx.x * kRowsPerBlock;
+    const int64_t r_end = (r_begin + kRowsPerBlock) < n ? (r_begin + kRowsPerBlock) : n;
+    const float inv_n = 1.0f / (float)n;
+    double acc = 0.0;
+    for (int64_t r = r_begin + w; r < r_end; r += kBlock / kWave) {
+        const float* x = logits + r * ldl;
+        float mx = -INFINITY;
+        for (int j = lane; j < c; j += kWave) mx = fmaxf(mx, x[j]);
+        mx = wave_max(mx);
+        float se = 0.f;
+        for (int j = lane; j < c; j += kWave) se += expf(x[j] - mx);
+        se = wave_sum(se);
+        const float lse = mx + logf(se);
+        const int y = labels[r];
+        const float xy = x[y];
+        for (int j = lane; j < c; j += kWave) {
+            const float p = expf(x[j] - lse);
+            dlogits[r * ldd + j] = (p - (j == y ? 1.f : 0.f)) * inv_n;
+        }
+        acc += (double)(lse - xy);
+    }
+    if (lane == 0) wsum[w] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) part[blockIdx.x] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+}
+
+__global__ __launch_bounds__(kBlock) void xent_final_kernel(const double* __restrict__ part,
+                                                            int64_t n_parts, int64_t n,
+                                                            double* __restrict__ loss)
+{
+    __shared__ double sh[kBlock];
+    double s = 0.0;
+    for (int64_t i = threadIdx.x; i < n_parts; i += kBlock) s += part[i];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = kBlock / 2; o > 0; o >>= 1) {
+        if (threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *loss = sh[0] / (double)n;
+}
+
+}  // namespace
+
+int launch_softmax_xent(const float* logits, int64_t ldl, const int32_t* labels, int64_t n,
+                        int32_t c, float* dlogits, int64_t ldd, double* loss, hipStream_t s)
+{
+    const int64_t n_parts = ceil_div(n, kRowsPerBlock);
+    void* scratch = nullptr;
+    MIXGCN_TRY(get_scratch(1, (size_t)n_parts * sizeof(double), &scratch));
+    hipLaunchKernelGGL(xent_rows_kernel, dim3((unsigned)n_parts), dim3(kBlock), 0, s, logits, ldl,
+                       labels, n, c, dlogits, ldd, (double*)scratch);
+    hipLaunchKernelGGL(xent_final_kernel, dim3(1), dim3(kBlock), 0, s, (const double*)scratch,
+                       n_parts, n, loss);
+    MIXGCN_HIP_TRY(hipGetLastError());
+    return MIXGCN_OK;
+}
+
+}  // namespace mixgcn

@@ -1,0 +1,389 @@
+"""GPU parity: every C-ABI call of the HIP path against the CPU oracle on the same seeded inputs.
+Integer results (CSR, degrees) must match bit for bit; fp32 tensors within 1e-4 (rule in
+tests/parity.py).  All tests here need a real MI355X."""
+import numpy as np
+import pytest
+
+import graphgen as gg
+import oracle
+from parity import RTOL_F32, assert_close, rel_fro, say
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def mg():
+    import paper_2501_01951_amd as m
+
+    m.load_library()
+    return m
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def edges_dev(src, dst):
+    return dev(src.astype(np.int32, copy=False).view(np.int32)), dev(dst.astype(np.int32, copy=False).view(np.int32))
+
+
+def u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+GRAPHS = {
+    "path5": lambda: (np.array([0, 1, 2, 3], np.uint32), np.array([1, 2, 3, 4], np.uint32), 5),
+    "dups_selfedges": lambda: (np.array([0, 0, 1, 2, 2, 3, 1, 0], np.uint32),
+                               np.array([1, 1, 0, 2, 3, 3, 2, 0], np.uint32), 4),
+    "isolated": lambda: (np.array([0, 1, 3, 4], np.uint32), np.array([1, 2, 4, 5], np.uint32), 7),
+    "edgeless": lambda: (np.zeros(0, np.uint32), np.zeros(0, np.uint32), 9),
+    "er_c1": lambda: gg.config_graph("c1"),
+    "rmat14": lambda: gg.config_graph("c2", scale_override=14),
+    "rmat16_ragged": lambda: gg.rmat_edges(7, 16, 300_001) + (65536,),
+    "not_pow2": lambda: gg.rmat_edges(9, 12, 20_000, n_limit=3001) + (3001,),
+}
+
+
+@pytest.mark.parametrize("name", sorted(GRAPHS))
+@pytest.mark.parametrize("sym,loops", [(True, True), (False, True), (True, False), (False, False)])
+def test_build_csr_and_normalize_bit_exact(mg, name, sym, loops):
+    src, dst, n = GRAPHS[name]()
+    say(f"build_csr {name} sym={sym} loops={loops} n={n} e={len(src)}")
+    og = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n, sym, loops)))
+    flags = (mg.SYMMETRIZE if sym else 0) | (mg.ADD_SELF_LOOPS if loops else 0) | mg.BUILD_TRANSPOSE
+    s, d = edges_dev(src, dst)
+    g = mg.build_csr(s, d, n, flags)
+    assert g.nnz == og.nnz
+    mg.normalize(g)
+    a = g.arrays()
+    assert np.array_equal(a["rowptr"].cpu().numpy(), og.rowptr)
+    assert np.array_equal(u32(a["col"]), og.col)
+    assert np.array_equal(u32(a["deg"]), og.deg)
+    assert np.array_equal(a["dinv"].cpu().numpy(), og.dinv.astype(np.float32))
+    assert np.array_equal(a["val"].cpu().numpy(), og.val_f32)
+    t = g.arrays(transpose=True)
+    assert np.array_equal(t["rowptr"].cpu().numpy(), og.t_rowptr)
+    assert np.array_equal(u32(t["col"]), og.t_col)
+    np.testing.assert_allclose(t["val"].cpu().numpy(), og.t_val, rtol=2e-7)
+    g.free()
+
+
+def test_build_csr_host_input_and_errors(mg):
+    src, dst, n = gg.config_graph("c1")
+    say("build_csr host input")
+    og = oracle.build_csr(src, dst, n)
+    g = mg.build_csr(torch.from_numpy(src.view(np.int32)), torch.from_numpy(dst.view(np.int32)), n)
+    assert np.array_equal(u32(g.arrays()["col"]), og.col)
+    g.free()
+    say("build_csr endpoint out of range -> EINVAL")
+    bad = src.copy()
+    bad[5] = n + 3
+    s, d = edges_dev(bad, dst)
+    with pytest.raises(mg.MixGCNError) as ei:
+        mg.build_csr(s, d, n)
+    assert ei.value.code == -1
+    say("aggregate before normalize -> ESTATE")
+    s, d = edges_dev(src, dst)
+    g = mg.build_csr(s, d, n)
+    h = torch.zeros(n, 16, device="cuda")
+    with pytest.raises(mg.MixGCNError) as ei:
+        mg.aggregate(g, h, torch.empty_like(h))
+    assert ei.value.code == -4
+    mg.normalize(g)
+    with pytest.raises(mg.MixGCNError):  # H and Z overlap
+        mg.aggregate(g, h, h)
+    with pytest.raises(mg.MixGCNError):  # column range not vector aligned
+        mg.aggregate(g, h, torch.empty_like(h), col_begin=2, col_end=8)
+    with pytest.raises(mg.MixGCNError):  # row range outside the graph
+        mg.aggregate(g, h, torch.empty_like(h), row_end=n + 1)
+    g.free()
+
+
+def _gpu_graph(mg, src, dst, n, sym=True, loops=True):
+    flags = (mg.SYMMETRIZE if sym else 0) | (mg.ADD_SELF_LOOPS if loops else 0) | mg.BUILD_TRANSPOSE
+    s, d = edges_dev(src, dst)
+    g = mg.build_csr(s, d, n, flags)
+    mg.normalize(g)
+    return g
+
+
+@pytest.fixture(scope="module")
+def rmat15(mg):
+    src, dst, n = gg.config_graph("c2", scale_override=15)
+    og = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n)))
+    g = _gpu_graph(mg, src, dst, n)
+    yield og, g
+    g.free()
+
+
+@pytest.mark.parametrize("f,ld", [(4, 4), (16, 16), (32, 32), (64, 64), (100, 128), (128, 128),
+                                  (256, 256), (300, 304), (512, 512)])
+def test_aggregate_full_width(mg, rmat15, f, ld):
+    og, g = rmat15
+    say(f"aggregate rmat15 f={f} ld={ld} nnz={og.nnz} maxdeg={og.deg.max()}")
+    h = gg.normal(11, f, og.n, f, ld=ld)
+    z = torch.full((og.n, ld), 7.0, device="cuda")
+    mg.aggregate(g, dev(h), z, col_end=f)
+    ref = oracle.spmm(og, h[:, :f].astype(np.float64))
+    z = z.cpu().numpy()
+    assert_close(z[:, :f], ref, RTOL_F32, f"Z f={f}")
+    up = (f + 3) // 4 * 4
+    assert np.all(z[:, up:] == 7.0)  # columns beyond the vector-rounded slice stay untouched
+
+
+def test_aggregate_slices_and_row_ranges(mg, rmat15):
+    og, g = rmat15
+    f = 128
+    h = gg.normal(12, 1, og.n, f)
+    ref = oracle.spmm(og, h.astype(np.float64))
+    hd = dev(h)
+    # MoP column slices [floor(d i / m), floor(d (i+1) / m)) for m = 8 workers
+    z = torch.zeros(og.n, f, device="cuda")
+    for i in range(8):
+        p, q = f * i // 8, f * (i + 1) // 8
+        say(f"aggregate slice [{p},{q})")
+        mg.aggregate(g, hd, z, col_begin=p, col_end=q)
+    assert_close(z.cpu().numpy(), ref, RTOL_F32, "column slices")
+    # row chunks, ragged, including empty and single-row ranges
+    z = torch.full((og.n, f), -3.0, device="cuda")
+    bounds = [0, 1, 1, 777, 4096, 20000, og.n - 1, og.n]
+    for r0, r1 in zip(bounds[:-1], bounds[1:]):
+        say(f"aggregate rows [{r0},{r1})")
+        mg.aggregate(g, hd, z, row_begin=r0, row_end=r1)
+    assert_close(z.cpu().numpy(), ref, RTOL_F32, "row chunks")
+    z = torch.full((og.n, f), -3.0, device="cuda")
+    mg.aggregate(g, hd, z, col_begin=32, col_end=96, row_begin=5000, row_end=9000)
+    zz = z.cpu().numpy()
+    assert_close(zz[5000:9000, 32:96], ref[5000:9000, 32:96], RTOL_F32, "slice x chunk")
+    zz[5000:9000, 32:96] = -3.0
+    assert np.all(zz == -3.0)
+
+
+def test_aggregate_is_deterministic(mg, rmat15):
+    og, g = rmat15
+    hd = dev(gg.normal(13, 1, og.n, 64))
+    z1 = torch.empty(og.n, 64, device="cuda")
+    z2 = torch.empty(og.n, 64, device="cuda")
+    mg.aggregate(g, hd, z1)
+    mg.aggregate(g, hd, z2)
+    assert torch.equal(z1, z2)
+
+
+@pytest.mark.parametrize("loops", [True, False])
+def test_aggregate_directed_transpose_and_empty_rows(mg, loops):
+    src, dst = gg.rmat_edges(21, 13, 40_000)
+    n = 1 << 13
+    say(f"aggregate directed loops={loops}")
+    og = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n, False, loops)))
+    g = _gpu_graph(mg, src, dst, n, sym=False, loops=loops)
+    if not loops:
+        assert (np.diff(og.rowptr) == 0).any()  # the case has empty rows
+    h = gg.normal(14, 1, n, 64)
+    hd = dev(h)
+    for tr in (False, True):
+        z = torch.full((n, 64), 5.0, device="cuda")
+        mg.aggregate(g, hd, z, transpose=tr)
+        ref = oracle.spmm(og, h.astype(np.float64), transposed=tr)
+        assert_close(z.cpu().numpy(), ref, RTOL_F32, f"directed transpose={tr}")
+    z = torch.full((n, 64), 5.0, device="cuda")
+    mg.aggregate(g, hd, z, row_begin=100, row_end=3000, transpose=True)
+    ref = oracle.spmm(og, h.astype(np.float64), transposed=True)
+    assert_close(z.cpu().numpy()[100:3000], ref[100:3000], RTOL_F32, "directed row range")
+    g.free()
+
+
+def test_aggregate_regular_graph_row_sums_and_eigenvector(mg):
+    n, k = 5000, 10
+    src, dst = gg.ring_lattice_edges(n, k)
+    g = _gpu_graph(mg, src, dst, n)
+    z = torch.empty(n, 4, device="cuda")
+    mg.aggregate(g, torch.ones(n, 4, device="cuda"), z)
+    np.testing.assert_allclose(z.cpu().numpy(), 1.0, rtol=1e-6)
+    g.free()
+    src, dst, n = gg.config_graph("c2", scale_override=16)
+    g = _gpu_graph(mg, src, dst, n)
+    deg = g.arrays()["deg"].cpu().numpy().astype(np.float64)
+    r = np.sqrt(deg)[:, None].repeat(4, axis=1).astype(np.float32)
+    z = torch.empty(n, 4, device="cuda")
+    mg.aggregate(g, dev(r), z)
+    np.testing.assert_allclose(z.cpu().numpy(), r, rtol=2e-5)
+    g.free()
+
+
+UPDATE_SHAPES = [(1000, 64, 32), (4173, 32, 8), (2048, 128, 256), (3000, 256, 16), (777, 100, 47),
+                 (1500, 128, 172), (130, 256, 256), (1, 16, 4), (5000, 128, 1024)]
+
+
+@pytest.mark.parametrize("n,k,m", UPDATE_SHAPES)
+def test_update_ops(mg, n, k, m):
+    say(f"update n={n} k={k} m={m}")
+    ldk, ldm = (k + 3) // 4 * 4, (m + 3) // 4 * 4
+    z = gg.normal(31, 1, n, k, ld=ldk)
+    w = gg.glorot(31, 2, k, m, ld=ldm)
+    gr = gg.normal(31, 3, n, m, ld=ldm)
+    z64, w64, g64 = z[:, :k].astype(np.float64), w[:, :m].astype(np.float64), gr[:, :m].astype(np.float64)
+    zd, wd, gd = dev(z), dev(w), dev(gr)
+    for relu in (False, True):
+        out = torch.full((n, ldm), 9.0, device="cuda")
+        mg.update(mg.OP_FWD_RELU if relu else mg.OP_FWD, zd, wd, out, n, k, m)
+        o = out.cpu().numpy()
+        assert_close(o[:, :m], oracle.update_fwd(z64, w64, relu), RTOL_F32, f"fwd relu={relu}")
+        assert np.all(o[:, m:] == 9.0)
+    href = oracle.update_fwd(z64, w64, True)
+    hd = torch.zeros(n, ldm, device="cuda")
+    hd[:, :m] = dev(href.astype(np.float32))
+    h64 = hd.cpu().numpy()[:, :m].astype(np.float64)
+    for ref_t, ref_np in ((None, None), (hd, h64)):
+        dp = oracle.relu_grad(g64, ref_np)
+        dz = torch.full((n, ldk), 9.0, device="cuda")
+        mg.update(mg.OP_DGRAD, gd, wd, dz, n, k, m, relu_ref=ref_t)
+        o = dz.cpu().numpy()
+        assert_close(o[:, :k], oracle.update_dgrad(dp, w64), RTOL_F32, "dgrad")
+        assert np.all(o[:, k:] == 9.0)
+        dw = torch.full((k, ldm), 9.0, device="cuda")
+        mg.update(mg.OP_WGRAD, zd, gd, dw, n, k, m, relu_ref=ref_t)
+        o = dw.cpu().numpy()
+        refw = oracle.update_wgrad(z64, dp)
+        assert_close(o[:, :m], refw, RTOL_F32, "wgrad")
+        assert np.all(o[:, m:] == 9.0)
+        mg.update(mg.OP_WGRAD, zd, gd, dw, n, k, m, relu_ref=ref_t, beta=1.0)
+        assert_close(dw.cpu().numpy()[:, :m], 2 * refw, RTOL_F32, "wgrad beta=1")
+
+
+@pytest.mark.parametrize("n,c", [(4096, 8), (10000, 16), (3000, 172), (999, 47)])
+def test_softmax_xent(mg, n, c):
+    say(f"softmax_xent n={n} c={c}")
+    x = gg.normal(41, c, n, c) * 3
+    y = gg.labels(41, 5, n, c)
+    loss_ref, d_ref = oracle.softmax_xent(x.astype(np.float64), y)
+    d = torch.empty(n, c, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    mg.softmax_xent(dev(x), dev(y), d, loss)
+    assert abs(loss.item() - loss_ref) <= 1e-5 * abs(loss_ref)
+    assert_close(d.cpu().numpy(), d_ref, RTOL_F32, "dlogits")
+    # W = 0 gives ln C exactly (to fp32 rounding)
+    mg.softmax_xent(torch.zeros(n, c, device="cuda"), dev(y), d, loss)
+    assert abs(loss.item() - np.log(c)) < 1e-6
+
+
+@pytest.mark.parametrize("n_chunks", [1, 5])
+def test_layer_fwd_bwd(mg, rmat15, n_chunks):
+    og, g = rmat15
+    n, k, m = og.n, 64, 96
+    say(f"layer fwd/bwd rmat15 k={k} m={m} chunks={n_chunks}")
+    h = gg.normal(51, 1, n, k)
+    w = gg.glorot(51, 2, k, m)
+    gr = gg.normal(51, 3, n, m)
+    pipe = mg.Pipeline()
+    hd, wd = dev(h), dev(w)
+    z = torch.empty(n, k, device="cuda")
+    out = torch.empty(n, m, device="cuda")
+    mg.layer_fwd(g, hd, wd, z, out, pipe, relu=True, n_chunks=n_chunks)
+    torch.cuda.synchronize()
+    z_ref = oracle.spmm(og, h.astype(np.float64))
+    assert_close(z.cpu().numpy(), z_ref, RTOL_F32, "Z")
+    out_ref = oracle.update_fwd(z_ref, w.astype(np.float64), True)
+    assert_close(out.cpu().numpy(), out_ref, RTOL_F32, "Hout")
+    # backward on the oracle's own stored tensors (rounded to fp32), so that both sides take the
+    # ReLU decision from identical bits
+    z32 = z_ref.astype(np.float32)
+    o32 = out_ref.astype(np.float32)
+    zd, od, gd = dev(z32), dev(o32), dev(gr)
+    dw = torch.empty(k, m, device="cuda")
+    dh = torch.empty(n, k, device="cuda")
+    mg.layer_bwd(g, zd, od, wd, gd, dw, dh, pipe, relu=True, n_chunks=n_chunks)
+    torch.cuda.synchronize()
+    dp = oracle.relu_grad(gr.astype(np.float64), o32.astype(np.float64))
+    assert_close(dw.cpu().numpy(), oracle.update_wgrad(z32.astype(np.float64), dp), RTOL_F32, "dW")
+    dz_ref = oracle.update_dgrad(dp, w.astype(np.float64))
+    assert_close(zd.cpu().numpy(), dz_ref, RTOL_F32, "dZ (written over Z)")
+    assert_close(dh.cpu().numpy(), oracle.spmm(og, dz_ref, transposed=True), RTOL_F32, "dH")
+    # dH == NULL: only dW
+    zd = dev(z32)
+    dw2 = torch.empty(k, m, device="cuda")
+    mg.layer_bwd(g, zd, od, wd, gd, dw2, None, pipe, relu=True, n_chunks=n_chunks)
+    torch.cuda.synchronize()
+    assert torch.equal(dw, dw2)
+    assert torch.equal(zd, dev(z32))
+    pipe.free()
+
+
+def run_model_gpu(mg, g, x, ws, y, n_chunks=1):
+    """L-layer GCN forward + backward through the C ABI only.  Returns loss, logits, dW list."""
+    n = x.shape[0]
+    L = len(ws)
+    pipe = mg.Pipeline()
+    hs = [dev(x)]
+    zs = []
+    wds = [dev(w) for w in ws]
+    for l, w in enumerate(wds):
+        z = torch.empty(n, w.shape[0], device="cuda")
+        out = torch.empty(n, w.shape[1], device="cuda")
+        mg.layer_fwd(g, hs[-1], w, z, out, pipe, relu=(l < L - 1), n_chunks=n_chunks)
+        zs.append(z)
+        hs.append(out)
+    logits = hs[-1].clone()
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    grad = torch.empty_like(hs[-1])
+    mg.softmax_xent(hs[-1], dev(y), grad, loss)
+    dws = [None] * L
+    for l in range(L - 1, -1, -1):
+        dws[l] = torch.empty_like(wds[l])
+        dh = torch.empty(n, wds[l].shape[0], device="cuda") if l > 0 else None
+        mg.layer_bwd(g, zs[l], hs[l + 1], wds[l], grad, dws[l], dh, pipe, relu=(l < L - 1),
+                     n_chunks=n_chunks)
+        grad = dh
+    torch.cuda.synchronize()
+    pipe.free()
+    return loss.item(), logits.cpu().numpy(), [d.cpu().numpy() for d in dws], [h.cpu().numpy() for h in hs]
+
+
+def check_model(mg, name, src, dst, n, x, ws, y, n_chunks):
+    og = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n)))
+    ref = oracle.gcn_step(og, x, ws, y)
+    g = _gpu_graph(mg, src, dst, n)
+    loss, logits, dws, hs = run_model_gpu(mg, g, x, ws, y, n_chunks)
+    g.free()
+    assert abs(loss - ref["loss"]) <= 1e-5 * abs(ref["loss"]), f"{name}: loss {loss} vs {ref['loss']}"
+    assert_close(logits, ref["logits"], RTOL_F32, f"{name}: logits")
+    L = len(ws)
+    assert_close(dws[L - 1], ref["dW"][L - 1], RTOL_F32, f"{name}: dW[{L - 1}]")
+    # Lower layers: the ReLU derivative is an integer decision that each side takes from its own
+    # stored activations.  Where those disagree the oracle's pre-activation must be within
+    # rounding of zero (validity), and the weight gradients must agree up to those few terms.
+    for l in range(1, L):
+        mask_gpu = hs[l] > 0
+        mask_ref = ref["H"][l] > 0
+        diff = mask_gpu != mask_ref
+        if diff.any():
+            scale = np.sqrt(np.mean(ref["H"][l] ** 2))
+            assert np.max(np.abs(ref["H"][l][diff])) <= 1e-4 * scale, f"{name}: ReLU flips at layer {l}"
+            assert diff.mean() < 1e-5
+    for l in range(L - 1):
+        flips = sum(int(((hs[j] > 0) != (ref["H"][j] > 0)).sum()) for j in range(l + 1, L))
+        if flips == 0:
+            assert_close(dws[l], ref["dW"][l], RTOL_F32, f"{name}: dW[{l}]")
+        else:
+            assert rel_fro(dws[l], ref["dW"][l]) < 2e-3, f"{name}: dW[{l}] with {flips} ReLU flips"
+
+
+@pytest.mark.parametrize("n_chunks", [1, 4])
+def test_config1_tiny_two_layer_gcn(mg, n_chunks):
+    say(f"config 1 end to end, chunks={n_chunks}")
+    src, dst, n = gg.config_graph("c1")
+    x = gg.uniform(gg.MASTER_SEED, 1, n, 64)
+    ws = [gg.glorot(gg.MASTER_SEED, 10, 64, 32), gg.glorot(gg.MASTER_SEED, 11, 32, 8)]
+    y = gg.labels(gg.MASTER_SEED, 5, n, 8)
+    check_model(mg, "c1", src, dst, n, x, ws, y, n_chunks)
+
+
+def test_config2_shape_three_layer_gcn_scale17(mg):
+    say("config 2 shape at R-MAT scale 17, end to end")
+    src, dst, n = gg.config_graph("c2", scale_override=17)
+    x = gg.normal(gg.MASTER_SEED, 1, n, 128)
+    ws = [gg.glorot(gg.MASTER_SEED, 10, 128, 256), gg.glorot(gg.MASTER_SEED, 11, 256, 256),
+          gg.glorot(gg.MASTER_SEED, 12, 256, 16)]
+    y = gg.labels(gg.MASTER_SEED, 5, n, 16)
+    check_model(mg, "c2@17", src, dst, n, x, ws, y, 4)
