@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the GCN hot path on one MI355X.
+
+One "step" = one full-graph epoch (forward + loss + backward) of the 3-layer GCN of the
+second benchmark configuration: R-MAT scale-20 graph (16 N directed edges, symmetrised,
+self-loops, sym-normalised), X = N x 128 ~ N(0,1), Glorot weights 128 -> 256 -> 256 -> 16,
+16 classes, fp32.  Inputs are synthetic and resident in HBM before the timed region.
+
+Prints ONE JSON line: whole-job throughput in edges*feat/s (sum over layers of
+nnz(A_hat) * d^(l), divided by the step time), the roofline of the dominant kernel (the
+aggregation gather at 256 columns) from HIP events recorded around its launches inside the
+timed region, and the CPU oracle timed on a bounded, down-scaled sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def model_dims(name):
+    if name == "c2":
+        return [128, 256, 256, 16]
+    if name == "c1":
+        return [64, 32, 8]
+    raise ValueError(name)
+
+
+def make_inputs(name, scale, seed):
+    import numpy as np
+
+    import graphgen as gg
+
+    dims = model_dims(name)
+    src, dst, n = gg.config_graph(name, seed=seed, scale_override=scale)
+    if name == "c1":
+        x = gg.uniform(seed, 1, n, dims[0])
+    else:
+        x = gg.normal(seed, 1, n, dims[0])
+    ws = [gg.glorot(seed, 10 + l, dims[l], dims[l + 1]) for l in range(len(dims) - 1)]
+    y = gg.labels(seed, 5, n, dims[-1])
+    return src, dst, n, x, ws, y, dims
+
+
+def cpu_baseline(name, scale, seed):
+    """The oracle as it stands on the host cores, one forward+backward step of a down-scaled
+    instance of the same generator and model."""
+    import oracle
+
+    src, dst, n, x, ws, y, dims = make_inputs(name, scale, seed)
+    g = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n)))
+    t0 = time.perf_counter()
+    oracle.gcn_step(g, x, ws, y)
+    dt = time.perf_counter() - t0
+    work = sum(g.nnz * d for d in dims[:-1])
+    return {
+        "value": work / dt, "unit": "edges*feat/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": f"same generator and model at R-MAT scale {scale} (N={n}, nnz={g.nnz}), "
+                  f"one fwd+bwd step, {dt:.1f} s",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="c2")
+    ap.add_argument("--scale", type=int, default=None, help="override the R-MAT scale")
+    ap.add_argument("--chunks", type=int, default=1, help="row chunks of the layer pipeline")
+    ap.add_argument("--seed", type=int, default=250101951)
+    ap.add_argument("--cpu-scale", type=int, default=20, help="R-MAT scale of the oracle sample")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-event-timing", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (no collectives are part of it); "
+                 "use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import paper_2501_01951_amd as mg
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    mg.load_library()
+    torch.cuda.set_device(0)
+
+    src, dst, n, x, ws, y, dims = make_inputs(args.config, args.scale, args.seed)
+
+    def dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    s_d, d_d = dev(src.view(np.int32)), dev(dst.view(np.int32))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    g = mg.build_csr(s_d, d_d, n)
+    mg.normalize(g)
+    torch.cuda.synchronize()
+    t_build = time.perf_counter() - t0
+    nnz = g.nnz
+    del s_d, d_d
+
+    pipe = mg.Pipeline()
+    step = mg.GCNStep(g, dev(x), [dev(w) for w in ws], dev(y), n_chunks=args.chunks, pipe=pipe)
+
+    # A plain copy kernel of known size: its FETCH_SIZE / WRITE_SIZE readings calibrate the
+    # counter units when this command runs under rocprofv3 --pmc.
+    calib_src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
+    calib_dst = torch.empty_like(calib_src)
+    calib_dst.copy_(calib_src)
+
+    for _ in range(args.warmup):
+        step.step()
+    torch.cuda.synchronize()
+    pipe.timing(not args.no_event_timing)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    loss = step.loss.item()
+
+    work = sum(nnz * d for d in dims[:-1])  # sum over layers of nnz * d^(l)
+    value = work / (dt / args.steps)
+
+    kinds = {}
+    if not args.no_event_timing:
+        names = ["agg_g4", "agg_g8", "agg_g16", "agg_g32", "agg_g64", "update_fwd", "update_dgrad",
+                 "update_wgrad"]
+        for k, nm in enumerate(names):
+            ms, cnt = pipe.timing_read(k)
+            if cnt:
+                kinds[nm] = {"total_ms": ms, "launches": cnt, "avg_ms": ms / cnt}
+    pipe.timing(False)
+
+    roofline = None
+    agg = {k: v for k, v in kinds.items() if k.startswith("agg")}
+    if agg:
+        dom = max(agg, key=lambda k: agg[k]["total_ms"])
+        gsz = int(dom.split("g")[-1])
+        f = gsz * 4  # slice width in fp32 columns handled by that kernel
+        # algorithmic minimum per full-graph launch: index + value stream, every feature row
+        # read once, every output row written once, one row pointer per row
+        full = 8.0 * nnz + 2.0 * n * f * 4 + 8.0 * n
+        launches_per_layer_call = max(1, args.chunks)
+        per_launch = full / launches_per_layer_call
+        avg_s = agg[dom]["avg_ms"] * 1e-3
+        achieved = per_launch / avg_s / 1e9
+        roofline = {
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+            "kernel": f"aggregate_kernel<G={gsz}> ({f} fp32 columns)",
+            "avg_launch_ms": agg[dom]["avg_ms"], "launches": agg[dom]["launches"],
+            "algorithmic_bytes_per_launch": per_launch,
+            "gather_bytes_per_launch": (nnz * (8.0 + f * 4) + n * f * 4) / launches_per_layer_call,
+        }
+
+    out = {
+        "metric": "GCN layer fwd+bwd edges*feat/s", "value": value, "unit": "edges*feat/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{args.config}: {len(dims) - 1}-layer GCN {'-'.join(map(str, dims))}, one "
+                        f"fwd+bwd epoch, R-MAT graph N={n}, nnz(A_hat)={nnz}",
+            "n_nodes": n, "nnz": nnz, "row_chunks": args.chunks, "seed": args.seed,
+        },
+        "loss": loss, "build_csr_normalize_ms": t_build * 1e3, "kernels": kinds,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config, args.cpu_scale, args.seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -133,7 +133,8 @@ int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void
  *   relu_ref   : R, the stored layer output H' whose sign gives the ReLU derivative
  *                (1[R > 0], 0 at 0); NULL = no mask.  Only DGRAD and WGRAD read it.
  *   beta       : WGRAD only, 0 or 1.
- * B (the weight matrix W[k x m], fp32) is always row-major k x m.  For WGRAD C is fp32.
+ * FWD, FWD_RELU, DGRAD: B is the weight matrix W[k x m], fp32, row-major.  WGRAD: A = Z
+ * [n x k], B = the upstream gradient [n x m], C = dW [k x m] fp32.
  */
 int mixgcn_update(int op, int dtype, const void* A, int64_t lda, const void* B, int64_t ldb,
                   void* C, int64_t ldc, int64_t n_rows, int32_t k, int32_t m,
@@ -171,6 +172,21 @@ int mixgcn_graph_free(mixgcn_graph* g);
 /* Two streams for the chunk pipeline: `primary` runs the aggregation, `secondary` the update. */
 int mixgcn_pipeline_create(void* primary_stream, void* secondary_stream, mixgcn_pipeline** out);
 int mixgcn_pipeline_destroy(mixgcn_pipeline* p);
+/*
+ * Per-launch timing for benchmarks: while enabled, mixgcn_layer_fwd / mixgcn_layer_bwd record a
+ * HIP event pair around every launch of the aggregation kernel and of the update kernels, on
+ * the stream of that launch.  mixgcn_pipeline_timing(p, enable) switches it and clears what was
+ * recorded.  mixgcn_pipeline_timing_read synchronises both streams and returns the summed
+ * duration (ms) and the number of launches of one kind (host pointers):
+ *   0..4  aggregation kernel with lane groups of 4, 8, 16, 32, 64 lanes (slice widths up to
+ *         16, 32, 64, 128, 256 fp32 columns; twice that for bf16)
+ *   5 update forward, 6 update dgrad, 7 update wgrad (split-K slab kernel).
+ */
+enum { MIXGCN_TIME_AGG_G4 = 0, MIXGCN_TIME_AGG_G8 = 1, MIXGCN_TIME_AGG_G16 = 2,
+       MIXGCN_TIME_AGG_G32 = 3, MIXGCN_TIME_AGG_G64 = 4, MIXGCN_TIME_UPDATE_FWD = 5,
+       MIXGCN_TIME_UPDATE_DGRAD = 6, MIXGCN_TIME_UPDATE_WGRAD = 7 };
+int mixgcn_pipeline_timing(mixgcn_pipeline* p, int enable);
+int mixgcn_pipeline_timing_read(mixgcn_pipeline* p, int kind, double* total_ms, int64_t* launches);
 const char* mixgcn_strerror(int code);
 const char* mixgcn_last_error(void);
 int mixgcn_version(void);

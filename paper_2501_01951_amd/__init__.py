@@ -9,3 +9,4 @@ from .binding import (  # noqa: F401
     BUILD_TRANSPOSE, INPUT_ON_HOST, Graph, LayerDesc, MixGCNError, Pipeline, aggregate, build_csr,
     layer_bwd, layer_fwd, lib_path, load_library, normalize, softmax_xent, update, version,
 )
+from .model import GCNStep  # noqa: F401

@@ -75,8 +75,12 @@ def load_library():
     lib.mixgcn_graph_free.argtypes = [vp]
     lib.mixgcn_pipeline_create.argtypes = [vp, vp, ctypes.POINTER(vp)]
     lib.mixgcn_pipeline_destroy.argtypes = [vp]
+    lib.mixgcn_pipeline_timing.argtypes = [vp, ctypes.c_int]
+    lib.mixgcn_pipeline_timing_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
+                                                ctypes.POINTER(ctypes.c_int64)]
     for name in ("build_csr", "normalize", "aggregate", "update", "layer_fwd", "layer_bwd",
-                 "softmax_xent", "graph_info", "graph_free", "pipeline_create", "pipeline_destroy"):
+                 "softmax_xent", "graph_info", "graph_free", "pipeline_create", "pipeline_destroy",
+                 "pipeline_timing", "pipeline_timing_read"):
         getattr(lib, "mixgcn_" + name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -192,6 +196,16 @@ class Pipeline:
                                                      ctypes.c_void_p(self.secondary.cuda_stream),
                                                      ctypes.byref(h)), "pipeline_create")
         self._h = h
+
+    def timing(self, enable: bool) -> None:
+        _check(load_library().mixgcn_pipeline_timing(self._h, int(enable)), "pipeline_timing")
+
+    def timing_read(self, kind: int):
+        """(total ms, launches) of one kernel kind since timing was enabled; synchronises."""
+        ms, cnt = ctypes.c_double(), ctypes.c_int64()
+        _check(load_library().mixgcn_pipeline_timing_read(self._h, kind, ctypes.byref(ms),
+                                                          ctypes.byref(cnt)), "pipeline_timing_read")
+        return ms.value, cnt.value
 
     def free(self):
         if self._h:

@@ -52,6 +52,36 @@ int get_scratch(int which, size_t bytes, void** out)
     return MIXGCN_OK;
 }
 
+int Timer::begin(int kind, hipStream_t s)
+{
+    if (used == recs.size()) {
+        Rec r;
+        MIXGCN_HIP_TRY(hipEventCreate(&r.a));
+        MIXGCN_HIP_TRY(hipEventCreate(&r.b));
+        recs.push_back(r);
+    }
+    recs[used].kind = kind;
+    MIXGCN_HIP_TRY(hipEventRecord(recs[used].a, s));
+    return MIXGCN_OK;
+}
+
+int Timer::end(hipStream_t s)
+{
+    MIXGCN_HIP_TRY(hipEventRecord(recs[used].b, s));
+    ++used;
+    return MIXGCN_OK;
+}
+
+void Timer::destroy()
+{
+    for (Rec& r : recs) {
+        if (r.a) (void)hipEventDestroy(r.a);
+        if (r.b) (void)hipEventDestroy(r.b);
+    }
+    recs.clear();
+    used = 0;
+}
+
 namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -192,9 +222,9 @@ int mixgcn_graph_info(const mixgcn_graph* g, mixgcn_graph_view* out)
     return MIXGCN_OK;
 }
 
-int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void* H, int64_t ldh,
-                     void* Z, int64_t ldz, int32_t col_begin, int32_t col_end, int64_t row_begin,
-                     int64_t row_end, void* stream)
+static int aggregate_impl(const mixgcn_graph* g, int transpose, int dtype, const void* H,
+                          int64_t ldh, void* Z, int64_t ldz, int32_t col_begin, int32_t col_end,
+                          int64_t row_begin, int64_t row_end, hipStream_t stream, Timer* timer)
 {
     if (!g) return fail(MIXGCN_EINVAL, "aggregate: graph is null");
     if (!g->normalized) return fail(MIXGCN_ESTATE, "aggregate: call mixgcn_normalize first");
@@ -227,12 +257,21 @@ int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void
     }
     if (row_end == row_begin || col_end == col_begin) return MIXGCN_OK;
     return launch_aggregate(g, *m, dtype, H, ldh, Z, ldz, col_begin, col_end, row_begin, row_end,
-                            (hipStream_t)stream);
+                            stream, timer);
 }
 
-int mixgcn_update(int op, int dtype, const void* A, int64_t lda, const void* B, int64_t ldb,
-                  void* C, int64_t ldc, int64_t n_rows, int32_t k, int32_t m,
-                  const void* relu_ref, int64_t ldr, float beta, void* stream)
+int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void* H, int64_t ldh,
+                     void* Z, int64_t ldz, int32_t col_begin, int32_t col_end, int64_t row_begin,
+                     int64_t row_end, void* stream)
+{
+    return aggregate_impl(g, transpose, dtype, H, ldh, Z, ldz, col_begin, col_end, row_begin,
+                          row_end, (hipStream_t)stream, nullptr);
+}
+
+static int update_impl(int op, int dtype, const void* A, int64_t lda, const void* B, int64_t ldb,
+                       void* C, int64_t ldc, int64_t n_rows, int32_t k, int32_t m,
+                       const void* relu_ref, int64_t ldr, float beta, hipStream_t stream,
+                       Timer* timer)
 {
     if (op < MIXGCN_OP_FWD || op > MIXGCN_OP_WGRAD) return fail(MIXGCN_EINVAL, "update: op");
     if (dtype != MIXGCN_F32 && dtype != MIXGCN_BF16) return fail(MIXGCN_EINVAL, "update: dtype");
@@ -260,7 +299,15 @@ int mixgcn_update(int op, int dtype, const void* A, int64_t lda, const void* B, 
         break;
     }
     return launch_update(op, dtype, A, lda, (const float*)B, ldb, C, ldc, n_rows, k, m, relu_ref,
-                         ldr, beta, (hipStream_t)stream);
+                         ldr, beta, stream, timer);
+}
+
+int mixgcn_update(int op, int dtype, const void* A, int64_t lda, const void* B, int64_t ldb,
+                  void* C, int64_t ldc, int64_t n_rows, int32_t k, int32_t m,
+                  const void* relu_ref, int64_t ldr, float beta, void* stream)
+{
+    return update_impl(op, dtype, A, lda, B, ldb, C, ldc, n_rows, k, m, relu_ref, ldr, beta,
+                       (hipStream_t)stream, nullptr);
 }
 
 int mixgcn_softmax_xent(const float* logits, int64_t ldl, const int32_t* labels, int64_t n,
@@ -297,8 +344,37 @@ int mixgcn_pipeline_destroy(mixgcn_pipeline* p)
     for (hipEvent_t e : p->events) (void)hipEventDestroy(e);
     if (p->ev_start) (void)hipEventDestroy(p->ev_start);
     if (p->ev_done) (void)hipEventDestroy(p->ev_done);
-    if (p->wt) (void)hipFree(p->wt);
+    p->timer.destroy();
     delete p;
+    return MIXGCN_OK;
+}
+
+int mixgcn_pipeline_timing(mixgcn_pipeline* p, int enable)
+{
+    if (!p) return fail(MIXGCN_EINVAL, "pipeline_timing: null pipeline");
+    p->timer.enabled = enable != 0;
+    p->timer.reset();
+    return MIXGCN_OK;
+}
+
+int mixgcn_pipeline_timing_read(mixgcn_pipeline* p, int kind, double* total_ms, int64_t* launches)
+{
+    if (!p || !total_ms || !launches) return fail(MIXGCN_EINVAL, "pipeline_timing_read: null");
+    if (kind < 0 || kind >= kTimeKinds) return fail(MIXGCN_EINVAL, "pipeline_timing_read: kind");
+    MIXGCN_HIP_TRY(hipStreamSynchronize(p->primary));
+    MIXGCN_HIP_TRY(hipStreamSynchronize(p->secondary));
+    double sum = 0.0;
+    int64_t cnt = 0;
+    for (size_t i = 0; i < p->timer.used; ++i) {
+        const Timer::Rec& r = p->timer.recs[i];
+        if (r.kind != kind) continue;
+        float ms = 0.f;
+        MIXGCN_HIP_TRY(hipEventElapsedTime(&ms, r.a, r.b));
+        sum += ms;
+        ++cnt;
+    }
+    *total_ms = sum;
+    *launches = cnt;
     return MIXGCN_OK;
 }
 
@@ -349,11 +425,12 @@ int mixgcn_layer_fwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, const vo
     const int es = elem_size(d->dtype);
     const int op = d->relu ? MIXGCN_OP_FWD_RELU : MIXGCN_OP_FWD;
     const int nc = d->n_chunks;
+    Timer* tm = p->timer.enabled ? &p->timer : nullptr;
     if (nc == 1 || p->secondary == p->primary) {
-        MIXGCN_TRY(mixgcn_aggregate(g, 0, d->dtype, H, d->ld_h, Z, d->ld_z, 0, d->f_in, 0, n,
-                                    p->primary));
-        return mixgcn_update(op, d->dtype, Z, d->ld_z, W, d->ld_w, Hout, d->ld_out, n, d->f_in,
-                             d->f_out, nullptr, 0, 0.f, p->primary);
+        MIXGCN_TRY(aggregate_impl(g, 0, d->dtype, H, d->ld_h, Z, d->ld_z, 0, d->f_in, 0, n,
+                                  p->primary, tm));
+        return update_impl(op, d->dtype, Z, d->ld_z, W, d->ld_w, Hout, d->ld_out, n, d->f_in,
+                           d->f_out, nullptr, 0, 0.f, p->primary, tm);
     }
     MIXGCN_TRY(ensure_events(p, (size_t)nc));
     // the dense stream may not start before everything queued on the sparse stream so far
@@ -362,14 +439,14 @@ int mixgcn_layer_fwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, const vo
     for (int c = 0; c < nc; ++c) {
         const int64_t r0 = chunk_bound(n, nc, c), r1 = chunk_bound(n, nc, c + 1);
         if (r1 <= r0) continue;
-        MIXGCN_TRY(mixgcn_aggregate(g, 0, d->dtype, H, d->ld_h, Z, d->ld_z, 0, d->f_in, r0, r1,
-                                    p->primary));
+        MIXGCN_TRY(aggregate_impl(g, 0, d->dtype, H, d->ld_h, Z, d->ld_z, 0, d->f_in, r0, r1,
+                                  p->primary, tm));
         MIXGCN_HIP_TRY(hipEventRecord(p->events[(size_t)c], p->primary));
         MIXGCN_HIP_TRY(hipStreamWaitEvent(p->secondary, p->events[(size_t)c], 0));
         const char* zc = (const char*)Z + (size_t)r0 * d->ld_z * es;
         char* oc = (char*)Hout + (size_t)r0 * d->ld_out * es;
-        MIXGCN_TRY(mixgcn_update(op, d->dtype, zc, d->ld_z, W, d->ld_w, oc, d->ld_out, r1 - r0,
-                                 d->f_in, d->f_out, nullptr, 0, 0.f, p->secondary));
+        MIXGCN_TRY(update_impl(op, d->dtype, zc, d->ld_z, W, d->ld_w, oc, d->ld_out, r1 - r0,
+                               d->f_in, d->f_out, nullptr, 0, 0.f, p->secondary, tm));
     }
     MIXGCN_HIP_TRY(hipEventRecord(p->ev_done, p->secondary));
     MIXGCN_HIP_TRY(hipStreamWaitEvent(p->primary, p->ev_done, 0));
@@ -386,22 +463,23 @@ int mixgcn_layer_bwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, void* Z,
     const void* R = d->relu ? Hout : nullptr;
     const bool two = p->secondary != p->primary && d->n_chunks > 1;
     hipStream_t dense = two ? p->secondary : p->primary;
+    Timer* tm = p->timer.enabled ? &p->timer : nullptr;
     if (two) {
         MIXGCN_HIP_TRY(hipEventRecord(p->ev_start, p->primary));
         MIXGCN_HIP_TRY(hipStreamWaitEvent(p->secondary, p->ev_start, 0));
     }
     // dW = Z^T dP must read Z before dZ overwrites it
-    MIXGCN_TRY(mixgcn_update(MIXGCN_OP_WGRAD, d->dtype, Z, d->ld_z, G, d->ld_out, dW, d->ld_w, n,
-                             d->f_in, d->f_out, R, d->ld_out, 0.f, dense));
+    MIXGCN_TRY(update_impl(MIXGCN_OP_WGRAD, d->dtype, Z, d->ld_z, G, d->ld_out, dW, d->ld_w, n,
+                           d->f_in, d->f_out, R, d->ld_out, 0.f, dense, tm));
     if (dH) {
-        MIXGCN_TRY(mixgcn_update(MIXGCN_OP_DGRAD, d->dtype, G, d->ld_out, W, d->ld_w, Z, d->ld_z, n,
-                                 d->f_in, d->f_out, R, d->ld_out, 0.f, dense));
+        MIXGCN_TRY(update_impl(MIXGCN_OP_DGRAD, d->dtype, G, d->ld_out, W, d->ld_w, Z, d->ld_z, n,
+                               d->f_in, d->f_out, R, d->ld_out, 0.f, dense, tm));
         if (two) {
             MIXGCN_HIP_TRY(hipEventRecord(p->ev_done, p->secondary));
             MIXGCN_HIP_TRY(hipStreamWaitEvent(p->primary, p->ev_done, 0));
         }
-        MIXGCN_TRY(mixgcn_aggregate(g, 1, d->dtype, Z, d->ld_z, dH, d->ld_h, 0, d->f_in, 0, n,
-                                    p->primary));
+        MIXGCN_TRY(aggregate_impl(g, 1, d->dtype, Z, d->ld_z, dH, d->ld_h, 0, d->f_in, 0, n,
+                                  p->primary, tm));
     } else if (two) {
         MIXGCN_HIP_TRY(hipEventRecord(p->ev_done, p->secondary));
         MIXGCN_HIP_TRY(hipStreamWaitEvent(p->primary, p->ev_done, 0));

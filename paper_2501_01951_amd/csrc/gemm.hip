@@ -316,7 +316,7 @@ int launch_rowblock(bool relu, const float* A, int64_t lda, const float* B, int6
 
 int launch_update(int op, int dtype, const void* A_, int64_t lda, const float* B, int64_t ldb,
                   void* C_, int64_t ldc, int64_t n, int32_t k, int32_t m, const void* R_,
-                  int64_t ldr, float beta, hipStream_t s)
+                  int64_t ldr, float beta, hipStream_t s, Timer* timer)
 {
     if (dtype != MIXGCN_F32) return fail(MIXGCN_EUNSUPPORTED, "update: bf16 storage not built yet");
     const float* A = (const float*)A_;
@@ -324,20 +324,24 @@ int launch_update(int op, int dtype, const void* A_, int64_t lda, const float* B
     const float* R = (const float*)R_;
     if (op == MIXGCN_OP_FWD || op == MIXGCN_OP_FWD_RELU) {
         const bool relu = op == MIXGCN_OP_FWD_RELU;
+        if (timer) MIXGCN_TRY(timer->begin(kTimeUpdateFwd, s));
         if (m > 64)
             MIXGCN_TRY((launch_rowblock<Shape128x128, false>(relu, A, lda, B, ldb, C, ldc, n, k, m,
                                                             nullptr, 0, s)));
         else
             MIXGCN_TRY((launch_rowblock<Shape128x32, false>(relu, A, lda, B, ldb, C, ldc, n, k, m,
                                                            nullptr, 0, s)));
+        if (timer) MIXGCN_TRY(timer->end(s));
     } else if (op == MIXGCN_OP_DGRAD) {
         // C[n x k] = (A (.) mask)[n x m] * W^T, W = B stored k x m: reduction over m
+        if (timer) MIXGCN_TRY(timer->begin(kTimeUpdateDgrad, s));
         if (k > 64)
             MIXGCN_TRY((launch_rowblock<Shape128x128, true>(false, A, lda, B, ldb, C, ldc, n, m, k,
                                                            R, ldr, s)));
         else
             MIXGCN_TRY((launch_rowblock<Shape128x32, true>(false, A, lda, B, ldb, C, ldc, n, m, k, R,
                                                           ldr, s)));
+        if (timer) MIXGCN_TRY(timer->end(s));
     } else if (op == MIXGCN_OP_WGRAD) {
         // C[k x m] = beta C + A[n x k]^T (B (.) mask)[n x m]; here `B` of the ABI is passed as B
         const bool wide = m > 64;
@@ -356,12 +360,14 @@ int launch_update(int op, int dtype, const void* A_, int64_t lda, const float* B
         MIXGCN_TRY(get_scratch(0, (size_t)n_slabs * cells * sizeof(float), &scratch));
         float* P = (float*)scratch;
         const unsigned grid = (unsigned)(n_slabs * tiles);
+        if (timer) MIXGCN_TRY(timer->begin(kTimeUpdateWgrad, s));
         if (wide)
             hipLaunchKernelGGL((wgrad_slab_kernel<Shape128x128>), dim3(grid), dim3(kBlock), 0, s, A,
                                lda, B, ldb, R, ldr, P, n, k, m, rows_per_slab, nit, njt);
         else
             hipLaunchKernelGGL((wgrad_slab_kernel<Shape128x32>), dim3(grid), dim3(kBlock), 0, s, A,
                                lda, B, ldb, R, ldr, P, n, k, m, rows_per_slab, nit, njt);
+        if (timer) MIXGCN_TRY(timer->end(s));
         hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)ceil_div(cells, kBlock)),
                            dim3(kBlock), 0, s, P, n_slabs, cells, m, C, ldc, beta);
     } else {

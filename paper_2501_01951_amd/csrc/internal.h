@@ -66,14 +66,44 @@ struct mixgcn_graph {
     mutable size_t partials_bytes = 0;
 };
 
+namespace mixgcn {
+
+// Optional per-launch timing with HIP events recorded on the stream of the launch.
+enum TimerKind {
+    kTimeAggG4 = 0,  // aggregation main kernel by lane-group size: 4, 8, 16, 32, 64
+    kTimeAggG8,
+    kTimeAggG16,
+    kTimeAggG32,
+    kTimeAggG64,
+    kTimeUpdateFwd,
+    kTimeUpdateDgrad,
+    kTimeUpdateWgrad,
+    kTimeKinds
+};
+
+struct Timer {
+    struct Rec {
+        hipEvent_t a = nullptr, b = nullptr;
+        int kind = 0;
+    };
+    bool enabled = false;
+    std::vector<Rec> recs;
+    size_t used = 0;
+    int begin(int kind, hipStream_t s);
+    int end(hipStream_t s);
+    void reset() { used = 0; }
+    void destroy();
+};
+
+}  // namespace mixgcn
+
 struct mixgcn_pipeline {
+    mixgcn::Timer timer;
     hipStream_t primary = nullptr;
     hipStream_t secondary = nullptr;
     std::vector<hipEvent_t> events;
     hipEvent_t ev_start = nullptr;
     hipEvent_t ev_done = nullptr;
-    float* wt = nullptr;  // transposed-weight / split-K scratch
-    size_t wt_bytes = 0;
 };
 
 namespace mixgcn {
@@ -102,11 +132,11 @@ int normalize_sym(mixgcn_graph* g, hipStream_t s);
 
 int launch_aggregate(const mixgcn_graph* g, const Csr& m, int dtype, const void* H, int64_t ldh,
                      void* Z, int64_t ldz, int32_t c0, int32_t c1, int64_t r0, int64_t r1,
-                     hipStream_t s);
+                     hipStream_t s, Timer* timer);
 
 int launch_update(int op, int dtype, const void* A, int64_t lda, const float* B, int64_t ldb,
                   void* C, int64_t ldc, int64_t n, int32_t k, int32_t m, const void* R,
-                  int64_t ldr, float beta, hipStream_t s);
+                  int64_t ldr, float beta, hipStream_t s, Timer* timer);
 
 int launch_softmax_xent(const float* logits, int64_t ldl, const int32_t* labels, int64_t n,
                         int32_t c, float* dlogits, int64_t ldd, double* loss, hipStream_t s);

@@ -1,0 +1,52 @@
+"""Sequencing helper: an L-layer GCN training step as a fixed series of C-ABI calls on
+preallocated device buffers.  No arithmetic happens here."""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+class GCNStep:
+    """Forward + loss + backward of an L-layer GCN (ReLU between layers, none after the last).
+
+    Buffers: Z_l and H_{l+1} per layer are kept for the backward pass; dH buffers are shared
+    by width.  dW_l are fp32 like W_l.  The input gradient is not computed (dX is not needed
+    for training)."""
+
+    def __init__(self, g: B.Graph, x, weights, labels, n_chunks: int = 1, pipe: B.Pipeline = None):
+        self.g = g
+        self.n = x.shape[0]
+        self.x = x
+        self.w = list(weights)
+        self.labels = labels
+        self.n_chunks = n_chunks
+        self.pipe = pipe if pipe is not None else B.Pipeline()
+        dev = x.device
+        L = len(self.w)
+        self.z = [torch.empty(self.n, w.shape[0], device=dev, dtype=x.dtype) for w in self.w]
+        self.h = [x] + [torch.empty(self.n, w.shape[1], device=dev, dtype=x.dtype) for w in self.w]
+        self.dw = [torch.empty_like(w) for w in self.w]
+        self.dlogits = torch.empty_like(self.h[L])
+        self.dh = [None] + [torch.empty(self.n, self.w[l].shape[0], device=dev, dtype=x.dtype)
+                            for l in range(1, L)]
+        self.loss = torch.zeros(1, dtype=torch.float64, device=dev)
+
+    def forward(self):
+        L = len(self.w)
+        for l in range(L):
+            B.layer_fwd(self.g, self.h[l], self.w[l], self.z[l], self.h[l + 1], self.pipe,
+                        relu=(l < L - 1), n_chunks=self.n_chunks)
+        B.softmax_xent(self.h[L], self.labels, self.dlogits, self.loss, stream=self.pipe.primary)
+
+    def backward(self):
+        L = len(self.w)
+        grad = self.dlogits
+        for l in range(L - 1, -1, -1):
+            B.layer_bwd(self.g, self.z[l], self.h[l + 1], self.w[l], grad, self.dw[l], self.dh[l],
+                        self.pipe, relu=(l < L - 1), n_chunks=self.n_chunks)
+            grad = self.dh[l]
+
+    def step(self):
+        self.forward()
+        self.backward()
