@@ -128,7 +128,7 @@ int mixgcn_build_csr(const uint32_t* src, const uint32_t* dst, uint64_t n_edges,
     if (!out) return fail(MIXGCN_EINVAL, "build_csr: out is null");
     *out = nullptr;
     if (n_nodes == 0) return fail(MIXGCN_EINVAL, "build_csr: n_nodes == 0");
-    if (n_nodes > 0x7FFFFFFFu) return fail(MIXGCN_EINVAL, "build_csr: n_nodes > 2^31 - 1");
+    if (n_nodes > 0x40000000u) return fail(MIXGCN_EINVAL, "build_csr: n_nodes > 2^30");
     if (n_edges > 0 && (!src || !dst)) return fail(MIXGCN_EINVAL, "build_csr: null edge list");
     if (n_edges > (1ull << 40)) return fail(MIXGCN_EINVAL, "build_csr: n_edges too large");
     if (flags & ~(uint32_t)(MIXGCN_SYMMETRIZE | MIXGCN_ADD_SELF_LOOPS | MIXGCN_BUILD_TRANSPOSE |

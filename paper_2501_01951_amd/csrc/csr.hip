@@ -69,12 +69,12 @@ __global__ __launch_bounds__(kBlock) void fill_i64_kernel(int64_t* p, int64_t n,
     if (i < n) p[i] = v;
 }
 
-// Writes col/colf for every distinct key and rowptr[q] = (index of the first entry with row >= q)
+// Writes col/cv for every distinct key and rowptr[q] = (index of the first entry with row >= q)
 // for every q up to the last non-empty row; later rows keep the preset value nnz.
 __global__ __launch_bounds__(kBlock) void unique_fill_kernel(
     const uint64_t* __restrict__ keys, int64_t n_keys, uint64_t drop, int bits,
     const uint64_t* __restrict__ tile_off, uint32_t* __restrict__ col,
-    uint32_t* __restrict__ colf, int64_t* __restrict__ rowptr)
+    uint2* __restrict__ cv, int64_t* __restrict__ rowptr)
 {
     __shared__ uint64_t lds[4];
     const int64_t base = (int64_t)blockIdx.x * kCompactTile + (int64_t)threadIdx.x * kCompactItems;
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(kBlock) void unique_fill_kernel(
         const uint64_t k = keys[i];
         const uint32_t c32 = (uint32_t)(k & cmask);
         col[pos] = c32;
-        colf[pos] = c32;
+        cv[pos] = make_uint2(c32, 0u);
         const int64_t row = (int64_t)(k >> bits);
         const int64_t prev = (i == 0) ? -1 : (int64_t)(keys[i - 1] >> bits);
         for (int64_t q = prev + 1; q <= row; ++q) rowptr[q] = (int64_t)pos;
@@ -103,15 +103,15 @@ __global__ __launch_bounds__(kBlock) void unique_fill_kernel(
     }
 }
 
-// Marks the last stored entry of every non-empty row in colf and reports empty rows.
+// Marks the last stored entry of every non-empty row in cv and reports empty rows.
 __global__ __launch_bounds__(kBlock) void mark_row_ends_kernel(const int64_t* __restrict__ rowptr,
-                                                               uint32_t n, uint32_t* colf,
+                                                               uint32_t n, uint2* cv,
                                                                uint32_t* __restrict__ any_empty)
 {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= n) return;
     const int64_t a = rowptr[r], b = rowptr[r + 1];
-    if (b > a) colf[b - 1] |= 0x80000000u;
+    if (b > a) cv[b - 1].x |= kEntryEndBit;
     else atomicOr(any_empty, 1u);
 }
 
@@ -155,7 +155,8 @@ __global__ __launch_bounds__(kBlock) void values_kernel(const int64_t* __restric
                                                         const uint32_t* __restrict__ col,
                                                         const float* __restrict__ dinv,
                                                         uint32_t n, int64_t nnz,
-                                                        float* __restrict__ val)
+                                                        float* __restrict__ val,
+                                                        uint2* __restrict__ cv)
 {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= nnz) return;
@@ -166,7 +167,9 @@ __global__ __launch_bounds__(kBlock) void values_kernel(const int64_t* __restric
         else hi = mid;
     }
     const int64_t row = lo - 1;
-    val[e] = dinv[row] * dinv[col[e]];
+    const float v = dinv[row] * dinv[col[e]];
+    val[e] = v;
+    cv[e].y = __float_as_uint(v);
 }
 
 template <typename T>
@@ -198,7 +201,7 @@ void csr_free(Csr* c)
 {
     if (c->rowptr) (void)hipFree(c->rowptr);
     if (c->col) (void)hipFree(c->col);
-    if (c->colf) (void)hipFree(c->colf);
+    if (c->cv) (void)hipFree(c->cv);
     if (c->val) (void)hipFree(c->val);
     if (c->grp_row) (void)hipFree(c->grp_row);
     *c = Csr();
@@ -261,25 +264,25 @@ int csr_from_edges(const uint32_t* d_src, const uint32_t* d_dst, uint64_t n_edge
     Csr c;
     c.nnz = nnz;
     c.n_groups = ceil_div(nnz, kGroupNnz);
-    c.nnz_padded = (c.n_groups + 1) * kGroupNnz;
+    c.nnz_padded = (c.n_groups + 1) * kGroupNnz + kEntryPad;
     int rc = MIXGCN_OK;
     do {
         if ((rc = dmalloc(&c.rowptr, (size_t)n + 1)) != MIXGCN_OK) break;
         if ((rc = dmalloc(&c.col, (size_t)nnz)) != MIXGCN_OK) break;
-        if ((rc = dmalloc(&c.colf, (size_t)c.nnz_padded)) != MIXGCN_OK) break;
+        if ((rc = dmalloc(&c.cv, (size_t)c.nnz_padded)) != MIXGCN_OK) break;
         if ((rc = dmalloc(&c.grp_row, (size_t)c.n_groups + 1)) != MIXGCN_OK) break;
-        if (hipMemsetAsync(c.colf, 0, (size_t)c.nnz_padded * 4, s) != hipSuccess) {
-            rc = fail(MIXGCN_EHIP, "hipMemsetAsync(colf)");
+        if (hipMemsetAsync(c.cv, 0, (size_t)c.nnz_padded * 8, s) != hipSuccess) {
+            rc = fail(MIXGCN_EHIP, "hipMemsetAsync(cv)");
             break;
         }
         hipLaunchKernelGGL(fill_i64_kernel, dim3((unsigned)ceil_div((int64_t)n + 1, kBlock)),
                            dim3(kBlock), 0, s, c.rowptr, (int64_t)n + 1, nnz);
         if (n_keys > 0)
             hipLaunchKernelGGL(unique_fill_kernel, dim3((unsigned)n_ctiles), dim3(kBlock), 0, s,
-                               sorted, n_keys, drop, bits, tile_off, c.col, c.colf, c.rowptr);
+                               sorted, n_keys, drop, bits, tile_off, c.col, c.cv, c.rowptr);
         if (n > 0)
             hipLaunchKernelGGL(mark_row_ends_kernel, dim3((unsigned)ceil_div(n, kBlock)),
-                               dim3(kBlock), 0, s, c.rowptr, n, c.colf, t.flags + 1);
+                               dim3(kBlock), 0, s, c.rowptr, n, c.cv, t.flags + 1);
         hipLaunchKernelGGL(group_rows_kernel, dim3((unsigned)ceil_div(c.n_groups + 1, kBlock)),
                            dim3(kBlock), 0, s, c.rowptr, n, nnz, c.n_groups, c.grp_row);
         c.h_rowptr.resize((size_t)n + 1);
@@ -311,13 +314,11 @@ int normalize_sym(mixgcn_graph* g, hipStream_t s)
     Csr* mats[2] = {&g->fwd, g->has_transpose ? &g->tr : nullptr};
     for (Csr* c : mats) {
         if (!c) continue;
-        if (!c->val) {
-            MIXGCN_TRY(dmalloc(&c->val, (size_t)c->nnz_padded));
-            MIXGCN_HIP_TRY(hipMemsetAsync(c->val, 0, (size_t)c->nnz_padded * 4, s));
-        }
+        if (!c->val) MIXGCN_TRY(dmalloc(&c->val, (size_t)c->nnz));
         if (c->nnz > 0)
             hipLaunchKernelGGL(values_kernel, dim3((unsigned)ceil_div(c->nnz, kBlock)),
-                               dim3(kBlock), 0, s, c->rowptr, c->col, g->dinv, n, c->nnz, c->val);
+                               dim3(kBlock), 0, s, c->rowptr, c->col, g->dinv, n, c->nnz, c->val,
+                               c->cv);
     }
     MIXGCN_HIP_TRY(hipGetLastError());
     g->normalized = true;

@@ -32,17 +32,24 @@ int fail(int code, const std::string& msg);
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // ---- graph ------------------------------------------------------------------------------------
-// Number of stored entries that one lane group of the aggregation kernel walks.
+// Granularity (in stored entries) of the table that maps an entry index to its row.
 constexpr int kGroupNnz = 256;
+// Padding of the kernel's entry array beyond nnz: the widest span one wavefront walks plus the
+// prefetch distance of its software pipeline.
+constexpr int kEntryPad = 8192;
+// Bits of an entry's column word that are not part of the column index.
+constexpr uint32_t kEntryEndBit = 0x80000000u;  // last stored entry of its row
+constexpr uint32_t kEntryColMask = 0x3FFFFFFFu;
 
 struct Csr {
     int64_t nnz = 0;
-    int64_t nnz_padded = 0;          // allocation length of colf / val (multiple of kGroupNnz)
+    int64_t nnz_padded = 0;          // allocation length of cv
     int64_t n_groups = 0;            // ceil(nnz / kGroupNnz)
     int64_t* rowptr = nullptr;       // [n + 1]
-    uint32_t* col = nullptr;         // [nnz]
-    uint32_t* colf = nullptr;        // [nnz_padded] col | (last entry of its row ? 1u << 31 : 0)
-    float* val = nullptr;            // [nnz_padded]
+    uint32_t* col = nullptr;         // [nnz]  (public form: plain ascending columns)
+    float* val = nullptr;            // [nnz]  (public form)
+    // The aggregation kernel's form: entry e = { col | end-of-row mark, val bits }, zero padded.
+    uint2* cv = nullptr;             // [nnz_padded]
     uint32_t* grp_row = nullptr;     // [n_groups + 1] row that holds entry g * kGroupNnz
     std::vector<int64_t> h_rowptr;   // host copy of rowptr
     bool has_empty_rows = false;

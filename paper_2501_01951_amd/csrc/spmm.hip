@@ -1,19 +1,25 @@
 // Neighbor aggregation  Z[r, c0:c1) = sum_e val[e] * H[col[e], c0:c1)  (paper Algorithm 2,
-// aggregation phase) as a gather kernel balanced by stored entries rather than by rows.
+// aggregation phase; with the transpose CSR its adjoint for the backward pass) as a gather
+// kernel balanced by stored entries rather than by rows.
 //
-// Work split.  The stored entries of the CSR are cut into consecutive windows of kGroupNnz
-// entries.  A "lane group" of G lanes (G * VEC = padded slice width; a 64-wide wavefront holds
-// 64 / G groups) walks one window front to back: every lane keeps VEC accumulators of one
-// output row, each entry costs one 16-byte load per lane from the neighbor's feature row
-// (a full row per group, coalesced), and the end-of-row mark stored in bit 31 of the column
-// index tells the group when to write the row out.  Hubs of a power-law graph are therefore
-// spread over many groups and low-degree rows share a group; every group does the same amount
-// of gather work whatever the degree distribution.
+// Work split.  A pass handles up to 256 fp32 (512 bf16) columns and is cut into column slices
+// of LPR lanes x 16 bytes.  One wavefront walks one *span* of consecutive stored entries for one
+// slice: its 64 lanes form 64 / LPR sub-groups, sub-group s takes entry s of every batch of
+// 64 / LPR entries, so one 16-byte load per lane fetches the slice of 64 / LPR neighbor rows.
+// Every wavefront does the same amount of gather work (256 such loads) whatever the degree
+// distribution: a hub is spread over many spans, a run of short rows shares one.  Control flow
+// is uniform across the wavefront: the end-of-row marks (bit 31 of an entry's column word) of a
+// batch are collected with one ballot, and only when a row ends inside the batch the sub-group
+// sums are combined with lane shuffles and the row is written.
 //
-// Rows that cross a window boundary are finished by a second, tiny kernel: a group stores the
-// piece that completes a row begun in an earlier window in its "head" slot and the piece of a
-// row it cannot complete in its "tail" slot; the fix-up kernel adds the pieces of each such row
-// in window order.  The result is deterministic (no atomics).
+// Rows that cross a span boundary are finished by a second, tiny kernel: a wavefront stores the
+// piece that completes a row begun in an earlier span in its "head" slot and the piece of a row
+// it cannot complete in its "tail" slot; the fix-up kernel adds the pieces of each such row in
+// span order.  No atomics: the result is deterministic.
+//
+// XCD mapping.  The slice index is taken from the low bits of the workgroup index.  Workgroups
+// are dealt round-robin to the 8 XCDs, so every slice is pinned to a fixed subset of the XCDs
+// and each private L2 caches only its own part of the hot feature rows.
 #include <cstdlib>
 
 #include "device_utils.h"
@@ -22,10 +28,10 @@
 namespace mixgcn {
 namespace {
 
-constexpr int kL = kGroupNnz;
-constexpr uint32_t kEndBit = 0x80000000u;
+constexpr int kBatchesPerSpan = 256;  // gather instructions per wavefront
+constexpr int kDepth = 8;             // gather instructions a wavefront keeps in flight
 
-// 16-byte feature load: 4 fp32 or 8 bf16 (widened to fp32)
+// 16-byte feature vector: 4 fp32 or 8 bf16 (widened to fp32)
 template <int DT>
 struct Feat;
 
@@ -83,211 +89,214 @@ struct Feat<MIXGCN_BF16> {
     }
 };
 
-__device__ inline uint32_t comp(const uint4& v, int i)
+// A value that is the same in every lane, moved to scalar registers.
+__device__ inline int uniform32(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ inline int64_t uniform64(int64_t v)
 {
-    return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w;
-}
-__device__ inline float comp(const float4& v, int i)
-{
-    return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w;
-}
-
-// State of one lane group while it walks its window.
-template <int VEC>
-struct GroupState {
-    float acc[VEC];
-    int64_t r;      // row being accumulated
-    bool head;      // the next completed piece belongs to a row begun in an earlier window
-    bool pending;   // acc holds entries of a row whose end has not been seen
-};
-
-// The walk is a rolling software pipeline over batches of U entries: while the feature rows of
-// batch b are consumed one by one, the load for the same slot of batch b + 1 is issued as soon
-// as the slot's data has been copied out, so a lane group keeps U row loads in flight all the
-// time.  Index and value of an entry are staged 4 per lane with one 16-byte load per chunk of
-// 4 G entries (the next chunk is fetched one chunk ahead) and broadcast inside the group with
-// lane shuffles.  All loads are in bounds by construction (padding entries carry column 0 and
-// value 0); with CHECK only the accumulation is predicated on the entry lying in [es, ee).
-template <int G, int DT, int U, bool HAS_EMPTY, bool CHECK>
-__device__ inline void roll(uint32_t (&c)[U], float (&a)[U], typename Feat<DT>::Raw (&h)[U],
-                            const uint4& ncc, const float4& nvv, int nj, bool issue, int64_t e,
-                            int64_t es, int64_t ee, const void* __restrict__ H, int64_t ldh,
-                            int64_t coff_load, void* __restrict__ Z, int64_t ldz, int64_t coff,
-                            bool active, float* my_part, int part_stride,
-                            const int64_t* __restrict__ rowptr, int64_t row_end,
-                            GroupState<Feat<DT>::VEC>& st)
-{
-    using F = Feat<DT>;
-    constexpr int VEC = F::VEC;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        float x[VEC];
-        F::widen(h[u], x);
-        const uint32_t cu = c[u];
-        const float au = a[u];
-        if (issue) {
-            c[u] = __shfl(comp(ncc, u & 3), nj + (u >> 2), G);
-            a[u] = __shfl(comp(nvv, u & 3), nj + (u >> 2), G);
-            h[u] = *F::ptr(H, (int64_t)(c[u] & ~kEndBit) * ldh + coff_load);
-        }
-        if (CHECK && !(e + u >= es && e + u < ee)) continue;
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) st.acc[i] = fmaf(au, x[i], st.acc[i]);
-        st.pending = true;
-        if (cu & kEndBit) {
-            if (active) {
-                if (st.head) {
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) my_part[i] = st.acc[i];
-                } else {
-                    F::store(Z, st.r * ldz + coff, st.acc);
-                }
-            }
-            st.head = false;
-            st.pending = false;
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) st.acc[i] = 0.f;
-            ++st.r;
-            if (HAS_EMPTY) {
-                while (st.r + 1 < row_end && rowptr[st.r + 1] <= e + u + 1) ++st.r;
-            }
-        }
-    }
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
-// Partial-sum slots: [window in call][head = 0 / tail = 1][part_stride] fp32, indexed by the
+// Sum over the 64 / LPR sub-groups of a wavefront (lanes that hold the same columns).
+template <int LPR, int VEC>
+__device__ inline void reduce_subgroups(float* v)
+{
+#pragma unroll
+    for (int d = LPR; d < kWave; d <<= 1)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) v[i] += __shfl_xor(v[i], d, kWave);
+}
+
+// Partial-sum slots: [span in call][head = 0 / tail = 1][part_stride] fp32, indexed by the
 // column offset within the pass.
-template <int G, int DT, int U, bool HAS_EMPTY>
+template <int LPR, int DT, bool HAS_EMPTY>
 __global__ __launch_bounds__(kBlock) void aggregate_kernel(
-    const int64_t* __restrict__ rowptr, const uint32_t* __restrict__ colf,
-    const float* __restrict__ val, const uint32_t* __restrict__ grp_row,
-    const void* __restrict__ H, int64_t ldh, void* __restrict__ Z, int64_t ldz, int c0, int width,
-    int64_t row_begin, int64_t row_end, int64_t e_begin, int64_t e_end, int64_t k_first,
-    int64_t n_groups_call, float* __restrict__ partials, int n_slices, int part_stride)
+    const int64_t* __restrict__ rowptr, const uint2* __restrict__ cv,
+    const uint32_t* __restrict__ grp_row, const void* __restrict__ H, int64_t ldh,
+    void* __restrict__ Z, int64_t ldz, int c0, int width, int64_t row_begin, int64_t row_end,
+    int64_t e_begin, int64_t e_end, int64_t span_first, int64_t n_spans,
+    float* __restrict__ partials, int n_slices, int part_stride)
 {
     using F = Feat<DT>;
     constexpr int VEC = F::VEC;
-    constexpr int GPB = kBlock / G;        // groups per block
-    constexpr int CHUNK = 4 * G;           // entries staged per index load
-    constexpr int BPC = CHUNK / U;         // batches per chunk
-    constexpr int PW = G * VEC;            // columns of one slice
-    static_assert(CHUNK % U == 0 && U % 4 == 0, "batch must tile the staged chunk");
-    const int lg = threadIdx.x % G;        // lane within group
-    // Consecutive workgroups are dealt round-robin to the 8 XCDs, so taking the column slice
-    // from the low bits of the block index pins every slice to a fixed subset of the XCDs:
-    // each L2 then caches only its own 1/n_slices of the hot feature rows.
+    constexpr int EPB = kWave / LPR;                  // entries per batch (= sub-groups)
+    constexpr int64_t SPAN = (int64_t)kBatchesPerSpan * EPB;
+    constexpr int PW = LPR * VEC;                     // columns of one slice
+    constexpr int D = (kDepth * EPB <= kWave) ? kDepth : (kWave / EPB);  // slots per round
+    constexpr uint64_t kLane0Mask = LPR == 64 ? 1ull
+                                  : LPR == 32 ? 0x0000000100000001ull
+                                  : LPR == 16 ? 0x0001000100010001ull
+                                  : LPR == 8  ? 0x0101010101010101ull
+                                              : 0x1111111111111111ull;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int sub = lane / LPR;   // entry of the batch this lane works on
+    const int lj = lane % LPR;    // position inside the slice
     const int slice = (int)(blockIdx.x % (unsigned)n_slices);
-    const int64_t gk = (int64_t)(blockIdx.x / (unsigned)n_slices) * GPB + threadIdx.x / G;
-    if (gk >= n_groups_call) return;
+    const int64_t sk = uniform64((int64_t)(blockIdx.x / (unsigned)n_slices) * (kBlock / kWave) +
+                                 (threadIdx.x >> 6));
+    if (sk >= n_spans) return;
     c0 += slice * PW;
     width -= slice * PW;
     if (width > PW) width = PW;
-    const int64_t k = k_first + gk;
-    const int64_t gs = k * kL;
+    const int64_t gs = (span_first + sk) * SPAN;
     const int64_t es = gs > e_begin ? gs : e_begin;
-    const int64_t ee = (gs + kL) < e_end ? (gs + kL) : e_end;
+    const int64_t ee = (gs + SPAN) < e_end ? (gs + SPAN) : e_end;
     if (es >= ee) return;
 
-    GroupState<VEC> st;
-    st.r = (gs < e_begin) ? row_begin : (int64_t)grp_row[k];
+    // row that holds the first entry of the span (uniform)
+    int64_t r = (gs < e_begin) ? row_begin : (int64_t)grp_row[gs / kGroupNnz];
+    r = uniform64(r);
     if (HAS_EMPTY) {
-        while (st.r + 1 < row_end && rowptr[st.r + 1] <= es) ++st.r;
+        while (r + 1 < row_end && rowptr[r + 1] <= es) ++r;
     }
-    st.head = es > rowptr[st.r];
-    st.pending = false;
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) st.acc[i] = 0.f;
-    const bool active = lg * VEC < width;
-    const int64_t coff = (int64_t)c0 + (int64_t)lg * VEC;
+    bool head = es > rowptr[r];  // the first completed piece belongs to a row begun earlier
+    bool pending = false;        // acc holds entries of a row whose end has not been seen
+    const bool active = lj * VEC < width;
+    const int64_t coff = (int64_t)c0 + (int64_t)lj * VEC;
     const int64_t coff_load = active ? coff : (int64_t)c0;  // idle lanes re-read column c0
-    float* my_part = partials + (size_t)gk * 2 * part_stride + (size_t)slice * PW + (size_t)lg * VEC;
+    float* const part = partials + (size_t)sk * 2 * part_stride + (size_t)slice * PW + (size_t)lj * VEC;
 
-    // chunks of this window that overlap [es, ee)
-    const int ch_begin = (int)((es - gs) / CHUNK);
-    const int ch_end = (int)((ee - gs + CHUNK - 1) / CHUNK);
-    // colf / val are padded to a whole number of windows, so staging loads stay in bounds
-    uint4 cc = *reinterpret_cast<const uint4*>(colf + gs + (int64_t)ch_begin * CHUNK + 4 * lg);
-    float4 vv = *reinterpret_cast<const float4*>(val + gs + (int64_t)ch_begin * CHUNK + 4 * lg);
-    uint32_t c[U];
-    float a[U];
-    typename F::Raw h[U];
+    float acc[VEC];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {  // prologue: first batch of the first chunk
-        c[u] = __shfl(comp(cc, u & 3), u >> 2, G);
-        a[u] = __shfl(comp(vv, u & 3), u >> 2, G);
-        h[u] = *F::ptr(H, (int64_t)(c[u] & ~kEndBit) * ldh + coff_load);
-    }
-    for (int ch = ch_begin; ch < ch_end; ++ch) {
-        const bool more = ch + 1 < ch_end;
-        uint4 ccn = cc;
-        float4 vvn = vv;
-        if (more) {
-            ccn = *reinterpret_cast<const uint4*>(colf + gs + (int64_t)(ch + 1) * CHUNK + 4 * lg);
-            vvn = *reinterpret_cast<const float4*>(val + gs + (int64_t)(ch + 1) * CHUNK + 4 * lg);
-        }
-        const int64_t cb = gs + (int64_t)ch * CHUNK;
-        const bool full = (cb >= es) && (cb + CHUNK <= ee);
-#pragma unroll 1
-        for (int jb = 0; jb < BPC; ++jb) {
-            const bool last = jb == BPC - 1;
-            const uint4 ncc = last ? ccn : cc;
-            const float4 nvv = last ? vvn : vv;
-            const int nj = last ? 0 : (jb + 1) * (U / 4);
-            const bool issue = !last || more;
-            const int64_t e = cb + (int64_t)jb * U;
-            if (full)
-                roll<G, DT, U, HAS_EMPTY, false>(c, a, h, ncc, nvv, nj, issue, e, es, ee, H, ldh,
-                                                 coff_load, Z, ldz, coff, active, my_part,
-                                                 part_stride, rowptr, row_end, st);
-            else
-                roll<G, DT, U, HAS_EMPTY, true>(c, a, h, ncc, nvv, nj, issue, e, es, ee, H, ldh,
-                                                coff_load, Z, ldz, coff, active, my_part,
-                                                part_stride, rowptr, row_end, st);
-        }
-        cc = ccn;
-        vv = vvn;
-    }
-    if (st.pending && active) {
+    for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+
+    // batches of this span that overlap [es, ee)
+    const int b0 = (int)((es - gs) / EPB);
+    const int b1 = (int)((ee - gs + EPB - 1) / EPB);
+
+    // Rolling pipeline over rounds of D batches; slot u of a round holds batch b + u.  The
+    // entries {column word, value} of a whole round are fetched with ONE coalesced 8-byte load
+    // per lane (lane l takes entry l of the round) two rounds ahead and handed to the lanes that
+    // need them with shuffles; the feature rows are gathered one round ahead.  cv is padded past
+    // nnz (zero entries: column 0, value 0, no mark), so nothing here needs a bounds check.
+    constexpr int RE = D * EPB;  // entries per round (<= 64)
+    static_assert(RE <= kWave, "a round's entries must fit one load per lane");
+    const uint2* const rcv = cv + gs + (lane < RE ? lane : 0);  // entry `lane` of round 0 of span
+    const int src_lane = sub;                                   // + u * EPB per slot
+    uint2 inext = rcv[(int64_t)b0 * EPB];        // entries of the round that starts at batch b0
+    uint32_t c[D];
+    float a[D];
+    typename F::Raw h[D];
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) my_part[part_stride + i] = st.acc[i];
+    for (int u = 0; u < D; ++u) {
+        c[u] = __shfl(inext.x, u * EPB + src_lane, kWave);
+        a[u] = __uint_as_float(__shfl(inext.y, u * EPB + src_lane, kWave));
+        h[u] = *F::ptr(H, (int64_t)(c[u] & kEntryColMask) * ldh + coff_load);
+    }
+    inext = rcv[(int64_t)(b0 + D) * EPB];        // round b0 + D
+
+    for (int b = b0; b < b1; b += D) {
+        const uint2 inext2 = rcv[(int64_t)(b + 2 * D) * EPB];  // two rounds ahead
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            const int bb = b + u;
+            if (bb >= b1) break;
+            float x[VEC];
+            F::widen(h[u], x);
+            uint32_t cu = c[u];
+            float au = a[u];
+            // refill the slot with batch bb + D
+            c[u] = __shfl(inext.x, u * EPB + src_lane, kWave);
+            a[u] = __uint_as_float(__shfl(inext.y, u * EPB + src_lane, kWave));
+            h[u] = *F::ptr(H, (int64_t)(c[u] & kEntryColMask) * ldh + coff_load);
+
+            const int64_t eb = gs + (int64_t)bb * EPB;  // first entry of the batch
+            if (eb < es || eb + EPB > ee) {             // batch straddles the range: mask lanes
+                const bool ok = (eb + sub >= es) && (eb + sub < ee);
+                if (!ok) {
+                    cu = 0;
+                    au = 0.f;
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) x[i] = 0.f;
+                }
+            }
+            uint64_t m = __ballot((int)cu < 0) & kLane0Mask;  // sub-groups whose entry ends a row
+            if (m == 0) {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[i] = fmaf(au, x[i], acc[i]);
+                pending = true;
+            } else {
+                int prev = -1;
+                while (m) {
+                    const int p = (int)(__ffsll((unsigned long long)m) - 1) / LPR;
+                    m &= m - 1;
+                    if (sub > prev && sub <= p) {
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) acc[i] = fmaf(au, x[i], acc[i]);
+                    }
+                    reduce_subgroups<LPR, VEC>(acc);
+                    if (sub == 0 && active) {
+                        if (head) {
+#pragma unroll
+                            for (int i = 0; i < VEC; ++i) part[i] = acc[i];
+                        } else {
+                            F::store(Z, r * ldz + coff, acc);
+                        }
+                    }
+                    head = false;
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+                    ++r;
+                    if (HAS_EMPTY) {
+                        while (r + 1 < row_end && rowptr[r + 1] <= eb + p + 1) ++r;
+                    }
+                    prev = p;
+                }
+                if (sub > prev) {
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) acc[i] = fmaf(au, x[i], acc[i]);
+                }
+                // entries after the last mark start a new row piece (only real ones count)
+                pending = (eb + prev + 1 < ee) && (prev + 1 < EPB);
+            }
+        }
+        inext = inext2;
+    }
+    if (pending) {
+        reduce_subgroups<LPR, VEC>(acc);
+        if (sub == 0 && active) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) part[part_stride + i] = acc[i];
+        }
     }
 }
 
-// One lane group per window boundary; the group whose boundary is the first one crossed by a
-// row adds that row's pieces in window order and writes the row.
-template <int G, int DT>
+// One lane group per span boundary; the group whose boundary is the first one crossed by a row
+// adds that row's pieces in span order and writes the row.
+template <int GF, int DT>
 __global__ __launch_bounds__(kBlock) void aggregate_fixup_kernel(
     const int64_t* __restrict__ rowptr, const uint32_t* __restrict__ grp_row,
     void* __restrict__ Z, int64_t ldz, int c0, int width, int64_t e_begin, int64_t e_end,
-    int64_t k_first, int64_t n_groups_call, const float* __restrict__ partials)
+    int64_t span, int64_t span_first, int64_t n_spans, const float* __restrict__ partials)
 {
     using F = Feat<DT>;
     constexpr int VEC = F::VEC;
-    constexpr int GPB = kBlock / G;
-    constexpr int PW = G * VEC;
-    const int lg = threadIdx.x % G;
-    const int64_t gk = (int64_t)blockIdx.x * GPB + threadIdx.x / G + 1;
-    if (gk >= n_groups_call) return;
-    const int64_t b = (k_first + gk) * kL;  // boundary between windows gk-1 and gk
+    constexpr int GPB = kBlock / GF;
+    constexpr int PS = GF * VEC;  // stride of a partial slot
+    const int lg = threadIdx.x % GF;
+    const int64_t sk = (int64_t)blockIdx.x * GPB + threadIdx.x / GF + 1;
+    if (sk >= n_spans) return;
+    const int64_t b = (span_first + sk) * span;  // boundary between spans sk-1 and sk
     if (b <= e_begin || b >= e_end) return;
-    const int64_t r = grp_row[k_first + gk];
+    const int64_t r = grp_row[b / kGroupNnz];
     const int64_t rs = rowptr[r];
-    if (rs >= b) return;                  // a row starts exactly here: nothing crosses
-    if ((rs / kL + 1) * kL != b) return;  // not the first boundary this row crosses
+    if (rs >= b) return;                    // a row starts exactly here: nothing crosses
+    if ((rs / span + 1) * span != b) return;  // not the first boundary this row crosses
     if (lg * VEC >= width) return;
     const int64_t re = rowptr[r + 1];
     float acc[VEC];
-    const float* p = partials + (size_t)(gk - 1) * 2 * PW + PW + (size_t)lg * VEC;  // tail
+    const float* p = partials + (size_t)(sk - 1) * 2 * PS + PS + (size_t)lg * VEC;  // tail
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] = p[i];
-    int64_t kk = gk;
-    while ((k_first + kk + 1) * kL < re) {  // windows that lie wholly inside the row
-        p = partials + (size_t)kk * 2 * PW + PW + (size_t)lg * VEC;
+    int64_t kk = sk;
+    while ((span_first + kk + 1) * span < re) {  // spans that lie wholly inside the row
+        p = partials + (size_t)kk * 2 * PS + PS + (size_t)lg * VEC;
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[i] += p[i];
         ++kk;
     }
-    p = partials + (size_t)kk * 2 * PW + (size_t)lg * VEC;  // head of the window where it ends
+    p = partials + (size_t)kk * 2 * PS + (size_t)lg * VEC;  // head of the span where it ends
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] += p[i];
     F::store(Z, r * ldz + (int64_t)c0 + (int64_t)lg * VEC, acc);
@@ -306,71 +315,58 @@ __global__ __launch_bounds__(kBlock) void zero_rows_kernel(void* Z, int64_t ldz,
     else reinterpret_cast<uint16_t*>(Z)[r * ldz + c] = 0;
 }
 
-// Row loads a lane group keeps in flight (8 or 16); MIXGCN_AGG_BATCH overrides for experiments.
-int batch_entries()
-{
-    static const int v = [] {
-        const char* e = getenv("MIXGCN_AGG_BATCH");
-        const int x = e ? atoi(e) : 8;
-        return x == 16 ? 16 : 8;
-    }();
-    return v;
-}
+template <int LPR>
+constexpr int64_t span_entries() { return (int64_t)kBatchesPerSpan * (kWave / LPR); }
 
-template <int G, int DT>
+template <int LPR, int DT>
 int launch_main(const Csr& m, const void* H, int64_t ldh, void* Z, int64_t ldz, int c0, int width,
                 int64_t r0, int64_t r1, int64_t e0, int64_t e1, float* partials, int part_stride,
                 hipStream_t s, Timer* timer)
 {
-    constexpr int GPB = kBlock / G;
-    constexpr int PW = G * Feat<DT>::VEC;
+    constexpr int PW = LPR * Feat<DT>::VEC;
+    constexpr int64_t SPAN = span_entries<LPR>();
     // timed by the width class of the whole pass (lanes that would span it), not of a slice
     const int gf = part_stride / Feat<DT>::VEC;
     const int kind = gf == 4 ? kTimeAggG4 : gf == 8 ? kTimeAggG8 : gf == 16 ? kTimeAggG16
                      : gf == 32 ? kTimeAggG32 : kTimeAggG64;
     const int n_slices = (int)ceil_div(width, PW);
-    const int64_t k_first = e0 / kL;
-    const int64_t n_groups = ceil_div(e1, kL) - k_first;
-    const int64_t grid64 = ceil_div(n_groups, GPB) * n_slices;
+    const int64_t span_first = e0 / SPAN;
+    const int64_t n_spans = ceil_div(e1, SPAN) - span_first;
+    const int64_t grid64 = ceil_div(n_spans, kBlock / kWave) * n_slices;
     if (grid64 > 0x7FFFFFFF) return fail(MIXGCN_EINVAL, "aggregate: grid too large");
     const unsigned grid = (unsigned)grid64;
     if (timer) MIXGCN_TRY(timer->begin(kind, s));
-#define MIXGCN_AGG_LAUNCH(UU, EMPTY)                                                              \
-    hipLaunchKernelGGL((aggregate_kernel<G, DT, UU, EMPTY>), dim3(grid), dim3(kBlock), 0, s,       \
-                       m.rowptr, m.colf, m.val, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0,  \
-                       e1, k_first, n_groups, partials, n_slices, part_stride)
-    if (batch_entries() == 16) {
-        if (m.has_empty_rows) MIXGCN_AGG_LAUNCH(16, true);
-        else MIXGCN_AGG_LAUNCH(16, false);
-    } else {
-        if (m.has_empty_rows) MIXGCN_AGG_LAUNCH(8, true);
-        else MIXGCN_AGG_LAUNCH(8, false);
-    }
-#undef MIXGCN_AGG_LAUNCH
+    if (m.has_empty_rows)
+        hipLaunchKernelGGL((aggregate_kernel<LPR, DT, true>), dim3(grid), dim3(kBlock), 0, s,
+                           m.rowptr, m.cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,
+                           span_first, n_spans, partials, n_slices, part_stride);
+    else
+        hipLaunchKernelGGL((aggregate_kernel<LPR, DT, false>), dim3(grid), dim3(kBlock), 0, s,
+                           m.rowptr, m.cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,
+                           span_first, n_spans, partials, n_slices, part_stride);
     if (timer) MIXGCN_TRY(timer->end(s));
     return MIXGCN_OK;
 }
 
 template <int GF, int DT>
 int launch_fixup(const Csr& m, void* Z, int64_t ldz, int c0, int width, int64_t e0, int64_t e1,
-                 const float* partials, hipStream_t s)
+                 int64_t span, const float* partials, hipStream_t s)
 {
     constexpr int GPB = kBlock / GF;
-    const int64_t k_first = e0 / kL;
-    const int64_t n_groups = ceil_div(e1, kL) - k_first;
-    if (n_groups > 1) {
-        const unsigned fgrid = (unsigned)ceil_div(n_groups - 1, GPB);
+    const int64_t span_first = e0 / span;
+    const int64_t n_spans = ceil_div(e1, span) - span_first;
+    if (n_spans > 1) {
+        const unsigned fgrid = (unsigned)ceil_div(n_spans - 1, GPB);
         hipLaunchKernelGGL((aggregate_fixup_kernel<GF, DT>), dim3(fgrid), dim3(kBlock), 0, s,
-                           m.rowptr, m.grp_row, Z, ldz, c0, width, e0, e1, k_first, n_groups,
-                           partials);
+                           m.rowptr, m.grp_row, Z, ldz, c0, width, e0, e1, span, span_first,
+                           n_spans, partials);
     }
     return MIXGCN_OK;
 }
 
-// Lanes per group of the main kernel (columns per slice = lanes * 4 fp32 or * 8 bf16).
-// 8 lanes = 128 bytes of every gathered row = one cache line.  MIXGCN_AGG_GROUP overrides it
-// (4, 8, 16, 32 or 64) for experiments.
-int slice_group_lanes()
+// Lanes per slice of the main kernel (columns per slice = lanes * 4 fp32 or * 8 bf16).
+// MIXGCN_AGG_GROUP overrides it (4, 8, 16, 32 or 64) for experiments.
+int slice_lanes()
 {
     static const int v = [] {
         const char* e = getenv("MIXGCN_AGG_GROUP");
@@ -386,7 +382,7 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, v
               Timer* timer)
 {
     constexpr int VEC = Feat<DT>::VEC;
-    constexpr int kMaxTile = 64 * VEC;  // widest slice one pass can hold
+    constexpr int kMaxTile = 64 * VEC;  // widest pass
     if (m.has_empty_rows) {
         const int64_t cells = (r1 - r0) * (int64_t)(c1 - c0);
         hipLaunchKernelGGL((zero_rows_kernel<DT>), dim3((unsigned)ceil_div(cells, kBlock)),
@@ -394,12 +390,15 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, v
     }
     const int64_t e0 = m.h_rowptr[(size_t)r0], e1 = m.h_rowptr[(size_t)r1];
     if (e1 <= e0) return MIXGCN_OK;
-    const int64_t n_groups = ceil_div(e1, kL) - e0 / kL;
-    // scratch for the row pieces: sized for the widest pass of this call
+    // scratch for the row pieces: sized for the widest pass and the shortest span of this call
     const int wmax = (c1 - c0) < kMaxTile ? (c1 - c0) : kMaxTile;
     int gmax = 4;
     while (gmax * VEC < wmax) gmax *= 2;
-    const size_t need = (size_t)n_groups * 2 * gmax * VEC * sizeof(float);
+    int lpr_min = slice_lanes();
+    if (lpr_min > gmax) lpr_min = gmax;
+    const int64_t span_min = (int64_t)kBatchesPerSpan * (kWave / lpr_min);
+    const int64_t max_spans = ceil_div(e1, span_min) - e0 / span_min;
+    const size_t need = (size_t)max_spans * 2 * gmax * VEC * sizeof(float);
     if (need > g->partials_bytes) {
         // growing the scratch waits for earlier work that may still read the old one
         MIXGCN_HIP_TRY(hipDeviceSynchronize());
@@ -414,14 +413,15 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, v
         const int w = (c1 - cb) < kMaxTile ? (c1 - cb) : kMaxTile;
         int GF = 4;  // lanes that span the whole pass: fix-up group and partial-slot stride
         while (GF * VEC < w) GF *= 2;
-        int G = slice_group_lanes();
-        if (G > GF) G = GF;
+        int LPR = slice_lanes();
+        if (LPR > GF) LPR = GF;
         const int ps = GF * VEC;
+        const int64_t span = (int64_t)kBatchesPerSpan * (kWave / LPR);
         float* P = g->partials;
-#define MIXGCN_AGG_MAIN(GG) \
-    MIXGCN_TRY((launch_main<GG, DT>(m, H, ldh, Z, ldz, cb, w, r0, r1, e0, e1, P, ps, s, timer)))
-#define MIXGCN_AGG_FIX(GG) MIXGCN_TRY((launch_fixup<GG, DT>(m, Z, ldz, cb, w, e0, e1, P, s)))
-        switch (G) {
+#define MIXGCN_AGG_MAIN(L) \
+    MIXGCN_TRY((launch_main<L, DT>(m, H, ldh, Z, ldz, cb, w, r0, r1, e0, e1, P, ps, s, timer)))
+#define MIXGCN_AGG_FIX(GG) MIXGCN_TRY((launch_fixup<GG, DT>(m, Z, ldz, cb, w, e0, e1, span, P, s)))
+        switch (LPR) {
         case 4: MIXGCN_AGG_MAIN(4); break;
         case 8: MIXGCN_AGG_MAIN(8); break;
         case 16: MIXGCN_AGG_MAIN(16); break;
