@@ -90,8 +90,15 @@ typedef struct mixgcn_layer_desc {
     int32_t dtype;    /* MIXGCN_F32 or MIXGCN_BF16 (storage of H, Z, Hout, G, dH) */
     int32_t relu;     /* 1: Hout = relu(Z W); 0: Hout = Z W (last layer) */
     int32_t n_chunks; /* row chunks of the fine-grain pipeline; 1 = no overlap */
-    int32_t reserved;
+    int32_t order;    /* MIXGCN_AGG_FIRST (Algorithm 2) or MIXGCN_UPDATE_FIRST */
 } mixgcn_layer_desc;
+
+/*
+ * Eq. 3 is associative: sigma((A_hat H) W) = sigma(A_hat (H W)).  Algorithm 2 aggregates first;
+ * when a layer narrows (f_out < f_in) updating first makes the aggregation f_in / f_out times
+ * cheaper.  Both orders give the same result up to rounding.
+ */
+enum { MIXGCN_AGG_FIRST = 0, MIXGCN_UPDATE_FIRST = 1 };
 
 /*
  * Sec. 2.1: A_tilde = A + I for a binary adjacency A.  Builds the sorted CSR of A_tilde from a
@@ -141,9 +148,12 @@ int mixgcn_update(int op, int dtype, const void* A, int64_t lda, const void* B, 
                   const void* relu_ref, int64_t ldr, float beta, void* stream);
 
 /*
- * One layer forward, Eq. 3 in the order of Algorithm 2:  Z = A_hat H;  Hout = sigma(Z W),
- * run as d->n_chunks row chunks with the aggregation of chunk k overlapping the update of
- * chunk k-1 on the pipeline's two streams (Sec. 3.2.2).  Z is kept for the backward pass.
+ * One layer forward, Eq. 3.
+ *   MIXGCN_AGG_FIRST (order of Algorithm 2):  Z = A_hat H [n x f_in];  Hout = sigma(Z W), run as
+ *     d->n_chunks row chunks with the aggregation of chunk k overlapping the update of chunk
+ *     k-1 on the pipeline's two streams (Sec. 3.2.2).  Z is kept for the backward pass.
+ *   MIXGCN_UPDATE_FIRST:  Z = H W [n x f_out, ld_z >= f_out] (workspace);  Hout = sigma(A_hat Z).
+ *     The backward pass needs H instead of Z.
  * On return the work is enqueued; the pipeline's primary stream is ordered after all of it.
  */
 int mixgcn_layer_fwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, const void* H,
@@ -151,12 +161,16 @@ int mixgcn_layer_fwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, const vo
 
 /*
  * One layer backward.  With dP = G (.) 1[Hout > 0] (d->relu) or dP = G:
- *   dW = Z^T dP;   dZ = dP W^T;   dH = A_hat^T dZ.
- * G may be overwritten.  dZ is written over Z.  dH == NULL skips dZ and dH (first layer when no
- * input gradient is wanted).  dW is fp32 [f_in x f_out] with leading dimension d->ld_w.
+ *   MIXGCN_AGG_FIRST:     dW = Z^T dP;   dZ = dP W^T (written over Z);   dH = A_hat^T dZ.
+ *                         H is not read (may be NULL).
+ *   MIXGCN_UPDATE_FIRST:  dQ = A_hat^T dP [n x f_out] (written to the workspace Z);
+ *                         dW = H^T dQ;   dH = dQ W^T.  H is the layer's input [n x f_in, ld_h].
+ * G may be overwritten.  dH == NULL skips the input gradient (first layer when none is wanted).
+ * dW is fp32 [f_in x f_out] with leading dimension d->ld_w.
  */
-int mixgcn_layer_bwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, void* Z, const void* Hout,
-                     const float* W, void* G, float* dW, void* dH, mixgcn_pipeline* p);
+int mixgcn_layer_bwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, const void* H, void* Z,
+                     const void* Hout, const float* W, void* G, float* dW, void* dH,
+                     mixgcn_pipeline* p);
 
 /*
  * Loss glue (Algorithm 2, loss line): mean softmax cross-entropy over n nodes and its gradient

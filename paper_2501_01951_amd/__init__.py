@@ -5,7 +5,7 @@ is computed in Python: the wrappers only marshal pointers, sizes and streams.  t
 for device memory and streams.  There is no CPU fallback: a missing library is an error.
 """
 from .binding import (  # noqa: F401
-    BF16, F32, OP_DGRAD, OP_FWD, OP_FWD_RELU, OP_WGRAD, SYMMETRIZE, ADD_SELF_LOOPS,
+    AGG_FIRST, UPDATE_FIRST, BF16, F32, OP_DGRAD, OP_FWD, OP_FWD_RELU, OP_WGRAD, SYMMETRIZE, ADD_SELF_LOOPS,
     BUILD_TRANSPOSE, INPUT_ON_HOST, Graph, LayerDesc, MixGCNError, Pipeline, aggregate, build_csr,
     layer_bwd, layer_fwd, lib_path, load_library, normalize, softmax_xent, update, version,
 )

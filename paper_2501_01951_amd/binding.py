@@ -13,6 +13,7 @@ _lib = None
 F32, BF16 = 0, 1
 OP_FWD, OP_FWD_RELU, OP_DGRAD, OP_WGRAD = 0, 1, 2, 3
 SYMMETRIZE, ADD_SELF_LOOPS, BUILD_TRANSPOSE, INPUT_ON_HOST = 1, 2, 4, 8
+AGG_FIRST, UPDATE_FIRST = 0, 1
 
 
 class MixGCNError(RuntimeError):
@@ -38,7 +39,7 @@ class LayerDesc(ctypes.Structure):
         ("f_in", ctypes.c_int32), ("f_out", ctypes.c_int32), ("ld_h", ctypes.c_int64),
         ("ld_z", ctypes.c_int64), ("ld_out", ctypes.c_int64), ("ld_w", ctypes.c_int64),
         ("dtype", ctypes.c_int32), ("relu", ctypes.c_int32), ("n_chunks", ctypes.c_int32),
-        ("reserved", ctypes.c_int32),
+        ("order", ctypes.c_int32),
     ]
 
 
@@ -69,7 +70,7 @@ def load_library():
     lib.mixgcn_update.argtypes = [ctypes.c_int, ctypes.c_int, vp, i64, vp, i64, vp, i64, i64, i32,
                                   i32, vp, i64, f32, vp]
     lib.mixgcn_layer_fwd.argtypes = [vp, ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp]
-    lib.mixgcn_layer_bwd.argtypes = [vp, ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp]
+    lib.mixgcn_layer_bwd.argtypes = [vp, ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp, vp]
     lib.mixgcn_softmax_xent.argtypes = [vp, i64, vp, i64, i32, vp, i64, vp, vp]
     lib.mixgcn_graph_info.argtypes = [vp, ctypes.POINTER(_GraphView)]
     lib.mixgcn_graph_free.argtypes = [vp]
@@ -257,27 +258,33 @@ def update(op: int, A, B, C, n_rows: int, k: int, m: int, relu_ref=None, beta: f
                                         _stream(stream)), "update")
 
 
-def _desc(H_like_in, Z, Hout_like, W, relu: bool, n_chunks: int) -> LayerDesc:
+def _desc(H_like_in, Z, Hout_like, W, relu: bool, n_chunks: int, order: int) -> LayerDesc:
     d = LayerDesc()
     d.f_in, d.f_out = W.shape[0], W.shape[1]
     d.ld_h, d.ld_z, d.ld_out, d.ld_w = _ld(H_like_in), _ld(Z), _ld(Hout_like), _ld(W)
     d.dtype = _dtype_of(Z)
     d.relu = int(relu)
     d.n_chunks = n_chunks
+    d.order = order
     return d
 
 
-def layer_fwd(g: Graph, H, W, Z, Hout, pipe: Pipeline, relu: bool = True, n_chunks: int = 1) -> None:
-    d = _desc(H, Z, Hout, W, relu, n_chunks)
+def layer_fwd(g: Graph, H, W, Z, Hout, pipe: Pipeline, relu: bool = True, n_chunks: int = 1,
+              order: int = AGG_FIRST) -> None:
+    """Z: n x f_in (kept for backward) with AGG_FIRST; n x f_out workspace with UPDATE_FIRST."""
+    d = _desc(H, Z, Hout, W, relu, n_chunks, order)
     _check(load_library().mixgcn_layer_fwd(g._h, ctypes.byref(d), _ptr(H), _ptr(W), _ptr(Z),
                                            _ptr(Hout), pipe._h), "layer_fwd")
 
 
 def layer_bwd(g: Graph, Z, Hout, W, G, dW, dH, pipe: Pipeline, relu: bool = True,
-              n_chunks: int = 1) -> None:
-    d = _desc(dH if dH is not None else Z, Z, G, W, relu, n_chunks)
-    _check(load_library().mixgcn_layer_bwd(g._h, ctypes.byref(d), _ptr(Z), _ptr(Hout), _ptr(W),
-                                           _ptr(G), _ptr(dW), _ptr(dH), pipe._h), "layer_bwd")
+              n_chunks: int = 1, order: int = AGG_FIRST, H=None) -> None:
+    """H (the layer input) is needed only with UPDATE_FIRST."""
+    h_like = dH if dH is not None else (H if H is not None else Z)
+    d = _desc(h_like, Z, G, W, relu, n_chunks, order)
+    _check(load_library().mixgcn_layer_bwd(g._h, ctypes.byref(d), _ptr(H), _ptr(Z), _ptr(Hout),
+                                           _ptr(W), _ptr(G), _ptr(dW), _ptr(dH), pipe._h),
+           "layer_bwd")
 
 
 def softmax_xent(logits, labels, dlogits, loss, stream=None) -> None:

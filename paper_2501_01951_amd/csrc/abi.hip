@@ -224,7 +224,8 @@ int mixgcn_graph_info(const mixgcn_graph* g, mixgcn_graph_view* out)
 
 static int aggregate_impl(const mixgcn_graph* g, int transpose, int dtype, const void* H,
                           int64_t ldh, void* Z, int64_t ldz, int32_t col_begin, int32_t col_end,
-                          int64_t row_begin, int64_t row_end, hipStream_t stream, Timer* timer)
+                          int64_t row_begin, int64_t row_end, int relu, hipStream_t stream,
+                          Timer* timer)
 {
     if (!g) return fail(MIXGCN_EINVAL, "aggregate: graph is null");
     if (!g->normalized) return fail(MIXGCN_ESTATE, "aggregate: call mixgcn_normalize first");
@@ -257,7 +258,7 @@ static int aggregate_impl(const mixgcn_graph* g, int transpose, int dtype, const
     }
     if (row_end == row_begin || col_end == col_begin) return MIXGCN_OK;
     return launch_aggregate(g, *m, dtype, H, ldh, Z, ldz, col_begin, col_end, row_begin, row_end,
-                            stream, timer);
+                            relu, stream, timer);
 }
 
 int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void* H, int64_t ldh,
@@ -265,7 +266,7 @@ int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void
                      int64_t row_end, void* stream)
 {
     return aggregate_impl(g, transpose, dtype, H, ldh, Z, ldz, col_begin, col_end, row_begin,
-                          row_end, (hipStream_t)stream, nullptr);
+                          row_end, 0, (hipStream_t)stream, nullptr);
 }
 
 static int update_impl(int op, int dtype, const void* A, int64_t lda, const void* B, int64_t ldb,
@@ -409,6 +410,8 @@ int check_layer(const char* who, const mixgcn_graph* g, const mixgcn_layer_desc*
         return fail(MIXGCN_EINVAL, std::string(who) + ": bad layer sizes");
     if (d->dtype != MIXGCN_F32 && d->dtype != MIXGCN_BF16)
         return fail(MIXGCN_EINVAL, std::string(who) + ": dtype");
+    if (d->order != MIXGCN_AGG_FIRST && d->order != MIXGCN_UPDATE_FIRST)
+        return fail(MIXGCN_EINVAL, std::string(who) + ": order");
     return MIXGCN_OK;
 }
 
@@ -426,8 +429,15 @@ int mixgcn_layer_fwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, const vo
     const int op = d->relu ? MIXGCN_OP_FWD_RELU : MIXGCN_OP_FWD;
     const int nc = d->n_chunks;
     Timer* tm = p->timer.enabled ? &p->timer : nullptr;
+    if (d->order == MIXGCN_UPDATE_FIRST) {
+        // Z = H W on the dense stream, then Hout = sigma(A_hat Z): the gather needs all of Z
+        MIXGCN_TRY(update_impl(MIXGCN_OP_FWD, d->dtype, H, d->ld_h, W, d->ld_w, Z, d->ld_z, n,
+                               d->f_in, d->f_out, nullptr, 0, 0.f, p->primary, tm));
+        return aggregate_impl(g, 0, d->dtype, Z, d->ld_z, Hout, d->ld_out, 0, d->f_out, 0, n,
+                              d->relu, p->primary, tm);
+    }
     if (nc == 1 || p->secondary == p->primary) {
-        MIXGCN_TRY(aggregate_impl(g, 0, d->dtype, H, d->ld_h, Z, d->ld_z, 0, d->f_in, 0, n,
+        MIXGCN_TRY(aggregate_impl(g, 0, d->dtype, H, d->ld_h, Z, d->ld_z, 0, d->f_in, 0, n, 0,
                                   p->primary, tm));
         return update_impl(op, d->dtype, Z, d->ld_z, W, d->ld_w, Hout, d->ld_out, n, d->f_in,
                            d->f_out, nullptr, 0, 0.f, p->primary, tm);
@@ -439,7 +449,7 @@ int mixgcn_layer_fwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, const vo
     for (int c = 0; c < nc; ++c) {
         const int64_t r0 = chunk_bound(n, nc, c), r1 = chunk_bound(n, nc, c + 1);
         if (r1 <= r0) continue;
-        MIXGCN_TRY(aggregate_impl(g, 0, d->dtype, H, d->ld_h, Z, d->ld_z, 0, d->f_in, r0, r1,
+        MIXGCN_TRY(aggregate_impl(g, 0, d->dtype, H, d->ld_h, Z, d->ld_z, 0, d->f_in, r0, r1, 0,
                                   p->primary, tm));
         MIXGCN_HIP_TRY(hipEventRecord(p->events[(size_t)c], p->primary));
         MIXGCN_HIP_TRY(hipStreamWaitEvent(p->secondary, p->events[(size_t)c], 0));
@@ -453,17 +463,32 @@ int mixgcn_layer_fwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, const vo
     return MIXGCN_OK;
 }
 
-int mixgcn_layer_bwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, void* Z, const void* Hout,
-                     const float* W, void* G, float* dW, void* dH, mixgcn_pipeline* p)
+int mixgcn_layer_bwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, const void* H, void* Z,
+                     const void* Hout, const float* W, void* G, float* dW, void* dH,
+                     mixgcn_pipeline* p)
 {
     MIXGCN_TRY(check_layer("layer_bwd", g, d, p));
     if (!Z || !W || !G || !dW) return fail(MIXGCN_EINVAL, "layer_bwd: null tensor");
     if (d->relu && !Hout) return fail(MIXGCN_EINVAL, "layer_bwd: relu layer needs Hout");
     const int64_t n = g->n;
     const void* R = d->relu ? Hout : nullptr;
+    Timer* tm = p->timer.enabled ? &p->timer : nullptr;
+    if (d->order == MIXGCN_UPDATE_FIRST) {
+        if (!H) return fail(MIXGCN_EINVAL, "layer_bwd: update-first layer needs H");
+        if (R) MIXGCN_TRY(launch_relu_mask(d->dtype, G, d->ld_out, R, d->ld_out, n, d->f_out,
+                                           p->primary));
+        // dQ = A_hat^T dP into the workspace, then the two dense products
+        MIXGCN_TRY(aggregate_impl(g, 1, d->dtype, G, d->ld_out, Z, d->ld_z, 0, d->f_out, 0, n, 0,
+                                  p->primary, tm));
+        MIXGCN_TRY(update_impl(MIXGCN_OP_WGRAD, d->dtype, H, d->ld_h, Z, d->ld_z, dW, d->ld_w, n,
+                               d->f_in, d->f_out, nullptr, 0, 0.f, p->primary, tm));
+        if (dH)
+            MIXGCN_TRY(update_impl(MIXGCN_OP_DGRAD, d->dtype, Z, d->ld_z, W, d->ld_w, dH, d->ld_h, n,
+                                   d->f_in, d->f_out, nullptr, 0, 0.f, p->primary, tm));
+        return MIXGCN_OK;
+    }
     const bool two = p->secondary != p->primary && d->n_chunks > 1;
     hipStream_t dense = two ? p->secondary : p->primary;
-    Timer* tm = p->timer.enabled ? &p->timer : nullptr;
     if (two) {
         MIXGCN_HIP_TRY(hipEventRecord(p->ev_start, p->primary));
         MIXGCN_HIP_TRY(hipStreamWaitEvent(p->secondary, p->ev_start, 0));
@@ -478,7 +503,7 @@ int mixgcn_layer_bwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, void* Z,
             MIXGCN_HIP_TRY(hipEventRecord(p->ev_done, p->secondary));
             MIXGCN_HIP_TRY(hipStreamWaitEvent(p->primary, p->ev_done, 0));
         }
-        MIXGCN_TRY(aggregate_impl(g, 1, d->dtype, Z, d->ld_z, dH, d->ld_h, 0, d->f_in, 0, n,
+        MIXGCN_TRY(aggregate_impl(g, 1, d->dtype, Z, d->ld_z, dH, d->ld_h, 0, d->f_in, 0, n, 0,
                                   p->primary, tm));
     } else if (two) {
         MIXGCN_HIP_TRY(hipEventRecord(p->ev_done, p->secondary));

@@ -294,6 +294,24 @@ __global__ __launch_bounds__(kBlock) void wgrad_reduce_kernel(const float* __res
     *o = (float)(beta != 0.f ? (double)beta * (double)*o + s : s);
 }
 
+// G <- G (.) 1[R > 0], four elements per thread.
+__global__ __launch_bounds__(kBlock) void relu_mask_kernel(float* __restrict__ G, int64_t ldg,
+                                                           const float* __restrict__ R,
+                                                           int64_t ldr, int64_t n, int m4)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n * m4) return;
+    const int64_t r = i / m4;
+    const int c = (int)(i % m4) * 4;
+    float4 g = *reinterpret_cast<float4*>(G + r * ldg + c);
+    const float4 h = *reinterpret_cast<const float4*>(R + r * ldr + c);
+    g.x = h.x > 0.f ? g.x : 0.f;
+    g.y = h.y > 0.f ? g.y : 0.f;
+    g.z = h.z > 0.f ? g.z : 0.f;
+    g.w = h.w > 0.f ? g.w : 0.f;
+    *reinterpret_cast<float4*>(G + r * ldg + c) = g;
+}
+
 template <class S, bool B_TRANS>
 int launch_rowblock(bool relu, const float* A, int64_t lda, const float* B, int64_t ldb, float* C,
                     int64_t ldc, int64_t n, int KD, int MD, const float* R, int64_t ldr,
@@ -313,6 +331,20 @@ int launch_rowblock(bool relu, const float* A, int64_t lda, const float* B, int6
 }
 
 }  // namespace
+
+int launch_relu_mask(int dtype, void* G, int64_t ldg, const void* R, int64_t ldr, int64_t n,
+                     int32_t m, hipStream_t s)
+{
+    if (dtype != MIXGCN_F32)
+        return fail(MIXGCN_EUNSUPPORTED, "relu mask: bf16 storage not built yet");
+    const int m4 = (m + 3) / 4;  // rows are padded to 16 bytes, so the last vector is in bounds
+    const int64_t total = n * m4;
+    if (total == 0) return MIXGCN_OK;
+    hipLaunchKernelGGL(relu_mask_kernel, dim3((unsigned)ceil_div(total, kBlock)), dim3(kBlock), 0,
+                       s, (float*)G, ldg, (const float*)R, ldr, n, m4);
+    MIXGCN_HIP_TRY(hipGetLastError());
+    return MIXGCN_OK;
+}
 
 int launch_update(int op, int dtype, const void* A_, int64_t lda, const float* B, int64_t ldb,
                   void* C_, int64_t ldc, int64_t n, int32_t k, int32_t m, const void* R_,

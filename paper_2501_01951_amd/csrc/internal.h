@@ -139,7 +139,11 @@ int normalize_sym(mixgcn_graph* g, hipStream_t s);
 
 int launch_aggregate(const mixgcn_graph* g, const Csr& m, int dtype, const void* H, int64_t ldh,
                      void* Z, int64_t ldz, int32_t c0, int32_t c1, int64_t r0, int64_t r1,
-                     hipStream_t s, Timer* timer);
+                     int relu, hipStream_t s, Timer* timer);
+
+// G <- G (.) 1[R > 0] in place (ReLU derivative taken from the stored activation R).
+int launch_relu_mask(int dtype, void* G, int64_t ldg, const void* R, int64_t ldr, int64_t n,
+                     int32_t m, hipStream_t s);
 
 int launch_update(int op, int dtype, const void* A, int64_t lda, const float* B, int64_t ldb,
                   void* C, int64_t ldc, int64_t n, int32_t k, int32_t m, const void* R,

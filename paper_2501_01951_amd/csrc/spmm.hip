@@ -116,7 +116,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
     const uint32_t* __restrict__ grp_row, const void* __restrict__ H, int64_t ldh,
     void* __restrict__ Z, int64_t ldz, int c0, int width, int64_t row_begin, int64_t row_end,
     int64_t e_begin, int64_t e_end, int64_t span_first, int64_t n_spans,
-    float* __restrict__ partials, int n_slices, int part_stride)
+    float* __restrict__ partials, int n_slices, int part_stride, int relu)
 {
     using F = Feat<DT>;
     constexpr int VEC = F::VEC;
@@ -231,6 +231,10 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
 #pragma unroll
                             for (int i = 0; i < VEC; ++i) part[i] = acc[i];
                         } else {
+                            if (relu) {
+#pragma unroll
+                                for (int i = 0; i < VEC; ++i) acc[i] = fmaxf(acc[i], 0.f);
+                            }
                             F::store(Z, r * ldz + coff, acc);
                         }
                     }
@@ -268,7 +272,8 @@ template <int GF, int DT>
 __global__ __launch_bounds__(kBlock) void aggregate_fixup_kernel(
     const int64_t* __restrict__ rowptr, const uint32_t* __restrict__ grp_row,
     void* __restrict__ Z, int64_t ldz, int c0, int width, int64_t e_begin, int64_t e_end,
-    int64_t span, int64_t span_first, int64_t n_spans, const float* __restrict__ partials)
+    int64_t span, int64_t span_first, int64_t n_spans, const float* __restrict__ partials,
+    int relu)
 {
     using F = Feat<DT>;
     constexpr int VEC = F::VEC;
@@ -299,6 +304,10 @@ __global__ __launch_bounds__(kBlock) void aggregate_fixup_kernel(
     p = partials + (size_t)kk * 2 * PS + (size_t)lg * VEC;  // head of the span where it ends
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] += p[i];
+    if (relu) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = fmaxf(acc[i], 0.f);
+    }
     F::store(Z, r * ldz + (int64_t)c0 + (int64_t)lg * VEC, acc);
 }
 
@@ -321,7 +330,7 @@ constexpr int64_t span_entries() { return (int64_t)kBatchesPerSpan * (kWave / LP
 template <int LPR, int DT>
 int launch_main(const Csr& m, const void* H, int64_t ldh, void* Z, int64_t ldz, int c0, int width,
                 int64_t r0, int64_t r1, int64_t e0, int64_t e1, float* partials, int part_stride,
-                hipStream_t s, Timer* timer)
+                int relu, hipStream_t s, Timer* timer)
 {
     constexpr int PW = LPR * Feat<DT>::VEC;
     constexpr int64_t SPAN = span_entries<LPR>();
@@ -339,18 +348,18 @@ int launch_main(const Csr& m, const void* H, int64_t ldh, void* Z, int64_t ldz, 
     if (m.has_empty_rows)
         hipLaunchKernelGGL((aggregate_kernel<LPR, DT, true>), dim3(grid), dim3(kBlock), 0, s,
                            m.rowptr, m.cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,
-                           span_first, n_spans, partials, n_slices, part_stride);
+                           span_first, n_spans, partials, n_slices, part_stride, relu);
     else
         hipLaunchKernelGGL((aggregate_kernel<LPR, DT, false>), dim3(grid), dim3(kBlock), 0, s,
                            m.rowptr, m.cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,
-                           span_first, n_spans, partials, n_slices, part_stride);
+                           span_first, n_spans, partials, n_slices, part_stride, relu);
     if (timer) MIXGCN_TRY(timer->end(s));
     return MIXGCN_OK;
 }
 
 template <int GF, int DT>
 int launch_fixup(const Csr& m, void* Z, int64_t ldz, int c0, int width, int64_t e0, int64_t e1,
-                 int64_t span, const float* partials, hipStream_t s)
+                 int64_t span, const float* partials, int relu, hipStream_t s)
 {
     constexpr int GPB = kBlock / GF;
     const int64_t span_first = e0 / span;
@@ -359,7 +368,7 @@ int launch_fixup(const Csr& m, void* Z, int64_t ldz, int c0, int width, int64_t 
         const unsigned fgrid = (unsigned)ceil_div(n_spans - 1, GPB);
         hipLaunchKernelGGL((aggregate_fixup_kernel<GF, DT>), dim3(fgrid), dim3(kBlock), 0, s,
                            m.rowptr, m.grp_row, Z, ldz, c0, width, e0, e1, span, span_first,
-                           n_spans, partials);
+                           n_spans, partials, relu);
     }
     return MIXGCN_OK;
 }
@@ -378,8 +387,8 @@ int slice_lanes()
 
 template <int DT>
 int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, void* Z,
-              int64_t ldz, int32_t c0, int32_t c1, int64_t r0, int64_t r1, hipStream_t s,
-              Timer* timer)
+              int64_t ldz, int32_t c0, int32_t c1, int64_t r0, int64_t r1, int relu,
+              hipStream_t s, Timer* timer)
 {
     constexpr int VEC = Feat<DT>::VEC;
     constexpr int kMaxTile = 64 * VEC;  // widest pass
@@ -419,8 +428,9 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, v
         const int64_t span = (int64_t)kBatchesPerSpan * (kWave / LPR);
         float* P = g->partials;
 #define MIXGCN_AGG_MAIN(L) \
-    MIXGCN_TRY((launch_main<L, DT>(m, H, ldh, Z, ldz, cb, w, r0, r1, e0, e1, P, ps, s, timer)))
-#define MIXGCN_AGG_FIX(GG) MIXGCN_TRY((launch_fixup<GG, DT>(m, Z, ldz, cb, w, e0, e1, span, P, s)))
+    MIXGCN_TRY((launch_main<L, DT>(m, H, ldh, Z, ldz, cb, w, r0, r1, e0, e1, P, ps, relu, s, timer)))
+#define MIXGCN_AGG_FIX(GG) \
+    MIXGCN_TRY((launch_fixup<GG, DT>(m, Z, ldz, cb, w, e0, e1, span, P, relu, s)))
         switch (LPR) {
         case 4: MIXGCN_AGG_MAIN(4); break;
         case 8: MIXGCN_AGG_MAIN(8); break;
@@ -446,11 +456,11 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, v
 
 int launch_aggregate(const mixgcn_graph* g, const Csr& m, int dtype, const void* H, int64_t ldh,
                      void* Z, int64_t ldz, int32_t c0, int32_t c1, int64_t r0, int64_t r1,
-                     hipStream_t s, Timer* timer)
+                     int relu, hipStream_t s, Timer* timer)
 {
     if (dtype == MIXGCN_F32)
-        return launch_dt<MIXGCN_F32>(g, m, H, ldh, Z, ldz, c0, c1, r0, r1, s, timer);
-    return launch_dt<MIXGCN_BF16>(g, m, H, ldh, Z, ldz, c0, c1, r0, r1, s, timer);
+        return launch_dt<MIXGCN_F32>(g, m, H, ldh, Z, ldz, c0, c1, r0, r1, relu, s, timer);
+    return launch_dt<MIXGCN_BF16>(g, m, H, ldh, Z, ldz, c0, c1, r0, r1, relu, s, timer);
 }
 
 }  // namespace mixgcn

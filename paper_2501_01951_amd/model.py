@@ -14,7 +14,8 @@ class GCNStep:
     by width.  dW_l are fp32 like W_l.  The input gradient is not computed (dX is not needed
     for training)."""
 
-    def __init__(self, g: B.Graph, x, weights, labels, n_chunks: int = 1, pipe: B.Pipeline = None):
+    def __init__(self, g: B.Graph, x, weights, labels, n_chunks: int = 1, pipe: B.Pipeline = None,
+                 reorder: bool = True):
         self.g = g
         self.n = x.shape[0]
         self.x = x
@@ -24,7 +25,12 @@ class GCNStep:
         self.pipe = pipe if pipe is not None else B.Pipeline()
         dev = x.device
         L = len(self.w)
-        self.z = [torch.empty(self.n, w.shape[0], device=dev, dtype=x.dtype) for w in self.w]
+        # a layer that narrows is updated first (Eq. 3 is associative): its aggregation then
+        # runs at the output width
+        self.order = [B.UPDATE_FIRST if (reorder and w.shape[1] < w.shape[0]) else B.AGG_FIRST
+                      for w in self.w]
+        self.z = [torch.empty(self.n, w.shape[1] if o == B.UPDATE_FIRST else w.shape[0], device=dev,
+                              dtype=x.dtype) for w, o in zip(self.w, self.order)]
         self.h = [x] + [torch.empty(self.n, w.shape[1], device=dev, dtype=x.dtype) for w in self.w]
         self.dw = [torch.empty_like(w) for w in self.w]
         self.dlogits = torch.empty_like(self.h[L])
@@ -36,7 +42,7 @@ class GCNStep:
         L = len(self.w)
         for l in range(L):
             B.layer_fwd(self.g, self.h[l], self.w[l], self.z[l], self.h[l + 1], self.pipe,
-                        relu=(l < L - 1), n_chunks=self.n_chunks)
+                        relu=(l < L - 1), n_chunks=self.n_chunks, order=self.order[l])
         B.softmax_xent(self.h[L], self.labels, self.dlogits, self.loss, stream=self.pipe.primary)
 
     def backward(self):
@@ -44,7 +50,8 @@ class GCNStep:
         grad = self.dlogits
         for l in range(L - 1, -1, -1):
             B.layer_bwd(self.g, self.z[l], self.h[l + 1], self.w[l], grad, self.dw[l], self.dh[l],
-                        self.pipe, relu=(l < L - 1), n_chunks=self.n_chunks)
+                        self.pipe, relu=(l < L - 1), n_chunks=self.n_chunks, order=self.order[l],
+                        H=self.h[l])
             grad = self.dh[l]
 
     def step(self):

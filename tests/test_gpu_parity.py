@@ -310,41 +310,54 @@ def test_layer_fwd_bwd(mg, rmat15, n_chunks):
     pipe.free()
 
 
-def run_model_gpu(mg, g, x, ws, y, n_chunks=1):
-    """L-layer GCN forward + backward through the C ABI only.  Returns loss, logits, dW list."""
-    n = x.shape[0]
-    L = len(ws)
+@pytest.mark.parametrize("relu", [True, False])
+def test_layer_update_first(mg, rmat15, relu):
+    """A narrowing layer run as sigma(A_hat (H W)) must match the oracle's sigma((A_hat H) W)."""
+    og, g = rmat15
+    n, k, m = og.n, 96, 32
+    say(f"layer update-first rmat15 k={k} m={m} relu={relu}")
+    h = gg.normal(61, 1, n, k)
+    w = gg.glorot(61, 2, k, m)
+    gr = gg.normal(61, 3, n, m)
     pipe = mg.Pipeline()
-    hs = [dev(x)]
-    zs = []
-    wds = [dev(w) for w in ws]
-    for l, w in enumerate(wds):
-        z = torch.empty(n, w.shape[0], device="cuda")
-        out = torch.empty(n, w.shape[1], device="cuda")
-        mg.layer_fwd(g, hs[-1], w, z, out, pipe, relu=(l < L - 1), n_chunks=n_chunks)
-        zs.append(z)
-        hs.append(out)
-    logits = hs[-1].clone()
-    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
-    grad = torch.empty_like(hs[-1])
-    mg.softmax_xent(hs[-1], dev(y), grad, loss)
-    dws = [None] * L
-    for l in range(L - 1, -1, -1):
-        dws[l] = torch.empty_like(wds[l])
-        dh = torch.empty(n, wds[l].shape[0], device="cuda") if l > 0 else None
-        mg.layer_bwd(g, zs[l], hs[l + 1], wds[l], grad, dws[l], dh, pipe, relu=(l < L - 1),
-                     n_chunks=n_chunks)
-        grad = dh
+    hd, wd = dev(h), dev(w)
+    work = torch.empty(n, m, device="cuda")
+    out = torch.empty(n, m, device="cuda")
+    mg.layer_fwd(g, hd, wd, work, out, pipe, relu=relu, order=mg.UPDATE_FIRST)
     torch.cuda.synchronize()
+    z_ref = oracle.spmm(og, h.astype(np.float64))
+    out_ref = oracle.update_fwd(z_ref, w.astype(np.float64), relu)
+    assert_close(out.cpu().numpy(), out_ref, RTOL_F32, "Hout")
+    o32 = out_ref.astype(np.float32)
+    od, gd = dev(o32), dev(gr)
+    dw = torch.empty(k, m, device="cuda")
+    dh = torch.empty(n, k, device="cuda")
+    mg.layer_bwd(g, work, od, wd, gd, dw, dh, pipe, relu=relu, order=mg.UPDATE_FIRST, H=hd)
+    torch.cuda.synchronize()
+    dp = oracle.relu_grad(gr.astype(np.float64), o32.astype(np.float64) if relu else None)
+    assert_close(dw.cpu().numpy(), oracle.update_wgrad(z_ref, dp), RTOL_F32, "dW")
+    dz_ref = oracle.update_dgrad(dp, w.astype(np.float64))
+    assert_close(dh.cpu().numpy(), oracle.spmm(og, dz_ref, transposed=True), RTOL_F32, "dH")
     pipe.free()
-    return loss.item(), logits.cpu().numpy(), [d.cpu().numpy() for d in dws], [h.cpu().numpy() for h in hs]
 
 
-def check_model(mg, name, src, dst, n, x, ws, y, n_chunks):
+def run_model_gpu(mg, g, x, ws, y, n_chunks=1, reorder=True):
+    """L-layer GCN forward + backward through the C ABI only, with the same sequencing helper
+    that bench.py times.  Returns loss, logits, dW list and the stored activations."""
+    step = mg.GCNStep(g, dev(x), [dev(w) for w in ws], dev(y), n_chunks=n_chunks, reorder=reorder)
+    step.step()
+    torch.cuda.synchronize()
+    out = (step.loss.item(), step.h[-1].cpu().numpy(), [d.cpu().numpy() for d in step.dw],
+           [h.cpu().numpy() for h in step.h])
+    step.pipe.free()
+    return out
+
+
+def check_model(mg, name, src, dst, n, x, ws, y, n_chunks, reorder=True):
     og = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n)))
     ref = oracle.gcn_step(og, x, ws, y)
     g = _gpu_graph(mg, src, dst, n)
-    loss, logits, dws, hs = run_model_gpu(mg, g, x, ws, y, n_chunks)
+    loss, logits, dws, hs = run_model_gpu(mg, g, x, ws, y, n_chunks, reorder)
     g.free()
     assert abs(loss - ref["loss"]) <= 1e-5 * abs(ref["loss"]), f"{name}: loss {loss} vs {ref['loss']}"
     assert_close(logits, ref["logits"], RTOL_F32, f"{name}: logits")
@@ -369,21 +382,23 @@ def check_model(mg, name, src, dst, n, x, ws, y, n_chunks):
             assert rel_fro(dws[l], ref["dW"][l]) < 2e-3, f"{name}: dW[{l}] with {flips} ReLU flips"
 
 
+@pytest.mark.parametrize("reorder", [False, True])
 @pytest.mark.parametrize("n_chunks", [1, 4])
-def test_config1_tiny_two_layer_gcn(mg, n_chunks):
-    say(f"config 1 end to end, chunks={n_chunks}")
+def test_config1_tiny_two_layer_gcn(mg, n_chunks, reorder):
+    say(f"config 1 end to end, chunks={n_chunks} reorder={reorder}")
     src, dst, n = gg.config_graph("c1")
     x = gg.uniform(gg.MASTER_SEED, 1, n, 64)
     ws = [gg.glorot(gg.MASTER_SEED, 10, 64, 32), gg.glorot(gg.MASTER_SEED, 11, 32, 8)]
     y = gg.labels(gg.MASTER_SEED, 5, n, 8)
-    check_model(mg, "c1", src, dst, n, x, ws, y, n_chunks)
+    check_model(mg, "c1", src, dst, n, x, ws, y, n_chunks, reorder)
 
 
-def test_config2_shape_three_layer_gcn_scale17(mg):
-    say("config 2 shape at R-MAT scale 17, end to end")
+@pytest.mark.parametrize("reorder", [False, True])
+def test_config2_shape_three_layer_gcn_scale17(mg, reorder):
+    say(f"config 2 shape at R-MAT scale 17, end to end, reorder={reorder}")
     src, dst, n = gg.config_graph("c2", scale_override=17)
     x = gg.normal(gg.MASTER_SEED, 1, n, 128)
     ws = [gg.glorot(gg.MASTER_SEED, 10, 128, 256), gg.glorot(gg.MASTER_SEED, 11, 256, 256),
           gg.glorot(gg.MASTER_SEED, 12, 256, 16)]
     y = gg.labels(gg.MASTER_SEED, 5, n, 16)
-    check_model(mg, "c2@17", src, dst, n, x, ws, y, 4)
+    check_model(mg, "c2@17", src, dst, n, x, ws, y, 4, reorder)
