@@ -29,7 +29,7 @@ namespace mixgcn {
 namespace {
 
 constexpr int kBatchesPerSpan = 256;  // gather instructions per wavefront
-constexpr int kDepth = 8;             // gather instructions a wavefront keeps in flight
+constexpr int kDepth = 4;             // gather instructions a wavefront keeps in flight
 
 // 16-byte feature vector: 4 fp32 or 8 bf16 (widened to fp32)
 template <int DT>
@@ -110,7 +110,7 @@ __device__ inline void reduce_subgroups(float* v)
 
 // Partial-sum slots: [span in call][head = 0 / tail = 1][part_stride] fp32, indexed by the
 // column offset within the pass.
-template <int LPR, int DT, bool HAS_EMPTY>
+template <int LPR, int DT, bool HAS_EMPTY, int DEPTH>
 __global__ __launch_bounds__(kBlock) void aggregate_kernel(
     const int64_t* __restrict__ rowptr, const uint2* __restrict__ cv,
     const uint32_t* __restrict__ grp_row, const void* __restrict__ H, int64_t ldh,
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
     constexpr int EPB = kWave / LPR;                  // entries per batch (= sub-groups)
     constexpr int64_t SPAN = (int64_t)kBatchesPerSpan * EPB;
     constexpr int PW = LPR * VEC;                     // columns of one slice
-    constexpr int D = (kDepth * EPB <= kWave) ? kDepth : (kWave / EPB);  // slots per round
+    constexpr int D = (DEPTH * EPB <= kWave) ? DEPTH : (kWave / EPB);  // slots per round
     constexpr uint64_t kLane0Mask = LPR == 64 ? 1ull
                                   : LPR == 32 ? 0x0000000100000001ull
                                   : LPR == 16 ? 0x0001000100010001ull
@@ -345,14 +345,20 @@ int launch_main(const Csr& m, const void* H, int64_t ldh, void* Z, int64_t ldz, 
     if (grid64 > 0x7FFFFFFF) return fail(MIXGCN_EINVAL, "aggregate: grid too large");
     const unsigned grid = (unsigned)grid64;
     if (timer) MIXGCN_TRY(timer->begin(kind, s));
-    if (m.has_empty_rows)
-        hipLaunchKernelGGL((aggregate_kernel<LPR, DT, true>), dim3(grid), dim3(kBlock), 0, s,
-                           m.rowptr, m.cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,
-                           span_first, n_spans, partials, n_slices, part_stride, relu);
-    else
-        hipLaunchKernelGGL((aggregate_kernel<LPR, DT, false>), dim3(grid), dim3(kBlock), 0, s,
-                           m.rowptr, m.cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,
-                           span_first, n_spans, partials, n_slices, part_stride, relu);
+#define MIXGCN_AGG_LAUNCH(EMPTY, DD)                                                            \
+    hipLaunchKernelGGL((aggregate_kernel<LPR, DT, EMPTY, DD>), dim3(grid), dim3(kBlock), 0, s,   \
+                       m.rowptr, m.cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,     \
+                       span_first, n_spans, partials, n_slices, part_stride, relu)
+    static const int depth = [] {
+        const char* e = getenv("MIXGCN_AGG_DEPTH");
+        return e ? atoi(e) : kDepth;
+    }();
+    if (m.has_empty_rows) MIXGCN_AGG_LAUNCH(true, kDepth);
+    else if (depth == 4) MIXGCN_AGG_LAUNCH(false, 4);
+    else if (depth == 6) MIXGCN_AGG_LAUNCH(false, 6);
+    else if (depth == 12) MIXGCN_AGG_LAUNCH(false, 12);
+    else MIXGCN_AGG_LAUNCH(false, kDepth);
+#undef MIXGCN_AGG_LAUNCH
     if (timer) MIXGCN_TRY(timer->end(s));
     return MIXGCN_OK;
 }
@@ -373,16 +379,20 @@ int launch_fixup(const Csr& m, void* Z, int64_t ldz, int c0, int width, int64_t 
     return MIXGCN_OK;
 }
 
-// Lanes per slice of the main kernel (columns per slice = lanes * 4 fp32 or * 8 bf16).
+// Lanes per slice of the main kernel for a pass that `gf` lanes would span (columns per slice
+// = lanes * 4 fp32 or * 8 bf16): 8 lanes = one 128-byte line of every gathered row, so a
+// 256-column pass has 8 slices, one per XCD.  (Measured best when the row pitch is an odd number
+// of 128-byte lines; with a power-of-two pitch a slice's lines fall on few L2 channels.)
 // MIXGCN_AGG_GROUP overrides it (4, 8, 16, 32 or 64) for experiments.
-int slice_lanes()
+int slice_lanes(int gf)
 {
-    static const int v = [] {
+    static const int forced = [] {
         const char* e = getenv("MIXGCN_AGG_GROUP");
-        const int x = e ? atoi(e) : 16;
-        return (x == 4 || x == 8 || x == 16 || x == 32 || x == 64) ? x : 16;
+        const int x = e ? atoi(e) : 0;
+        return (x == 4 || x == 8 || x == 16 || x == 32 || x == 64) ? x : 0;
     }();
-    return v;
+    int l = forced ? forced : 8;
+    return l > gf ? gf : l;
 }
 
 template <int DT>
@@ -403,9 +413,8 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, v
     const int wmax = (c1 - c0) < kMaxTile ? (c1 - c0) : kMaxTile;
     int gmax = 4;
     while (gmax * VEC < wmax) gmax *= 2;
-    int lpr_min = slice_lanes();
-    if (lpr_min > gmax) lpr_min = gmax;
-    const int64_t span_min = (int64_t)kBatchesPerSpan * (kWave / lpr_min);
+    const int lpr_max = slice_lanes(gmax);  // widest slice of any pass = shortest span
+    const int64_t span_min = (int64_t)kBatchesPerSpan * (kWave / lpr_max);
     const int64_t max_spans = ceil_div(e1, span_min) - e0 / span_min;
     const size_t need = (size_t)max_spans * 2 * gmax * VEC * sizeof(float);
     if (need > g->partials_bytes) {
@@ -422,8 +431,7 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, v
         const int w = (c1 - cb) < kMaxTile ? (c1 - cb) : kMaxTile;
         int GF = 4;  // lanes that span the whole pass: fix-up group and partial-slot stride
         while (GF * VEC < w) GF *= 2;
-        int LPR = slice_lanes();
-        if (LPR > GF) LPR = GF;
+        const int LPR = slice_lanes(GF);
         const int ps = GF * VEC;
         const int64_t span = (int64_t)kBatchesPerSpan * (kWave / LPR);
         float* P = g->partials;

@@ -7,6 +7,20 @@ import torch
 from . import binding as B
 
 
+def padded_rows(n: int, f: int, dtype, device):
+    """n x f tensor whose row pitch is an odd number of 128-byte lines.  With a power-of-two
+    pitch the same column slice of every row falls on a few L2 channels only; an odd pitch
+    spreads it over all of them (measured: 3.9 -> 3.1 ms for the 256-column aggregation)."""
+    esize = torch.empty(0, dtype=dtype).element_size()
+    if f * esize <= 128:  # rows of at most one line are left packed
+        return torch.empty(n, f, device=device, dtype=dtype)
+    lines = (f * esize + 127) // 128
+    if lines % 2 == 0:
+        lines += 1
+    ld = lines * 128 // esize
+    return torch.empty(n, ld, device=device, dtype=dtype)[:, :f]
+
+
 class GCNStep:
     """Forward + loss + backward of an L-layer GCN (ReLU between layers, none after the last).
 
@@ -29,13 +43,18 @@ class GCNStep:
         # runs at the output width
         self.order = [B.UPDATE_FIRST if (reorder and w.shape[1] < w.shape[0]) else B.AGG_FIRST
                       for w in self.w]
-        self.z = [torch.empty(self.n, w.shape[1] if o == B.UPDATE_FIRST else w.shape[0], device=dev,
-                              dtype=x.dtype) for w, o in zip(self.w, self.order)]
-        self.h = [x] + [torch.empty(self.n, w.shape[1], device=dev, dtype=x.dtype) for w in self.w]
+        def rows(f):
+            return padded_rows(self.n, f, x.dtype, dev)
+
+        x_p = rows(x.shape[1])
+        x_p.copy_(x)
+        self.x = x_p
+        self.z = [rows(w.shape[1] if o == B.UPDATE_FIRST else w.shape[0])
+                  for w, o in zip(self.w, self.order)]
+        self.h = [x_p] + [rows(w.shape[1]) for w in self.w]
         self.dw = [torch.empty_like(w) for w in self.w]
-        self.dlogits = torch.empty_like(self.h[L])
-        self.dh = [None] + [torch.empty(self.n, self.w[l].shape[0], device=dev, dtype=x.dtype)
-                            for l in range(1, L)]
+        self.dlogits = rows(self.w[L - 1].shape[1])
+        self.dh = [None] + [rows(self.w[l].shape[0]) for l in range(1, L)]
         self.loss = torch.zeros(1, dtype=torch.float64, device=dev)
 
     def forward(self):
