@@ -7,7 +7,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libmixgcn.so")
+# MIXGCN_LIB points at another build of the same library (kernel experiments)
+_LIB_PATH = os.environ.get("MIXGCN_LIB") or os.path.join(_HERE, "libmixgcn.so")
 _lib = None
 
 F32, BF16 = 0, 1

@@ -40,17 +40,19 @@ def _newer(src: str, out: str) -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = False, verbose: bool = False) -> str:
-    os.makedirs(BUILD_DIR, exist_ok=True)
+def build(force: bool = False, verbose: bool = False, extra_flags=(), out: str = LIB_PATH,
+          build_dir: str = BUILD_DIR) -> str:
+    """extra_flags / out / build_dir let an experiment build a variant next to the product."""
+    os.makedirs(build_dir, exist_ok=True)
     hipcc = _hipcc()
     objs = []
     jobs = []
     for name in SOURCES:
         src = os.path.join(CSRC, name)
-        obj = os.path.join(BUILD_DIR, name.replace(".hip", ".o"))
+        obj = os.path.join(build_dir, name.replace(".hip", ".o"))
         objs.append(obj)
         if force or _newer(src, obj):
-            jobs.append([hipcc, *HIPCC_FLAGS, "-c", src, "-o", obj])
+            jobs.append([hipcc, *HIPCC_FLAGS, *extra_flags, "-c", src, "-o", obj])
 
     def run(cmd):
         if verbose:
@@ -64,9 +66,9 @@ def build(force: bool = False, verbose: bool = False) -> str:
 
     with ThreadPoolExecutor(max_workers=min(8, max(1, len(jobs)))) as ex:
         list(ex.map(run, jobs))
-    if jobs or not os.path.exists(LIB_PATH):
-        run([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB_PATH, *objs])
-    return LIB_PATH
+    if jobs or not os.path.exists(out):
+        run([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", out, *objs])
+    return out
 
 
 if __name__ == "__main__":

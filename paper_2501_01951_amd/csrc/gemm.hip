@@ -25,7 +25,8 @@ struct Shape {
 using Shape128x128 = Shape<2, 2, 2, 2>;
 using Shape128x32 = Shape<4, 1, 1, 1>;
 
-// acc += As[kk][a-rows] (x) Bs[kk][b-cols] over the BK staged reduction steps.
+// acc += As[kk][a-rows] (x) Bs[kk][b-cols] over the BK staged reduction steps.  The operand
+// registers of step k2 + 2 are read from LDS before the MFMAs of step k2 are issued.
 // MFMA 32x32x2 operand layout: lane l supplies A[i = l % 32][k = l / 32] and B[k = l / 32][j = l % 32].
 template <class S>
 __device__ inline void mma_step(const float* As, const float* Bs, int wm, int wn, int lane,
@@ -33,63 +34,99 @@ __device__ inline void mma_step(const float* As, const float* Bs, int wm, int wn
 {
     constexpr int LDA = S::BM + kLdsPad, LDB = S::BN + kLdsPad;
     const int li = lane & 31, lk = lane >> 5;
+    const float* ap = As + lk * LDA + wm * S::TM * 32 + li;
+    const float* bp = Bs + lk * LDB + wn * S::TN * 32 + li;
+    float a[2][S::TM], b[2][S::TN];
+#pragma unroll
+    for (int tm = 0; tm < S::TM; ++tm) a[0][tm] = ap[tm * 32];
+#pragma unroll
+    for (int tn = 0; tn < S::TN; ++tn) b[0][tn] = bp[tn * 32];
 #pragma unroll
     for (int k2 = 0; k2 < BK; k2 += 2) {
-        float a[S::TM], b[S::TN];
+        const int cur = (k2 >> 1) & 1, nxt = cur ^ 1;
+        if (k2 + 2 < BK) {
 #pragma unroll
-        for (int tm = 0; tm < S::TM; ++tm)
-            a[tm] = As[(k2 + lk) * LDA + (wm * S::TM + tm) * 32 + li];
+            for (int tm = 0; tm < S::TM; ++tm) a[nxt][tm] = ap[(k2 + 2) * LDA + tm * 32];
 #pragma unroll
-        for (int tn = 0; tn < S::TN; ++tn)
-            b[tn] = Bs[(k2 + lk) * LDB + (wn * S::TN + tn) * 32 + li];
+            for (int tn = 0; tn < S::TN; ++tn) b[nxt][tn] = bp[(k2 + 2) * LDB + tn * 32];
+        }
 #pragma unroll
         for (int tm = 0; tm < S::TM; ++tm)
 #pragma unroll
             for (int tn = 0; tn < S::TN; ++tn)
-                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][tm], b[cur][tn],
+                                                                   acc[tm][tn], 0, 0, 0);
     }
 }
 
-// Loads a float4 of a row-major matrix with zero fill outside [0, rows) x [0, cols) and an
-// optional ReLU-derivative mask taken from R (same indexing): x * 1[R > 0].
-__device__ inline float4 load4_masked(const float* __restrict__ M, int64_t ld, int64_t r, int c,
-                                      int64_t rows, int cols, const float* __restrict__ R,
-                                      int64_t ldr)
-{
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (r < rows && c < cols) {
-        v = *reinterpret_cast<const float4*>(M + r * ld + c);
-        if (R) {
-            const float4 m = *reinterpret_cast<const float4*>(R + r * ldr + c);
-            v.x = m.x > 0.f ? v.x : 0.f;
-            v.y = m.y > 0.f ? v.y : 0.f;
-            v.z = m.z > 0.f ? v.z : 0.f;
-            v.w = m.w > 0.f ? v.w : 0.f;
-        }
-        if (c + 1 >= cols) v.y = 0.f;
-        if (c + 2 >= cols) v.z = 0.f;
-        if (c + 3 >= cols) v.w = 0.f;
+// One 16-byte piece of an operand tile on its way from global memory to LDS.  issue() only
+// starts the loads (addresses are clamped into the matrix, so they are unconditional and
+// nothing waits on them); value() applies the zero fill outside [0, rows) x [0, cols) and the
+// optional ReLU-derivative mask x * 1[R > 0] when the piece is written to LDS one step later.
+template <bool MASK>
+struct Piece {
+    float4 v;
+    float4 m;
+    int nvalid;  // leading components inside the matrix (0..4)
+
+    __device__ inline void issue(const float* __restrict__ M, int64_t ld, int64_t r, int c,
+                                 int64_t rows, int cols, const float* __restrict__ R, int64_t ldr)
+    {
+        const bool ok = r < rows && c < cols;
+        nvalid = ok ? (cols - c < 4 ? cols - c : 4) : 0;
+        const int64_t rr = r < rows ? r : rows - 1;
+        const int cc = c < cols ? c : 0;
+        v = *reinterpret_cast<const float4*>(M + rr * ld + cc);
+        if (MASK) m = *reinterpret_cast<const float4*>(R + rr * ldr + cc);
     }
-    return v;
+    __device__ inline float4 value() const
+    {
+        float4 o = v;
+        if (MASK) {
+            o.x = m.x > 0.f ? o.x : 0.f;
+            o.y = m.y > 0.f ? o.y : 0.f;
+            o.z = m.z > 0.f ? o.z : 0.f;
+            o.w = m.w > 0.f ? o.w : 0.f;
+        }
+        if (nvalid < 4) {
+            if (nvalid < 1) o.x = 0.f;
+            if (nvalid < 2) o.y = 0.f;
+            if (nvalid < 3) o.z = 0.f;
+            o.w = 0.f;
+        }
+        return o;
+    }
+};
+
+// Workgroups are dealt round-robin to the 8 XCDs.  This maps the hardware block index to a
+// logical one such that consecutive logical indices run on the same XCD, so tiles that share
+// an operand (the column tiles of one row block) find it in that XCD's L2.
+__device__ inline unsigned xcd_local_index(unsigned bid, unsigned grid)
+{
+    const unsigned q = grid / 8, rem = grid % 8, x = bid % 8;
+    return x * q + (x < rem ? x : rem) + bid / 8;
 }
 
 // ---- row-block kernel: C[n x MD] = op(A)[n x KD] * Bop[KD x MD] -------------------------------
 //   B_TRANS = false: Bop[kk][j] = B[kk * ldb + j]   (forward:  Z W)
 //   B_TRANS = true : Bop[kk][j] = B[j * ldb + kk]   (dgrad:   dP W^T with W stored k x m)
+//   MASK: A is multiplied by 1[R > 0] on the way in (dgrad of a ReLU layer).
 // A is staged transposed (reduction-major) so that the MFMA operand reads are unit-stride.
-template <class S, bool B_TRANS, bool RELU>
+// LDS tiles are double buffered: one barrier per reduction step.
+template <class S, bool B_TRANS, bool RELU, bool MASK>
 __global__ __launch_bounds__(kBlock) void rowblock_gemm_kernel(
     const float* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb,
     float* __restrict__ C, int64_t ldc, int64_t n, int KD, int MD, const float* __restrict__ R,
     int64_t ldr, int n_col_tiles)
 {
     constexpr int LDA = S::BM + kLdsPad, LDB = S::BN + kLdsPad;
-    __shared__ float As[BK * LDA];
-    __shared__ float Bs[BK * LDB];
+    __shared__ float As[2][BK * LDA];
+    __shared__ float Bs[2][BK * LDB];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / S::WN, wn = wave % S::WN;
-    const int64_t row0 = (int64_t)(blockIdx.x / n_col_tiles) * S::BM;
-    const int col0 = (int)(blockIdx.x % n_col_tiles) * S::BN;
+    const unsigned lid = xcd_local_index(blockIdx.x, gridDim.x);
+    const int64_t row0 = (int64_t)(lid / n_col_tiles) * S::BM;
+    const int col0 = (int)(lid % n_col_tiles) * S::BN;
 
     floatx16 acc[S::TM][S::TN];
 #pragma unroll
@@ -105,51 +142,47 @@ __global__ __launch_bounds__(kBlock) void rowblock_gemm_kernel(
     constexpr int BN_F4 = S::BN / 4;                           // float4 per staged B row
     constexpr int B_ROWS_PER_PASS = kBlock / BN_F4;
     constexpr int B_PASSES = (BK + B_ROWS_PER_PASS - 1) / B_ROWS_PER_PASS;
-    float4 ra[A_PASSES];
-    float4 rb[B_TRANS ? BT_PASSES : B_PASSES];
+    Piece<MASK> ra[A_PASSES];
+    Piece<false> rb[B_TRANS ? BT_PASSES : B_PASSES];
 
-    auto load_tiles = [&](int k0) {
+    auto issue_tiles = [&](int k0) {
 #pragma unroll
-        for (int p = 0; p < A_PASSES; ++p) {
-            const int i = p * 64 + tid / 4;
-            ra[p] = load4_masked(A, lda, row0 + i, k0 + 4 * (tid & 3), n, KD, R, ldr);
-        }
+        for (int p = 0; p < A_PASSES; ++p)
+            ra[p].issue(A, lda, row0 + p * 64 + tid / 4, k0 + 4 * (tid & 3), n, KD, R, ldr);
         if (B_TRANS) {
 #pragma unroll
             for (int p = 0; p < BT_PASSES; ++p) {
                 const int j = p * 64 + tid / 4;
-                rb[p] = (j < S::BN) ? load4_masked(B, ldb, col0 + j, k0 + 4 * (tid & 3), MD, KD,
-                                                   nullptr, 0)
-                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+                rb[p].issue(B, ldb, col0 + (j < S::BN ? j : 0), k0 + 4 * (tid & 3), MD, KD, nullptr, 0);
             }
         } else {
 #pragma unroll
             for (int p = 0; p < B_PASSES; ++p) {
                 const int kk = p * B_ROWS_PER_PASS + tid / BN_F4;
-                rb[p] = (kk < BK) ? load4_masked(B, ldb, k0 + kk, col0 + 4 * (tid % BN_F4), KD, MD,
-                                                 nullptr, 0)
-                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+                rb[p].issue(B, ldb, k0 + (kk < BK ? kk : 0), col0 + 4 * (tid % BN_F4), KD, MD, nullptr, 0);
             }
         }
     };
-    auto store_tiles = [&]() {
+    auto store_tiles = [&](float* as, float* bs) {
 #pragma unroll
         for (int p = 0; p < A_PASSES; ++p) {
             const int i = p * 64 + tid / 4, kq = 4 * (tid & 3);
-            As[(kq + 0) * LDA + i] = ra[p].x;
-            As[(kq + 1) * LDA + i] = ra[p].y;
-            As[(kq + 2) * LDA + i] = ra[p].z;
-            As[(kq + 3) * LDA + i] = ra[p].w;
+            const float4 v = ra[p].value();
+            as[(kq + 0) * LDA + i] = v.x;
+            as[(kq + 1) * LDA + i] = v.y;
+            as[(kq + 2) * LDA + i] = v.z;
+            as[(kq + 3) * LDA + i] = v.w;
         }
         if (B_TRANS) {
 #pragma unroll
             for (int p = 0; p < BT_PASSES; ++p) {
                 const int j = p * 64 + tid / 4, kq = 4 * (tid & 3);
                 if (j < S::BN) {
-                    Bs[(kq + 0) * LDB + j] = rb[p].x;
-                    Bs[(kq + 1) * LDB + j] = rb[p].y;
-                    Bs[(kq + 2) * LDB + j] = rb[p].z;
-                    Bs[(kq + 3) * LDB + j] = rb[p].w;
+                    const float4 v = rb[p].value();
+                    bs[(kq + 0) * LDB + j] = v.x;
+                    bs[(kq + 1) * LDB + j] = v.y;
+                    bs[(kq + 2) * LDB + j] = v.z;
+                    bs[(kq + 3) * LDB + j] = v.w;
                 }
             }
         } else {
@@ -157,17 +190,20 @@ __global__ __launch_bounds__(kBlock) void rowblock_gemm_kernel(
             for (int p = 0; p < B_PASSES; ++p) {
                 const int kk = p * B_ROWS_PER_PASS + tid / BN_F4;
                 if (kk < BK)
-                    *reinterpret_cast<float4*>(&Bs[kk * LDB + 4 * (tid % BN_F4)]) = rb[p];
+                    *reinterpret_cast<float4*>(&bs[kk * LDB + 4 * (tid % BN_F4)]) = rb[p].value();
             }
         }
     };
 
-    load_tiles(0);
-    for (int k0 = 0; k0 < KD; k0 += BK) {
-        store_tiles();
-        __syncthreads();
-        if (k0 + BK < KD) load_tiles(k0 + BK);
-        mma_step<S>(As, Bs, wm, wn, lane, acc);
+    const int nk = (KD + BK - 1) / BK;
+    issue_tiles(0);
+    store_tiles(As[0], Bs[0]);
+    __syncthreads();
+    for (int i = 0; i < nk; ++i) {
+        const int cur = i & 1;
+        if (i + 1 < nk) issue_tiles((i + 1) * BK);
+        mma_step<S>(As[cur], Bs[cur], wm, wn, lane, acc);
+        if (i + 1 < nk) store_tiles(As[cur ^ 1], Bs[cur ^ 1]);
         __syncthreads();
     }
 
@@ -194,20 +230,21 @@ __global__ __launch_bounds__(kBlock) void rowblock_gemm_kernel(
 // ---- slab kernel: P[slab][KD x MD] = A[rows of slab][KD]^T * (B (.) 1[R > 0])[rows][MD] --------
 // Both operands are staged exactly as they lie in memory (node-major), which already is the
 // reduction-major layout the MFMA operand reads want.
-template <class S>
+template <class S, bool MASK>
 __global__ __launch_bounds__(kBlock) void wgrad_slab_kernel(
     const float* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb,
     const float* __restrict__ R, int64_t ldr, float* __restrict__ P, int64_t n, int KD, int MD,
     int64_t rows_per_slab, int n_i_tiles, int n_j_tiles)
 {
     constexpr int LDA = S::BM + kLdsPad, LDB = S::BN + kLdsPad;
-    __shared__ float As[BK * LDA];
-    __shared__ float Bs[BK * LDB];
+    __shared__ float As[2][BK * LDA];
+    __shared__ float Bs[2][BK * LDB];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / S::WN, wn = wave % S::WN;
     const int tiles = n_i_tiles * n_j_tiles;
-    const int64_t slab = blockIdx.x / tiles;
-    const int t = (int)(blockIdx.x % tiles);
+    const unsigned lid = xcd_local_index(blockIdx.x, gridDim.x);
+    const int64_t slab = lid / tiles;
+    const int t = (int)(lid % tiles);
     const int i0 = (t / n_j_tiles) * S::BM, j0 = (t % n_j_tiles) * S::BN;
     const int64_t r_begin = slab * rows_per_slab;
     const int64_t r_end = (r_begin + rows_per_slab) < n ? (r_begin + rows_per_slab) : n;
@@ -223,44 +260,44 @@ __global__ __launch_bounds__(kBlock) void wgrad_slab_kernel(
     constexpr int AM_F4 = S::BM / 4, BN_F4 = S::BN / 4;
     constexpr int A_RPP = kBlock / AM_F4, B_RPP = kBlock / BN_F4;
     constexpr int A_PASSES = (BK + A_RPP - 1) / A_RPP, B_PASSES = (BK + B_RPP - 1) / B_RPP;
-    float4 ra[A_PASSES], rb[B_PASSES];
+    Piece<false> ra[A_PASSES];
+    Piece<MASK> rb[B_PASSES];
 
-    auto load_tiles = [&](int64_t r0) {
+    auto issue_tiles = [&](int64_t r0) {
 #pragma unroll
         for (int p = 0; p < A_PASSES; ++p) {
             const int kk = p * A_RPP + tid / AM_F4;
-            ra[p] = (kk < BK) ? load4_masked(A, lda, r0 + kk, i0 + 4 * (tid % AM_F4), r_end, KD,
-                                             nullptr, 0)
-                              : make_float4(0.f, 0.f, 0.f, 0.f);
+            ra[p].issue(A, lda, r0 + (kk < BK ? kk : 0), i0 + 4 * (tid % AM_F4), r_end, KD, nullptr, 0);
         }
 #pragma unroll
         for (int p = 0; p < B_PASSES; ++p) {
             const int kk = p * B_RPP + tid / BN_F4;
-            rb[p] = (kk < BK) ? load4_masked(B, ldb, r0 + kk, j0 + 4 * (tid % BN_F4), r_end, MD, R,
-                                             ldr)
-                              : make_float4(0.f, 0.f, 0.f, 0.f);
+            rb[p].issue(B, ldb, r0 + (kk < BK ? kk : 0), j0 + 4 * (tid % BN_F4), r_end, MD, R, ldr);
         }
     };
-    auto store_tiles = [&]() {
+    auto store_tiles = [&](float* as, float* bs) {
 #pragma unroll
         for (int p = 0; p < A_PASSES; ++p) {
             const int kk = p * A_RPP + tid / AM_F4;
-            if (kk < BK) *reinterpret_cast<float4*>(&As[kk * LDA + 4 * (tid % AM_F4)]) = ra[p];
+            if (kk < BK) *reinterpret_cast<float4*>(&as[kk * LDA + 4 * (tid % AM_F4)]) = ra[p].value();
         }
 #pragma unroll
         for (int p = 0; p < B_PASSES; ++p) {
             const int kk = p * B_RPP + tid / BN_F4;
-            if (kk < BK) *reinterpret_cast<float4*>(&Bs[kk * LDB + 4 * (tid % BN_F4)]) = rb[p];
+            if (kk < BK) *reinterpret_cast<float4*>(&bs[kk * LDB + 4 * (tid % BN_F4)]) = rb[p].value();
         }
     };
 
     if (r_begin < r_end) {
-        load_tiles(r_begin);
-        for (int64_t r0 = r_begin; r0 < r_end; r0 += BK) {
-            store_tiles();
-            __syncthreads();
-            if (r0 + BK < r_end) load_tiles(r0 + BK);
-            mma_step<S>(As, Bs, wm, wn, lane, acc);
+        const int64_t nk = (r_end - r_begin + BK - 1) / BK;
+        issue_tiles(r_begin);
+        store_tiles(As[0], Bs[0]);
+        __syncthreads();
+        for (int64_t i = 0; i < nk; ++i) {
+            const int cur = (int)(i & 1);
+            if (i + 1 < nk) issue_tiles(r_begin + (i + 1) * BK);
+            mma_step<S>(As[cur], Bs[cur], wm, wn, lane, acc);
+            if (i + 1 < nk) store_tiles(As[cur ^ 1], Bs[cur ^ 1]);
             __syncthreads();
         }
     }
@@ -280,18 +317,27 @@ __global__ __launch_bounds__(kBlock) void wgrad_slab_kernel(
         }
 }
 
-// dW = beta * dW + sum over slabs (added in slab order, in fp64).
+// dW = beta * dW + sum over slabs.  A block owns 64 consecutive cells; its four waves each add
+// every fourth slab (in slab order, fp64) and the four sums are combined in a fixed order, so
+// the result is deterministic.
 __global__ __launch_bounds__(kBlock) void wgrad_reduce_kernel(const float* __restrict__ P,
                                                               int64_t n_slabs, int64_t cells,
                                                               int MD, float* __restrict__ dW,
                                                               int64_t ldw, float beta)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= cells) return;
+    __shared__ double part[kBlock / kWave][kWave];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t i = (int64_t)blockIdx.x * kWave + lane;
     double s = 0.0;
-    for (int64_t b = 0; b < n_slabs; ++b) s += (double)P[(size_t)b * cells + i];
-    float* o = dW + (i / MD) * ldw + (i % MD);
-    *o = (float)(beta != 0.f ? (double)beta * (double)*o + s : s);
+    if (i < cells)
+        for (int64_t b = w; b < n_slabs; b += kBlock / kWave) s += (double)P[(size_t)b * cells + i];
+    part[w][lane] = s;
+    __syncthreads();
+    if (w == 0 && i < cells) {
+        const double t = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
+        float* o = dW + (i / MD) * ldw + (i % MD);
+        *o = (float)(beta != 0.f ? (double)beta * (double)*o + t : t);
+    }
 }
 
 // G <- G (.) 1[R > 0], four elements per thread.
@@ -321,12 +367,13 @@ int launch_rowblock(bool relu, const float* A, int64_t lda, const float* B, int6
     const int64_t grid = ceil_div(n, S::BM) * nct;
     if (grid <= 0) return MIXGCN_OK;
     if (grid > 0x7FFFFFFF) return fail(MIXGCN_EINVAL, "update: too many row tiles");
-    if (relu)
-        hipLaunchKernelGGL((rowblock_gemm_kernel<S, B_TRANS, true>), dim3((unsigned)grid),
-                           dim3(kBlock), 0, s, A, lda, B, ldb, C, ldc, n, KD, MD, R, ldr, nct);
-    else
-        hipLaunchKernelGGL((rowblock_gemm_kernel<S, B_TRANS, false>), dim3((unsigned)grid),
-                           dim3(kBlock), 0, s, A, lda, B, ldb, C, ldc, n, KD, MD, R, ldr, nct);
+#define MIXGCN_ROWBLOCK(RELU, MASK)                                                              \
+    hipLaunchKernelGGL((rowblock_gemm_kernel<S, B_TRANS, RELU, MASK>), dim3((unsigned)grid),      \
+                       dim3(kBlock), 0, s, A, lda, B, ldb, C, ldc, n, KD, MD, R, ldr, nct)
+    if (R) MIXGCN_ROWBLOCK(false, true);
+    else if (relu) MIXGCN_ROWBLOCK(true, false);
+    else MIXGCN_ROWBLOCK(false, false);
+#undef MIXGCN_ROWBLOCK
     return MIXGCN_OK;
 }
 
@@ -381,7 +428,7 @@ int launch_update(int op, int dtype, const void* A_, int64_t lda, const float* B
         const int nit = (int)ceil_div(k, bm), njt = (int)ceil_div(m, bn);
         const int tiles = nit * njt;
         int64_t n_slabs = ceil_div(n, 1024);
-        const int64_t cap = tiles >= 2048 ? 1 : 2048 / tiles;
+        const int64_t cap = tiles >= 1024 ? 1 : 1024 / tiles;
         if (n_slabs > cap) n_slabs = cap;
         if (n_slabs < 1) n_slabs = 1;
         int64_t rows_per_slab = ceil_div(ceil_div(n, n_slabs), BK) * BK;
@@ -393,14 +440,19 @@ int launch_update(int op, int dtype, const void* A_, int64_t lda, const float* B
         float* P = (float*)scratch;
         const unsigned grid = (unsigned)(n_slabs * tiles);
         if (timer) MIXGCN_TRY(timer->begin(kTimeUpdateWgrad, s));
-        if (wide)
-            hipLaunchKernelGGL((wgrad_slab_kernel<Shape128x128>), dim3(grid), dim3(kBlock), 0, s, A,
-                               lda, B, ldb, R, ldr, P, n, k, m, rows_per_slab, nit, njt);
-        else
-            hipLaunchKernelGGL((wgrad_slab_kernel<Shape128x32>), dim3(grid), dim3(kBlock), 0, s, A,
-                               lda, B, ldb, R, ldr, P, n, k, m, rows_per_slab, nit, njt);
+#define MIXGCN_WGRAD(SHAPE, MASK)                                                              \
+    hipLaunchKernelGGL((wgrad_slab_kernel<SHAPE, MASK>), dim3(grid), dim3(kBlock), 0, s, A, lda, B, \
+                       ldb, R, ldr, P, n, k, m, rows_per_slab, nit, njt)
+        if (wide) {
+            if (R) MIXGCN_WGRAD(Shape128x128, true);
+            else MIXGCN_WGRAD(Shape128x128, false);
+        } else {
+            if (R) MIXGCN_WGRAD(Shape128x32, true);
+            else MIXGCN_WGRAD(Shape128x32, false);
+        }
+#undef MIXGCN_WGRAD
         if (timer) MIXGCN_TRY(timer->end(s));
-        hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)ceil_div(cells, kBlock)),
+        hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)ceil_div(cells, kWave)),
                            dim3(kBlock), 0, s, P, n_slabs, cells, m, C, ldc, beta);
     } else {
         return fail(MIXGCN_EINVAL, "update: unknown op");

@@ -174,7 +174,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
     static_assert(RE <= kWave, "a round's entries must fit one load per lane");
     const uint2* const rcv = cv + gs + (lane < RE ? lane : 0);  // entry `lane` of round 0 of span
     const int src_lane = sub;                                   // + u * EPB per slot
-    uint2 inext = rcv[(int64_t)b0 * EPB];        // entries of the round that starts at batch b0
+    uint2 inext = rcv[(int64_t)b0 * EPB];  // entries of the round at batch b0
     uint32_t c[D];
     float a[D];
     typename F::Raw h[D];
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
         a[u] = __uint_as_float(__shfl(inext.y, u * EPB + src_lane, kWave));
         h[u] = *F::ptr(H, (int64_t)(c[u] & kEntryColMask) * ldh + coff_load);
     }
-    inext = rcv[(int64_t)(b0 + D) * EPB];        // round b0 + D
+    inext = rcv[(int64_t)(b0 + D) * EPB];  // round b0 + D
 
     for (int b = b0; b < b1; b += D) {
         const uint2 inext2 = rcv[(int64_t)(b + 2 * D) * EPB];  // two rounds ahead
