@@ -174,10 +174,11 @@ int mixgcn_layer_bwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, const vo
 
 /*
  * Loss glue (Algorithm 2, loss line): mean softmax cross-entropy over n nodes and its gradient
- * dlogits = (softmax - onehot) / n (may alias logits).  loss: one device double.
+ * dlogits = (softmax - onehot) / n (may alias logits).  logits and dlogits are stored as
+ * `dtype` (the arithmetic is fp32, the loss sum fp64).  loss: one device double.
  */
-int mixgcn_softmax_xent(const float* logits, int64_t ldl, const int32_t* labels, int64_t n,
-                        int32_t n_classes, float* dlogits, int64_t ldd, double* loss,
+int mixgcn_softmax_xent(int dtype, const void* logits, int64_t ldl, const int32_t* labels,
+                        int64_t n, int32_t n_classes, void* dlogits, int64_t ldd, double* loss,
                         void* stream);
 
 /* Helpers. */

@@ -287,7 +287,9 @@ double oracle_softmax_xent(const double* logits, int64_t ldl, const int32_t* lab
  * dims has L+1 entries.  All matrices are dense row-major with ld == their column count.
  * W[l]: dims[l] x dims[l+1].  Zs[l]: n x dims[l].  Hs[l] (l = 1..L): n x dims[l] with Hs[L] =
  * logits; Hs[0] is not written.  dW[l] like W[l].  dX (n x dims[0]) may be NULL.
- * linear != 0 replaces every ReLU by the identity.  Returns the loss.
+ * linear != 0 replaces every ReLU by the identity.  q != 0 rounds every stored n x F tensor
+ * (Z_l, H_l including the logits, the loss gradient, dZ_l, dH_l, dP_l) to fp32 / bf16 where it
+ * is written; weights, A_hat, the loss and dW stay in double.  Returns the loss.
  */
 double oracle_gcn_step(const int64_t* rowptr, const uint32_t* col, const double* val,
                        const int64_t* t_rowptr, const uint32_t* t_col, const double* t_val,
@@ -301,13 +303,15 @@ double oracle_gcn_step(const int64_t* rowptr, const uint32_t* col, const double*
         oracle_spmm(rowptr, col, val, Hin, dims[l], Zs[l], dims[l], 0, dims[l], 0, n, q);
         int relu = (l < L - 1) && !linear;
         oracle_update_fwd(Zs[l], dims[l], W[l], dims[l + 1], Hs[l + 1], dims[l + 1], n, dims[l],
-                          dims[l + 1], relu, (l == L - 1 && q == 2) ? 1 : q);
+                          dims[l + 1], relu, q);
         Hin = Hs[l + 1];
     }
     const int64_t C = dims[L];
     std::vector<double> dP((size_t)n * C);
     double loss = oracle_softmax_xent(Hs[L], C, labels, n, C, dP.data(), C);
     if (!dW) return loss;
+    if (q)  /* the loss gradient is a stored n x C tensor like every other one */
+        for (size_t i = 0; i < dP.size(); ++i) dP[i] = quantize(dP[i], q);
     for (int l = L - 1; l >= 0; --l) {
         const int64_t k = dims[l], m = dims[l + 1];
         oracle_update_wgrad(Zs[l], k, dP.data(), m, dW[l], m, n, k, m);

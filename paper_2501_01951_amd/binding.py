@@ -72,7 +72,7 @@ def load_library():
                                   i32, vp, i64, f32, vp]
     lib.mixgcn_layer_fwd.argtypes = [vp, ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp]
     lib.mixgcn_layer_bwd.argtypes = [vp, ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp, vp]
-    lib.mixgcn_softmax_xent.argtypes = [vp, i64, vp, i64, i32, vp, i64, vp, vp]
+    lib.mixgcn_softmax_xent.argtypes = [ctypes.c_int, vp, i64, vp, i64, i32, vp, i64, vp, vp]
     lib.mixgcn_graph_info.argtypes = [vp, ctypes.POINTER(_GraphView)]
     lib.mixgcn_graph_free.argtypes = [vp]
     lib.mixgcn_pipeline_create.argtypes = [vp, vp, ctypes.POINTER(vp)]
@@ -281,6 +281,8 @@ def layer_fwd(g: Graph, H, W, Z, Hout, pipe: Pipeline, relu: bool = True, n_chun
 def layer_bwd(g: Graph, Z, Hout, W, G, dW, dH, pipe: Pipeline, relu: bool = True,
               n_chunks: int = 1, order: int = AGG_FIRST, H=None) -> None:
     """H (the layer input) is needed only with UPDATE_FIRST."""
+    assert _ld(dW) == _ld(W), "dW must have the leading dimension of W"
+    assert dH is None or H is None or _ld(dH) == _ld(H), "dH must have the leading dimension of H"
     h_like = dH if dH is not None else (H if H is not None else Z)
     d = _desc(h_like, Z, G, W, relu, n_chunks, order)
     _check(load_library().mixgcn_layer_bwd(g._h, ctypes.byref(d), _ptr(H), _ptr(Z), _ptr(Hout),
@@ -290,6 +292,7 @@ def layer_bwd(g: Graph, Z, Hout, W, G, dW, dH, pipe: Pipeline, relu: bool = True
 
 def softmax_xent(logits, labels, dlogits, loss, stream=None) -> None:
     n, c = logits.shape
-    _check(load_library().mixgcn_softmax_xent(_ptr(logits), _ld(logits), _ptr(labels), n, c,
+    _check(load_library().mixgcn_softmax_xent(_dtype_of(logits), _ptr(logits), _ld(logits),
+                                              _ptr(labels), n, c,
                                               _ptr(dlogits), _ld(dlogits), _ptr(loss),
                                               _stream(stream)), "softmax_xent")

@@ -299,7 +299,7 @@ static int update_impl(int op, int dtype, const void* A, int64_t lda, const void
         if (relu_ref) MIXGCN_TRY(check_matrix("update: relu_ref", relu_ref, ldr, m, es));
         break;
     }
-    return launch_update(op, dtype, A, lda, (const float*)B, ldb, C, ldc, n_rows, k, m, relu_ref,
+    return launch_update(op, dtype, A, lda, B, ldb, C, ldc, n_rows, k, m, relu_ref,
                          ldr, beta, stream, timer);
 }
 
@@ -311,14 +311,15 @@ int mixgcn_update(int op, int dtype, const void* A, int64_t lda, const void* B, 
                        (hipStream_t)stream, nullptr);
 }
 
-int mixgcn_softmax_xent(const float* logits, int64_t ldl, const int32_t* labels, int64_t n,
-                        int32_t n_classes, float* dlogits, int64_t ldd, double* loss,
+int mixgcn_softmax_xent(int dtype, const void* logits, int64_t ldl, const int32_t* labels,
+                        int64_t n, int32_t n_classes, void* dlogits, int64_t ldd, double* loss,
                         void* stream)
 {
+    if (dtype != MIXGCN_F32 && dtype != MIXGCN_BF16) return fail(MIXGCN_EINVAL, "softmax_xent: dtype");
     if (!logits || !labels || !dlogits || !loss) return fail(MIXGCN_EINVAL, "softmax_xent: null");
     if (n <= 0 || n_classes <= 0 || ldl < n_classes || ldd < n_classes)
         return fail(MIXGCN_EINVAL, "softmax_xent: sizes");
-    return launch_softmax_xent(logits, ldl, labels, n, n_classes, dlogits, ldd, loss,
+    return launch_softmax_xent(dtype, logits, ldl, labels, n, n_classes, dlogits, ldd, loss,
                                (hipStream_t)stream);
 }
 

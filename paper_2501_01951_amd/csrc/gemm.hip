@@ -63,30 +63,59 @@ __device__ inline void mma_step(const float* As, const float* Bs, int wm, int wn
 // starts the loads (addresses are clamped into the matrix, so they are unconditional and
 // nothing waits on them); value() applies the zero fill outside [0, rows) x [0, cols) and the
 // optional ReLU-derivative mask x * 1[R > 0] when the piece is written to LDS one step later.
-template <bool MASK>
+// Feature tensors are fp32 (float) or bf16 (uint16_t, widened to fp32 on the way to LDS and
+// rounded to nearest even on the way out); weights are always fp32.
+template <typename T>
+struct Raw4;
+template <>
+struct Raw4<float> {
+    float4 q;
+    __device__ inline float4 widen() const { return q; }
+};
+template <>
+struct Raw4<uint16_t> {
+    uint2 q;
+    __device__ inline float4 widen() const
+    {
+        return make_float4(__uint_as_float(q.x << 16), __uint_as_float(q.x & 0xFFFF0000u),
+                           __uint_as_float(q.y << 16), __uint_as_float(q.y & 0xFFFF0000u));
+    }
+};
+
+__device__ inline uint16_t bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7F800000u) != 0x7F800000u) u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ inline void store_elem(float* p, float x) { *p = x; }
+__device__ inline void store_elem(uint16_t* p, float x) { *p = bf16_rne(x); }
+
+template <bool MASK, typename T>
 struct Piece {
-    float4 v;
-    float4 m;
+    Raw4<T> v;
+    Raw4<T> m;
     int nvalid;  // leading components inside the matrix (0..4)
 
-    __device__ inline void issue(const float* __restrict__ M, int64_t ld, int64_t r, int c,
-                                 int64_t rows, int cols, const float* __restrict__ R, int64_t ldr)
+    __device__ inline void issue(const T* __restrict__ M, int64_t ld, int64_t r, int c,
+                                 int64_t rows, int cols, const T* __restrict__ R, int64_t ldr)
     {
         const bool ok = r < rows && c < cols;
         nvalid = ok ? (cols - c < 4 ? cols - c : 4) : 0;
         const int64_t rr = r < rows ? r : rows - 1;
         const int cc = c < cols ? c : 0;
-        v = *reinterpret_cast<const float4*>(M + rr * ld + cc);
-        if (MASK) m = *reinterpret_cast<const float4*>(R + rr * ldr + cc);
+        v = *reinterpret_cast<const Raw4<T>*>(M + rr * ld + cc);
+        if (MASK) m = *reinterpret_cast<const Raw4<T>*>(R + rr * ldr + cc);
     }
     __device__ inline float4 value() const
     {
-        float4 o = v;
+        float4 o = v.widen();
         if (MASK) {
-            o.x = m.x > 0.f ? o.x : 0.f;
-            o.y = m.y > 0.f ? o.y : 0.f;
-            o.z = m.z > 0.f ? o.z : 0.f;
-            o.w = m.w > 0.f ? o.w : 0.f;
+            const float4 mm = m.widen();
+            o.x = mm.x > 0.f ? o.x : 0.f;
+            o.y = mm.y > 0.f ? o.y : 0.f;
+            o.z = mm.z > 0.f ? o.z : 0.f;
+            o.w = mm.w > 0.f ? o.w : 0.f;
         }
         if (nvalid < 4) {
             if (nvalid < 1) o.x = 0.f;
@@ -113,10 +142,10 @@ __device__ inline unsigned xcd_local_index(unsigned bid, unsigned grid)
 //   MASK: A is multiplied by 1[R > 0] on the way in (dgrad of a ReLU layer).
 // A is staged transposed (reduction-major) so that the MFMA operand reads are unit-stride.
 // LDS tiles are double buffered: one barrier per reduction step.
-template <class S, bool B_TRANS, bool RELU, bool MASK>
+template <class S, bool B_TRANS, bool RELU, bool MASK, typename T>
 __global__ __launch_bounds__(kBlock) void rowblock_gemm_kernel(
-    const float* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb,
-    float* __restrict__ C, int64_t ldc, int64_t n, int KD, int MD, const float* __restrict__ R,
+    const T* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb,
+    T* __restrict__ C, int64_t ldc, int64_t n, int KD, int MD, const T* __restrict__ R,
     int64_t ldr, int n_col_tiles)
 {
     constexpr int LDA = S::BM + kLdsPad, LDB = S::BN + kLdsPad;
@@ -142,8 +171,8 @@ __global__ __launch_bounds__(kBlock) void rowblock_gemm_kernel(
     constexpr int BN_F4 = S::BN / 4;                           // float4 per staged B row
     constexpr int B_ROWS_PER_PASS = kBlock / BN_F4;
     constexpr int B_PASSES = (BK + B_ROWS_PER_PASS - 1) / B_ROWS_PER_PASS;
-    Piece<MASK> ra[A_PASSES];
-    Piece<false> rb[B_TRANS ? BT_PASSES : B_PASSES];
+    Piece<MASK, T> ra[A_PASSES];
+    Piece<false, float> rb[B_TRANS ? BT_PASSES : B_PASSES];
 
     auto issue_tiles = [&](int k0) {
 #pragma unroll
@@ -221,7 +250,7 @@ __global__ __launch_bounds__(kBlock) void rowblock_gemm_kernel(
                 if (r < n) {
                     float x = acc[tm][tn][v];
                     if (RELU) x = x > 0.f ? x : 0.f;
-                    C[r * ldc + c] = x;
+                    store_elem(&C[r * ldc + c], x);
                 }
             }
         }
@@ -230,10 +259,10 @@ __global__ __launch_bounds__(kBlock) void rowblock_gemm_kernel(
 // ---- slab kernel: P[slab][KD x MD] = A[rows of slab][KD]^T * (B (.) 1[R > 0])[rows][MD] --------
 // Both operands are staged exactly as they lie in memory (node-major), which already is the
 // reduction-major layout the MFMA operand reads want.
-template <class S, bool MASK>
+template <class S, bool MASK, typename T>
 __global__ __launch_bounds__(kBlock) void wgrad_slab_kernel(
-    const float* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb,
-    const float* __restrict__ R, int64_t ldr, float* __restrict__ P, int64_t n, int KD, int MD,
+    const T* __restrict__ A, int64_t lda, const T* __restrict__ B, int64_t ldb,
+    const T* __restrict__ R, int64_t ldr, float* __restrict__ P, int64_t n, int KD, int MD,
     int64_t rows_per_slab, int n_i_tiles, int n_j_tiles)
 {
     constexpr int LDA = S::BM + kLdsPad, LDB = S::BN + kLdsPad;
@@ -260,8 +289,8 @@ __global__ __launch_bounds__(kBlock) void wgrad_slab_kernel(
     constexpr int AM_F4 = S::BM / 4, BN_F4 = S::BN / 4;
     constexpr int A_RPP = kBlock / AM_F4, B_RPP = kBlock / BN_F4;
     constexpr int A_PASSES = (BK + A_RPP - 1) / A_RPP, B_PASSES = (BK + B_RPP - 1) / B_RPP;
-    Piece<false> ra[A_PASSES];
-    Piece<MASK> rb[B_PASSES];
+    Piece<false, T> ra[A_PASSES];
+    Piece<MASK, T> rb[B_PASSES];
 
     auto issue_tiles = [&](int64_t r0) {
 #pragma unroll
@@ -340,27 +369,27 @@ __global__ __launch_bounds__(kBlock) void wgrad_reduce_kernel(const float* __res
     }
 }
 
-// G <- G (.) 1[R > 0], four elements per thread.
-__global__ __launch_bounds__(kBlock) void relu_mask_kernel(float* __restrict__ G, int64_t ldg,
-                                                           const float* __restrict__ R,
-                                                           int64_t ldr, int64_t n, int m4)
+// G <- G (.) 1[R > 0], four elements per thread (bf16: zeroing keeps the bits exact).
+template <typename T>
+__global__ __launch_bounds__(kBlock) void relu_mask_kernel(T* __restrict__ G, int64_t ldg,
+                                                           const T* __restrict__ R, int64_t ldr,
+                                                           int64_t n, int m4)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n * m4) return;
     const int64_t r = i / m4;
     const int c = (int)(i % m4) * 4;
-    float4 g = *reinterpret_cast<float4*>(G + r * ldg + c);
-    const float4 h = *reinterpret_cast<const float4*>(R + r * ldr + c);
-    g.x = h.x > 0.f ? g.x : 0.f;
-    g.y = h.y > 0.f ? g.y : 0.f;
-    g.z = h.z > 0.f ? g.z : 0.f;
-    g.w = h.w > 0.f ? g.w : 0.f;
-    *reinterpret_cast<float4*>(G + r * ldg + c) = g;
+    T* gp = G + r * ldg + c;
+    const float4 h = reinterpret_cast<const Raw4<T>*>(R + r * ldr + c)->widen();
+    if (!(h.x > 0.f)) gp[0] = (T)0;
+    if (!(h.y > 0.f)) gp[1] = (T)0;
+    if (!(h.z > 0.f)) gp[2] = (T)0;
+    if (!(h.w > 0.f)) gp[3] = (T)0;
 }
 
-template <class S, bool B_TRANS>
-int launch_rowblock(bool relu, const float* A, int64_t lda, const float* B, int64_t ldb, float* C,
-                    int64_t ldc, int64_t n, int KD, int MD, const float* R, int64_t ldr,
+template <class S, bool B_TRANS, typename T>
+int launch_rowblock(bool relu, const T* A, int64_t lda, const float* B, int64_t ldb, T* C,
+                    int64_t ldc, int64_t n, int KD, int MD, const T* R, int64_t ldr,
                     hipStream_t s)
 {
     const int nct = (int)ceil_div(MD, S::BN);
@@ -368,7 +397,7 @@ int launch_rowblock(bool relu, const float* A, int64_t lda, const float* B, int6
     if (grid <= 0) return MIXGCN_OK;
     if (grid > 0x7FFFFFFF) return fail(MIXGCN_EINVAL, "update: too many row tiles");
 #define MIXGCN_ROWBLOCK(RELU, MASK)                                                              \
-    hipLaunchKernelGGL((rowblock_gemm_kernel<S, B_TRANS, RELU, MASK>), dim3((unsigned)grid),      \
+    hipLaunchKernelGGL((rowblock_gemm_kernel<S, B_TRANS, RELU, MASK, T>), dim3((unsigned)grid),   \
                        dim3(kBlock), 0, s, A, lda, B, ldb, C, ldc, n, KD, MD, R, ldr, nct)
     if (R) MIXGCN_ROWBLOCK(false, true);
     else if (relu) MIXGCN_ROWBLOCK(true, false);
@@ -382,47 +411,55 @@ int launch_rowblock(bool relu, const float* A, int64_t lda, const float* B, int6
 int launch_relu_mask(int dtype, void* G, int64_t ldg, const void* R, int64_t ldr, int64_t n,
                      int32_t m, hipStream_t s)
 {
-    if (dtype != MIXGCN_F32)
-        return fail(MIXGCN_EUNSUPPORTED, "relu mask: bf16 storage not built yet");
     const int m4 = (m + 3) / 4;  // rows are padded to 16 bytes, so the last vector is in bounds
     const int64_t total = n * m4;
     if (total == 0) return MIXGCN_OK;
-    hipLaunchKernelGGL(relu_mask_kernel, dim3((unsigned)ceil_div(total, kBlock)), dim3(kBlock), 0,
-                       s, (float*)G, ldg, (const float*)R, ldr, n, m4);
+    const dim3 grid((unsigned)ceil_div(total, kBlock));
+    if (dtype == MIXGCN_F32)
+        hipLaunchKernelGGL(relu_mask_kernel<float>, grid, dim3(kBlock), 0, s, (float*)G, ldg,
+                           (const float*)R, ldr, n, m4);
+    else
+        hipLaunchKernelGGL(relu_mask_kernel<uint16_t>, grid, dim3(kBlock), 0, s, (uint16_t*)G, ldg,
+                           (const uint16_t*)R, ldr, n, m4);
     MIXGCN_HIP_TRY(hipGetLastError());
     return MIXGCN_OK;
 }
 
-int launch_update(int op, int dtype, const void* A_, int64_t lda, const float* B, int64_t ldb,
-                  void* C_, int64_t ldc, int64_t n, int32_t k, int32_t m, const void* R_,
-                  int64_t ldr, float beta, hipStream_t s, Timer* timer)
+namespace {
+
+template <typename T>
+int update_typed(int op, const T* A, int64_t lda, const void* B_, int64_t ldb, void* C_,
+                 int64_t ldc, int64_t n, int32_t k, int32_t m, const T* R, int64_t ldr, float beta,
+                 hipStream_t s, Timer* timer)
 {
-    if (dtype != MIXGCN_F32) return fail(MIXGCN_EUNSUPPORTED, "update: bf16 storage not built yet");
-    const float* A = (const float*)A_;
-    float* C = (float*)C_;
-    const float* R = (const float*)R_;
     if (op == MIXGCN_OP_FWD || op == MIXGCN_OP_FWD_RELU) {
         const bool relu = op == MIXGCN_OP_FWD_RELU;
+        const float* B = (const float*)B_;
+        T* C = (T*)C_;
         if (timer) MIXGCN_TRY(timer->begin(kTimeUpdateFwd, s));
         if (m > 64)
-            MIXGCN_TRY((launch_rowblock<Shape128x128, false>(relu, A, lda, B, ldb, C, ldc, n, k, m,
-                                                            nullptr, 0, s)));
+            MIXGCN_TRY((launch_rowblock<Shape128x128, false, T>(relu, A, lda, B, ldb, C, ldc, n, k, m,
+                                                               nullptr, 0, s)));
         else
-            MIXGCN_TRY((launch_rowblock<Shape128x32, false>(relu, A, lda, B, ldb, C, ldc, n, k, m,
-                                                           nullptr, 0, s)));
+            MIXGCN_TRY((launch_rowblock<Shape128x32, false, T>(relu, A, lda, B, ldb, C, ldc, n, k, m,
+                                                              nullptr, 0, s)));
         if (timer) MIXGCN_TRY(timer->end(s));
     } else if (op == MIXGCN_OP_DGRAD) {
         // C[n x k] = (A (.) mask)[n x m] * W^T, W = B stored k x m: reduction over m
+        const float* B = (const float*)B_;
+        T* C = (T*)C_;
         if (timer) MIXGCN_TRY(timer->begin(kTimeUpdateDgrad, s));
         if (k > 64)
-            MIXGCN_TRY((launch_rowblock<Shape128x128, true>(false, A, lda, B, ldb, C, ldc, n, m, k,
-                                                           R, ldr, s)));
+            MIXGCN_TRY((launch_rowblock<Shape128x128, true, T>(false, A, lda, B, ldb, C, ldc, n, m, k,
+                                                              R, ldr, s)));
         else
-            MIXGCN_TRY((launch_rowblock<Shape128x32, true>(false, A, lda, B, ldb, C, ldc, n, m, k, R,
-                                                          ldr, s)));
+            MIXGCN_TRY((launch_rowblock<Shape128x32, true, T>(false, A, lda, B, ldb, C, ldc, n, m, k,
+                                                             R, ldr, s)));
         if (timer) MIXGCN_TRY(timer->end(s));
     } else if (op == MIXGCN_OP_WGRAD) {
-        // C[k x m] = beta C + A[n x k]^T (B (.) mask)[n x m]; here `B` of the ABI is passed as B
+        // C[k x m] = beta C + A[n x k]^T (B (.) mask)[n x m]
+        const T* B = (const T*)B_;
+        float* C = (float*)C_;
         const bool wide = m > 64;
         const int bm = 128, bn = wide ? 128 : 32;
         const int nit = (int)ceil_div(k, bm), njt = (int)ceil_div(m, bn);
@@ -440,9 +477,9 @@ int launch_update(int op, int dtype, const void* A_, int64_t lda, const float* B
         float* P = (float*)scratch;
         const unsigned grid = (unsigned)(n_slabs * tiles);
         if (timer) MIXGCN_TRY(timer->begin(kTimeUpdateWgrad, s));
-#define MIXGCN_WGRAD(SHAPE, MASK)                                                              \
-    hipLaunchKernelGGL((wgrad_slab_kernel<SHAPE, MASK>), dim3(grid), dim3(kBlock), 0, s, A, lda, B, \
-                       ldb, R, ldr, P, n, k, m, rows_per_slab, nit, njt)
+#define MIXGCN_WGRAD(SHAPE, MASK)                                                                \
+    hipLaunchKernelGGL((wgrad_slab_kernel<SHAPE, MASK, T>), dim3(grid), dim3(kBlock), 0, s, A, lda, \
+                       B, ldb, R, ldr, P, n, k, m, rows_per_slab, nit, njt)
         if (wide) {
             if (R) MIXGCN_WGRAD(Shape128x128, true);
             else MIXGCN_WGRAD(Shape128x128, false);
@@ -459,6 +496,19 @@ int launch_update(int op, int dtype, const void* A_, int64_t lda, const float* B
     }
     MIXGCN_HIP_TRY(hipGetLastError());
     return MIXGCN_OK;
+}
+
+}  // namespace
+
+int launch_update(int op, int dtype, const void* A, int64_t lda, const void* B, int64_t ldb,
+                  void* C, int64_t ldc, int64_t n, int32_t k, int32_t m, const void* R,
+                  int64_t ldr, float beta, hipStream_t s, Timer* timer)
+{
+    if (dtype == MIXGCN_F32)
+        return update_typed<float>(op, (const float*)A, lda, B, ldb, C, ldc, n, k, m,
+                                   (const float*)R, ldr, beta, s, timer);
+    return update_typed<uint16_t>(op, (const uint16_t*)A, lda, B, ldb, C, ldc, n, k, m,
+                                  (const uint16_t*)R, ldr, beta, s, timer);
 }
 
 }  // namespace mixgcn

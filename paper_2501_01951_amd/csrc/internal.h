@@ -145,11 +145,12 @@ int launch_aggregate(const mixgcn_graph* g, const Csr& m, int dtype, const void*
 int launch_relu_mask(int dtype, void* G, int64_t ldg, const void* R, int64_t ldr, int64_t n,
                      int32_t m, hipStream_t s);
 
-int launch_update(int op, int dtype, const void* A, int64_t lda, const float* B, int64_t ldb,
+int launch_update(int op, int dtype, const void* A, int64_t lda, const void* B, int64_t ldb,
                   void* C, int64_t ldc, int64_t n, int32_t k, int32_t m, const void* R,
                   int64_t ldr, float beta, hipStream_t s, Timer* timer);
 
-int launch_softmax_xent(const float* logits, int64_t ldl, const int32_t* labels, int64_t n,
-                        int32_t c, float* dlogits, int64_t ldd, double* loss, hipStream_t s);
+int launch_softmax_xent(int dtype, const void* logits, int64_t ldl, const int32_t* labels,
+                        int64_t n, int32_t c, void* dlogits, int64_t ldd, double* loss,
+                        hipStream_t s);
 
 }  // namespace mixgcn

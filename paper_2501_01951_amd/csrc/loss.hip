@@ -22,10 +22,21 @@ __device__ inline float wave_sum(float v)
     return v;
 }
 
-__global__ __launch_bounds__(kBlock) void xent_rows_kernel(const float* logits,
-                                                           int64_t ldl,
+__device__ inline float ld_elem(const float* p) { return *p; }
+__device__ inline float ld_elem(const uint16_t* p) { return __uint_as_float((uint32_t)*p << 16); }
+__device__ inline void st_elem(float* p, float x) { *p = x; }
+__device__ inline void st_elem(uint16_t* p, float x)
+{
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7F800000u) != 0x7F800000u) u += 0x7FFFu + ((u >> 16) & 1u);
+    *p = (uint16_t)(u >> 16);
+}
+
+// T: storage type of logits and dlogits (fp32, or bf16 widened to fp32 for the arithmetic).
+template <typename T>
+__global__ __launch_bounds__(kBlock) void xent_rows_kernel(const T* logits, int64_t ldl,
                                                            const int32_t* __restrict__ labels,
-                                                           int64_t n, int c, float* dlogits,
+                                                           int64_t n, int c, T* dlogits,
                                                            int64_t ldd, double* __restrict__ part)
 {
     __shared__ double wsum[kBlock / kWave];
@@ -35,19 +46,19 @@ __global__ __launch_bounds__(kBlock) void xent_rows_kernel(const float* logits,
     const float inv_n = 1.0f / (float)n;
     double acc = 0.0;
     for (int64_t r = r_begin + w; r < r_end; r += kBlock / kWave) {
-        const float* x = logits + r * ldl;
+        const T* x = logits + r * ldl;
         float mx = -INFINITY;
-        for (int j = lane; j < c; j += kWave) mx = fmaxf(mx, x[j]);
+        for (int j = lane; j < c; j += kWave) mx = fmaxf(mx, ld_elem(x + j));
         mx = wave_max(mx);
         float se = 0.f;
-        for (int j = lane; j < c; j += kWave) se += expf(x[j] - mx);
+        for (int j = lane; j < c; j += kWave) se += expf(ld_elem(x + j) - mx);
         se = wave_sum(se);
         const float lse = mx + logf(se);
         const int y = labels[r];
-        const float xy = x[y];
+        const float xy = ld_elem(x + y);
         for (int j = lane; j < c; j += kWave) {
-            const float p = expf(x[j] - lse);
-            dlogits[r * ldd + j] = (p - (j == y ? 1.f : 0.f)) * inv_n;
+            const float p = expf(ld_elem(x + j) - lse);
+            st_elem(dlogits + r * ldd + j, (p - (j == y ? 1.f : 0.f)) * inv_n);
         }
         acc += (double)(lse - xy);
     }
@@ -74,14 +85,21 @@ __global__ __launch_bounds__(kBlock) void xent_final_kernel(const double* __rest
 
 }  // namespace
 
-int launch_softmax_xent(const float* logits, int64_t ldl, const int32_t* labels, int64_t n,
-                        int32_t c, float* dlogits, int64_t ldd, double* loss, hipStream_t s)
+int launch_softmax_xent(int dtype, const void* logits, int64_t ldl, const int32_t* labels,
+                        int64_t n, int32_t c, void* dlogits, int64_t ldd, double* loss,
+                        hipStream_t s)
 {
     const int64_t n_parts = ceil_div(n, kRowsPerBlock);
     void* scratch = nullptr;
     MIXGCN_TRY(get_scratch(1, (size_t)n_parts * sizeof(double), &scratch));
-    hipLaunchKernelGGL(xent_rows_kernel, dim3((unsigned)n_parts), dim3(kBlock), 0, s, logits, ldl,
-                       labels, n, c, dlogits, ldd, (double*)scratch);
+    if (dtype == MIXGCN_F32)
+        hipLaunchKernelGGL(xent_rows_kernel<float>, dim3((unsigned)n_parts), dim3(kBlock), 0, s,
+                           (const float*)logits, ldl, labels, n, c, (float*)dlogits, ldd,
+                           (double*)scratch);
+    else
+        hipLaunchKernelGGL(xent_rows_kernel<uint16_t>, dim3((unsigned)n_parts), dim3(kBlock), 0, s,
+                           (const uint16_t*)logits, ldl, labels, n, c, (uint16_t*)dlogits, ldd,
+                           (double*)scratch);
     hipLaunchKernelGGL(xent_final_kernel, dim3(1), dim3(kBlock), 0, s, (const double*)scratch,
                        n_parts, n, loss);
     MIXGCN_HIP_TRY(hipGetLastError());

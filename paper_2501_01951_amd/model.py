@@ -12,8 +12,10 @@ def padded_rows(n: int, f: int, dtype, device):
     pitch the same column slice of every row falls on a few L2 channels only; an odd pitch
     spreads it over all of them (measured: 3.9 -> 3.1 ms for the 256-column aggregation)."""
     esize = torch.empty(0, dtype=dtype).element_size()
-    if f * esize <= 128:  # rows of at most one line are left packed
-        return torch.empty(n, f, device=device, dtype=dtype)
+    if f * esize <= 128:  # rows of at most one line are left packed (16-byte granules)
+        per16 = 16 // esize
+        ld = (f + per16 - 1) // per16 * per16
+        return torch.empty(n, ld, device=device, dtype=dtype)[:, :f]
     lines = (f * esize + 127) // 128
     if lines % 2 == 0:
         lines += 1
@@ -52,7 +54,8 @@ class GCNStep:
         self.z = [rows(w.shape[1] if o == B.UPDATE_FIRST else w.shape[0])
                   for w, o in zip(self.w, self.order)]
         self.h = [x_p] + [rows(w.shape[1]) for w in self.w]
-        self.dw = [torch.empty_like(w) for w in self.w]
+        # dW shares W's leading dimension (one ld_w in the layer descriptor)
+        self.dw = [torch.empty_strided(w.shape, w.stride(), dtype=w.dtype, device=dev) for w in self.w]
         self.dlogits = rows(self.w[L - 1].shape[1])
         self.dh = [None] + [rows(self.w[l].shape[0]) for l in range(1, L)]
         self.loss = torch.zeros(1, dtype=torch.float64, device=dev)

@@ -6,7 +6,7 @@ import pytest
 
 import graphgen as gg
 import oracle
-from parity import RTOL_F32, assert_close, rel_fro, say
+from parity import RTOL_BF16, RTOL_F32, assert_close, rel_fro, say
 
 pytestmark = pytest.mark.gpu
 
@@ -402,3 +402,92 @@ def test_config2_shape_three_layer_gcn_scale17(mg, reorder):
           gg.glorot(gg.MASTER_SEED, 12, 256, 16)]
     y = gg.labels(gg.MASTER_SEED, 5, n, 16)
     check_model(mg, "c2@17", src, dst, n, x, ws, y, 4, reorder)
+
+
+# ------------------------------------------------------------------------------------------
+# bf16 storage (config 5 shape): every n x F tensor is stored in bf16, arithmetic is fp32
+# ------------------------------------------------------------------------------------------
+def bf16_round(a):
+    """numpy fp32 -> values representable in bf16 (round to nearest even), as fp32."""
+    return torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).to(torch.float32).numpy()
+
+
+def dev_bf16(a, ld=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16)
+    if ld is None:
+        return t.cuda()
+    out = torch.zeros(a.shape[0], ld, dtype=torch.bfloat16, device="cuda")
+    out[:, :a.shape[1]] = t.cuda()
+    return out[:, :a.shape[1]]
+
+
+@pytest.mark.parametrize("f,ld", [(8, 8), (64, 64), (100, 128), (256, 256), (512, 520)])
+def test_aggregate_bf16(mg, rmat15, f, ld):
+    og, g = rmat15
+    say(f"aggregate bf16 f={f} ld={ld}")
+    h = bf16_round(gg.normal(71, f, og.n, f))
+    hd = dev_bf16(h, ld)
+    z = torch.full((og.n, ld), 7.0, dtype=torch.bfloat16, device="cuda")[:, :f]
+    mg.aggregate(g, hd, z)
+    ref = oracle.spmm(og, h.astype(np.float64), q=oracle.Q_BF16)
+    assert_close(z.float().cpu().numpy(), ref, RTOL_BF16, f"Z bf16 f={f}")
+
+
+@pytest.mark.parametrize("n,k,m", [(3000, 100, 256), (2048, 256, 256), (1111, 256, 47), (500, 64, 8)])
+def test_update_ops_bf16(mg, n, k, m):
+    say(f"update bf16 n={n} k={k} m={m}")
+    ldk, ldm = (k + 7) // 8 * 8, (m + 7) // 8 * 8
+    z = bf16_round(gg.normal(72, 1, n, k))
+    w = gg.glorot(72, 2, k, m, ld=(m + 3) // 4 * 4)
+    gr = bf16_round(gg.normal(72, 3, n, m))
+    z64, w64, g64 = z.astype(np.float64), w[:, :m].astype(np.float64), gr.astype(np.float64)
+    zd, gd, wd = dev_bf16(z, ldk), dev_bf16(gr, ldm), dev(w)[:, :m]
+    out = torch.zeros(n, ldm, dtype=torch.bfloat16, device="cuda")[:, :m]
+    mg.update(mg.OP_FWD_RELU, zd, wd, out, n, k, m)
+    href = oracle.update_fwd(z64, w64, True, q=oracle.Q_BF16)
+    assert_close(out.float().cpu().numpy(), href, RTOL_BF16, "fwd relu bf16")
+    hd = dev_bf16(href.astype(np.float32), ldm)
+    dp = oracle.relu_grad(g64, href)
+    dz = torch.zeros(n, ldk, dtype=torch.bfloat16, device="cuda")[:, :k]
+    mg.update(mg.OP_DGRAD, gd, wd, dz, n, k, m, relu_ref=hd)
+    assert_close(dz.float().cpu().numpy(), oracle.update_dgrad(dp, w64, q=oracle.Q_BF16), RTOL_BF16,
+                 "dgrad bf16")
+    dw = torch.zeros(k, wd.stride(0), device="cuda")[:, :m]
+    mg.update(mg.OP_WGRAD, zd, gd, dw, n, k, m, relu_ref=hd)
+    assert_close(dw.cpu().numpy(), oracle.update_wgrad(z64, dp), 1e-3, "wgrad bf16 inputs, fp32 sum")
+
+
+def test_softmax_xent_bf16(mg):
+    n, c = 5000, 47
+    x = bf16_round(gg.normal(73, c, n, c) * 3)
+    y = gg.labels(73, 5, n, c)
+    loss_ref, d_ref = oracle.softmax_xent(x.astype(np.float64), y)
+    d = torch.zeros(n, 48, dtype=torch.bfloat16, device="cuda")[:, :c]
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    mg.softmax_xent(dev_bf16(x, 48), dev(y), d, loss)
+    assert abs(loss.item() - loss_ref) <= 1e-5 * abs(loss_ref)
+    assert_close(d.float().cpu().numpy(), d_ref, RTOL_BF16, "dlogits bf16")
+
+
+@pytest.mark.parametrize("reorder", [False, True])
+def test_config5_shape_bf16_three_layer_gcn_scale16(mg, reorder):
+    say(f"config 5 shape (bf16 storage) at R-MAT scale 16, reorder={reorder}")
+    src, dst, n = gg.config_graph("c5", scale_override=16)
+    x = bf16_round(gg.uniform(gg.MASTER_SEED, 1, n, 100))
+    ws = [gg.glorot(gg.MASTER_SEED, 10, 100, 256), gg.glorot(gg.MASTER_SEED, 11, 256, 256),
+          gg.glorot(gg.MASTER_SEED, 12, 256, 47, ld=48)[:, :47]]
+    y = gg.labels(gg.MASTER_SEED, 5, n, 47)
+    og = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n)))
+    ref = oracle.gcn_step(og, x, [np.ascontiguousarray(w) for w in ws], y, q=oracle.Q_BF16)
+    g = _gpu_graph(mg, src, dst, n)
+    wd = [dev(gg.glorot(gg.MASTER_SEED, 10, 100, 256)), dev(gg.glorot(gg.MASTER_SEED, 11, 256, 256)),
+          dev(gg.glorot(gg.MASTER_SEED, 12, 256, 47, ld=48))[:, :47]]
+    step = mg.GCNStep(g, dev_bf16(x), wd, dev(y), n_chunks=2, reorder=reorder)
+    step.step()
+    torch.cuda.synchronize()
+    assert abs(step.loss.item() - ref["loss"]) <= 2e-3 * abs(ref["loss"])
+    assert_close(step.h[-1].float().cpu().numpy(), ref["logits"], RTOL_BF16, "logits bf16")
+    for l in range(3):
+        assert rel_fro(step.dw[l].cpu().numpy(), ref["dW"][l]) < RTOL_BF16, f"dW[{l}] bf16"
+    step.pipe.free()
+    g.free()
