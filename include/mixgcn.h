@@ -184,6 +184,13 @@ int mixgcn_softmax_xent(int dtype, const void* logits, int64_t ldl, const int32_
 /* Helpers. */
 int mixgcn_graph_info(const mixgcn_graph* g, mixgcn_graph_view* out);
 int mixgcn_graph_free(mixgcn_graph* g);
+/*
+ * A stream whose kernels run on a subset of the compute units, for splitting the GPU between
+ * the sparse and the dense half of the pipeline: CU c is enabled iff (c / 8) % groups lies in
+ * [lo, hi).  Default priority.  Destroy with mixgcn_stream_destroy (after its work is done).
+ */
+int mixgcn_stream_create_cu_subset(int lo, int hi, int groups, void** stream);
+int mixgcn_stream_destroy(void* stream);
 /* Two streams for the chunk pipeline: `primary` runs the aggregation, `secondary` the update. */
 int mixgcn_pipeline_create(void* primary_stream, void* secondary_stream, mixgcn_pipeline** out);
 int mixgcn_pipeline_destroy(mixgcn_pipeline* p);

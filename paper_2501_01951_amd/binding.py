@@ -77,12 +77,15 @@ def load_library():
     lib.mixgcn_graph_free.argtypes = [vp]
     lib.mixgcn_pipeline_create.argtypes = [vp, vp, ctypes.POINTER(vp)]
     lib.mixgcn_pipeline_destroy.argtypes = [vp]
+    lib.mixgcn_stream_create_cu_subset.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                   ctypes.POINTER(vp)]
+    lib.mixgcn_stream_destroy.argtypes = [vp]
     lib.mixgcn_pipeline_timing.argtypes = [vp, ctypes.c_int]
     lib.mixgcn_pipeline_timing_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                                 ctypes.POINTER(ctypes.c_int64)]
     for name in ("build_csr", "normalize", "aggregate", "update", "layer_fwd", "layer_bwd",
                  "softmax_xent", "graph_info", "graph_free", "pipeline_create", "pipeline_destroy",
-                 "pipeline_timing", "pipeline_timing_read"):
+                 "pipeline_timing", "pipeline_timing_read", "stream_create_cu_subset", "stream_destroy"):
         getattr(lib, "mixgcn_" + name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -185,6 +188,15 @@ class Graph:
             self.free()
         except Exception:
             pass
+
+
+def cu_subset_stream(lo: int, hi: int, groups: int):
+    """torch stream whose kernels run only on the CUs c with (c / 8) % groups in [lo, hi).
+    The stream lives until the process ends."""
+    h = ctypes.c_void_p()
+    _check(load_library().mixgcn_stream_create_cu_subset(lo, hi, groups, ctypes.byref(h)),
+           "stream_create_cu_subset")
+    return torch.cuda.ExternalStream(h.value)
 
 
 class Pipeline:

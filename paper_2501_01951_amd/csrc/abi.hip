@@ -323,6 +323,36 @@ int mixgcn_softmax_xent(int dtype, const void* logits, int64_t ldl, const int32_
                                (hipStream_t)stream);
 }
 
+int mixgcn_stream_create_cu_subset(int lo, int hi, int groups, void** stream)
+{
+    if (!stream) return fail(MIXGCN_EINVAL, "stream_create_cu_subset: null");
+    *stream = nullptr;
+    if (groups < 1 || groups > 8 || lo < 0 || hi > groups || lo >= hi)
+        return fail(MIXGCN_EINVAL, "stream_create_cu_subset: need 0 <= lo < hi <= groups <= 8");
+    int dev = 0, n_cu = 0;
+    MIXGCN_HIP_TRY(hipGetDevice(&dev));
+    MIXGCN_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    std::vector<uint32_t> mask((size_t)(n_cu + 31) / 32, 0u);
+    // CU c is enabled iff (c / 8) % groups lies in [lo, hi): blocks of 8 consecutive CU indices
+    // alternate between the subsets, which selects the same share of every XCD whether the
+    // runtime numbers the CUs XCD by XCD or round-robin across the XCDs.
+    for (int c = 0; c < n_cu; ++c) {
+        const int gsel = (c / 8) % groups;
+        if (gsel >= lo && gsel < hi) mask[(size_t)c / 32] |= 1u << (c % 32);
+    }
+    hipStream_t s = nullptr;
+    MIXGCN_HIP_TRY(hipExtStreamCreateWithCUMask(&s, (uint32_t)mask.size(), mask.data()));
+    *stream = (void*)s;
+    return MIXGCN_OK;
+}
+
+int mixgcn_stream_destroy(void* stream)
+{
+    if (!stream) return MIXGCN_OK;
+    MIXGCN_HIP_TRY(hipStreamDestroy((hipStream_t)stream));
+    return MIXGCN_OK;
+}
+
 int mixgcn_pipeline_create(void* primary_stream, void* secondary_stream, mixgcn_pipeline** out)
 {
     if (!out) return fail(MIXGCN_EINVAL, "pipeline_create: out is null");

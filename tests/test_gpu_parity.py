@@ -491,3 +491,121 @@ def test_config5_shape_bf16_three_layer_gcn_scale16(mg, reorder):
         assert rel_fro(step.dw[l].cpu().numpy(), ref["dW"][l]) < RTOL_BF16, f"dW[{l}] bf16"
     step.pipe.free()
     g.free()
+
+
+# ------------------------------------------------------------------------------------------
+# full benchmark sizes
+# ------------------------------------------------------------------------------------------
+def test_config2_full_size_three_layer_gcn(mg):
+    """Config 2 at its full size (R-MAT scale 20), in the launch configuration bench.py times
+    (GCNStep defaults), against a full oracle run."""
+    say("config 2 full size: generating inputs")
+    src, dst, n = gg.config_graph("c2")
+    x = gg.normal(gg.MASTER_SEED, 1, n, 128)
+    ws = [gg.glorot(gg.MASTER_SEED, 10, 128, 256), gg.glorot(gg.MASTER_SEED, 11, 256, 256),
+          gg.glorot(gg.MASTER_SEED, 12, 256, 16)]
+    y = gg.labels(gg.MASTER_SEED, 5, n, 16)
+    say("config 2 full size: oracle + GPU step")
+    check_model(mg, "c2", src, dst, n, x, ws, y, 1, True)
+
+
+def test_config3_full_size_single_layer(mg):
+    """Config 3: one layer forward + backward at N = 2^24 on a 128-column slice of a 1024-wide
+    layer.  The oracle cannot run the dense products at this size, so it computes Z = A_hat H in
+    full (O(nnz F)), and then checks exactly: sampled rows of H' and dZ, sampled rows of dH
+    (from oracle dZ rows of their neighbors), and sampled columns of dW (a column of dW needs
+    only one column of P = Z W, of the mask and of G).  Plus the eigenvector identity on A_hat."""
+    free, total = torch.cuda.mem_get_info()
+    if total < 200e9:
+        pytest.skip("needs the 288 GB of an MI355X")
+    scale, k, m = 24, 128, 1024
+    n = 1 << scale
+    say("config 3: generating the graph")
+    src, dst = gg.rmat_edges(gg.MASTER_SEED, scale, 8 * n)
+    say("config 3: oracle CSR")
+    og = oracle.normalize(oracle.build_csr(src, dst, n))
+    say(f"config 3: nnz={og.nnz}; GPU CSR")
+    g = _gpu_graph(mg, src, dst, n)
+    a = g.arrays()
+    assert np.array_equal(a["rowptr"].cpu().numpy(), og.rowptr)
+    assert np.array_equal(u32(a["col"]), og.col)
+    assert np.array_equal(a["val"].cpu().numpy(), og.val_f32)
+    del a
+    say("config 3: generating H, W, G")
+    h = gg.normal(gg.MASTER_SEED, 1, n, k)
+    w = gg.glorot(gg.MASTER_SEED, 10, k, m)
+    from paper_2501_01951_amd.model import padded_rows
+
+    hd = padded_rows(n, k, torch.float32, "cuda")
+    hd.copy_(torch.from_numpy(h))
+    gd = padded_rows(n, m, torch.float32, "cuda")
+    rng_cols = np.sort(np.random.default_rng(3).choice(m, 6, replace=False))
+    rows_s = np.sort(np.random.default_rng(4).choice(n, 64, replace=False))
+    blk = 1 << 20
+    g_cols = np.empty((n, len(rng_cols)), dtype=np.float32)
+    g_rows = {}
+    for b0 in range(0, n, blk):  # G is generated and uploaded block by block (68.7 GB in all)
+        gb = np.empty((blk, m), dtype=np.float32)
+        gg._load().gg_fill_normal(gg.MASTER_SEED, 3 + (b0 // blk), blk, m, m, gg._ptr(gb))
+        gd[b0:b0 + blk].copy_(torch.from_numpy(gb))
+        g_cols[b0:b0 + blk] = gb[:, rng_cols]
+        for r in rows_s[(rows_s >= b0) & (rows_s < b0 + blk)]:
+            g_rows[int(r)] = gb[r - b0].copy()
+        if (b0 // blk) % 4 == 0:
+            say(f"config 3: G block {b0 // blk + 1} of {n // blk}")
+    wd = dev(w)
+    zd = padded_rows(n, k, torch.float32, "cuda")
+    outd = padded_rows(n, m, torch.float32, "cuda")
+    dhd = padded_rows(n, k, torch.float32, "cuda")
+    dwd = torch.empty(k, m, device="cuda")
+    pipe = mg.Pipeline()
+    say("config 3: GPU layer forward + backward")
+    mg.layer_fwd(g, hd, wd, zd, outd, pipe, relu=True, n_chunks=1)
+    torch.cuda.synchronize()
+    z_gpu_rows = zd[torch.from_numpy(rows_s).cuda()].cpu().numpy()
+    out_cols = outd[:, torch.from_numpy(rng_cols).cuda()].cpu().numpy()
+    out_rows = outd[torch.from_numpy(rows_s).cuda()].cpu().numpy()
+    mg.layer_bwd(g, zd, outd, wd, gd, dwd, dhd, pipe, relu=True, n_chunks=1)
+    torch.cuda.synchronize()
+    say("config 3: oracle Z (full SpMM)")
+    z_ref = oracle.spmm(og, h.astype(np.float64))
+    w64 = w.astype(np.float64)
+    assert_close(z_gpu_rows, z_ref[rows_s], RTOL_F32, "Z rows")
+    # eigenvector identity at full size, through the GPU kernel
+    say("config 3: identity A_hat d^(1/2) = d^(1/2)")
+    r4 = np.sqrt(og.deg.astype(np.float64))[:, None].repeat(4, axis=1).astype(np.float32)
+    z4 = torch.empty(n, 4, device="cuda")
+    mg.aggregate(g, dev(r4), z4)
+    np.testing.assert_allclose(z4.cpu().numpy(), r4, rtol=3e-5)
+    # sampled rows of H' and dZ
+    p_rows = z_ref[rows_s] @ w64
+    assert_close(out_rows, np.maximum(p_rows, 0), RTOL_F32, "H' rows")
+    g_rows_m = np.stack([g_rows[int(r)] for r in rows_s]).astype(np.float64)
+    dp_rows = g_rows_m * (out_rows > 0)  # the mask both sides use is the stored H'
+    dz_rows = zd[torch.from_numpy(rows_s).cuda()].cpu().numpy()
+    assert_close(dz_rows, dp_rows @ w64.T, RTOL_F32, "dZ rows")
+    # sampled columns of dW: exact, a column needs one column of P, of the mask and of G
+    say("config 3: dW columns")
+    dw_gpu = dwd.cpu().numpy()
+    for ci, j in enumerate(rng_cols):
+        pj = z_ref @ w64[:, j]
+        mask_ref = pj > 0
+        mask_gpu = out_cols[:, ci] > 0
+        flips = int((mask_ref != mask_gpu).sum())
+        if flips:
+            assert np.max(np.abs(pj[mask_ref != mask_gpu])) < 1e-4 * np.sqrt(np.mean(pj * pj))
+        col = z_ref.T @ (g_cols[:, ci].astype(np.float64) * mask_gpu)
+        assert_close(dw_gpu[:, j], col, RTOL_F32, f"dW[:, {j}] ({flips} ReLU flips)")
+    # sampled rows of dH = A_hat^T dZ (A_hat symmetric): low-degree rows, from oracle dZ rows
+    say("config 3: dH rows")
+    small = [int(r) for r in rows_s if og.deg[r] <= 64][:24]
+    dh_gpu = dhd[torch.tensor(small).cuda()].cpu().numpy()
+    for i, r in enumerate(small):
+        nb = og.col[og.rowptr[r]:og.rowptr[r + 1]].astype(np.int64)
+        out_nb = outd[torch.from_numpy(nb).cuda()].cpu().numpy()
+        g_nb = gd[torch.from_numpy(nb).cuda()].cpu().numpy().astype(np.float64)
+        dz_nb = (g_nb * (out_nb > 0)) @ w64.T
+        ref = og.val[og.rowptr[r]:og.rowptr[r + 1]] @ dz_nb
+        assert_close(dh_gpu[i], ref, RTOL_F32, f"dH row {r}")
+    pipe.free()
+    g.free()
