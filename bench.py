@@ -26,6 +26,21 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 
+def measured_traffic(config, width):
+    """HBM bytes per launch of the dominant kernel, taken from the committed rocprofv3 --pmc
+    summary of this same command (counters cannot be read from inside the run)."""
+    if config != "c2" or width != 256:
+        return None
+    path = os.path.join(ROOT, "profiles", "c2_aggregate_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split()[1])
+    except OSError:
+        pass
+    return None
+
+
 def model_dims(name):
     if name == "c2":
         return [128, 256, 256, 16]
@@ -68,6 +83,72 @@ def cpu_baseline(name, scale, seed):
     }
 
 
+def bench_single_layer(args, mg, dev):
+    """Config 3 (not the default line): one layer forward + backward on a 128-column slice of a
+    1024-wide layer, R-MAT scale 24 with 8 N directed edges.  H comes from the seeded generator;
+    the 68.7 GB upstream gradient G is drawn on the device (its values do not matter here)."""
+    import numpy as np
+    import torch
+
+    import graphgen as gg
+    from paper_2501_01951_amd.model import padded_rows
+
+    scale = args.scale or 24
+    n, k, m = 1 << scale, 128, 1024
+    src, dst = gg.rmat_edges(args.seed, scale, 8 * n)
+    g = mg.build_csr(dev(src.view(np.int32)), dev(dst.view(np.int32)), n)
+    mg.normalize(g)
+    nnz = g.nnz
+    hd = padded_rows(n, k, torch.float32, "cuda")
+    hd.copy_(torch.from_numpy(gg.normal(args.seed, 1, n, k)))
+    wd = dev(gg.glorot(args.seed, 10, k, m))
+    gd = padded_rows(n, m, torch.float32, "cuda")
+    gd.normal_()
+    zd = padded_rows(n, k, torch.float32, "cuda")
+    outd = padded_rows(n, m, torch.float32, "cuda")
+    dhd = padded_rows(n, k, torch.float32, "cuda")
+    dwd = torch.empty(k, m, device="cuda")
+    pipe = mg.Pipeline()
+
+    def step():
+        mg.layer_fwd(g, hd, wd, zd, outd, pipe, relu=True, n_chunks=args.chunks)
+        mg.layer_bwd(g, zd, outd, wd, gd, dwd, dhd, pipe, relu=True, n_chunks=args.chunks)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    pipe.timing(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    names = ["agg_g4", "agg_g8", "agg_g16", "agg_g32", "agg_g64", "update_fwd", "update_dgrad",
+             "update_wgrad"]
+    kinds = {}
+    for i, nm in enumerate(names):
+        ms, cnt = pipe.timing_read(i)
+        if cnt:
+            kinds[nm] = {"total_ms": ms, "launches": cnt, "avg_ms": ms / cnt}
+    agg_ms = kinds["agg_g32"]["avg_ms"]
+    algo = 8.0 * nnz + 2.0 * n * k * 4 + 8.0 * n
+    print(json.dumps({
+        "metric": "GCN layer fwd+bwd edges*feat/s", "value": nnz * k / dt, "unit": "edges*feat/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"c3: one GCN layer 128->1024 fwd+bwd, R-MAT scale {scale}, N={n}, "
+                               f"nnz(A_hat)={nnz}", "n_nodes": n, "nnz": nnz},
+        "kernels": kinds,
+        "roofline": {"bound": "hbm", "achieved": algo / (agg_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": algo / (agg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": None, "kernel": "aggregate_kernel, 128 fp32 columns",
+                     "avg_launch_ms": agg_ms, "algorithmic_bytes_per_launch": algo},
+        "gemm_tflops": {kk: 2.0 * n * k * m / (kinds[kk]["avg_ms"] * 1e-3) / 1e12
+                        for kk in ("update_fwd", "update_dgrad", "update_wgrad")},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -94,10 +175,12 @@ def main():
     mg.load_library()
     torch.cuda.set_device(0)
 
-    src, dst, n, x, ws, y, dims = make_inputs(args.config, args.scale, args.seed)
-
     def dev(a):
         return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    if args.config == "c3":
+        return bench_single_layer(args, mg, dev)
+    src, dst, n, x, ws, y, dims = make_inputs(args.config, args.scale, args.seed)
 
     s_d, d_d = dev(src.view(np.int32)), dev(dst.view(np.int32))
     torch.cuda.synchronize()
@@ -158,8 +241,9 @@ def main():
         achieved = per_launch / avg_s / 1e9
         roofline = {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-            "kernel": f"aggregate_kernel<G={gsz}> ({f} fp32 columns)",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": measured_traffic(args.config, f) if args.chunks == 1 else None,
+            "kernel": f"aggregate_kernel<8, {gsz}, 0, false> ({f} fp32 columns)",
             "avg_launch_ms": agg[dom]["avg_ms"], "launches": agg[dom]["launches"],
             "algorithmic_bytes_per_launch": per_launch,
             "gather_bytes_per_launch": (nnz * (8.0 + f * 4) + n * f * 4) / launches_per_layer_call,

@@ -20,8 +20,6 @@
 // XCD mapping.  The slice index is taken from the low bits of the workgroup index.  Workgroups
 // are dealt round-robin to the 8 XCDs, so every slice is pinned to a fixed subset of the XCDs
 // and each private L2 caches only its own part of the hot feature rows.
-#include <cstdlib>
-
 #include "device_utils.h"
 #include "internal.h"
 
@@ -110,20 +108,23 @@ __device__ inline void reduce_subgroups(float* v)
 
 // Partial-sum slots: [span in call][head = 0 / tail = 1][part_stride] fp32, indexed by the
 // column offset within the pass.
-template <int LPR, int DT, bool HAS_EMPTY, int DEPTH>
+// GF = lanes that would span the whole pass (its width class: 4 GF fp32 or 8 GF bf16 columns);
+// it fixes the stride of the partial-sum slots and names the instantiation in profiles.
+template <int LPR, int GF, int DT, bool HAS_EMPTY>
 __global__ __launch_bounds__(kBlock) void aggregate_kernel(
     const int64_t* __restrict__ rowptr, const uint2* __restrict__ cv,
     const uint32_t* __restrict__ grp_row, const void* __restrict__ H, int64_t ldh,
     void* __restrict__ Z, int64_t ldz, int c0, int width, int64_t row_begin, int64_t row_end,
     int64_t e_begin, int64_t e_end, int64_t span_first, int64_t n_spans,
-    float* __restrict__ partials, int n_slices, int part_stride, int relu)
+    float* __restrict__ partials, int n_slices, int relu)
 {
     using F = Feat<DT>;
     constexpr int VEC = F::VEC;
+    constexpr int part_stride = GF * VEC;
     constexpr int EPB = kWave / LPR;                  // entries per batch (= sub-groups)
     constexpr int64_t SPAN = (int64_t)kBatchesPerSpan * EPB;
     constexpr int PW = LPR * VEC;                     // columns of one slice
-    constexpr int D = (DEPTH * EPB <= kWave) ? DEPTH : (kWave / EPB);  // slots per round
+    constexpr int D = (kDepth * EPB <= kWave) ? kDepth : (kWave / EPB);  // slots per round
     constexpr uint64_t kLane0Mask = LPR == 64 ? 1ull
                                   : LPR == 32 ? 0x0000000100000001ull
                                   : LPR == 16 ? 0x0001000100010001ull
@@ -327,17 +328,16 @@ __global__ __launch_bounds__(kBlock) void zero_rows_kernel(void* Z, int64_t ldz,
 template <int LPR>
 constexpr int64_t span_entries() { return (int64_t)kBatchesPerSpan * (kWave / LPR); }
 
-template <int LPR, int DT>
+template <int LPR, int GF, int DT>
 int launch_main(const Csr& m, const void* H, int64_t ldh, void* Z, int64_t ldz, int c0, int width,
-                int64_t r0, int64_t r1, int64_t e0, int64_t e1, float* partials, int part_stride,
-                int relu, hipStream_t s, Timer* timer)
+                int64_t r0, int64_t r1, int64_t e0, int64_t e1, float* partials, int relu,
+                hipStream_t s, Timer* timer)
 {
     constexpr int PW = LPR * Feat<DT>::VEC;
     constexpr int64_t SPAN = span_entries<LPR>();
-    // timed by the width class of the whole pass (lanes that would span it), not of a slice
-    const int gf = part_stride / Feat<DT>::VEC;
-    const int kind = gf == 4 ? kTimeAggG4 : gf == 8 ? kTimeAggG8 : gf == 16 ? kTimeAggG16
-                     : gf == 32 ? kTimeAggG32 : kTimeAggG64;
+    // timed by the width class of the whole pass
+    constexpr int kind = GF == 4 ? kTimeAggG4 : GF == 8 ? kTimeAggG8 : GF == 16 ? kTimeAggG16
+                         : GF == 32 ? kTimeAggG32 : kTimeAggG64;
     const int n_slices = (int)ceil_div(width, PW);
     const int64_t span_first = e0 / SPAN;
     const int64_t n_spans = ceil_div(e1, SPAN) - span_first;
@@ -345,20 +345,14 @@ int launch_main(const Csr& m, const void* H, int64_t ldh, void* Z, int64_t ldz, 
     if (grid64 > 0x7FFFFFFF) return fail(MIXGCN_EINVAL, "aggregate: grid too large");
     const unsigned grid = (unsigned)grid64;
     if (timer) MIXGCN_TRY(timer->begin(kind, s));
-#define MIXGCN_AGG_LAUNCH(EMPTY, DD)                                                            \
-    hipLaunchKernelGGL((aggregate_kernel<LPR, DT, EMPTY, DD>), dim3(grid), dim3(kBlock), 0, s,   \
-                       m.rowptr, m.cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,     \
-                       span_first, n_spans, partials, n_slices, part_stride, relu)
-    static const int depth = [] {
-        const char* e = getenv("MIXGCN_AGG_DEPTH");
-        return e ? atoi(e) : kDepth;
-    }();
-    if (m.has_empty_rows) MIXGCN_AGG_LAUNCH(true, kDepth);
-    else if (depth == 4) MIXGCN_AGG_LAUNCH(false, 4);
-    else if (depth == 6) MIXGCN_AGG_LAUNCH(false, 6);
-    else if (depth == 12) MIXGCN_AGG_LAUNCH(false, 12);
-    else MIXGCN_AGG_LAUNCH(false, kDepth);
-#undef MIXGCN_AGG_LAUNCH
+    if (m.has_empty_rows)
+        hipLaunchKernelGGL((aggregate_kernel<LPR, GF, DT, true>), dim3(grid), dim3(kBlock), 0, s,
+                           m.rowptr, m.cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,
+                           span_first, n_spans, partials, n_slices, relu);
+    else
+        hipLaunchKernelGGL((aggregate_kernel<LPR, GF, DT, false>), dim3(grid), dim3(kBlock), 0, s,
+                           m.rowptr, m.cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,
+                           span_first, n_spans, partials, n_slices, relu);
     if (timer) MIXGCN_TRY(timer->end(s));
     return MIXGCN_OK;
 }
@@ -383,17 +377,7 @@ int launch_fixup(const Csr& m, void* Z, int64_t ldz, int c0, int width, int64_t 
 // = lanes * 4 fp32 or * 8 bf16): 8 lanes = one 128-byte line of every gathered row, so a
 // 256-column pass has 8 slices, one per XCD.  (Measured best when the row pitch is an odd number
 // of 128-byte lines; with a power-of-two pitch a slice's lines fall on few L2 channels.)
-// MIXGCN_AGG_GROUP overrides it (4, 8, 16, 32 or 64) for experiments.
-int slice_lanes(int gf)
-{
-    static const int forced = [] {
-        const char* e = getenv("MIXGCN_AGG_GROUP");
-        const int x = e ? atoi(e) : 0;
-        return (x == 4 || x == 8 || x == 16 || x == 32 || x == 64) ? x : 0;
-    }();
-    int l = forced ? forced : 8;
-    return l > gf ? gf : l;
-}
+constexpr int slice_lanes(int gf) { return gf < 8 ? gf : 8; }
 
 template <int DT>
 int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, void* Z,
@@ -431,30 +415,20 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, v
         const int w = (c1 - cb) < kMaxTile ? (c1 - cb) : kMaxTile;
         int GF = 4;  // lanes that span the whole pass: fix-up group and partial-slot stride
         while (GF * VEC < w) GF *= 2;
-        const int LPR = slice_lanes(GF);
-        const int ps = GF * VEC;
-        const int64_t span = (int64_t)kBatchesPerSpan * (kWave / LPR);
+        const int64_t span = (int64_t)kBatchesPerSpan * (kWave / slice_lanes(GF));
         float* P = g->partials;
-#define MIXGCN_AGG_MAIN(L) \
-    MIXGCN_TRY((launch_main<L, DT>(m, H, ldh, Z, ldz, cb, w, r0, r1, e0, e1, P, ps, relu, s, timer)))
-#define MIXGCN_AGG_FIX(GG) \
+#define MIXGCN_AGG_PASS(GG)                                                                      \
+    MIXGCN_TRY((launch_main<slice_lanes(GG), GG, DT>(m, H, ldh, Z, ldz, cb, w, r0, r1, e0, e1, P,  \
+                                                     relu, s, timer)));                           \
     MIXGCN_TRY((launch_fixup<GG, DT>(m, Z, ldz, cb, w, e0, e1, span, P, relu, s)))
-        switch (LPR) {
-        case 4: MIXGCN_AGG_MAIN(4); break;
-        case 8: MIXGCN_AGG_MAIN(8); break;
-        case 16: MIXGCN_AGG_MAIN(16); break;
-        case 32: MIXGCN_AGG_MAIN(32); break;
-        default: MIXGCN_AGG_MAIN(64); break;
-        }
         switch (GF) {
-        case 4: MIXGCN_AGG_FIX(4); break;
-        case 8: MIXGCN_AGG_FIX(8); break;
-        case 16: MIXGCN_AGG_FIX(16); break;
-        case 32: MIXGCN_AGG_FIX(32); break;
-        default: MIXGCN_AGG_FIX(64); break;
+        case 4: MIXGCN_AGG_PASS(4); break;
+        case 8: MIXGCN_AGG_PASS(8); break;
+        case 16: MIXGCN_AGG_PASS(16); break;
+        case 32: MIXGCN_AGG_PASS(32); break;
+        default: MIXGCN_AGG_PASS(64); break;
         }
-#undef MIXGCN_AGG_MAIN
-#undef MIXGCN_AGG_FIX
+#undef MIXGCN_AGG_PASS
     }
     MIXGCN_HIP_TRY(hipGetLastError());
     return MIXGCN_OK;
