@@ -40,7 +40,7 @@ def _load():
         lib.gg_rmat_edges.restype = None
         lib.gg_er_edges.argtypes = [u64, ctypes.c_uint32, dbl, p, p, u64]
         lib.gg_er_edges.restype = u64
-        lib.gg_zipf_edges.argtypes = [u64, ctypes.c_uint32, u64, dbl, ctypes.c_uint32, p, p]
+        lib.gg_zipf_edges.argtypes = [u64, ctypes.c_uint32, u64, dbl, dbl, p, p]
         lib.gg_zipf_edges.restype = None
         lib.gg_fill_uniform.argtypes = [u64, u64, i64, i64, i64, dbl, dbl, p]
         lib.gg_fill_uniform.restype = None
@@ -78,11 +78,12 @@ def er_edges(seed: int, n: int, avg_degree: float):
     return src, dst
 
 
-def zipf_edges(seed: int, n: int, n_edges: int, alpha: float = 2.1, n_heavy: int = 1 << 20):
-    """Directed edges: source ~ Zipf(alpha) over n_heavy ranks, destination uniform."""
+def zipf_edges(seed: int, n: int, n_edges: int, alpha: float = 2.1, max_degree: float = 1 << 20):
+    """Directed edges: out-degrees follow a power law with tail exponent alpha (largest expected
+    out-degree about max_degree), destinations uniform."""
     src = np.empty(n_edges, dtype=np.uint32)
     dst = np.empty(n_edges, dtype=np.uint32)
-    _load().gg_zipf_edges(seed, n, n_edges, alpha, min(n_heavy, n), _ptr(src), _ptr(dst))
+    _load().gg_zipf_edges(seed, n, n_edges, alpha, float(max_degree), _ptr(src), _ptr(dst))
     return src, dst
 
 
@@ -137,6 +138,8 @@ def config_graph(name: str, seed: int = MASTER_SEED, scale_override: int | None 
     c1: Erdos-Renyi N=4096, average degree 10.
     c2: R-MAT scale 20, 16*N directed edges.
     c3: R-MAT scale 24, 8*N directed edges (average degree 16 after symmetrisation).
+    c4: N = 111,000,000, 1.6e9 directed edges with power-law (alpha = 2.1) out-degrees;
+        scale_override = s gives the same recipe at N = 2^s with 14.4 N edges.
     c5: R-MAT scale 22 with ids >= 2,450,000 rejected, 25*N directed edges.
     """
     if name == "c1":
@@ -152,6 +155,14 @@ def config_graph(name: str, seed: int = MASTER_SEED, scale_override: int | None 
         scale = scale_override or 24
         n = 1 << scale
         s, d = rmat_edges(seed, scale, 8 * n)
+        return s, d, n
+    if name == "c4":
+        if scale_override:
+            n = 1 << scale_override
+            e = int(14.4 * n)
+        else:
+            n, e = 111_000_000, 1_600_000_000
+        s, d = zipf_edges(seed, n, e, 2.1, min(1 << 20, n // 64))
         return s, d, n
     if name == "c5":
         if scale_override:

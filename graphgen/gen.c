@@ -122,27 +122,31 @@ uint64_t gg_er_edges(uint64_t seed, uint32_t n, double p, uint32_t* src, uint32_
 }
 
 /*
- * Power-law edge list: the source of every edge is drawn with probability proportional to
- * rank^(-alpha) over `n_heavy` ranks (inverse CDF over the prefix sums of the weights, ranks
- * mapped to node ids by a fixed multiplicative bijection modulo n), the destination is
- * uniform over [0, n).
+ * Power-law edge list.  Node out-degrees follow a discrete power law with tail exponent alpha
+ * (P(deg = k) ~ k^-alpha): the node of rank r (r = 1 is the largest) is drawn as the source of an
+ * edge with probability proportional to (r + r0)^(-1/(alpha-1)), the rank-size form of that law,
+ * where r0 shifts the head so that the expected largest out-degree is about max_degree.  Ranks
+ * are drawn by inverting the continuous CDF in closed form (no table) and mapped to node ids by
+ * a fixed multiplicative bijection modulo n; destinations are uniform over [0, n).
  */
-void gg_zipf_edges(uint64_t seed, uint32_t n, uint64_t n_edges, double alpha, uint32_t n_heavy,
+void gg_zipf_edges(uint64_t seed, uint32_t n, uint64_t n_edges, double alpha, double max_degree,
                    uint32_t* src, uint32_t* dst)
 {
     const uint64_t key = stream_key(seed, 0x5A495046ull /* "ZIPF" */);
-    if (n_heavy == 0 || n_heavy > n) n_heavy = n;
-    double* cdf = (double*)malloc(sizeof(double) * (size_t)n_heavy);
-    double acc = 0.0;
-    for (uint32_t r = 0; r < n_heavy; ++r) {
-        acc += pow((double)(r + 1), -alpha);
-        cdf[r] = acc;
+    const double beta = 1.0 / (alpha - 1.0); /* rank-size exponent, < 1 for alpha > 2 */
+    const double ob = 1.0 - beta;
+    /* find r0: expected degree of the top rank = n_edges * r0^-beta / integral <= max_degree */
+    double r0 = 1.0;
+    for (int it = 0; it < 60; ++it) {
+        double total = (pow((double)n + r0, ob) - pow(r0, ob)) / ob;
+        double top = (double)n_edges * pow(r0, -beta) / total;
+        if (top <= max_degree) break;
+        r0 *= 1.25;
     }
-    const double total = acc;
-    /* odd multiplier coprime with n is needed for a bijection; walk until gcd == 1 */
+    const double lo = pow(r0, ob), hi = pow((double)n + r0, ob);
     uint64_t mult = 0x9E3779B1ull % n;
     if (mult == 0) mult = 1;
-    for (;;) {
+    for (;;) { /* multiplier coprime with n: a bijection of the ranks onto the node ids */
         uint64_t x = mult, y = n;
         while (y) { uint64_t t = x % y; x = y; y = t; }
         if (x == 1) break;
@@ -151,17 +155,14 @@ void gg_zipf_edges(uint64_t seed, uint32_t n, uint64_t n_edges, double alpha, ui
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < (int64_t)n_edges; ++i) {
         uint64_t r = draw(key, (uint64_t)i);
-        double uu = ((double)(r >> 11) + 0.5) * (1.0 / 9007199254740992.0) * total;
-        uint32_t lo = 0, hi = n_heavy - 1;
-        while (lo < hi) {
-            uint32_t mid = lo + (hi - lo) / 2;
-            if (cdf[mid] < uu) lo = mid + 1; else hi = mid;
-        }
+        double uu = ((double)(r >> 11) + 0.5) * (1.0 / 9007199254740992.0);
+        double rank = pow(lo + uu * (hi - lo), 1.0 / ob) - r0;
+        uint64_t rk = rank <= 0.0 ? 0 : (uint64_t)rank;
+        if (rk >= n) rk = n - 1;
         uint64_t r2 = draw(key ^ 0xA5A5A5A5A5A5A5A5ull, (uint64_t)i);
-        src[i] = (uint32_t)(((uint64_t)lo * mult) % n);
+        src[i] = (uint32_t)((rk * mult) % n);
         dst[i] = (uint32_t)(((r2 >> 32) * (uint64_t)n) >> 32);
     }
-    free(cdf);
 }
 
 /* ---- dense tensors: rows x cols values laid out with leading dimension ld (pad = 0) ------ */
