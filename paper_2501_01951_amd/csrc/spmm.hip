@@ -169,41 +169,42 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
     // Rolling pipeline over rounds of D batches; slot u of a round holds batch b + u.  The
     // entries {column word, value} of a whole round are fetched with ONE coalesced 8-byte load
     // per lane (lane l takes entry l of the round) two rounds ahead and handed to the lanes that
-    // need them with shuffles; the feature rows are gathered one round ahead.  cv is padded past
-    // nnz (zero entries: column 0, value 0, no mark), so nothing here needs a bounds check.
+    // need them with shuffles; the feature rows are gathered one round ahead.  Two rounds are
+    // written out per loop trip with the entry registers swapping roles, so no value that is
+    // still in flight is ever copied (a copy would make the wavefront wait for the load).  cv is
+    // padded past nnz (zero entries: column 0, value 0, no mark), so nothing here needs a bounds
+    // check.
     constexpr int RE = D * EPB;  // entries per round (<= 64)
     static_assert(RE <= kWave, "a round's entries must fit one load per lane");
     const uint2* const rcv = cv + gs + (lane < RE ? lane : 0);  // entry `lane` of round 0 of span
-    const int src_lane = sub;                                   // + u * EPB per slot
-    uint2 inext = rcv[(int64_t)b0 * EPB];  // entries of the round at batch b0
+    // byte address of this lane's 16 bytes in feature row 0; a row pitch always fits 32 bits, so
+    // the address of a gathered row is one 32 x 32 + 64-bit multiply-add
+    const char* const hbase = reinterpret_cast<const char*>(F::ptr(H, coff_load));
+    const uint32_t pitch = (uint32_t)(ldh * (int64_t)(sizeof(typename F::Raw) / VEC));
     uint32_t c[D];
     float a[D];
     typename F::Raw h[D];
-#pragma unroll
-    for (int u = 0; u < D; ++u) {
-        c[u] = __shfl(inext.x, u * EPB + src_lane, kWave);
-        a[u] = __uint_as_float(__shfl(inext.y, u * EPB + src_lane, kWave));
-        h[u] = *F::ptr(H, (int64_t)(c[u] & kEntryColMask) * ldh + coff_load);
-    }
-    inext = rcv[(int64_t)(b0 + D) * EPB];  // round b0 + D
+    uint2 ea, eb2;
 
-    for (int b = b0; b < b1; b += D) {
-        const uint2 inext2 = rcv[(int64_t)(b + 2 * D) * EPB];  // two rounds ahead
+    auto fill = [&](int u, const uint2& en) {  // slot u <- entry u * EPB + sub of the round `en`
+        c[u] = __shfl(en.x, u * EPB + sub, kWave);
+        a[u] = __uint_as_float(__shfl(en.y, u * EPB + sub, kWave));
+        h[u] = *reinterpret_cast<const typename F::Raw*>(
+            hbase + (uint64_t)(c[u] & kEntryColMask) * pitch);
+    };
+    // one round: use the D slots (batches b .. b + D - 1), refilling each from `en` (the entries
+    // of the round after).  No early exit: a batch past the end of the range has every lane
+    // masked and adds nothing, which keeps the loop free of side exits so that the compiler can
+    // count exactly how many younger loads may stay in flight at each use.
+    auto round = [&](int b, const uint2& en) {
 #pragma unroll
         for (int u = 0; u < D; ++u) {
-            const int bb = b + u;
-            if (bb >= b1) break;
-            float x[VEC];
-            F::widen(h[u], x);
+            const int64_t eb = gs + (int64_t)(b + u) * EPB;  // first entry of the batch
             uint32_t cu = c[u];
             float au = a[u];
-            // refill the slot with batch bb + D
-            c[u] = __shfl(inext.x, u * EPB + src_lane, kWave);
-            a[u] = __uint_as_float(__shfl(inext.y, u * EPB + src_lane, kWave));
-            h[u] = *F::ptr(H, (int64_t)(c[u] & kEntryColMask) * ldh + coff_load);
-
-            const int64_t eb = gs + (int64_t)bb * EPB;  // first entry of the batch
-            if (eb < es || eb + EPB > ee) {             // batch straddles the range: mask lanes
+            float x[VEC];
+            F::widen(h[u], x);
+            if (eb < es || eb + EPB > ee) {  // batch straddles the range: idle lanes add zero
                 const bool ok = (eb + sub >= es) && (eb + sub < ee);
                 if (!ok) {
                     cu = 0;
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
             if (m == 0) {
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) acc[i] = fmaf(au, x[i], acc[i]);
-                pending = true;
+                pending = pending || eb < ee;
             } else {
                 int prev = -1;
                 while (m) {
@@ -255,8 +256,19 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
                 // entries after the last mark start a new row piece (only real ones count)
                 pending = (eb + prev + 1 < ee) && (prev + 1 < EPB);
             }
+            fill(u, en);  // the batch D later
         }
-        inext = inext2;
+    };
+
+    ea = rcv[(int64_t)b0 * EPB];         // entries of the round at batch b0
+    eb2 = rcv[(int64_t)(b0 + D) * EPB];  // round b0 + D
+#pragma unroll
+    for (int u = 0; u < D; ++u) fill(u, ea);
+    for (int b = b0; b < b1; b += 2 * D) {
+        ea = rcv[(int64_t)(b + 2 * D) * EPB];
+        round(b, eb2);
+        eb2 = rcv[(int64_t)(b + 3 * D) * EPB];
+        round(b + D, ea);
     }
     if (pending) {
         reduce_subgroups<LPR, VEC>(acc);
