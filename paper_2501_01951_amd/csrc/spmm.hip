@@ -110,7 +110,9 @@ __device__ inline void reduce_subgroups(float* v)
 // column offset within the pass.
 // GF = lanes that would span the whole pass (its width class: 4 GF fp32 or 8 GF bf16 columns);
 // it fixes the stride of the partial-sum slots and names the instantiation in profiles.
-template <int LPR, int GF, int DT, bool HAS_EMPTY>
+// OFF32: every byte offset into H fits 32 bits and every column index 24 bits, so a gather
+// address is a scalar base plus one 24-bit multiply-add per lane.
+template <int LPR, int GF, int DT, bool HAS_EMPTY, bool OFF32>
 __global__ __launch_bounds__(kBlock) void aggregate_kernel(
     const int64_t* __restrict__ rowptr, const uint2* __restrict__ cv,
     const uint32_t* __restrict__ grp_row, const void* __restrict__ H, int64_t ldh,
@@ -162,9 +164,13 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
 
-    // batches of this span that overlap [es, ee)
-    const int b0 = (int)((es - gs) / EPB);
-    const int b1 = (int)((ee - gs + EPB - 1) / EPB);
+    // batches of this span that overlap [es, ee), and those that lie wholly inside it; all
+    // per-batch bookkeeping is done on 32-bit positions relative to the span start
+    const int es_rel = (int)(es - gs), ee_rel = (int)(ee - gs);
+    const int b0 = es_rel / EPB;
+    const int b1 = (ee_rel + EPB - 1) / EPB;
+    const int b_in0 = (es_rel + EPB - 1) / EPB;  // first batch with no entry before es
+    const int b_in1 = ee_rel / EPB;              // first batch with an entry at or after ee
 
     // Rolling pipeline over rounds of D batches; slot u of a round holds batch b + u.  The
     // entries {column word, value} of a whole round are fetched with ONE coalesced 8-byte load
@@ -179,8 +185,10 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
     const uint2* const rcv = cv + gs + (lane < RE ? lane : 0);  // entry `lane` of round 0 of span
     // byte address of this lane's 16 bytes in feature row 0; a row pitch always fits 32 bits, so
     // the address of a gathered row is one 32 x 32 + 64-bit multiply-add
+    constexpr int ES = (int)sizeof(typename F::Raw) / VEC;  // bytes per stored element
     const char* const hbase = reinterpret_cast<const char*>(F::ptr(H, coff_load));
-    const uint32_t pitch = (uint32_t)(ldh * (int64_t)(sizeof(typename F::Raw) / VEC));
+    const uint32_t pitch = (uint32_t)(ldh * ES);
+    const uint32_t lane_off = (uint32_t)(coff_load * ES);
     uint32_t c[D];
     float a[D];
     typename F::Raw h[D];
@@ -189,8 +197,14 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
     auto fill = [&](int u, const uint2& en) {  // slot u <- entry u * EPB + sub of the round `en`
         c[u] = __shfl(en.x, u * EPB + sub, kWave);
         a[u] = __uint_as_float(__shfl(en.y, u * EPB + sub, kWave));
-        h[u] = *reinterpret_cast<const typename F::Raw*>(
-            hbase + (uint64_t)(c[u] & kEntryColMask) * pitch);
+        if (OFF32) {
+            // the 24-bit multiply ignores the mark bits of the column word
+            const uint32_t off = __umul24(c[u], pitch) + lane_off;
+            h[u] = *reinterpret_cast<const typename F::Raw*>(reinterpret_cast<const char*>(H) + off);
+        } else {
+            h[u] = *reinterpret_cast<const typename F::Raw*>(
+                hbase + (uint64_t)(c[u] & kEntryColMask) * pitch);
+        }
     };
     // one round: use the D slots (batches b .. b + D - 1), refilling each from `en` (the entries
     // of the round after).  No early exit: a batch past the end of the range has every lane
@@ -199,13 +213,14 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
     auto round = [&](int b, const uint2& en) {
 #pragma unroll
         for (int u = 0; u < D; ++u) {
-            const int64_t eb = gs + (int64_t)(b + u) * EPB;  // first entry of the batch
+            const int bb = b + u;
+            const int eb = bb * EPB;  // first entry of the batch, relative to the span start
             uint32_t cu = c[u];
             float au = a[u];
             float x[VEC];
             F::widen(h[u], x);
-            if (eb < es || eb + EPB > ee) {  // batch straddles the range: idle lanes add zero
-                const bool ok = (eb + sub >= es) && (eb + sub < ee);
+            if (__builtin_expect(bb < b_in0 || bb >= b_in1, 0)) {  // batch straddles the range
+                const bool ok = (eb + sub >= es_rel) && (eb + sub < ee_rel);
                 if (!ok) {
                     cu = 0;
                     au = 0.f;
@@ -214,48 +229,59 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
                 }
             }
             uint64_t m = __ballot((int)cu < 0) & kLane0Mask;  // sub-groups whose entry ends a row
-            if (m == 0) {
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) acc[i] = fmaf(au, x[i], acc[i]);
-                pending = pending || eb < ee;
+            if (__builtin_expect(m == 0, 1)) {
+                pending = pending || bb < b1;
             } else {
+                // Rows end in this batch.  t carries the open row's sum so far; each marked
+                // sub-group closes one row: the lanes up to and including it add their products,
+                // the sub-group sums are combined and the row (or its piece) is written.  acc is
+                // only read here and restarts from zero, so the common multiply-add below is
+                // the one place that writes it.
+                float t[VEC];
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) t[i] = acc[i];
                 int prev = -1;
                 while (m) {
                     const int p = (int)(__ffsll((unsigned long long)m) - 1) / LPR;
                     m &= m - 1;
                     if (sub > prev && sub <= p) {
 #pragma unroll
-                        for (int i = 0; i < VEC; ++i) acc[i] = fmaf(au, x[i], acc[i]);
+                        for (int i = 0; i < VEC; ++i) t[i] = fmaf(au, x[i], t[i]);
                     }
-                    reduce_subgroups<LPR, VEC>(acc);
+                    reduce_subgroups<LPR, VEC>(t);
                     if (sub == 0 && active) {
                         if (head) {
 #pragma unroll
-                            for (int i = 0; i < VEC; ++i) part[i] = acc[i];
+                            for (int i = 0; i < VEC; ++i) part[i] = t[i];
                         } else {
                             if (relu) {
 #pragma unroll
-                                for (int i = 0; i < VEC; ++i) acc[i] = fmaxf(acc[i], 0.f);
+                                for (int i = 0; i < VEC; ++i) t[i] = fmaxf(t[i], 0.f);
                             }
-                            F::store(Z, r * ldz + coff, acc);
+                            F::store(Z, r * ldz + coff, t);
                         }
                     }
                     head = false;
 #pragma unroll
-                    for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+                    for (int i = 0; i < VEC; ++i) t[i] = 0.f;
                     ++r;
                     if (HAS_EMPTY) {
-                        while (r + 1 < row_end && rowptr[r + 1] <= eb + p + 1) ++r;
+                        while (r + 1 < row_end && rowptr[r + 1] <= gs + eb + p + 1) ++r;
                     }
                     prev = p;
                 }
-                if (sub > prev) {
 #pragma unroll
-                    for (int i = 0; i < VEC; ++i) acc[i] = fmaf(au, x[i], acc[i]);
+                for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+                if (sub <= prev) {  // these lanes' entries went into the rows just closed
+                    au = 0.f;
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) x[i] = 0.f;
                 }
                 // entries after the last mark start a new row piece (only real ones count)
-                pending = (eb + prev + 1 < ee) && (prev + 1 < EPB);
+                pending = (eb + prev + 1 < ee_rel) && (prev + 1 < EPB);
             }
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] = fmaf(au, x[i], acc[i]);
             fill(u, en);  // the batch D later
         }
     };
@@ -341,7 +367,8 @@ template <int LPR>
 constexpr int64_t span_entries() { return (int64_t)kBatchesPerSpan * (kWave / LPR); }
 
 template <int LPR, int GF, int DT>
-int launch_main(const Csr& m, const void* H, int64_t ldh, void* Z, int64_t ldz, int c0, int width,
+int launch_main(const Csr& m, int64_t n_nodes, const void* H, int64_t ldh, void* Z, int64_t ldz,
+                int c0, int width,
                 int64_t r0, int64_t r1, int64_t e0, int64_t e1, float* partials, int relu,
                 hipStream_t s, Timer* timer)
 {
@@ -356,15 +383,24 @@ int launch_main(const Csr& m, const void* H, int64_t ldh, void* Z, int64_t ldz, 
     const int64_t grid64 = ceil_div(n_spans, kBlock / kWave) * n_slices;
     if (grid64 > 0x7FFFFFFF) return fail(MIXGCN_EINVAL, "aggregate: grid too large");
     const unsigned grid = (unsigned)grid64;
+    // 32-bit gather offsets when the whole feature matrix (as addressed from H) lies within
+    // 4 GiB, its pitch fits 24 bits and the column indices fit 24 bits
+    const int64_t esz = (int64_t)sizeof(typename Feat<DT>::Raw) / Feat<DT>::VEC;
+    const bool off32 = (int64_t)n_nodes * ldh * esz + (int64_t)(c0 + width) * esz < (1ll << 32) &&
+                       ldh * esz < (1ll << 24) && n_nodes <= (1ll << 24);
     if (timer) MIXGCN_TRY(timer->begin(kind, s));
-    if (m.has_empty_rows)
-        hipLaunchKernelGGL((aggregate_kernel<LPR, GF, DT, true>), dim3(grid), dim3(kBlock), 0, s,
-                           m.rowptr, m.cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,
-                           span_first, n_spans, partials, n_slices, relu);
-    else
-        hipLaunchKernelGGL((aggregate_kernel<LPR, GF, DT, false>), dim3(grid), dim3(kBlock), 0, s,
-                           m.rowptr, m.cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,
-                           span_first, n_spans, partials, n_slices, relu);
+#define MIXGCN_AGG_LAUNCH(EMPTY, O32)                                                            \
+    hipLaunchKernelGGL((aggregate_kernel<LPR, GF, DT, EMPTY, O32>), dim3(grid), dim3(kBlock), 0, \
+                       s, m.rowptr, m.cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,  \
+                       span_first, n_spans, partials, n_slices, relu)
+    if (m.has_empty_rows) {
+        if (off32) MIXGCN_AGG_LAUNCH(true, true);
+        else MIXGCN_AGG_LAUNCH(true, false);
+    } else {
+        if (off32) MIXGCN_AGG_LAUNCH(false, true);
+        else MIXGCN_AGG_LAUNCH(false, false);
+    }
+#undef MIXGCN_AGG_LAUNCH
     if (timer) MIXGCN_TRY(timer->end(s));
     return MIXGCN_OK;
 }
@@ -430,8 +466,8 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, v
         const int64_t span = (int64_t)kBatchesPerSpan * (kWave / slice_lanes(GF));
         float* P = g->partials;
 #define MIXGCN_AGG_PASS(GG)                                                                      \
-    MIXGCN_TRY((launch_main<slice_lanes(GG), GG, DT>(m, H, ldh, Z, ldz, cb, w, r0, r1, e0, e1, P,  \
-                                                     relu, s, timer)));                           \
+    MIXGCN_TRY((launch_main<slice_lanes(GG), GG, DT>(m, (int64_t)g->n, H, ldh, Z, ldz, cb, w, r0,  \
+                                                     r1, e0, e1, P, relu, s, timer)));            \
     MIXGCN_TRY((launch_fixup<GG, DT>(m, Z, ldz, cb, w, e0, e1, span, P, relu, s)))
         switch (GF) {
         case 4: MIXGCN_AGG_PASS(4); break;
