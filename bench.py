@@ -29,9 +29,10 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 def measured_traffic(config, width):
     """HBM bytes per launch of the dominant kernel, taken from the committed rocprofv3 --pmc
     summary of this same command (counters cannot be read from inside the run)."""
-    if config != "c2" or width != 256:
+    files = {("c2", 256): "c2_aggregate_pmc.txt", ("c4", 128): "c4_aggregate_pmc.txt"}
+    if (config, width) not in files:
         return None
-    path = os.path.join(ROOT, "profiles", "c2_aggregate_pmc.txt")
+    path = os.path.join(ROOT, "profiles", files[(config, width)])
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):
@@ -84,35 +85,57 @@ def cpu_baseline(name, scale, seed):
 
 
 def bench_single_layer(args, mg, dev):
-    """Config 3 (not the default line): one layer forward + backward on a 128-column slice of a
-    1024-wide layer, R-MAT scale 24 with 8 N directed edges.  H comes from the seeded generator;
-    the 68.7 GB upstream gradient G is drawn on the device (its values do not matter here)."""
+    """Configs 3 and 4 (not the default line): one layer forward + backward at the real shape.
+
+    c3: a 128-column slice of a 1024-wide layer, R-MAT scale 24 with 8 N directed edges; H comes
+    from the seeded generator, the 68.7 GB upstream gradient G is drawn on the device.
+    c4: N = 1.11e8 with 1.6e9 power-law directed edges, one 128 -> 128 layer in the last-layer
+    form (no ReLU).  Three N x 128 tensors (56.8 GB each) plus the graph (54 GB) are resident:
+    the upstream gradient reuses the layer output's storage and dH is written over H, which the
+    backward pass no longer reads.  Tensor values are drawn on the device (they do not matter for
+    the timing; parity at this size is covered by the tests)."""
     import numpy as np
     import torch
 
     import graphgen as gg
     from paper_2501_01951_amd.model import padded_rows
 
-    scale = args.scale or 24
-    n, k, m = 1 << scale, 128, 1024
-    src, dst = gg.rmat_edges(args.seed, scale, 8 * n)
-    g = mg.build_csr(dev(src.view(np.int32)), dev(dst.view(np.int32)), n)
+    if args.config == "c3":
+        scale = args.scale or 24
+        n, k, m, relu = 1 << scale, 128, 1024, True
+        src, dst = gg.rmat_edges(args.seed, scale, 8 * n)
+        what = f"c3: one GCN layer 128->1024 fwd+bwd, R-MAT scale {scale}"
+    else:
+        src, dst, n = gg.config_graph("c4", args.seed, args.scale)
+        k, m, relu = 128, 128, False
+        what = "c4: one GCN layer 128->128 fwd+bwd (no ReLU), power-law graph"
+    s_d, d_d = dev(src.view(np.int32)), dev(dst.view(np.int32))
+    del src, dst
+    g = mg.build_csr(s_d, d_d, n)
+    del s_d, d_d
+    torch.cuda.empty_cache()
     mg.normalize(g)
     nnz = g.nnz
     hd = padded_rows(n, k, torch.float32, "cuda")
-    hd.copy_(torch.from_numpy(gg.normal(args.seed, 1, n, k)))
+    if args.config == "c3":
+        hd.copy_(torch.from_numpy(gg.normal(args.seed, 1, n, k)))
+    else:
+        hd.normal_()
     wd = dev(gg.glorot(args.seed, 10, k, m))
-    gd = padded_rows(n, m, torch.float32, "cuda")
-    gd.normal_()
     zd = padded_rows(n, k, torch.float32, "cuda")
     outd = padded_rows(n, m, torch.float32, "cuda")
-    dhd = padded_rows(n, k, torch.float32, "cuda")
+    if args.config == "c3":
+        gd = padded_rows(n, m, torch.float32, "cuda")
+        gd.normal_()
+        dhd = padded_rows(n, k, torch.float32, "cuda")
+    else:
+        gd, dhd = outd, hd
     dwd = torch.empty(k, m, device="cuda")
     pipe = mg.Pipeline()
 
     def step():
-        mg.layer_fwd(g, hd, wd, zd, outd, pipe, relu=True, n_chunks=args.chunks)
-        mg.layer_bwd(g, zd, outd, wd, gd, dwd, dhd, pipe, relu=True, n_chunks=args.chunks)
+        mg.layer_fwd(g, hd, wd, zd, outd, pipe, relu=relu, n_chunks=args.chunks)
+        mg.layer_bwd(g, zd, outd, wd, gd, dwd, dhd, pipe, relu=relu, n_chunks=args.chunks)
 
     for _ in range(args.warmup):
         step()
@@ -132,17 +155,17 @@ def bench_single_layer(args, mg, dev):
             kinds[nm] = {"total_ms": ms, "launches": cnt, "avg_ms": ms / cnt}
     agg_ms = kinds["agg_g32"]["avg_ms"]
     algo = 8.0 * nnz + 2.0 * n * k * 4 + 8.0 * n
+    traffic = measured_traffic(args.config, k)
     print(json.dumps({
         "metric": "GCN layer fwd+bwd edges*feat/s", "value": nnz * k / dt, "unit": "edges*feat/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"c3: one GCN layer 128->1024 fwd+bwd, R-MAT scale {scale}, N={n}, "
-                               f"nnz(A_hat)={nnz}", "n_nodes": n, "nnz": nnz},
+        "config": {"workload": f"{what}, N={n}, nnz(A_hat)={nnz}", "n_nodes": n, "nnz": nnz},
         "kernels": kinds,
         "roofline": {"bound": "hbm", "achieved": algo / (agg_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": algo / (agg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "traffic": None, "kernel": "aggregate_kernel, 128 fp32 columns",
+                     "traffic": traffic, "kernel": "aggregate_kernel, 128 fp32 columns",
                      "avg_launch_ms": agg_ms, "algorithmic_bytes_per_launch": algo},
         "gemm_tflops": {kk: 2.0 * n * k * m / (kinds[kk]["avg_ms"] * 1e-3) / 1e12
                         for kk in ("update_fwd", "update_dgrad", "update_wgrad")},
@@ -178,7 +201,7 @@ def main():
     def dev(a):
         return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
-    if args.config == "c3":
+    if args.config in ("c3", "c4"):
         return bench_single_layer(args, mg, dev)
     src, dst, n, x, ws, y, dims = make_inputs(args.config, args.scale, args.seed)
 
@@ -243,7 +266,7 @@ def main():
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": measured_traffic(args.config, f) if args.chunks == 1 else None,
-            "kernel": f"aggregate_kernel<8, {gsz}, 0, false> ({f} fp32 columns)",
+            "kernel": f"aggregate_kernel<8, {gsz}, 0, false, true> ({f} fp32 columns)",
             "avg_launch_ms": agg[dom]["avg_ms"], "launches": agg[dom]["launches"],
             "algorithmic_bytes_per_launch": per_launch,
             "gather_bytes_per_launch": (nnz * (8.0 + f * 4) + n * f * 4) / launches_per_layer_call,
