@@ -47,6 +47,8 @@ def model_dims(name):
         return [128, 256, 256, 16]
     if name == "c1":
         return [64, 32, 8]
+    if name == "c5":
+        return [100, 256, 256, 47]
     raise ValueError(name)
 
 
@@ -57,11 +59,13 @@ def make_inputs(name, scale, seed):
 
     dims = model_dims(name)
     src, dst, n = gg.config_graph(name, seed=seed, scale_override=scale)
-    if name == "c1":
+    if name in ("c1", "c5"):
         x = gg.uniform(seed, 1, n, dims[0])
     else:
         x = gg.normal(seed, 1, n, dims[0])
-    ws = [gg.glorot(seed, 10 + l, dims[l], dims[l + 1]) for l in range(len(dims) - 1)]
+    # weights with a leading dimension of whole 16-byte groups (47 columns -> ld 48)
+    ws = [gg.glorot(seed, 10 + l, dims[l], dims[l + 1], ld=(dims[l + 1] + 3) // 4 * 4)[:, :dims[l + 1]]
+          for l in range(len(dims) - 1)]
     y = gg.labels(seed, 5, n, dims[-1])
     return src, dst, n, x, ws, y, dims
 
@@ -69,12 +73,18 @@ def make_inputs(name, scale, seed):
 def cpu_baseline(name, scale, seed):
     """The oracle as it stands on the host cores, one forward+backward step of a down-scaled
     instance of the same generator and model."""
+    import numpy as np
+
     import oracle
 
     src, dst, n, x, ws, y, dims = make_inputs(name, scale, seed)
     g = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n)))
+    ws = [np.ascontiguousarray(w) for w in ws]
     t0 = time.perf_counter()
-    oracle.gcn_step(g, x, ws, y)
+    if name == "c5":
+        oracle.gcn_step(g, x, ws, y, q=oracle.Q_BF16)
+    else:
+        oracle.gcn_step(g, x, ws, y)
     dt = time.perf_counter() - t0
     work = sum(g.nnz * d for d in dims[:-1])
     return {
@@ -216,7 +226,13 @@ def main():
     del s_d, d_d
 
     pipe = mg.Pipeline()
-    step = mg.GCNStep(g, dev(x), [dev(w) for w in ws], dev(y), n_chunks=args.chunks, pipe=pipe)
+    bf16 = args.config == "c5"  # config 5 stores features in bf16
+    x_d = torch.from_numpy(x).cuda()
+    if bf16:
+        x_d = x_d.to(torch.bfloat16)
+    w_d = [torch.from_numpy(np.ascontiguousarray(w.base if w.base is not None else w)).cuda()[:, :w.shape[1]]
+           for w in ws]
+    step = mg.GCNStep(g, x_d, w_d, dev(y), n_chunks=args.chunks, pipe=pipe)
 
     # A plain copy kernel of known size: its FETCH_SIZE / WRITE_SIZE readings calibrate the
     # counter units when this command runs under rocprofv3 --pmc.
@@ -254,10 +270,11 @@ def main():
     if agg:
         dom = max(agg, key=lambda k: agg[k]["total_ms"])
         gsz = int(dom.split("g")[-1])
-        f = gsz * 4  # slice width in fp32 columns handled by that kernel
+        esz = 2 if bf16 else 4
+        f = gsz * 16 // esz  # columns of a pass of that width class (16 bytes per lane)
         # algorithmic minimum per full-graph launch: index + value stream, every feature row
         # read once, every output row written once, one row pointer per row
-        full = 8.0 * nnz + 2.0 * n * f * 4 + 8.0 * n
+        full = 8.0 * nnz + 2.0 * n * f * esz + 8.0 * n
         launches_per_layer_call = max(1, args.chunks)
         per_launch = full / launches_per_layer_call
         avg_s = agg[dom]["avg_ms"] * 1e-3
@@ -266,16 +283,18 @@ def main():
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": measured_traffic(args.config, f) if args.chunks == 1 else None,
-            "kernel": f"aggregate_kernel<8, {gsz}, 0, false, true> ({f} fp32 columns)",
+            "kernel": f"aggregate_kernel<8, {gsz}, {1 if bf16 else 0}, false, true> "
+                      f"({f} {'bf16' if bf16 else 'fp32'} columns)",
             "avg_launch_ms": agg[dom]["avg_ms"], "launches": agg[dom]["launches"],
             "algorithmic_bytes_per_launch": per_launch,
-            "gather_bytes_per_launch": (nnz * (8.0 + f * 4) + n * f * 4) / launches_per_layer_call,
+            "gather_bytes_per_launch": (nnz * (8.0 + f * esz) + n * f * esz) / launches_per_layer_call,
         }
 
     out = {
         "metric": "GCN layer fwd+bwd edges*feat/s", "value": value, "unit": "edges*feat/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 storage, f32 accumulate" if bf16 else "f32",
         "data": "synthetic",
         "config": {
             "workload": f"{args.config}: {len(dims) - 1}-layer GCN {'-'.join(map(str, dims))}, one "

@@ -425,6 +425,15 @@ int launch_relu_mask(int dtype, void* G, int64_t ldg, const void* R, int64_t ldr
     return MIXGCN_OK;
 }
 
+int launch_wgrad_reduce(const float* P, int64_t n_slabs, int64_t cells, int32_t m, float* dW,
+                        int64_t ldw, float beta, hipStream_t s)
+{
+    if (cells <= 0) return MIXGCN_OK;
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)ceil_div(cells, kWave)), dim3(kBlock),
+                       0, s, P, n_slabs, cells, m, dW, ldw, beta);
+    return MIXGCN_OK;
+}
+
 namespace {
 
 template <typename T>
@@ -489,8 +498,7 @@ int update_typed(int op, const T* A, int64_t lda, const void* B_, int64_t ldb, v
         }
 #undef MIXGCN_WGRAD
         if (timer) MIXGCN_TRY(timer->end(s));
-        hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)ceil_div(cells, kWave)),
-                           dim3(kBlock), 0, s, P, n_slabs, cells, m, C, ldc, beta);
+        MIXGCN_TRY(launch_wgrad_reduce(P, n_slabs, cells, m, C, ldc, beta, s));
     } else {
         return fail(MIXGCN_EINVAL, "update: unknown op");
     }
@@ -507,8 +515,8 @@ int launch_update(int op, int dtype, const void* A, int64_t lda, const void* B, 
     if (dtype == MIXGCN_F32)
         return update_typed<float>(op, (const float*)A, lda, B, ldb, C, ldc, n, k, m,
                                    (const float*)R, ldr, beta, s, timer);
-    return update_typed<uint16_t>(op, (const uint16_t*)A, lda, B, ldb, C, ldc, n, k, m,
-                                  (const uint16_t*)R, ldr, beta, s, timer);
+    return launch_update_bf16(op, (const uint16_t*)A, lda, B, ldb, C, ldc, n, k, m,
+                              (const uint16_t*)R, ldr, beta, s, timer);
 }
 
 }  // namespace mixgcn

@@ -1,0 +1,451 @@
+// Node update and its backward products for bf16-stored features (paper Algorithm 2, update
+// phase) on the bf16 matrix cores: v_mfma_f32_32x32x16_bf16, fp32 accumulation.
+//
+// Activations and gradients are bf16 in memory and enter the MFMA as they are.  Weights are
+// fp32: every call first splits W = hi + lo into two bf16 terms (|W - hi - lo| < 2^-16 |W|) in
+// the layout the B operand wants (output index major, reduction index contiguous, zero padded
+// to whole tiles), so a product with W is two MFMAs and keeps fp32-class weights.  The weight
+// gradient multiplies two bf16 tensors and needs no split.
+//
+// MFMA 32x32x16 operand layout: lane l supplies A[i = l % 32][k = 8 (l / 32) + 0..7] and
+// B[k = 8 (l / 32) + 0..7][j = l % 32] as eight consecutive bf16; D as for the fp32 32x32 MFMA.
+// Tiles are therefore staged row-major with the reduction index contiguous and read with one
+// 16-byte LDS load per operand.
+#include "device_utils.h"
+#include "internal.h"
+
+namespace mixgcn {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BKB = 32;       // reduction depth staged per step (bf16 elements)
+constexpr int LDT = BKB + 8;  // LDS row stride: 80 bytes, so 16-byte reads of 16 rows hit all banks
+
+template <int WM_, int WN_, int TM_, int TN_>
+struct Shape {
+    static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_;
+    static constexpr int BM = WM * TM * 32;
+    static constexpr int BN = WN * TN * 32;
+    static_assert(WM * WN == 4, "four waves per block");
+};
+using Shape128x128 = Shape<2, 2, 2, 2>;
+using Shape128x32 = Shape<4, 1, 1, 1>;
+
+__device__ inline uint16_t bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7F800000u) != 0x7F800000u) u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ inline unsigned xcd_local_index(unsigned bid, unsigned grid)
+{
+    const unsigned q = grid / 8, rem = grid % 8, x = bid % 8;
+    return x * q + (x < rem ? x : rem) + bid / 8;
+}
+
+// out[j][kk] = transpose ? W[kk][j] : W[j][kk], zero outside W, as bf16 hi and lo parts.
+__global__ __launch_bounds__(kBlock) void split_weights_kernel(
+    const float* __restrict__ W, int64_t ldw, int rows_w, int cols_w, int transpose,
+    uint16_t* __restrict__ hi, uint16_t* __restrict__ lo, int out_rows, int out_cols)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= out_rows * out_cols) return;
+    const int j = idx / out_cols, kk = idx % out_cols;
+    const int r = transpose ? kk : j, c = transpose ? j : kk;
+    const float x = (r < rows_w && c < cols_w) ? W[(int64_t)r * ldw + c] : 0.f;
+    const uint16_t h = bf16_rne(x);
+    const float rest = x - __uint_as_float((uint32_t)h << 16);
+    hi[idx] = h;
+    lo[idx] = (rest == rest && fabsf(rest) <= 3.0e38f) ? bf16_rne(rest) : (uint16_t)0;
+}
+
+// Eight bf16 of a feature tile on their way from global memory to LDS: issue() starts the
+// loads from an address clamped into the matrix, value() zeroes what lies outside it and, with
+// MASK, what the ReLU-derivative mask 1[R > 0] removes.
+template <bool MASK>
+struct Piece8 {
+    uint4 v, m;
+    int nvalid;  // leading elements inside the matrix (0..8)
+
+    __device__ inline void issue(const uint16_t* __restrict__ M, int64_t ld, int64_t r, int c,
+                                 int64_t rows, int cols, const uint16_t* __restrict__ R,
+                                 int64_t ldr)
+    {
+        const bool ok = r < rows && c < cols;
+        nvalid = ok ? (cols - c < 8 ? cols - c : 8) : 0;
+        const int64_t rr = r < rows ? r : rows - 1;
+        const int cc = c < cols ? c : 0;
+        v = *reinterpret_cast<const uint4*>(M + rr * ld + cc);
+        if (MASK) m = *reinterpret_cast<const uint4*>(R + rr * ldr + cc);
+        else m = make_uint4(0u, 0u, 0u, 0u);
+    }
+    __device__ static inline uint32_t keep_word(uint32_t x, uint32_t r, int left)
+    {
+        uint32_t keep = 0;
+        if (left > 0) keep |= 0x0000FFFFu;
+        if (left > 1) keep |= 0xFFFF0000u;
+        if (MASK) {
+            if (!(__uint_as_float(r << 16) > 0.f)) keep &= 0xFFFF0000u;
+            if (!(__uint_as_float(r & 0xFFFF0000u) > 0.f)) keep &= 0x0000FFFFu;
+        }
+        return x & keep;
+    }
+    __device__ inline uint4 value() const
+    {
+        uint4 o;
+        o.x = keep_word(v.x, m.x, nvalid);
+        o.y = keep_word(v.y, m.y, nvalid - 2);
+        o.z = keep_word(v.z, m.z, nvalid - 4);
+        o.w = keep_word(v.w, m.w, nvalid - 6);
+        return o;
+    }
+};
+
+__device__ inline bf16x8 lds_operand(const uint16_t* p)
+{
+    return *reinterpret_cast<const bf16x8*>(p);
+}
+
+// ---- row-block kernel: C[n x MD] = (A (.) 1[R > 0])[n x KD] * Bop[KD x MD] ---------------------
+// Bop is given split and transposed: Bh/Bl[j][kk], j < n_col_tiles * BN, kk < ldb (a multiple of
+// BKB), zero outside the weights.
+template <class S, bool RELU, bool MASK>
+__global__ __launch_bounds__(kBlock) void rowblock_bf16_kernel(
+    const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ Bh,
+    const uint16_t* __restrict__ Bl, int ldb, uint16_t* __restrict__ C, int64_t ldc, int64_t n,
+    int KD, int MD, const uint16_t* __restrict__ R, int64_t ldr, int n_col_tiles)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][S::BM * LDT];
+    __shared__ __attribute__((aligned(16))) uint16_t Bhs[2][S::BN * LDT];
+    __shared__ __attribute__((aligned(16))) uint16_t Bls[2][S::BN * LDT];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / S::WN, wn = wave % S::WN;
+    const unsigned lid = xcd_local_index(blockIdx.x, gridDim.x);
+    const int64_t row0 = (int64_t)(lid / n_col_tiles) * S::BM;
+    const int col0 = (int)(lid % n_col_tiles) * S::BN;
+
+    floatx16 acc[S::TM][S::TN];
+#pragma unroll
+    for (int tm = 0; tm < S::TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < S::TN; ++tn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
+
+    // a tile row holds BKB bf16 = 4 pieces of 16 bytes; a pass of the block covers 64 tile rows
+    constexpr int A_PASSES = S::BM / 64;
+    constexpr int B_PASSES = (S::BN + 63) / 64;
+    Piece8<MASK> ra[A_PASSES];
+    uint4 rbh[B_PASSES], rbl[B_PASSES];
+    const int prow = tid / 4, pk = 8 * (tid & 3);
+
+    auto issue_tiles = [&](int k0) {
+#pragma unroll
+        for (int p = 0; p < A_PASSES; ++p)
+            ra[p].issue(A, lda, row0 + p * 64 + prow, k0 + pk, n, KD, R, ldr);
+#pragma unroll
+        for (int p = 0; p < B_PASSES; ++p) {
+            const int j = p * 64 + prow;
+            const int64_t off = (int64_t)(col0 + (j < S::BN ? j : 0)) * ldb + k0 + pk;
+            rbh[p] = *reinterpret_cast<const uint4*>(Bh + off);
+            rbl[p] = *reinterpret_cast<const uint4*>(Bl + off);
+        }
+    };
+    auto store_tiles = [&](uint16_t* as, uint16_t* bh, uint16_t* bl) {
+#pragma unroll
+        for (int p = 0; p < A_PASSES; ++p)
+            *reinterpret_cast<uint4*>(&as[(p * 64 + prow) * LDT + pk]) = ra[p].value();
+#pragma unroll
+        for (int p = 0; p < B_PASSES; ++p) {
+            const int j = p * 64 + prow;
+            if (j < S::BN) {
+                *reinterpret_cast<uint4*>(&bh[j * LDT + pk]) = rbh[p];
+                *reinterpret_cast<uint4*>(&bl[j * LDT + pk]) = rbl[p];
+            }
+        }
+    };
+    const int li = lane & 31, lk = lane >> 5;
+    auto mma_step = [&](const uint16_t* as, const uint16_t* bh, const uint16_t* bl) {
+#pragma unroll
+        for (int kc = 0; kc < BKB; kc += 16) {
+            bf16x8 a[S::TM], h[S::TN], l[S::TN];
+#pragma unroll
+            for (int tm = 0; tm < S::TM; ++tm)
+                a[tm] = lds_operand(&as[((wm * S::TM + tm) * 32 + li) * LDT + kc + 8 * lk]);
+#pragma unroll
+            for (int tn = 0; tn < S::TN; ++tn) {
+                h[tn] = lds_operand(&bh[((wn * S::TN + tn) * 32 + li) * LDT + kc + 8 * lk]);
+                l[tn] = lds_operand(&bl[((wn * S::TN + tn) * 32 + li) * LDT + kc + 8 * lk]);
+            }
+#pragma unroll
+            for (int tm = 0; tm < S::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < S::TN; ++tn) {
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], l[tn],
+                                                                          acc[tm][tn], 0, 0, 0);
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], h[tn],
+                                                                          acc[tm][tn], 0, 0, 0);
+                }
+        }
+    };
+
+    const int nk = (KD + BKB - 1) / BKB;
+    issue_tiles(0);
+    store_tiles(As[0], Bhs[0], Bls[0]);
+    __syncthreads();
+    for (int i = 0; i < nk; ++i) {
+        const int cur = i & 1;
+        if (i + 1 < nk) issue_tiles((i + 1) * BKB);
+        mma_step(As[cur], Bhs[cur], Bls[cur]);
+        if (i + 1 < nk) store_tiles(As[cur ^ 1], Bhs[cur ^ 1], Bls[cur ^ 1]);
+        __syncthreads();
+    }
+
+    // D layout: lane l, register v -> row 8*(v/4) + 4*(l/32) + v%4, col l%32
+#pragma unroll
+    for (int tm = 0; tm < S::TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < S::TN; ++tn) {
+            const int c = col0 + (wn * S::TN + tn) * 32 + li;
+            if (c >= MD) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t r = row0 + (wm * S::TM + tm) * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
+                if (r < n) {
+                    float x = acc[tm][tn][v];
+                    if (RELU) x = x > 0.f ? x : 0.f;
+                    C[r * ldc + c] = bf16_rne(x);
+                }
+            }
+        }
+}
+
+// ---- slab kernel: P[slab][KD x MD] = A[rows of slab][KD]^T * (B (.) 1[R > 0])[rows][MD] --------
+// The reduction runs over node rows, which is the slow index of both operands in memory, so a
+// tile is transposed on its way into LDS: a thread takes the same eight columns of two
+// consecutive rows and writes eight 32-bit words, each holding one column's pair of rows.
+template <class S, bool MASK>
+__global__ __launch_bounds__(kBlock) void wgrad_bf16_kernel(
+    const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ B, int64_t ldb,
+    const uint16_t* __restrict__ R, int64_t ldr, float* __restrict__ P, int64_t n, int KD, int MD,
+    int64_t rows_per_slab, int n_i_tiles, int n_j_tiles)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][S::BM * LDT];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][S::BN * LDT];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / S::WN, wn = wave % S::WN;
+    const int tiles = n_i_tiles * n_j_tiles;
+    const unsigned lid = xcd_local_index(blockIdx.x, gridDim.x);
+    const int64_t slab = lid / tiles;
+    const int t = (int)(lid % tiles);
+    const int i0 = (t / n_j_tiles) * S::BM, j0 = (t % n_j_tiles) * S::BN;
+    const int64_t r_begin = slab * rows_per_slab;
+    const int64_t r_end = (r_begin + rows_per_slab) < n ? (r_begin + rows_per_slab) : n;
+
+    floatx16 acc[S::TM][S::TN];
+#pragma unroll
+    for (int tm = 0; tm < S::TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < S::TN; ++tn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
+
+    // 16 row pairs x (tile width / 8) column groups per step; one block pass covers 16 groups
+    constexpr int A_PASSES = S::BM / 128 > 0 ? S::BM / 128 : 1;
+    constexpr int B_PASSES = S::BN / 128 > 0 ? S::BN / 128 : 1;
+    const int rp = tid / 16, cg = tid % 16;
+    Piece8<false> a0[A_PASSES], a1[A_PASSES];
+    Piece8<MASK> b0[B_PASSES], b1[B_PASSES];
+
+    auto issue_tiles = [&](int64_t r0) {
+        const int64_t ra = r0 + 2 * rp;
+#pragma unroll
+        for (int p = 0; p < A_PASSES; ++p) {
+            const int c = 8 * (p * 16 + cg);
+            const int cc = c < S::BM ? c : 0;
+            a0[p].issue(A, lda, ra, i0 + cc, r_end, KD, nullptr, 0);
+            a1[p].issue(A, lda, ra + 1, i0 + cc, r_end, KD, nullptr, 0);
+        }
+#pragma unroll
+        for (int p = 0; p < B_PASSES; ++p) {
+            const int c = 8 * (p * 16 + cg);
+            const int cc = c < S::BN ? c : 0;
+            b0[p].issue(B, ldb, ra, j0 + cc, r_end, MD, R, ldr);
+            b1[p].issue(B, ldb, ra + 1, j0 + cc, r_end, MD, R, ldr);
+        }
+    };
+    // words of the two rows -> LDS[(column)][row pair]
+    auto scatter = [&](uint16_t* tile, int c, const uint4& x, const uint4& y) {
+        uint32_t* t32 = reinterpret_cast<uint32_t*>(tile);
+        const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            t32[(c + 2 * w) * (LDT / 2) + rp] = (xs[w] & 0xFFFFu) | (ys[w] << 16);
+            t32[(c + 2 * w + 1) * (LDT / 2) + rp] = (xs[w] >> 16) | (ys[w] & 0xFFFF0000u);
+        }
+    };
+    auto store_tiles = [&](uint16_t* as, uint16_t* bs) {
+#pragma unroll
+        for (int p = 0; p < A_PASSES; ++p) {
+            const int c = 8 * (p * 16 + cg);
+            if (c < S::BM) scatter(as, c, a0[p].value(), a1[p].value());
+        }
+#pragma unroll
+        for (int p = 0; p < B_PASSES; ++p) {
+            const int c = 8 * (p * 16 + cg);
+            if (c < S::BN) scatter(bs, c, b0[p].value(), b1[p].value());
+        }
+    };
+    const int li = lane & 31, lk = lane >> 5;
+    auto mma_step = [&](const uint16_t* as, const uint16_t* bs) {
+#pragma unroll
+        for (int kc = 0; kc < BKB; kc += 16) {
+            bf16x8 a[S::TM], b[S::TN];
+#pragma unroll
+            for (int tm = 0; tm < S::TM; ++tm)
+                a[tm] = lds_operand(&as[((wm * S::TM + tm) * 32 + li) * LDT + kc + 8 * lk]);
+#pragma unroll
+            for (int tn = 0; tn < S::TN; ++tn)
+                b[tn] = lds_operand(&bs[((wn * S::TN + tn) * 32 + li) * LDT + kc + 8 * lk]);
+#pragma unroll
+            for (int tm = 0; tm < S::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < S::TN; ++tn)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], b[tn],
+                                                                          acc[tm][tn], 0, 0, 0);
+        }
+    };
+
+    if (r_begin < r_end) {
+        const int64_t nk = (r_end - r_begin + BKB - 1) / BKB;
+        issue_tiles(r_begin);
+        store_tiles(As[0], Bs[0]);
+        __syncthreads();
+        for (int64_t i = 0; i < nk; ++i) {
+            const int cur = (int)(i & 1);
+            if (i + 1 < nk) issue_tiles(r_begin + (i + 1) * BKB);
+            mma_step(As[cur], Bs[cur]);
+            if (i + 1 < nk) store_tiles(As[cur ^ 1], Bs[cur ^ 1]);
+            __syncthreads();
+        }
+    }
+    float* out = P + (size_t)slab * KD * MD;
+#pragma unroll
+    for (int tm = 0; tm < S::TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < S::TN; ++tn) {
+            const int j = j0 + (wn * S::TN + tn) * 32 + li;
+            if (j >= MD) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = i0 + (wm * S::TM + tm) * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
+                if (i < KD) out[(size_t)i * MD + j] = acc[tm][tn][v];
+            }
+        }
+}
+
+// C[n x out_dim] = (A (.) mask)[n x red_dim] * Wop, Wop[kk][j] = transpose_w ? W[kk][j] : W[j][kk]
+template <class S>
+int launch_rowblock_bf16(bool relu, const uint16_t* A, int64_t lda, const float* W, int64_t ldw,
+                         int w_rows, int w_cols, bool transpose_w, uint16_t* C, int64_t ldc,
+                         int64_t n, int red_dim, int out_dim, const uint16_t* R, int64_t ldr,
+                         hipStream_t s)
+{
+    const int nct = (int)ceil_div(out_dim, S::BN);
+    const int64_t grid = ceil_div(n, S::BM) * nct;
+    if (grid <= 0) return MIXGCN_OK;
+    if (grid > 0x7FFFFFFF) return fail(MIXGCN_EINVAL, "update: too many row tiles");
+    const int out_rows = nct * S::BN, out_cols = (int)ceil_div(red_dim, BKB) * BKB;
+    void* scratch = nullptr;
+    MIXGCN_TRY(get_scratch(2, (size_t)2 * out_rows * out_cols * sizeof(uint16_t), &scratch));
+    uint16_t* hi = (uint16_t*)scratch;
+    uint16_t* lo = hi + (size_t)out_rows * out_cols;
+    hipLaunchKernelGGL(split_weights_kernel, dim3((unsigned)ceil_div(out_rows * out_cols, kBlock)),
+                       dim3(kBlock), 0, s, W, ldw, w_rows, w_cols, transpose_w ? 1 : 0, hi, lo,
+                       out_rows, out_cols);
+#define MIXGCN_ROWBLOCK(RELU, MASK)                                                              \
+    hipLaunchKernelGGL((rowblock_bf16_kernel<S, RELU, MASK>), dim3((unsigned)grid), dim3(kBlock), \
+                       0, s, A, lda, hi, lo, out_cols, C, ldc, n, red_dim, out_dim, R, ldr, nct)
+    if (R) MIXGCN_ROWBLOCK(false, true);
+    else if (relu) MIXGCN_ROWBLOCK(true, false);
+    else MIXGCN_ROWBLOCK(false, false);
+#undef MIXGCN_ROWBLOCK
+    return MIXGCN_OK;
+}
+
+}  // namespace
+
+int launch_update_bf16(int op, const uint16_t* A, int64_t lda, const void* B_, int64_t ldb,
+                       void* C_, int64_t ldc, int64_t n, int32_t k, int32_t m, const uint16_t* R,
+                       int64_t ldr, float beta, hipStream_t s, Timer* timer)
+{
+    if (op == MIXGCN_OP_FWD || op == MIXGCN_OP_FWD_RELU) {
+        // C[n x m] = A[n x k] W, W stored k x m: operand rows = output columns -> transposed split
+        const bool relu = op == MIXGCN_OP_FWD_RELU;
+        if (timer) MIXGCN_TRY(timer->begin(kTimeUpdateFwd, s));
+        if (m > 64)
+            MIXGCN_TRY((launch_rowblock_bf16<Shape128x128>(relu, A, lda, (const float*)B_, ldb, k, m,
+                                                          true, (uint16_t*)C_, ldc, n, k, m,
+                                                          nullptr, 0, s)));
+        else
+            MIXGCN_TRY((launch_rowblock_bf16<Shape128x32>(relu, A, lda, (const float*)B_, ldb, k, m,
+                                                         true, (uint16_t*)C_, ldc, n, k, m, nullptr,
+                                                         0, s)));
+        if (timer) MIXGCN_TRY(timer->end(s));
+    } else if (op == MIXGCN_OP_DGRAD) {
+        // C[n x k] = (A (.) mask)[n x m] W^T, W stored k x m: operand rows = rows of W
+        if (timer) MIXGCN_TRY(timer->begin(kTimeUpdateDgrad, s));
+        if (k > 64)
+            MIXGCN_TRY((launch_rowblock_bf16<Shape128x128>(false, A, lda, (const float*)B_, ldb, k, m,
+                                                          false, (uint16_t*)C_, ldc, n, m, k, R,
+                                                          ldr, s)));
+        else
+            MIXGCN_TRY((launch_rowblock_bf16<Shape128x32>(false, A, lda, (const float*)B_, ldb, k, m,
+                                                         false, (uint16_t*)C_, ldc, n, m, k, R, ldr,
+                                                         s)));
+        if (timer) MIXGCN_TRY(timer->end(s));
+    } else if (op == MIXGCN_OP_WGRAD) {
+        // C[k x m] = beta C + A[n x k]^T (B (.) mask)[n x m]
+        const uint16_t* B = (const uint16_t*)B_;
+        float* C = (float*)C_;
+        const bool wide = m > 64;
+        const int bm = 128, bn = wide ? 128 : 32;
+        const int nit = (int)ceil_div(k, bm), njt = (int)ceil_div(m, bn);
+        const int tiles = nit * njt;
+        int64_t n_slabs = ceil_div(n, 2048);
+        const int64_t cap = tiles >= 1024 ? 1 : 1024 / tiles;
+        if (n_slabs > cap) n_slabs = cap;
+        if (n_slabs < 1) n_slabs = 1;
+        int64_t rows_per_slab = ceil_div(ceil_div(n, n_slabs), BKB) * BKB;
+        if (rows_per_slab < BKB) rows_per_slab = BKB;
+        n_slabs = n > 0 ? ceil_div(n, rows_per_slab) : 1;
+        const int64_t cells = (int64_t)k * m;
+        void* scratch = nullptr;
+        MIXGCN_TRY(get_scratch(0, (size_t)n_slabs * cells * sizeof(float), &scratch));
+        float* P = (float*)scratch;
+        const unsigned grid = (unsigned)(n_slabs * tiles);
+        if (timer) MIXGCN_TRY(timer->begin(kTimeUpdateWgrad, s));
+#define MIXGCN_WGRAD(SHAPE, MASK)                                                                \
+    hipLaunchKernelGGL((wgrad_bf16_kernel<SHAPE, MASK>), dim3(grid), dim3(kBlock), 0, s, A, lda, B, \
+                       ldb, R, ldr, P, n, k, m, rows_per_slab, nit, njt)
+        if (wide) {
+            if (R) MIXGCN_WGRAD(Shape128x128, true);
+            else MIXGCN_WGRAD(Shape128x128, false);
+        } else {
+            if (R) MIXGCN_WGRAD(Shape128x32, true);
+            else MIXGCN_WGRAD(Shape128x32, false);
+        }
+#undef MIXGCN_WGRAD
+        if (timer) MIXGCN_TRY(timer->end(s));
+        MIXGCN_TRY(launch_wgrad_reduce(P, n_slabs, cells, m, C, ldc, beta, s));
+    } else {
+        return fail(MIXGCN_EINVAL, "update: unknown op");
+    }
+    MIXGCN_HIP_TRY(hipGetLastError());
+    return MIXGCN_OK;
+}
+
+}  // namespace mixgcn

@@ -149,6 +149,15 @@ int launch_update(int op, int dtype, const void* A, int64_t lda, const void* B, 
                   void* C, int64_t ldc, int64_t n, int32_t k, int32_t m, const void* R,
                   int64_t ldr, float beta, hipStream_t s, Timer* timer);
 
+// bf16-stored features on the bf16 matrix cores (weights stay fp32, split into two bf16 terms)
+int launch_update_bf16(int op, const uint16_t* A, int64_t lda, const void* B, int64_t ldb, void* C,
+                       int64_t ldc, int64_t n, int32_t k, int32_t m, const uint16_t* R,
+                       int64_t ldr, float beta, hipStream_t s, Timer* timer);
+
+// dW = beta dW + sum of the slab partials P[slab][cells], in slab order in fp64
+int launch_wgrad_reduce(const float* P, int64_t n_slabs, int64_t cells, int32_t m, float* dW,
+                        int64_t ldw, float beta, hipStream_t s);
+
 int launch_softmax_xent(int dtype, const void* logits, int64_t ldl, const int32_t* labels,
                         int64_t n, int32_t c, void* dlogits, int64_t ldd, double* loss,
                         hipStream_t s);
