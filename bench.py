@@ -304,6 +304,13 @@ def main():
         "loss": loss, "build_csr_normalize_ms": t_build * 1e3, "kernels": kinds,
         "roofline": roofline,
     }
+    # what this device sustains on a plain copy and on register-only MFMA chains (outside the
+    # timed region): context for the published peaks the fractions above are quoted against
+    del step, calib_src, calib_dst
+    torch.cuda.empty_cache()
+    read_gbs, copy_gbs, f32_tf, bf16_tf = mg.measure_peaks()
+    out["measured_peaks"] = {"read_GBps": read_gbs, "copy_GBps": copy_gbs,
+                             "mfma_f32_TFLOPs": f32_tf, "mfma_bf16_TFLOPs": bf16_tf}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, args.cpu_scale, args.seed)
     print(json.dumps(out))

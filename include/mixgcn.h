@@ -209,6 +209,15 @@ enum { MIXGCN_TIME_AGG_G4 = 0, MIXGCN_TIME_AGG_G8 = 1, MIXGCN_TIME_AGG_G16 = 2,
        MIXGCN_TIME_UPDATE_DGRAD = 6, MIXGCN_TIME_UPDATE_WGRAD = 7 };
 int mixgcn_pipeline_timing(mixgcn_pipeline* p, int enable);
 int mixgcn_pipeline_timing_read(mixgcn_pipeline* p, int kind, double* total_ms, int64_t* launches);
+/*
+ * Measurement aid, not part of the training path: the rates this device sustains on a 4 GiB
+ * streaming read and a 4 GiB streaming copy (GB/s; the copy counts read + write) and on
+ * register-only MFMA chains in fp32 (32x32x2) and bf16 (32x32x16), in TFLOP/s, for comparison
+ * with the published peaks that the roofline fractions are quoted against.  Outputs are host
+ * pointers.  Allocates and frees 8 GiB of device memory; synchronises the stream.
+ */
+int mixgcn_measure_peaks(double* read_gbs, double* copy_gbs, double* mfma_f32_tflops,
+                         double* mfma_bf16_tflops, void* stream);
 const char* mixgcn_strerror(int code);
 const char* mixgcn_last_error(void);
 int mixgcn_version(void);

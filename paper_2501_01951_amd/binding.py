@@ -95,6 +95,15 @@ def version() -> int:
     return load_library().mixgcn_version()
 
 
+def measure_peaks(stream=None):
+    """(read GB/s, copy GB/s, fp32 MFMA TFLOP/s, bf16 MFMA TFLOP/s) this device sustains on
+    kernels that do nothing else.  A measurement aid for bench.py."""
+    r, c, f, b = ctypes.c_double(), ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    _check(load_library().mixgcn_measure_peaks(ctypes.byref(r), ctypes.byref(c), ctypes.byref(f),
+                                               ctypes.byref(b), _stream(stream)), "measure_peaks")
+    return r.value, c.value, f.value, b.value
+
+
 def _check(rc: int, where: str) -> None:
     if rc != 0:
         raise MixGCNError(rc, where)

@@ -435,7 +435,8 @@ def test_aggregate_bf16(mg, rmat15, f, ld):
     assert_close(z.float().cpu().numpy(), ref, RTOL_BF16, f"Z bf16 f={f}")
 
 
-@pytest.mark.parametrize("n,k,m", [(3000, 100, 256), (2048, 256, 256), (1111, 256, 47), (500, 64, 8)])
+@pytest.mark.parametrize("n,k,m", [(3000, 100, 256), (2048, 256, 256), (1111, 256, 47), (500, 64, 8),
+                                   (1, 16, 8), (33, 40, 172), (2500, 72, 130), (4173, 264, 300)])
 def test_update_ops_bf16(mg, n, k, m):
     say(f"update bf16 n={n} k={k} m={m}")
     ldk, ldm = (k + 7) // 8 * 8, (m + 7) // 8 * 8
