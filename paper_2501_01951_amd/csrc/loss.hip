@@ -1,5 +1,5 @@
 // Loss glue (paper Algorithm 2, loss line): mean softmax cross-entropy over all nodes and its
-// gradient (softmax - onehot) / n.  One wavefront per node row; block partial sums of the loss
+// gradient (softmax - onehot) / n.  A group of lanes per node row; block partial sums of the loss
 // are combined in a fixed order by a second kernel, so the result is deterministic.
 #include "device_utils.h"
 #include "internal.h"
@@ -9,16 +9,19 @@ namespace {
 
 constexpr int kRowsPerBlock = 256;
 
-__device__ inline float wave_max(float v)
+// reductions over the G lanes that share a node row (G a power of two, groups are lane aligned)
+template <int G>
+__device__ inline float group_max(float v)
 {
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    for (int o = G / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
     return v;
 }
-__device__ inline float wave_sum(float v)
+template <int G>
+__device__ inline float group_sum(float v)
 {
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    for (int o = G / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
     return v;
 }
 
@@ -33,35 +36,47 @@ __device__ inline void st_elem(uint16_t* p, float x)
 }
 
 // T: storage type of logits and dlogits (fp32, or bf16 widened to fp32 for the arithmetic).
-template <typename T>
+// G lanes work on one node row (G = the power of two that covers the class count, at most 64),
+// so a wavefront handles 64 / G rows at a time.
+template <typename T, int G>
 __global__ __launch_bounds__(kBlock) void xent_rows_kernel(const T* logits, int64_t ldl,
                                                            const int32_t* __restrict__ labels,
                                                            int64_t n, int c, T* dlogits,
                                                            int64_t ldd, double* __restrict__ part)
 {
+    constexpr int RPW = kWave / G;  // rows per wavefront and trip
     __shared__ double wsum[kBlock / kWave];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int gl = lane % G, gi = lane / G;
     const int64_t r_begin = (int64_t)blockIdx.x * kRowsPerBlock;
     const int64_t r_end = (r_begin + kRowsPerBlock) < n ? (r_begin + kRowsPerBlock) : n;
     const float inv_n = 1.0f / (float)n;
     double acc = 0.0;
-    for (int64_t r = r_begin + w; r < r_end; r += kBlock / kWave) {
-        const T* x = logits + r * ldl;
+    for (int64_t r0 = r_begin + (int64_t)w * RPW; r0 < r_end; r0 += (kBlock / kWave) * RPW) {
+        const int64_t r = r0 + gi;
+        const bool live = r < r_end;
+        const int64_t rr = live ? r : r_end - 1;  // idle groups redo the last row, write nothing
+        const T* x = logits + rr * ldl;
         float mx = -INFINITY;
-        for (int j = lane; j < c; j += kWave) mx = fmaxf(mx, ld_elem(x + j));
-        mx = wave_max(mx);
+        for (int j = gl; j < c; j += G) mx = fmaxf(mx, ld_elem(x + j));
+        mx = group_max<G>(mx);
         float se = 0.f;
-        for (int j = lane; j < c; j += kWave) se += expf(ld_elem(x + j) - mx);
-        se = wave_sum(se);
+        for (int j = gl; j < c; j += G) se += expf(ld_elem(x + j) - mx);
+        se = group_sum<G>(se);
         const float lse = mx + logf(se);
-        const int y = labels[r];
+        const int y = labels[rr];
         const float xy = ld_elem(x + y);
-        for (int j = lane; j < c; j += kWave) {
-            const float p = expf(ld_elem(x + j) - lse);
-            st_elem(dlogits + r * ldd + j, (p - (j == y ? 1.f : 0.f)) * inv_n);
+        if (live) {
+            for (int j = gl; j < c; j += G) {
+                const float p = expf(ld_elem(x + j) - lse);
+                st_elem(dlogits + r * ldd + j, (p - (j == y ? 1.f : 0.f)) * inv_n);
+            }
+            if (gl == 0) acc += (double)(lse - xy);
         }
-        acc += (double)(lse - xy);
     }
+    // the row leaders of a wavefront, in a fixed order
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, kWave);
     if (lane == 0) wsum[w] = acc;
     __syncthreads();
     if (threadIdx.x == 0) part[blockIdx.x] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
@@ -92,14 +107,21 @@ int launch_softmax_xent(int dtype, const void* logits, int64_t ldl, const int32_
     const int64_t n_parts = ceil_div(n, kRowsPerBlock);
     void* scratch = nullptr;
     MIXGCN_TRY(get_scratch(1, (size_t)n_parts * sizeof(double), &scratch));
-    if (dtype == MIXGCN_F32)
-        hipLaunchKernelGGL(xent_rows_kernel<float>, dim3((unsigned)n_parts), dim3(kBlock), 0, s,
-                           (const float*)logits, ldl, labels, n, c, (float*)dlogits, ldd,
-                           (double*)scratch);
-    else
-        hipLaunchKernelGGL(xent_rows_kernel<uint16_t>, dim3((unsigned)n_parts), dim3(kBlock), 0, s,
-                           (const uint16_t*)logits, ldl, labels, n, c, (uint16_t*)dlogits, ldd,
-                           (double*)scratch);
+#define MIXGCN_XENT(T, G)                                                                        \
+    hipLaunchKernelGGL((xent_rows_kernel<T, G>), dim3((unsigned)n_parts), dim3(kBlock), 0, s,     \
+                       (const T*)logits, ldl, labels, n, c, (T*)dlogits, ldd, (double*)scratch)
+#define MIXGCN_XENT_G(T)                                                                         \
+    do {                                                                                         \
+        if (c <= 4) MIXGCN_XENT(T, 4);                                                           \
+        else if (c <= 8) MIXGCN_XENT(T, 8);                                                      \
+        else if (c <= 16) MIXGCN_XENT(T, 16);                                                    \
+        else if (c <= 32) MIXGCN_XENT(T, 32);                                                    \
+        else MIXGCN_XENT(T, 64);                                                                 \
+    } while (0)
+    if (dtype == MIXGCN_F32) MIXGCN_XENT_G(float);
+    else MIXGCN_XENT_G(uint16_t);
+#undef MIXGCN_XENT_G
+#undef MIXGCN_XENT
     hipLaunchKernelGGL(xent_final_kernel, dim3(1), dim3(kBlock), 0, s, (const double*)scratch,
                        n_parts, n, loss);
     MIXGCN_HIP_TRY(hipGetLastError());

@@ -254,7 +254,8 @@ def test_update_ops(mg, n, k, m):
         assert_close(dw.cpu().numpy()[:, :m], 2 * refw, RTOL_F32, "wgrad beta=1")
 
 
-@pytest.mark.parametrize("n,c", [(4096, 8), (10000, 16), (3000, 172), (999, 47)])
+@pytest.mark.parametrize("n,c", [(4096, 8), (10000, 16), (3000, 172), (999, 47), (5, 3), (1, 2),
+                                 (777, 20), (1001, 64), (50, 65)])
 def test_softmax_xent(mg, n, c):
     say(f"softmax_xent n={n} c={c}")
     x = gg.normal(41, c, n, c) * 3
