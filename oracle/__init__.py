@@ -47,6 +47,10 @@ def _load():
         lib.oracle_transpose.restype = None
         lib.oracle_spmm.argtypes = [p, p, p, p, i64, p, i64, i64, i64, i64, i64, i32]
         lib.oracle_spmm.restype = None
+        lib.oracle_relu_bitmap.argtypes = [p, i64, i64, i64, p, i64]
+        lib.oracle_relu_bitmap.restype = None
+        lib.oracle_sspmm.argtypes = [p, p, p, p, i64, p, i64, i64, i64, i64, i64, p, i64, i32]
+        lib.oracle_sspmm.restype = None
         lib.oracle_update_fwd.argtypes = [p, i64, p, i64, p, i64, i64, i64, i64, i32, i32]
         lib.oracle_update_fwd.restype = None
         lib.oracle_relu_grad.argtypes = [p, i64, p, i64, p, i64, i64, i64, i32]
@@ -139,6 +143,33 @@ def spmm(g: Graph, H, c0=0, c1=None, r0=0, r1=None, transposed=False, q=Q_NONE, 
         rp, cl, vl = g.rowptr, g.col, g.val
     _load().oracle_spmm(_p(rp), _p(cl), _p(vl), _p(H), H.shape[1], _p(Z), Z.shape[1], c0, c1, r0,
                         r1, q)
+    return Z
+
+
+def relu_bitmap(X):
+    """uint32 bitmap [n, ceil(m / 32)]: bit (j % 32) of word j // 32 of row v is X[v, j] > 0."""
+    X = _f64(X)
+    n, m = X.shape
+    bits = np.zeros((n, (m + 31) // 32), dtype=np.uint32)
+    _load().oracle_relu_bitmap(_p(X), m, n, m, _p(bits), bits.shape[1])
+    return bits
+
+
+def sspmm(g: Graph, H, bits, c0=0, c1=None, r0=0, r1=None, transposed=False, q=Q_NONE, out=None):
+    """S-SpMM: Z[r0:r1, c0:c1] = ((A_hat or A_hat^T) @ H)[r0:r1, c0:c1] masked by the bitmap."""
+    H = _f64(H)
+    bits = np.ascontiguousarray(bits, dtype=np.uint32)
+    c1 = H.shape[1] if c1 is None else c1
+    r1 = g.n if r1 is None else r1
+    Z = np.zeros_like(H) if out is None else out
+    if transposed:
+        if g.t_rowptr is None:
+            transpose(g)
+        rp, cl, vl = g.t_rowptr, g.t_col, g.t_val
+    else:
+        rp, cl, vl = g.rowptr, g.col, g.val
+    _load().oracle_sspmm(_p(rp), _p(cl), _p(vl), _p(H), H.shape[1], _p(Z), Z.shape[1], c0, c1, r0,
+                         r1, _p(bits), bits.shape[1], q)
     return Z
 
 

@@ -13,7 +13,9 @@
  * dense boolean matrix built independently; A_hat values against regular graphs, complete
  * graphs, edgeless graphs and the eigenvector identity A_hat d^(1/2) = d^(1/2); the products
  * against dense brute force and adjoint identities; the loss against ln C at W = 0; the whole
- * forward+backward against central finite differences and the linear-activation closed form.
+ * forward+backward against central finite differences and the linear-activation closed form;
+ * the masked aggregation (S-SpMM) against a dense masked product, the complement identity
+ * Z(M) + Z(not M) = A_hat H, and Z = M on regular graphs with H = 1; the bitmap against numpy.
  */
 #include <algorithm>
 #include <cmath>
@@ -171,6 +173,39 @@ void oracle_spmm(const int64_t* rowptr, const uint32_t* col, const double* val,
             for (int64_t j = c0; j < c1; ++j) Z[v * ldz + j] = quantize(acc[j - c0], q);
         }
     }
+}
+
+/*
+ * Output sparsity in bitmap form (Sec. 3.2.1: the mask of a ReLU layer is kept as a bitmap):
+ * bit (j mod 32) of bits[v * ldb + j / 32] is set iff X[v, j] > 0.  Bits past column m are clear.
+ */
+void oracle_relu_bitmap(const double* X, int64_t ldx, int64_t n, int64_t m, uint32_t* bits,
+                        int64_t ldb)
+{
+    for (int64_t v = 0; v < n; ++v) {
+        for (int64_t w = 0; w < ldb; ++w) bits[v * ldb + w] = 0u;
+        for (int64_t j = 0; j < m; ++j)
+            if (X[v * ldx + j] > 0.0) bits[v * ldb + j / 32] |= 1u << (j % 32);
+    }
+}
+
+/*
+ * S-SpMM (Sec. 3.2.1, Eq. 4):  Z = (A H) (.) M  with the mask M given as a bitmap (layout as
+ * above).  Every output is the full neighbor sum of the plain aggregation, kept where the mask
+ * bit is set and zero elsewhere.
+ */
+void oracle_sspmm(const int64_t* rowptr, const uint32_t* col, const double* val, const double* H,
+                  int64_t ldh, double* Z, int64_t ldz, int64_t c0, int64_t c1, int64_t r0,
+                  int64_t r1, const uint32_t* bits, int64_t ldb, int q)
+{
+    for (int64_t v = r0; v < r1; ++v)
+        for (int64_t j = c0; j < c1; ++j) {
+            double acc = 0.0;
+            for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e)
+                acc += val[e] * H[(int64_t)col[e] * ldh + j];
+            const bool keep = (bits[v * ldb + j / 32] >> (j % 32)) & 1u;
+            Z[v * ldz + j] = keep ? quantize(acc, q) : 0.0;
+        }
 }
 
 /* Node update (Algorithm 2, update phase):  P = Z W  (n x k times k x m), then optional ReLU. */

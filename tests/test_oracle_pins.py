@@ -187,6 +187,73 @@ def test_spmm_vs_dense_with_slices_and_row_ranges():
     np.testing.assert_allclose(z, ref, rtol=1e-12, atol=1e-14)
 
 
+# ------------------------------------------------------------------------------------------
+# S-SpMM (Sec. 3.2.1, Eq. 4) and the bitmap form of the ReLU mask
+# ------------------------------------------------------------------------------------------
+def unpack_bits(bits, m):
+    """numpy-only reading of the bitmap layout: column j is bit j % 32 of word j // 32."""
+    n = bits.shape[0]
+    out = np.zeros((n, m), dtype=bool)
+    for j in range(m):
+        out[:, j] = (bits[:, j // 32] >> np.uint32(j % 32)) & np.uint32(1)
+    return out
+
+
+def test_relu_bitmap_layout_and_counts():
+    rng = np.random.default_rng(11)
+    x = rng.normal(size=(37, 70))
+    x[3, 5] = 0.0       # zero is not positive
+    x[4, 6] = -0.0
+    x[5, 33] = np.nan   # neither is NaN
+    bits = oracle.relu_bitmap(x)
+    assert bits.shape == (37, 3) and bits.dtype == np.uint32
+    np.testing.assert_array_equal(unpack_bits(bits, 70), x > 0)
+    assert not (bits[:, 2] >> np.uint32(6)).any()  # bits past column 70 stay clear
+    one = np.full((2, 40), -1.0)
+    one[1, 35] = 2.0
+    b = oracle.relu_bitmap(one)
+    assert b[0].tolist() == [0, 0] and b[1].tolist() == [0, 1 << 3]
+
+
+def test_sspmm_vs_dense_masked_product_slices_and_transpose():
+    rng = np.random.default_rng(12)
+    n = 53
+    src = rng.integers(0, n, 260)
+    dst = rng.integers(0, n, 260)
+    h = rng.normal(size=(n, 40))
+    mask = rng.random(size=(n, 40)) < 0.5
+    bits = oracle.relu_bitmap(np.where(mask, 1.0, -1.0))
+    g = oracle.normalize(oracle.build_csr(src, dst, n))
+    ah = dense_ahat(dense_atilde(src, dst, n))
+    np.testing.assert_allclose(oracle.sspmm(g, h, bits), (ah @ h) * mask, rtol=1e-12, atol=1e-14)
+    z = oracle.sspmm(g, h, bits, c0=4, c1=36, r0=7, r1=40)
+    ref = np.zeros_like(h)
+    ref[7:40, 4:36] = ((ah @ h) * mask)[7:40, 4:36]
+    np.testing.assert_allclose(z, ref, rtol=1e-12, atol=1e-14)
+    # directed graph: the transposed operator is the dense transpose
+    gd = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n, symmetrize=False)))
+    ad = dense_ahat(dense_atilde(src, dst, n, symmetrize=False))
+    np.testing.assert_allclose(oracle.sspmm(gd, h, bits, transposed=True), (ad.T @ h) * mask,
+                               rtol=1e-12, atol=1e-14)
+
+
+def test_sspmm_complement_identity_and_regular_graph_closed_form():
+    rng = np.random.default_rng(13)
+    n, k = 64, 6
+    src, dst = gg.ring_lattice_edges(n, k)
+    g = oracle.normalize(oracle.build_csr(src, dst, n))
+    mask = rng.random(size=(n, 33)) < 0.5
+    bits = oracle.relu_bitmap(np.where(mask, 1.0, -1.0))
+    nbits = oracle.relu_bitmap(np.where(mask, -1.0, 1.0))
+    h = rng.normal(size=(n, 33))
+    # every output is either kept or zero: the two halves add up to the plain aggregation exactly
+    np.testing.assert_array_equal(oracle.sspmm(g, h, bits) + oracle.sspmm(g, h, nbits),
+                                  oracle.spmm(g, h))
+    # k-regular graph with self-loops: A_hat 1 = 1, so S-SpMM of the all-ones matrix is the mask
+    np.testing.assert_allclose(oracle.sspmm(g, np.ones((n, 33)), bits), mask.astype(np.float64),
+                               rtol=0, atol=1e-15)
+
+
 def test_transpose_on_directed_input_adjoint_and_dense():
     rng = np.random.default_rng(4)
     n = 40
