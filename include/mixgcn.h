@@ -135,6 +135,28 @@ int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void
                      int64_t row_end, void* stream);
 
 /*
+ * Sec. 3.2.1, Eq. 4 (S-SpMM): Z = (M_op H) (.) mask on the same ranges as mixgcn_aggregate, the
+ * output mask given in bitmap form: column c of row r is bit (c mod 32) of the uint32 word
+ * mask[r * ld_mask + c / 32] (device memory, ld_mask >= ceil(col_end / 32) words).  An output
+ * whose bit is clear is written as zero; one whose bit is set is the full neighbor sum.  In the
+ * backward pass with mask = 1[H > 0] of the layer input this produces the masked gradient dP of
+ * the layer below directly.
+ */
+int mixgcn_aggregate_masked(const mixgcn_graph* g, int transpose, int dtype, const void* H,
+                            int64_t ldh, void* Z, int64_t ldz, int32_t col_begin, int32_t col_end,
+                            int64_t row_begin, int64_t row_end, const uint32_t* mask,
+                            int64_t ld_mask, void* stream);
+
+/*
+ * The output sparsity of a ReLU layer in the bitmap form above (Sec. 3.2.1): bit (c mod 32) of
+ * mask[r * ld_mask + c / 32] = X[r, c] > 0 for c < n_cols; every word of a row up to ld_mask is
+ * written, bits past n_cols are clear.  X is n_rows x n_cols (device, fp32 or bf16, 16-byte
+ * aligned, ldx a whole number of 16-byte groups like every feature matrix here).
+ */
+int mixgcn_relu_bitmap(int dtype, const void* X, int64_t ldx, int64_t n_rows, int32_t n_cols,
+                       uint32_t* mask, int64_t ld_mask, void* stream);
+
+/*
  * Algorithm 2, update phase, and the two products of its backward pass (see MIXGCN_OP_*).
  *   A, B, C    : operands as listed per op; n_rows = n, k = d^(l), m = d^(l+1).
  *   relu_ref   : R, the stored layer output H' whose sign gives the ReLU derivative

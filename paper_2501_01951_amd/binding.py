@@ -68,6 +68,11 @@ def load_library():
     lib.mixgcn_normalize.argtypes = [vp, ctypes.c_int, vp]
     lib.mixgcn_aggregate.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, i64, vp, i64, i32, i32,
                                      i64, i64, vp]
+    lib.mixgcn_aggregate_masked.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, i64, vp, i64, i32,
+                                            i32, i64, i64, vp, i64, vp]
+    lib.mixgcn_relu_bitmap.argtypes = [ctypes.c_int, vp, i64, i64, i32, vp, i64, vp]
+    dp = ctypes.POINTER(ctypes.c_double)
+    lib.mixgcn_measure_peaks.argtypes = [dp, dp, dp, dp, vp]
     lib.mixgcn_update.argtypes = [ctypes.c_int, ctypes.c_int, vp, i64, vp, i64, vp, i64, i64, i32,
                                   i32, vp, i64, f32, vp]
     lib.mixgcn_layer_fwd.argtypes = [vp, ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp]
@@ -83,7 +88,8 @@ def load_library():
     lib.mixgcn_pipeline_timing.argtypes = [vp, ctypes.c_int]
     lib.mixgcn_pipeline_timing_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                                 ctypes.POINTER(ctypes.c_int64)]
-    for name in ("build_csr", "normalize", "aggregate", "update", "layer_fwd", "layer_bwd",
+    for name in ("build_csr", "normalize", "aggregate", "aggregate_masked", "relu_bitmap",
+                 "measure_peaks", "update", "layer_fwd", "layer_bwd",
                  "softmax_xent", "graph_info", "graph_free", "pipeline_create", "pipeline_destroy",
                  "pipeline_timing", "pipeline_timing_read", "stream_create_cu_subset", "stream_destroy"):
         getattr(lib, "mixgcn_" + name).restype = ctypes.c_int
@@ -269,6 +275,28 @@ def aggregate(g: Graph, H, Z, col_begin=0, col_end=None, row_begin=0, row_end=No
     _check(load_library().mixgcn_aggregate(g._h, int(transpose), _dtype_of(H), _ptr(H), _ld(H),
                                            _ptr(Z), _ld(Z), col_begin, col_end, row_begin, row_end,
                                            _stream(stream)), "aggregate")
+
+
+def aggregate_masked(g: Graph, H, Z, mask, col_begin=0, col_end=None, row_begin=0, row_end=None,
+                     transpose=False, stream=None) -> None:
+    """S-SpMM: Z = (A_hat H) masked by the bitmap `mask` (int32/uint32 tensor [n, words])."""
+    col_end = H.shape[1] if col_end is None else col_end
+    row_end = g.n if row_end is None else row_end
+    assert mask.dtype in (torch.int32, torch.uint32) and mask.stride(1) == 1
+    _check(load_library().mixgcn_aggregate_masked(g._h, int(transpose), _dtype_of(H), _ptr(H), _ld(H),
+                                                  _ptr(Z), _ld(Z), col_begin, col_end, row_begin,
+                                                  row_end, _ptr(mask), mask.stride(0),
+                                                  _stream(stream)), "aggregate_masked")
+
+
+def relu_bitmap(X, mask=None, stream=None):
+    """Bitmap of the positive entries of X: int32 tensor [n, ceil(cols / 32)]."""
+    n, cols = X.shape
+    if mask is None:
+        mask = torch.empty(n, (cols + 31) // 32, dtype=torch.int32, device=X.device)
+    _check(load_library().mixgcn_relu_bitmap(_dtype_of(X), _ptr(X), _ld(X), n, cols, _ptr(mask),
+                                             mask.stride(0), _stream(stream)), "relu_bitmap")
+    return mask
 
 
 def update(op: int, A, B, C, n_rows: int, k: int, m: int, relu_ref=None, beta: float = 0.0,

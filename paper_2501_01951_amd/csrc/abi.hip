@@ -225,7 +225,7 @@ int mixgcn_graph_info(const mixgcn_graph* g, mixgcn_graph_view* out)
 static int aggregate_impl(const mixgcn_graph* g, int transpose, int dtype, const void* H,
                           int64_t ldh, void* Z, int64_t ldz, int32_t col_begin, int32_t col_end,
                           int64_t row_begin, int64_t row_end, int relu, hipStream_t stream,
-                          Timer* timer)
+                          Timer* timer, const uint32_t* mask = nullptr, int64_t ld_mask = 0)
 {
     if (!g) return fail(MIXGCN_EINVAL, "aggregate: graph is null");
     if (!g->normalized) return fail(MIXGCN_ESTATE, "aggregate: call mixgcn_normalize first");
@@ -256,9 +256,11 @@ static int aggregate_impl(const mixgcn_graph* g, int transpose, int dtype, const
             return fail(MIXGCN_ESTATE, "aggregate: transpose needs MIXGCN_BUILD_TRANSPOSE");
         m = &g->tr;
     }
+    if (mask && ld_mask < ((int64_t)col_end + 31) / 32)
+        return fail(MIXGCN_EINVAL, "aggregate: ld_mask shorter than ceil(col_end / 32) words");
     if (row_end == row_begin || col_end == col_begin) return MIXGCN_OK;
     return launch_aggregate(g, *m, dtype, H, ldh, Z, ldz, col_begin, col_end, row_begin, row_end,
-                            relu, stream, timer);
+                            relu, mask, ld_mask, stream, timer);
 }
 
 int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void* H, int64_t ldh,
@@ -267,6 +269,29 @@ int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void
 {
     return aggregate_impl(g, transpose, dtype, H, ldh, Z, ldz, col_begin, col_end, row_begin,
                           row_end, 0, (hipStream_t)stream, nullptr);
+}
+
+int mixgcn_aggregate_masked(const mixgcn_graph* g, int transpose, int dtype, const void* H,
+                            int64_t ldh, void* Z, int64_t ldz, int32_t col_begin, int32_t col_end,
+                            int64_t row_begin, int64_t row_end, const uint32_t* mask,
+                            int64_t ld_mask, void* stream)
+{
+    if (!mask) return fail(MIXGCN_EINVAL, "aggregate_masked: mask is null");
+    return aggregate_impl(g, transpose, dtype, H, ldh, Z, ldz, col_begin, col_end, row_begin,
+                          row_end, 0, (hipStream_t)stream, nullptr, mask, ld_mask);
+}
+
+int mixgcn_relu_bitmap(int dtype, const void* X, int64_t ldx, int64_t n_rows, int32_t n_cols,
+                       uint32_t* mask, int64_t ld_mask, void* stream)
+{
+    if (dtype != MIXGCN_F32 && dtype != MIXGCN_BF16)
+        return fail(MIXGCN_EINVAL, "relu_bitmap: dtype");
+    if (n_rows < 0 || n_cols <= 0) return fail(MIXGCN_EINVAL, "relu_bitmap: sizes");
+    if (!mask) return fail(MIXGCN_EINVAL, "relu_bitmap: null pointer");
+    MIXGCN_TRY(check_matrix("relu_bitmap: X", X, ldx, n_cols, elem_size(dtype)));
+    if (ld_mask < ((int64_t)n_cols + 31) / 32)
+        return fail(MIXGCN_EINVAL, "relu_bitmap: ld_mask shorter than ceil(n_cols / 32) words");
+    return launch_relu_bitmap(dtype, X, ldx, n_rows, n_cols, mask, ld_mask, (hipStream_t)stream);
 }
 
 static int update_impl(int op, int dtype, const void* A, int64_t lda, const void* B, int64_t ldb,

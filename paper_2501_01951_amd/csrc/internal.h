@@ -137,9 +137,14 @@ int csr_from_edges(const uint32_t* d_src, const uint32_t* d_dst, uint64_t n_edge
 void csr_free(Csr* c);
 int normalize_sym(mixgcn_graph* g, hipStream_t s);
 
+// mask: optional bitmap applied to the written outputs (bit c % 32 of mask[r * ldm + c / 32])
 int launch_aggregate(const mixgcn_graph* g, const Csr& m, int dtype, const void* H, int64_t ldh,
                      void* Z, int64_t ldz, int32_t c0, int32_t c1, int64_t r0, int64_t r1,
-                     int relu, hipStream_t s, Timer* timer);
+                     int relu, const uint32_t* mask, int64_t ldm, hipStream_t s, Timer* timer);
+
+// bits[r * ldb + c / 32] bit c % 32 = X[r, c] > 0; every word of a row up to ldb is written
+int launch_relu_bitmap(int dtype, const void* X, int64_t ldx, int64_t n, int32_t cols,
+                       uint32_t* bits, int64_t ldb, hipStream_t s);
 
 // G <- G (.) 1[R > 0] in place (ReLU derivative taken from the stored activation R).
 int launch_relu_mask(int dtype, void* G, int64_t ldg, const void* R, int64_t ldr, int64_t n,

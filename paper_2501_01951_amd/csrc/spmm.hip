@@ -106,6 +106,18 @@ __device__ inline void reduce_subgroups(float* v)
         for (int i = 0; i < VEC; ++i) v[i] += __shfl_xor(v[i], d, kWave);
 }
 
+// Output mask of the S-SpMM (paper Eq. 4), a bitmap: column c of row r is bit c % 32 of word
+// mask[r * ldm + c / 32].  A lane's VEC consecutive columns start at a multiple of VEC, so
+// their bits lie in one word.
+template <int VEC>
+__device__ inline void apply_mask(float* t, const uint32_t* __restrict__ mask, int64_t ldm,
+                                  int64_t r, int64_t c)
+{
+    const uint32_t bits = mask[r * ldm + (c >> 5)] >> (c & 31);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) t[i] = ((bits >> i) & 1u) ? t[i] : 0.f;
+}
+
 // Partial-sum slots: [span in call][head = 0 / tail = 1][part_stride] fp32, indexed by the
 // column offset within the pass.
 // GF = lanes that would span the whole pass (its width class: 4 GF fp32 or 8 GF bf16 columns);
@@ -118,7 +130,8 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
     const uint32_t* __restrict__ grp_row, const void* __restrict__ H, int64_t ldh,
     void* __restrict__ Z, int64_t ldz, int c0, int width, int64_t row_begin, int64_t row_end,
     int64_t e_begin, int64_t e_end, int64_t span_first, int64_t n_spans,
-    float* __restrict__ partials, int n_slices, int relu)
+    float* __restrict__ partials, int n_slices, int relu, const uint32_t* __restrict__ mask,
+    int64_t ldm)
 {
     using F = Feat<DT>;
     constexpr int VEC = F::VEC;
@@ -258,6 +271,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
 #pragma unroll
                                 for (int i = 0; i < VEC; ++i) t[i] = fmaxf(t[i], 0.f);
                             }
+                            if (mask) apply_mask<VEC>(t, mask, ldm, r, coff);
                             F::store(Z, r * ldz + coff, t);
                         }
                     }
@@ -312,7 +326,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_fixup_kernel(
     const int64_t* __restrict__ rowptr, const uint32_t* __restrict__ grp_row,
     void* __restrict__ Z, int64_t ldz, int c0, int width, int64_t e_begin, int64_t e_end,
     int64_t span, int64_t span_first, int64_t n_spans, const float* __restrict__ partials,
-    int relu)
+    int relu, const uint32_t* __restrict__ mask, int64_t ldm)
 {
     using F = Feat<DT>;
     constexpr int VEC = F::VEC;
@@ -347,6 +361,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_fixup_kernel(
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[i] = fmaxf(acc[i], 0.f);
     }
+    if (mask) apply_mask<VEC>(acc, mask, ldm, r, (int64_t)c0 + (int64_t)lg * VEC);
     F::store(Z, r * ldz + (int64_t)c0 + (int64_t)lg * VEC, acc);
 }
 
@@ -370,7 +385,7 @@ template <int LPR, int GF, int DT>
 int launch_main(const Csr& m, int64_t n_nodes, const void* H, int64_t ldh, void* Z, int64_t ldz,
                 int c0, int width,
                 int64_t r0, int64_t r1, int64_t e0, int64_t e1, float* partials, int relu,
-                hipStream_t s, Timer* timer)
+                const uint32_t* mask, int64_t ldm, hipStream_t s, Timer* timer)
 {
     constexpr int PW = LPR * Feat<DT>::VEC;
     constexpr int64_t SPAN = span_entries<LPR>();
@@ -392,7 +407,7 @@ int launch_main(const Csr& m, int64_t n_nodes, const void* H, int64_t ldh, void*
 #define MIXGCN_AGG_LAUNCH(EMPTY, O32)                                                            \
     hipLaunchKernelGGL((aggregate_kernel<LPR, GF, DT, EMPTY, O32>), dim3(grid), dim3(kBlock), 0, \
                        s, m.rowptr, m.cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,  \
-                       span_first, n_spans, partials, n_slices, relu)
+                       span_first, n_spans, partials, n_slices, relu, mask, ldm)
     if (m.has_empty_rows) {
         if (off32) MIXGCN_AGG_LAUNCH(true, true);
         else MIXGCN_AGG_LAUNCH(true, false);
@@ -407,7 +422,8 @@ int launch_main(const Csr& m, int64_t n_nodes, const void* H, int64_t ldh, void*
 
 template <int GF, int DT>
 int launch_fixup(const Csr& m, void* Z, int64_t ldz, int c0, int width, int64_t e0, int64_t e1,
-                 int64_t span, const float* partials, int relu, hipStream_t s)
+                 int64_t span, const float* partials, int relu, const uint32_t* mask,
+                 int64_t ldm, hipStream_t s)
 {
     constexpr int GPB = kBlock / GF;
     const int64_t span_first = e0 / span;
@@ -416,7 +432,7 @@ int launch_fixup(const Csr& m, void* Z, int64_t ldz, int c0, int width, int64_t 
         const unsigned fgrid = (unsigned)ceil_div(n_spans - 1, GPB);
         hipLaunchKernelGGL((aggregate_fixup_kernel<GF, DT>), dim3(fgrid), dim3(kBlock), 0, s,
                            m.rowptr, m.grp_row, Z, ldz, c0, width, e0, e1, span, span_first,
-                           n_spans, partials, relu);
+                           n_spans, partials, relu, mask, ldm);
     }
     return MIXGCN_OK;
 }
@@ -430,7 +446,7 @@ constexpr int slice_lanes(int gf) { return gf < 8 ? gf : 8; }
 template <int DT>
 int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, void* Z,
               int64_t ldz, int32_t c0, int32_t c1, int64_t r0, int64_t r1, int relu,
-              hipStream_t s, Timer* timer)
+              const uint32_t* mask, int64_t ldm, hipStream_t s, Timer* timer)
 {
     constexpr int VEC = Feat<DT>::VEC;
     constexpr int kMaxTile = 64 * VEC;  // widest pass
@@ -467,8 +483,8 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, v
         float* P = g->partials;
 #define MIXGCN_AGG_PASS(GG)                                                                      \
     MIXGCN_TRY((launch_main<slice_lanes(GG), GG, DT>(m, (int64_t)g->n, H, ldh, Z, ldz, cb, w, r0,  \
-                                                     r1, e0, e1, P, relu, s, timer)));            \
-    MIXGCN_TRY((launch_fixup<GG, DT>(m, Z, ldz, cb, w, e0, e1, span, P, relu, s)))
+                                                     r1, e0, e1, P, relu, mask, ldm, s, timer))); \
+    MIXGCN_TRY((launch_fixup<GG, DT>(m, Z, ldz, cb, w, e0, e1, span, P, relu, mask, ldm, s)))
         switch (GF) {
         case 4: MIXGCN_AGG_PASS(4); break;
         case 8: MIXGCN_AGG_PASS(8); break;
@@ -482,15 +498,68 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, v
     return MIXGCN_OK;
 }
 
+// bit c % 32 of bits[r * ldb + c / 32] = X[r, c] > 0.  A lane takes the 16 bytes that hold
+// columns [VEC q, VEC q + VEC) of one row, 32 / VEC neighboring lanes combine their bits into
+// one word with OR-shuffles and the first of them writes it.  words = words written per row.
+template <int DT>
+__global__ __launch_bounds__(kBlock) void relu_bitmap_kernel(const void* __restrict__ X,
+                                                             int64_t ldx, int64_t n, int cols,
+                                                             int words, uint32_t* __restrict__ bits,
+                                                             int64_t ldb)
+{
+    using F = Feat<DT>;
+    constexpr int VEC = F::VEC;       // 4 fp32 or 8 bf16 per lane
+    constexpr int LPW = 32 / VEC;     // lanes per word
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int qpr = words * LPW;      // lanes per row
+    const int64_t r = i / qpr;
+    const int q = (int)(i % qpr);
+    const int c = q * VEC;
+    uint32_t nib = 0;
+    if (r < n && c < cols) {
+        float x[VEC];
+        F::widen(*F::ptr(X, r * ldx + c), x);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+            if (c + e < cols && x[e] > 0.f) nib |= 1u << e;
+    }
+    uint32_t w = nib << (VEC * (q % LPW));
+#pragma unroll
+    for (int o = 1; o < LPW; o <<= 1) w |= __shfl_xor(w, o, kWave);
+    if (q % LPW == 0 && r < n) bits[r * ldb + q / LPW] = w;
+}
+
 }  // namespace
+
+int launch_relu_bitmap(int dtype, const void* X, int64_t ldx, int64_t n, int32_t cols,
+                       uint32_t* bits, int64_t ldb, hipStream_t s)
+{
+    if (n == 0) return MIXGCN_OK;
+    // every word of a row up to ldb is written (zero past cols); a row takes whole lane groups,
+    // and kBlock is a multiple of the group size, so a group never straddles a wavefront
+    const int words = (int)ldb;
+    const int es = dtype == MIXGCN_F32 ? 4 : 2;
+    const int lanes_per_word = 32 / (16 / es);
+    const int64_t total = n * (int64_t)words * lanes_per_word;
+    const dim3 grid((unsigned)ceil_div(total, kBlock));
+    if (dtype == MIXGCN_F32)
+        hipLaunchKernelGGL(relu_bitmap_kernel<MIXGCN_F32>, grid, dim3(kBlock), 0, s, X, ldx, n, cols,
+                           words, bits, ldb);
+    else
+        hipLaunchKernelGGL(relu_bitmap_kernel<MIXGCN_BF16>, grid, dim3(kBlock), 0, s, X, ldx, n,
+                           cols, words, bits, ldb);
+    MIXGCN_HIP_TRY(hipGetLastError());
+    return MIXGCN_OK;
+}
 
 int launch_aggregate(const mixgcn_graph* g, const Csr& m, int dtype, const void* H, int64_t ldh,
                      void* Z, int64_t ldz, int32_t c0, int32_t c1, int64_t r0, int64_t r1,
-                     int relu, hipStream_t s, Timer* timer)
+                     int relu, const uint32_t* mask, int64_t ldm, hipStream_t s, Timer* timer)
 {
     if (dtype == MIXGCN_F32)
-        return launch_dt<MIXGCN_F32>(g, m, H, ldh, Z, ldz, c0, c1, r0, r1, relu, s, timer);
-    return launch_dt<MIXGCN_BF16>(g, m, H, ldh, Z, ldz, c0, c1, r0, r1, relu, s, timer);
+        return launch_dt<MIXGCN_F32>(g, m, H, ldh, Z, ldz, c0, c1, r0, r1, relu, mask, ldm, s,
+                                     timer);
+    return launch_dt<MIXGCN_BF16>(g, m, H, ldh, Z, ldz, c0, c1, r0, r1, relu, mask, ldm, s, timer);
 }
 
 }  // namespace mixgcn

@@ -163,6 +163,103 @@ def test_aggregate_slices_and_row_ranges(mg, rmat15):
     assert np.all(zz == -3.0)
 
 
+# S-SpMM (Sec. 3.2.1, Eq. 4): masked aggregation with the mask in bitmap form
+@pytest.mark.parametrize("n,c", [(1, 1), (77, 31), (1000, 32), (513, 33), (300, 64), (2049, 100),
+                                 (999, 256), (64, 300)])
+def test_relu_bitmap_bit_exact(mg, n, c):
+    say(f"relu_bitmap n={n} c={c}")
+    ld = (c + 7) // 8 * 8
+    xp = gg.normal(31, c, n, c, ld=ld)
+    xp[:, c:] = 1.0  # row padding must not leak into the bits
+    xp[0, 0] = 0.0
+    x = xp[:, :c]
+    ref = oracle.relu_bitmap(x.astype(np.float64))
+    xd = dev(xp)[:, :c]
+    bits = mg.relu_bitmap(xd)
+    assert np.array_equal(bits.cpu().numpy().view(np.uint32), ref)
+    # a wider destination: every word of the row is written, the extra ones as zero
+    wide = torch.full((n, ref.shape[1] + 2), -1, dtype=torch.int32, device="cuda")
+    mg.relu_bitmap(xd, wide)
+    w = wide.cpu().numpy().view(np.uint32)
+    assert np.array_equal(w[:, :ref.shape[1]], ref) and not w[:, ref.shape[1]:].any()
+    # bf16 storage
+    xb = bf16_round(x)
+    bits = mg.relu_bitmap(dev_bf16(xb, ld))
+    assert np.array_equal(bits.cpu().numpy().view(np.uint32), oracle.relu_bitmap(xb.astype(np.float64)))
+
+
+@pytest.mark.parametrize("f,ld", [(4, 4), (16, 16), (40, 40), (100, 128), (256, 256), (300, 304)])
+def test_aggregate_masked_full_width(mg, rmat15, f, ld):
+    og, g = rmat15
+    say(f"aggregate_masked rmat15 f={f} ld={ld}")
+    h = gg.normal(32, f, og.n, f, ld=ld)
+    act = gg.normal(33, f, og.n, f)  # the activation whose sign pattern is the mask (about 50 %)
+    ref_bits = oracle.relu_bitmap(act.astype(np.float64))
+    bits = mg.relu_bitmap(dev(act))
+    z = torch.full((og.n, ld), 7.0, device="cuda")
+    mg.aggregate_masked(g, dev(h), z, bits, col_end=f)
+    ref = oracle.sspmm(og, h[:, :f].astype(np.float64), ref_bits)
+    z = z.cpu().numpy()
+    assert_close(z[:, :f], ref, RTOL_F32, f"S-SpMM f={f}")
+    assert np.array_equal(z[:, :f] == 0.0, ref == 0.0)  # masked outputs are exact zeros
+    up = (f + 3) // 4 * 4
+    assert np.all(z[:, up:] == 7.0)
+
+
+def test_aggregate_masked_slices_rows_transpose_bf16(mg, rmat15):
+    og, g = rmat15
+    f = 128
+    h = gg.normal(34, 1, og.n, f)
+    act = gg.normal(35, 1, og.n, f)
+    ref_bits = oracle.relu_bitmap(act.astype(np.float64))
+    bits = mg.relu_bitmap(dev(act))
+    ref = oracle.sspmm(og, h.astype(np.float64), ref_bits)
+    hd = dev(h)
+    z = torch.full((og.n, f), -3.0, device="cuda")
+    say("aggregate_masked column slices x row chunks")
+    bounds = [0, 1, 1, 777, 20000, og.n]
+    for r0, r1 in zip(bounds[:-1], bounds[1:]):
+        for i in range(4):
+            mg.aggregate_masked(g, hd, z, bits, col_begin=f * i // 4, col_end=f * (i + 1) // 4,
+                                row_begin=r0, row_end=r1)
+    assert_close(z.cpu().numpy(), ref, RTOL_F32, "S-SpMM slices x chunks")
+    say("aggregate_masked bf16")
+    hb = bf16_round(h)
+    zb = torch.full((og.n, f), 7.0, dtype=torch.bfloat16, device="cuda")
+    mg.aggregate_masked(g, dev_bf16(hb), zb, bits)
+    refb = oracle.sspmm(og, hb.astype(np.float64), ref_bits, q=oracle.Q_BF16)
+    assert_close(zb.float().cpu().numpy(), refb, RTOL_BF16, "S-SpMM bf16")
+    say("aggregate_masked directed, transposed, with empty rows")
+    src, dst = gg.rmat_edges(21, 13, 40_000)
+    n = 1 << 13
+    og2 = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n, False, False)))
+    g2 = _gpu_graph(mg, src, dst, n, sym=False, loops=False)
+    h2 = gg.normal(36, 1, n, 64)
+    a2 = gg.normal(37, 1, n, 64)
+    b2 = oracle.relu_bitmap(a2.astype(np.float64))
+    z2 = torch.full((n, 64), 5.0, device="cuda")
+    mg.aggregate_masked(g2, dev(h2), z2, mg.relu_bitmap(dev(a2)), transpose=True)
+    assert_close(z2.cpu().numpy(), oracle.sspmm(og2, h2.astype(np.float64), b2, transposed=True),
+                 RTOL_F32, "S-SpMM directed transpose")
+    g2.free()
+    with pytest.raises(mg.MixGCNError):  # bitmap rows shorter than the column range needs
+        mg.aggregate_masked(g, hd, z, bits[:, :2].contiguous())
+
+
+def test_aggregate_masked_backward_use_matches_mask_after_aggregate(mg, rmat15):
+    """The backward use: dP = (A_hat^T dZ) (.) 1[H > 0] in one pass equals the plain aggregation
+    followed by the ReLU-derivative mask, bit for bit."""
+    og, g = rmat15
+    f = 64
+    dz = dev(gg.normal(38, 1, og.n, f))
+    hprev = dev(np.maximum(gg.normal(39, 1, og.n, f), 0.0))
+    fused = torch.empty(og.n, f, device="cuda")
+    mg.aggregate_masked(g, dz, fused, mg.relu_bitmap(hprev), transpose=True)
+    plain = torch.empty(og.n, f, device="cuda")
+    mg.aggregate(g, dz, plain, transpose=True)
+    assert torch.equal(fused, torch.where(hprev > 0, plain, torch.zeros_like(plain)))
+
+
 def test_aggregate_is_deterministic(mg, rmat15):
     og, g = rmat15
     hd = dev(gg.normal(13, 1, og.n, 64))
