@@ -3,6 +3,8 @@
 // (v_mfma_f32_32x32x2_f32).  Row-block kernels: the node dimension is the long one, the feature
 // dimensions are at most a few hundred, so a workgroup owns 128 node rows (forward / dgrad) or
 // a slab of node rows (wgrad, split over the reduction and combined in fp64 by a second kernel).
+#include <type_traits>
+
 #include "device_utils.h"
 #include "internal.h"
 
@@ -56,6 +58,10 @@ __device__ inline void mma_step(const float* As, const float* Bs, int wm, int wn
             for (int tn = 0; tn < S::TN; ++tn)
                 acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][tm], b[cur][tn],
                                                                    acc[tm][tn], 0, 0, 0);
+        // keep the order written here: the LDS reads of step k2 + 2 go out before the MFMAs of
+        // step k2, so their latency hides behind the matrix pipe instead of in front of it
+        __builtin_amdgcn_sched_group_barrier(0x100, S::TM + S::TN, 0);  // DS reads
+        __builtin_amdgcn_sched_group_barrier(0x008, S::TM * S::TN, 0);  // MFMAs
     }
 }
 
@@ -107,6 +113,8 @@ struct Piece {
         v = *reinterpret_cast<const Raw4<T>*>(M + rr * ld + cc);
         if (MASK) m = *reinterpret_cast<const Raw4<T>*>(R + rr * ldr + cc);
     }
+    // CHECKED = false: the caller knows the piece lies wholly inside the matrix
+    template <bool CHECKED = true>
     __device__ inline float4 value() const
     {
         float4 o = v.widen();
@@ -117,7 +125,7 @@ struct Piece {
             o.z = mm.z > 0.f ? o.z : 0.f;
             o.w = mm.w > 0.f ? o.w : 0.f;
         }
-        if (nvalid < 4) {
+        if (CHECKED && nvalid < 4) {
             if (nvalid < 1) o.x = 0.f;
             if (nvalid < 2) o.y = 0.f;
             if (nvalid < 3) o.z = 0.f;
@@ -192,11 +200,14 @@ __global__ __launch_bounds__(kBlock) void rowblock_gemm_kernel(
             }
         }
     };
-    auto store_tiles = [&](float* as, float* bs) {
+    // CHECKED = false when every piece of the two tiles lies inside its matrix (uniform): the
+    // zero fill then costs no vector ALU work next to the MFMAs
+    auto store_tiles_as = [&](float* as, float* bs, auto checked) {
+        constexpr bool CHECKED = decltype(checked)::value;
 #pragma unroll
         for (int p = 0; p < A_PASSES; ++p) {
             const int i = p * 64 + tid / 4, kq = 4 * (tid & 3);
-            const float4 v = ra[p].value();
+            const float4 v = ra[p].template value<CHECKED>();
             as[(kq + 0) * LDA + i] = v.x;
             as[(kq + 1) * LDA + i] = v.y;
             as[(kq + 2) * LDA + i] = v.z;
@@ -207,7 +218,7 @@ __global__ __launch_bounds__(kBlock) void rowblock_gemm_kernel(
             for (int p = 0; p < BT_PASSES; ++p) {
                 const int j = p * 64 + tid / 4, kq = 4 * (tid & 3);
                 if (j < S::BN) {
-                    const float4 v = rb[p].value();
+                    const float4 v = rb[p].template value<CHECKED>();
                     bs[(kq + 0) * LDB + j] = v.x;
                     bs[(kq + 1) * LDB + j] = v.y;
                     bs[(kq + 2) * LDB + j] = v.z;
@@ -219,20 +230,26 @@ __global__ __launch_bounds__(kBlock) void rowblock_gemm_kernel(
             for (int p = 0; p < B_PASSES; ++p) {
                 const int kk = p * B_ROWS_PER_PASS + tid / BN_F4;
                 if (kk < BK)
-                    *reinterpret_cast<float4*>(&bs[kk * LDB + 4 * (tid % BN_F4)]) = rb[p].value();
+                    *reinterpret_cast<float4*>(&bs[kk * LDB + 4 * (tid % BN_F4)]) =
+                        rb[p].template value<CHECKED>();
             }
         }
+    };
+    const bool tile_inside = row0 + S::BM <= n && col0 + S::BN <= MD;
+    auto store_tiles = [&](float* as, float* bs, int k0) {
+        if (tile_inside && k0 + BK <= KD) store_tiles_as(as, bs, std::false_type{});
+        else store_tiles_as(as, bs, std::true_type{});
     };
 
     const int nk = (KD + BK - 1) / BK;
     issue_tiles(0);
-    store_tiles(As[0], Bs[0]);
+    store_tiles(As[0], Bs[0], 0);
     __syncthreads();
     for (int i = 0; i < nk; ++i) {
         const int cur = i & 1;
         if (i + 1 < nk) issue_tiles((i + 1) * BK);
         mma_step<S>(As[cur], Bs[cur], wm, wn, lane, acc);
-        if (i + 1 < nk) store_tiles(As[cur ^ 1], Bs[cur ^ 1]);
+        if (i + 1 < nk) store_tiles(As[cur ^ 1], Bs[cur ^ 1], (i + 1) * BK);
         __syncthreads();
     }
 
@@ -304,29 +321,39 @@ __global__ __launch_bounds__(kBlock) void wgrad_slab_kernel(
             rb[p].issue(B, ldb, r0 + (kk < BK ? kk : 0), j0 + 4 * (tid % BN_F4), r_end, MD, R, ldr);
         }
     };
-    auto store_tiles = [&](float* as, float* bs) {
+    auto store_tiles_as = [&](float* as, float* bs, auto checked) {
+        constexpr bool CHECKED = decltype(checked)::value;
 #pragma unroll
         for (int p = 0; p < A_PASSES; ++p) {
             const int kk = p * A_RPP + tid / AM_F4;
-            if (kk < BK) *reinterpret_cast<float4*>(&as[kk * LDA + 4 * (tid % AM_F4)]) = ra[p].value();
+            if (kk < BK)
+                *reinterpret_cast<float4*>(&as[kk * LDA + 4 * (tid % AM_F4)]) =
+                    ra[p].template value<CHECKED>();
         }
 #pragma unroll
         for (int p = 0; p < B_PASSES; ++p) {
             const int kk = p * B_RPP + tid / BN_F4;
-            if (kk < BK) *reinterpret_cast<float4*>(&bs[kk * LDB + 4 * (tid % BN_F4)]) = rb[p].value();
+            if (kk < BK)
+                *reinterpret_cast<float4*>(&bs[kk * LDB + 4 * (tid % BN_F4)]) =
+                    rb[p].template value<CHECKED>();
         }
+    };
+    const bool tile_inside = i0 + S::BM <= KD && j0 + S::BN <= MD;
+    auto store_tiles = [&](float* as, float* bs, int64_t r0) {
+        if (tile_inside && r0 + BK <= r_end) store_tiles_as(as, bs, std::false_type{});
+        else store_tiles_as(as, bs, std::true_type{});
     };
 
     if (r_begin < r_end) {
         const int64_t nk = (r_end - r_begin + BK - 1) / BK;
         issue_tiles(r_begin);
-        store_tiles(As[0], Bs[0]);
+        store_tiles(As[0], Bs[0], r_begin);
         __syncthreads();
         for (int64_t i = 0; i < nk; ++i) {
             const int cur = (int)(i & 1);
             if (i + 1 < nk) issue_tiles(r_begin + (i + 1) * BK);
             mma_step<S>(As[cur], Bs[cur], wm, wn, lane, acc);
-            if (i + 1 < nk) store_tiles(As[cur ^ 1], Bs[cur ^ 1]);
+            if (i + 1 < nk) store_tiles(As[cur ^ 1], Bs[cur ^ 1], r_begin + (i + 1) * BK);
             __syncthreads();
         }
     }
