@@ -47,6 +47,12 @@ def _load():
         lib.oracle_transpose.restype = None
         lib.oracle_spmm.argtypes = [p, p, p, p, i64, p, i64, i64, i64, i64, i64, i32]
         lib.oracle_spmm.restype = None
+        lib.oracle_rcm.argtypes = [p, p, u32, p]
+        lib.oracle_rcm.restype = None
+        lib.oracle_bandwidth.argtypes = [p, p, u32, p]
+        lib.oracle_bandwidth.restype = i64
+        lib.oracle_pipeline_stages.argtypes = [i64, i64]
+        lib.oracle_pipeline_stages.restype = i64
         lib.oracle_relu_bitmap.argtypes = [p, i64, i64, i64, p, i64]
         lib.oracle_relu_bitmap.restype = None
         lib.oracle_sspmm.argtypes = [p, p, p, p, i64, p, i64, i64, i64, i64, i64, p, i64, i32]
@@ -144,6 +150,26 @@ def spmm(g: Graph, H, c0=0, c1=None, r0=0, r1=None, transposed=False, q=Q_NONE, 
     _load().oracle_spmm(_p(rp), _p(cl), _p(vl), _p(H), H.shape[1], _p(Z), Z.shape[1], c0, c1, r0,
                         r1, q)
     return Z
+
+
+def rcm(g: Graph):
+    """Reverse Cuthill-McKee positions pos[v] (uint32[n]) of the nodes of g."""
+    pos = np.empty(g.n, dtype=np.uint32)
+    _load().oracle_rcm(_p(g.rowptr), _p(g.col), g.n, _p(pos))
+    return pos
+
+
+def bandwidth(g: Graph, pos=None) -> int:
+    """max |pos[u] - pos[v]| over the stored entries; pos None = identity."""
+    if pos is not None:
+        pos = np.ascontiguousarray(pos, dtype=np.uint32)
+    return int(_load().oracle_bandwidth(_p(g.rowptr), _p(g.col), g.n,
+                                        _p(pos) if pos is not None else None))
+
+
+def pipeline_stages(n: int, b: int) -> int:
+    """Smallest number of batches s with (n - b) / (2 n) >= 1 / s; 0 if there is none."""
+    return int(_load().oracle_pipeline_stages(n, b))
 
 
 def relu_bitmap(X):

@@ -208,6 +208,71 @@ void oracle_sspmm(const int64_t* rowptr, const uint32_t* col, const double* val,
         }
 }
 
+/*
+ * Node reordering (Sec. 3.2.2): reverse Cuthill-McKee positions.  pos[v] = place of node v in
+ * the processing sequence (the paper's p_v).  The rule, made deterministic:
+ *   - the degree of a node is the number of stored entries of its row;
+ *   - a component is started from the unvisited node with the smallest (degree, id);
+ *   - nodes are visited in queue order, and the unvisited neighbors of the node being visited
+ *     join the queue in increasing (degree, id);
+ *   - the final sequence is the visiting sequence reversed.
+ */
+void oracle_rcm(const int64_t* rowptr, const uint32_t* col, uint32_t n, uint32_t* pos)
+{
+    std::vector<uint32_t> by_deg(n), order;
+    order.reserve(n);
+    for (uint32_t v = 0; v < n; ++v) by_deg[v] = v;
+    auto deg = [&](uint32_t v) { return rowptr[v + 1] - rowptr[v]; };
+    auto less = [&](uint32_t a, uint32_t b) {
+        return deg(a) != deg(b) ? deg(a) < deg(b) : a < b;
+    };
+    std::sort(by_deg.begin(), by_deg.end(), less);
+    std::vector<char> seen(n, 0);
+    std::vector<uint32_t> nb;
+    size_t head = 0;
+    for (uint32_t root : by_deg) {
+        if (seen[root]) continue;
+        seen[root] = 1;
+        order.push_back(root);
+        while (head < order.size()) {
+            const uint32_t u = order[head++];
+            nb.clear();
+            for (int64_t e = rowptr[u]; e < rowptr[u + 1]; ++e)
+                if (!seen[col[e]]) {
+                    seen[col[e]] = 1;
+                    nb.push_back(col[e]);
+                }
+            std::sort(nb.begin(), nb.end(), less);
+            order.insert(order.end(), nb.begin(), nb.end());
+        }
+    }
+    for (uint32_t i = 0; i < n; ++i) pos[order[i]] = n - 1 - i;
+}
+
+/* Graph bandwidth under a processing sequence (Sec. 3.2.2): b = max over stored entries (u, v)
+ * of |p_v - p_u|; pos == NULL means the identity sequence. */
+int64_t oracle_bandwidth(const int64_t* rowptr, const uint32_t* col, uint32_t n,
+                         const uint32_t* pos)
+{
+    int64_t b = 0;
+    for (uint32_t u = 0; u < n; ++u)
+        for (int64_t e = rowptr[u]; e < rowptr[u + 1]; ++e) {
+            const int64_t pu = pos ? pos[u] : u, pv = pos ? pos[col[e]] : col[e];
+            b = std::max<int64_t>(b, pu > pv ? pu - pv : pv - pu);
+        }
+    return b;
+}
+
+/* Proposition 3.5: the idleness of the fine-grain pipeline can be removed when
+ * (n - b) / (2 n) >= 1 / s; the smallest such number of batches s, or 0 if there is none
+ * (b >= n). */
+int64_t oracle_pipeline_stages(int64_t n, int64_t b)
+{
+    if (n <= 0 || b >= n) return 0;
+    for (int64_t s = 1;; ++s)  /* by definition: first s that satisfies the inequality */
+        if ((n - b) * s >= 2 * n) return s;
+}
+
 /* Node update (Algorithm 2, update phase):  P = Z W  (n x k times k x m), then optional ReLU. */
 void oracle_update_fwd(const double* Z, int64_t ldz, const double* W, int64_t ldw, double* Hout,
                        int64_t ldo, int64_t n, int64_t k, int64_t m, int relu, int q)

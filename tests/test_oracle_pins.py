@@ -254,6 +254,104 @@ def test_sspmm_complement_identity_and_regular_graph_closed_form():
                                rtol=0, atol=1e-15)
 
 
+# ------------------------------------------------------------------------------------------
+# node reordering (Sec. 3.2.2): reverse Cuthill-McKee, bandwidth, Proposition 3.5
+# ------------------------------------------------------------------------------------------
+def scrambled(src, dst, n, seed):
+    perm = np.random.default_rng(seed).permutation(n)
+    return perm[np.asarray(src)], perm[np.asarray(dst)]
+
+
+def test_rcm_golden_hand_example():
+    edges, pos, b = [], None, None
+    for line in open(os.path.join(GOLD, "rcm_hand6.txt")):
+        t = line.split()
+        if not t or t[0] == "#":
+            continue
+        if t[0] == "pos":
+            pos = [int(x) for x in t[1:]]
+        elif t[0] == "bandwidth":
+            b = int(t[1])
+        else:
+            edges.append((int(t[0]), int(t[1])))
+    g = oracle.build_csr([e[0] for e in edges], [e[1] for e in edges], 6)
+    got = oracle.rcm(g)
+    assert got.tolist() == pos
+    assert oracle.bandwidth(g, got) == b
+
+
+def test_rcm_closed_forms_path_cycle_star_complete():
+    n = 40
+    # a path, however it is labelled, is laid out end to end: bandwidth 1; two paths as well
+    s, d = scrambled(np.arange(n - 1), np.arange(1, n), n, 1)
+    g = oracle.build_csr(s, d, n)
+    pos = oracle.rcm(g)
+    assert sorted(pos.tolist()) == list(range(n))
+    assert oracle.bandwidth(g, pos) == 1 and oracle.bandwidth(g) > 1
+    a = np.r_[np.arange(0, 19), np.arange(20, 39)]
+    s, d = scrambled(a, a + 1, n, 2)
+    g = oracle.build_csr(s, d, n)
+    assert oracle.bandwidth(g, oracle.rcm(g)) == 1
+    # a cycle is folded: bandwidth 2
+    s, d = scrambled(np.arange(n), (np.arange(n) + 1) % n, n, 3)
+    g = oracle.build_csr(s, d, n)
+    assert oracle.bandwidth(g, oracle.rcm(g)) == 2
+    # a star started from a leaf: leaf, centre, the other leaves -> the centre is n - 2 places
+    # away from the last leaf
+    s, d = scrambled(np.zeros(n - 1, dtype=int), np.arange(1, n), n, 4)
+    g = oracle.build_csr(s, d, n)
+    assert oracle.bandwidth(g, oracle.rcm(g)) == n - 2
+    # complete graph: every sequence has bandwidth n - 1
+    iu = np.triu_indices(12, 1)
+    g = oracle.build_csr(iu[0], iu[1], 12)
+    assert oracle.bandwidth(g, oracle.rcm(g)) == 11 == oracle.bandwidth(g)
+
+
+def test_rcm_grid_and_brute_force_lower_bound():
+    # r x c grid, scrambled: breadth-first levels from a corner are anti-diagonals of at most
+    # min(r, c) nodes and edges join consecutive levels, so the bandwidth stays below 2 min(r, c)
+    r, c = 7, 30
+    idx = np.arange(r * c).reshape(r, c)
+    s = np.r_[idx[:, :-1].ravel(), idx[:-1, :].ravel()]
+    d = np.r_[idx[:, 1:].ravel(), idx[1:, :].ravel()]
+    s, d = scrambled(s, d, r * c, 5)
+    g = oracle.build_csr(s, d, r * c)
+    b = oracle.bandwidth(g, oracle.rcm(g))
+    assert r <= b < 2 * r and oracle.bandwidth(g) > 4 * r
+    # tiny graphs: never better than the optimum found by trying every sequence
+    import itertools
+    rng = np.random.default_rng(6)
+    for _ in range(5):
+        n = 7
+        s, d = rng.integers(0, n, 9), rng.integers(0, n, 9)
+        g = oracle.build_csr(s, d, n)
+        best = min(oracle.bandwidth(g, np.array(p, dtype=np.uint32))
+                   for p in itertools.permutations(range(n)))
+        got = oracle.bandwidth(g, oracle.rcm(g))
+        assert best <= got <= oracle.bandwidth(g) or got <= n - 1
+
+
+def test_bandwidth_definition_vs_numpy():
+    rng = np.random.default_rng(7)
+    n = 200
+    s, d = rng.integers(0, n, 900), rng.integers(0, n, 900)
+    g = oracle.build_csr(s, d, n)
+    pos = rng.permutation(n).astype(np.uint32)
+    keep = s != d
+    assert oracle.bandwidth(g) == np.abs(s[keep] - d[keep]).max()
+    assert oracle.bandwidth(g, pos) == np.abs(pos[s[keep]].astype(np.int64) - pos[d[keep]]).max()
+
+
+def test_pipeline_stages_is_proposition_3_5():
+    for n in (10, 100, 4096, 1 << 20):
+        for b in (0, 1, n // 3, n // 2, n - 2, n - 1):
+            s = oracle.pipeline_stages(n, b)
+            assert s == -(-2 * n // (n - b))            # ceil(2n / (n - b))
+            assert (n - b) * s >= 2 * n and (s == 1 or (n - b) * (s - 1) < 2 * n)
+        assert oracle.pipeline_stages(n, n) == 0 and oracle.pipeline_stages(n, n + 5) == 0
+    assert oracle.pipeline_stages(100, 0) == 2  # no dependence at all still needs two batches
+
+
 def test_transpose_on_directed_input_adjoint_and_dense():
     rng = np.random.default_rng(4)
     n = 40
