@@ -232,6 +232,36 @@ enum { MIXGCN_TIME_AGG_G4 = 0, MIXGCN_TIME_AGG_G8 = 1, MIXGCN_TIME_AGG_G16 = 2,
 int mixgcn_pipeline_timing(mixgcn_pipeline* p, int enable);
 int mixgcn_pipeline_timing_read(mixgcn_pipeline* p, int kind, double* total_ms, int64_t* launches);
 /*
+ * Sec. 3.2.2 (pipeline scheduler with node reordering).  mixgcn_reorder_rcm writes the position
+ * p_v of every node in a reverse Cuthill-McKee processing sequence to pos[v] (device, n_nodes
+ * uint32), computed from the stored rows of the graph (for a symmetrised graph: its undirected
+ * form).  The rule is deterministic: degree = stored entries of the row; a component starts
+ * from the unvisited node of smallest (degree, id); nodes are visited in queue order and the
+ * unvisited neighbors of the visited node join the queue in increasing (degree, id); the
+ * sequence is the visiting order reversed.  Synchronises the stream (one small read-back per
+ * breadth-first level, so the time grows with the number of levels).
+ *
+ * mixgcn_bandwidth: b = max over stored entries (u, v) of |p_v - p_u| (the paper's graph
+ * bandwidth); pos == NULL takes the identity sequence.  *bandwidth is a host pointer.
+ *
+ * mixgcn_pipeline_stages: Proposition 3.5 - the smallest number of batches s with
+ * (n - b) / (2 n) >= 1 / s, i.e. ceil(2 n / (n - b)); 0 if b >= n (no such s).  Host arithmetic.
+ *
+ * mixgcn_relabel_edges: src_out[i] = pos[src[i]], dst_out[i] = pos[dst[i]] (device arrays; the
+ * outputs may alias the inputs), the edge list of the same graph in the new numbering.
+ * mixgcn_permute_rows: Y[pos[v], :] = X[v, :] for an n_rows x n_cols feature matrix (device,
+ * 16-byte aligned, ld a whole number of 16-byte groups; X and Y must not overlap).
+ */
+int mixgcn_reorder_rcm(const mixgcn_graph* g, uint32_t* pos, void* stream);
+int mixgcn_bandwidth(const mixgcn_graph* g, const uint32_t* pos, int64_t* bandwidth, void* stream);
+int64_t mixgcn_pipeline_stages(int64_t n_nodes, int64_t bandwidth);
+int mixgcn_relabel_edges(const uint32_t* src, const uint32_t* dst, uint64_t n_edges,
+                         const uint32_t* pos, uint32_t n_nodes, uint32_t* src_out,
+                         uint32_t* dst_out, void* stream);
+int mixgcn_permute_rows(int dtype, const void* X, int64_t ldx, void* Y, int64_t ldy, int64_t n_rows,
+                        int32_t n_cols, const uint32_t* pos, void* stream);
+
+/*
  * Measurement aid, not part of the training path: the rates this device sustains on a 4 GiB
  * streaming read and a 4 GiB streaming copy (GB/s; the copy counts read + write) and on
  * register-only MFMA chains in fp32 (32x32x2) and bf16 (32x32x16), in TFLOP/s, for comparison

@@ -71,6 +71,12 @@ def load_library():
     lib.mixgcn_aggregate_masked.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, i64, vp, i64, i32,
                                             i32, i64, i64, vp, i64, vp]
     lib.mixgcn_relu_bitmap.argtypes = [ctypes.c_int, vp, i64, i64, i32, vp, i64, vp]
+    lib.mixgcn_reorder_rcm.argtypes = [vp, vp, vp]
+    lib.mixgcn_bandwidth.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int64), vp]
+    lib.mixgcn_pipeline_stages.argtypes = [i64, i64]
+    lib.mixgcn_pipeline_stages.restype = i64
+    lib.mixgcn_relabel_edges.argtypes = [vp, vp, u64, vp, u32, vp, vp, vp]
+    lib.mixgcn_permute_rows.argtypes = [ctypes.c_int, vp, i64, vp, i64, i64, i32, vp, vp]
     dp = ctypes.POINTER(ctypes.c_double)
     lib.mixgcn_measure_peaks.argtypes = [dp, dp, dp, dp, vp]
     lib.mixgcn_update.argtypes = [ctypes.c_int, ctypes.c_int, vp, i64, vp, i64, vp, i64, i64, i32,
@@ -89,7 +95,8 @@ def load_library():
     lib.mixgcn_pipeline_timing_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                                 ctypes.POINTER(ctypes.c_int64)]
     for name in ("build_csr", "normalize", "aggregate", "aggregate_masked", "relu_bitmap",
-                 "measure_peaks", "update", "layer_fwd", "layer_bwd",
+                 "measure_peaks", "reorder_rcm", "bandwidth", "relabel_edges", "permute_rows",
+                 "update", "layer_fwd", "layer_bwd",
                  "softmax_xent", "graph_info", "graph_free", "pipeline_create", "pipeline_destroy",
                  "pipeline_timing", "pipeline_timing_read", "stream_create_cu_subset", "stream_destroy"):
         getattr(lib, "mixgcn_" + name).restype = ctypes.c_int
@@ -287,6 +294,42 @@ def aggregate_masked(g: Graph, H, Z, mask, col_begin=0, col_end=None, row_begin=
                                                   _ptr(Z), _ld(Z), col_begin, col_end, row_begin,
                                                   row_end, _ptr(mask), mask.stride(0),
                                                   _stream(stream)), "aggregate_masked")
+
+
+def reorder_rcm(g: Graph, stream=None):
+    """Reverse Cuthill-McKee positions pos[v] of the nodes of g (int32 tensor [n] on the device)."""
+    pos = torch.empty(g.n, dtype=torch.int32, device="cuda")
+    _check(load_library().mixgcn_reorder_rcm(g._h, _ptr(pos), _stream(stream)), "reorder_rcm")
+    return pos
+
+
+def bandwidth(g: Graph, pos=None, stream=None) -> int:
+    b = ctypes.c_int64()
+    _check(load_library().mixgcn_bandwidth(g._h, _ptr(pos), ctypes.byref(b), _stream(stream)),
+           "bandwidth")
+    return b.value
+
+
+def pipeline_stages(n: int, b: int) -> int:
+    return load_library().mixgcn_pipeline_stages(n, b)
+
+
+def relabel_edges(src, dst, pos, n: int, stream=None):
+    """(pos[src], pos[dst]) as new int32 device tensors."""
+    so, do = torch.empty_like(src), torch.empty_like(dst)
+    _check(load_library().mixgcn_relabel_edges(_ptr(src), _ptr(dst), src.numel(), _ptr(pos), n,
+                                               _ptr(so), _ptr(do), _stream(stream)), "relabel_edges")
+    return so, do
+
+
+def permute_rows(X, pos, Y=None, stream=None):
+    """Y[pos[v]] = X[v]."""
+    if Y is None:
+        Y = torch.empty_strided(X.shape, X.stride(), dtype=X.dtype, device=X.device)
+    _check(load_library().mixgcn_permute_rows(_dtype_of(X), _ptr(X), _ld(X), _ptr(Y), _ld(Y),
+                                              X.shape[0], X.shape[1], _ptr(pos), _stream(stream)),
+           "permute_rows")
+    return Y
 
 
 def relu_bitmap(X, mask=None, stream=None):

@@ -14,7 +14,7 @@ BUILD_DIR = os.path.join(_HERE, "_build")
 LIB_PATH = os.path.join(_HERE, "libmixgcn.so")
 
 SOURCES = ["abi.hip", "scan.hip", "sort.hip", "csr.hip", "spmm.hip", "gemm.hip", "gemm_bf16.hip",
-           "loss.hip", "peaks.hip"]
+           "loss.hip", "peaks.hip", "reorder.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

@@ -26,7 +26,7 @@ struct Scratch {
     size_t bytes = 0;
 };
 constexpr int kMaxDevices = 16;
-constexpr int kScratchKinds = 3;  // wgrad slabs, loss partials, split weights
+constexpr int kScratchKinds = 4;  // wgrad slabs, loss partials, split weights, small results
 Scratch g_scratch[kMaxDevices][kScratchKinds];
 std::mutex g_scratch_mu;
 }  // namespace

@@ -260,6 +260,90 @@ def test_aggregate_masked_backward_use_matches_mask_after_aggregate(mg, rmat15):
     assert torch.equal(fused, torch.where(hprev > 0, plain, torch.zeros_like(plain)))
 
 
+# node reordering (Sec. 3.2.2): reverse Cuthill-McKee, bandwidth, Proposition 3.5
+def _reorder_cases():
+    rng = np.random.default_rng(5)
+    cases = {}
+    n = 300
+    perm = rng.permutation(n)
+    cases["path300_scrambled"] = (perm[:-1], perm[1:], n, True, True)
+    r, c = 24, 40
+    idx = rng.permutation(r * c).reshape(r, c)
+    cases["grid24x40_scrambled"] = (np.r_[idx[:, :-1].ravel(), idx[:-1, :].ravel()],
+                                    np.r_[idx[:, 1:].ravel(), idx[1:, :].ravel()], r * c, True, True)
+    n = 5000
+    cases["many_small_components"] = (rng.integers(0, n, 1800), rng.integers(0, n, 1800), n, True, True)
+    cases["no_self_loops"] = (rng.integers(0, n, 9000), rng.integers(0, n, 9000), n, True, False)
+    s, d = gg.rmat_edges(21, 13, 40_000)
+    cases["directed_rmat13"] = (s, d, 1 << 13, False, False)
+    s, d, n1 = gg.config_graph("c1")
+    cases["c1"] = (s, d, n1, True, True)
+    s, d, n2 = gg.config_graph("c2", scale_override=15)
+    cases["c2@15"] = (s, d, n2, True, True)
+    s, d = gg.ring_lattice_edges(2000, 6)
+    cases["ring2000_k6"] = (s, d, 2000, True, True)
+    return cases
+
+
+@pytest.mark.parametrize("name", ["path300_scrambled", "grid24x40_scrambled", "many_small_components",
+                                  "no_self_loops", "directed_rmat13", "c1", "c2@15", "ring2000_k6"])
+def test_reorder_rcm_bit_exact_and_bandwidth(mg, name):
+    src, dst, n, sym, loops = _reorder_cases()[name]
+    src = np.asarray(src, dtype=np.uint32)
+    dst = np.asarray(dst, dtype=np.uint32)
+    say(f"reorder_rcm {name} n={n}")
+    og = oracle.build_csr(src, dst, n, sym, loops)
+    want = oracle.rcm(og)
+    g = _gpu_graph(mg, src, dst, n, sym=sym, loops=loops)
+    pos = mg.reorder_rcm(g)
+    got = pos.cpu().numpy().view(np.uint32)
+    assert np.array_equal(np.sort(got), np.arange(n, dtype=np.uint32))  # a permutation
+    assert np.array_equal(got, want)
+    b0, b1 = mg.bandwidth(g), mg.bandwidth(g, pos)
+    assert b0 == oracle.bandwidth(og) and b1 == oracle.bandwidth(og, want)
+    assert mg.pipeline_stages(n, b1) == oracle.pipeline_stages(n, b1)
+    if name.startswith("path"):
+        assert b1 == 1
+    # the relabelled edge list builds the same graph in the new numbering: its identity
+    # bandwidth is b1 and it has as many stored entries
+    s_d, d_d = edges_dev(src, dst)
+    s2, d2 = mg.relabel_edges(s_d, d_d, pos, n)
+    assert np.array_equal(s2.cpu().numpy().view(np.uint32), want[src])
+    assert np.array_equal(d2.cpu().numpy().view(np.uint32), want[dst])
+    flags = (mg.SYMMETRIZE if sym else 0) | (mg.ADD_SELF_LOOPS if loops else 0)
+    g2 = mg.build_csr(s2, d2, n, flags)
+    assert g2.nnz == g.nnz and mg.bandwidth(g2) == b1
+    g2.free()
+    g.free()
+
+
+def test_reordered_graph_gives_the_permuted_aggregation(mg):
+    src, dst, n = gg.config_graph("c2", scale_override=15)
+    g = _gpu_graph(mg, src, dst, n)
+    pos = mg.reorder_rcm(g)
+    s_d, d_d = edges_dev(src, dst)
+    s2, d2 = mg.relabel_edges(s_d, d_d, pos, n)
+    g2 = mg.build_csr(s2, d2, n, mg.SYMMETRIZE | mg.ADD_SELF_LOOPS)
+    mg.normalize(g2)
+    f = 100
+    h = dev(gg.normal(41, 1, n, f, ld=104))[:, :f]
+    hp = mg.permute_rows(h, pos)
+    p = pos.long()
+    assert torch.equal(hp[p], h)
+    z = torch.empty(n, 104, device="cuda")[:, :f]
+    z2 = torch.empty(n, 104, device="cuda")[:, :f]
+    mg.aggregate(g, h, z)
+    mg.aggregate(g2, hp, z2)
+    # same sums over the same neighbours, in a different order
+    torch.testing.assert_close(z2[p], z, rtol=2e-5, atol=2e-5)
+    with pytest.raises(mg.MixGCNError):
+        bad = s_d.clone()
+        bad[3] = n + 7
+        mg.relabel_edges(bad, d_d, pos, n)
+    g.free()
+    g2.free()
+
+
 def test_aggregate_is_deterministic(mg, rmat15):
     og, g = rmat15
     hd = dev(gg.normal(13, 1, og.n, 64))
