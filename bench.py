@@ -194,6 +194,9 @@ def main():
     ap.add_argument("--cpu-scale", type=int, default=20, help="R-MAT scale of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-event-timing", action="store_true")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="record the step into a HIP graph and time its replays (one stream, no "
+                         "per-kernel events): for small inputs, where launches dominate")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no collectives are part of it); "
@@ -240,13 +243,19 @@ def main():
     calib_dst = torch.empty_like(calib_src)
     calib_dst.copy_(calib_src)
 
+    run_step = step.step
+    if args.hip_graph:
+        assert args.chunks == 1, "--hip-graph times the single-stream schedule"
+        args.no_event_timing = True
+        step.capture()
+        run_step = step.replay
     for _ in range(args.warmup):
-        step.step()
+        run_step()
     torch.cuda.synchronize()
     pipe.timing(not args.no_event_timing)
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step.step()
+        run_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
@@ -300,6 +309,7 @@ def main():
             "workload": f"{args.config}: {len(dims) - 1}-layer GCN {'-'.join(map(str, dims))}, one "
                         f"fwd+bwd epoch, R-MAT graph N={n}, nnz(A_hat)={nnz}",
             "n_nodes": n, "nnz": nnz, "row_chunks": args.chunks, "seed": args.seed,
+            "hip_graph": bool(args.hip_graph),
         },
         "loss": loss, "build_csr_normalize_ms": t_build * 1e3, "kernels": kinds,
         "roofline": roofline,

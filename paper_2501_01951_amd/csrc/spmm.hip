@@ -20,13 +20,15 @@
 // XCD mapping.  The slice index is taken from the low bits of the workgroup index.  Workgroups
 // are dealt round-robin to the 8 XCDs, so every slice is pinned to a fixed subset of the XCDs
 // and each private L2 caches only its own part of the hot feature rows.
+#include <vector>
+
 #include "device_utils.h"
 #include "internal.h"
 
 namespace mixgcn {
 namespace {
 
-constexpr int kBatchesPerSpan = 256;  // gather instructions per wavefront
+constexpr int kBatchesPerSpan = 256;  // gather instructions per wavefront (fewer on small inputs)
 constexpr int kDepth = 4;             // gather instructions a wavefront keeps in flight
 
 // 16-byte feature vector: 4 fp32 or 8 bf16 (widened to fp32)
@@ -131,13 +133,13 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
     void* __restrict__ Z, int64_t ldz, int c0, int width, int64_t row_begin, int64_t row_end,
     int64_t e_begin, int64_t e_end, int64_t span_first, int64_t n_spans,
     float* __restrict__ partials, int n_slices, int relu, const uint32_t* __restrict__ mask,
-    int64_t ldm)
+    int64_t ldm, int span_batches)
 {
     using F = Feat<DT>;
     constexpr int VEC = F::VEC;
     constexpr int part_stride = GF * VEC;
     constexpr int EPB = kWave / LPR;                  // entries per batch (= sub-groups)
-    constexpr int64_t SPAN = (int64_t)kBatchesPerSpan * EPB;
+    const int64_t SPAN = (int64_t)span_batches * EPB; // a multiple of kGroupNnz
     constexpr int PW = LPR * VEC;                     // columns of one slice
     constexpr int D = (kDepth * EPB <= kWave) ? kDepth : (kWave / EPB);  // slots per round
     constexpr uint64_t kLane0Mask = LPR == 64 ? 1ull
@@ -378,17 +380,25 @@ __global__ __launch_bounds__(kBlock) void zero_rows_kernel(void* Z, int64_t ldz,
     else reinterpret_cast<uint16_t*>(Z)[r * ldz + c] = 0;
 }
 
-template <int LPR>
-constexpr int64_t span_entries() { return (int64_t)kBatchesPerSpan * (kWave / LPR); }
+// Entries per span of a pass: kBatchesPerSpan batches, halved while the launch would have fewer
+// than 8192 wavefronts (a small graph is otherwise walked by a handful of long-running
+// wavefronts), but never below the kGroupNnz entries that the span-start table resolves.
+inline int64_t span_entries(int lpr, int64_t entries, int n_slices)
+{
+    const int epb = kWave / lpr;
+    int64_t batches = kBatchesPerSpan;
+    while (batches * epb > kGroupNnz && ceil_div(entries, batches * epb) * n_slices < 8192)
+        batches /= 2;
+    return batches * epb;
+}
 
 template <int LPR, int GF, int DT>
 int launch_main(const Csr& m, int64_t n_nodes, const void* H, int64_t ldh, void* Z, int64_t ldz,
                 int c0, int width,
-                int64_t r0, int64_t r1, int64_t e0, int64_t e1, float* partials, int relu,
-                const uint32_t* mask, int64_t ldm, hipStream_t s, Timer* timer)
+                int64_t r0, int64_t r1, int64_t e0, int64_t e1, int64_t SPAN, float* partials,
+                int relu, const uint32_t* mask, int64_t ldm, hipStream_t s, Timer* timer)
 {
     constexpr int PW = LPR * Feat<DT>::VEC;
-    constexpr int64_t SPAN = span_entries<LPR>();
     // timed by the width class of the whole pass
     constexpr int kind = GF == 4 ? kTimeAggG4 : GF == 8 ? kTimeAggG8 : GF == 16 ? kTimeAggG16
                          : GF == 32 ? kTimeAggG32 : kTimeAggG64;
@@ -407,7 +417,8 @@ int launch_main(const Csr& m, int64_t n_nodes, const void* H, int64_t ldh, void*
 #define MIXGCN_AGG_LAUNCH(EMPTY, O32)                                                            \
     hipLaunchKernelGGL((aggregate_kernel<LPR, GF, DT, EMPTY, O32>), dim3(grid), dim3(kBlock), 0, \
                        s, m.rowptr, m.cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,  \
-                       span_first, n_spans, partials, n_slices, relu, mask, ldm)
+                       span_first, n_spans, partials, n_slices, relu, mask, ldm,                 \
+                       (int)(SPAN / (kWave / LPR)))
     if (m.has_empty_rows) {
         if (off32) MIXGCN_AGG_LAUNCH(true, true);
         else MIXGCN_AGG_LAUNCH(true, false);
@@ -457,14 +468,24 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, v
     }
     const int64_t e0 = m.h_rowptr[(size_t)r0], e1 = m.h_rowptr[(size_t)r1];
     if (e1 <= e0) return MIXGCN_OK;
-    // scratch for the row pieces: sized for the widest pass and the shortest span of this call
-    const int wmax = (c1 - c0) < kMaxTile ? (c1 - c0) : kMaxTile;
-    int gmax = 4;
-    while (gmax * VEC < wmax) gmax *= 2;
-    const int lpr_max = slice_lanes(gmax);  // widest slice of any pass = shortest span
-    const int64_t span_min = (int64_t)kBatchesPerSpan * (kWave / lpr_max);
-    const int64_t max_spans = ceil_div(e1, span_min) - e0 / span_min;
-    const size_t need = (size_t)max_spans * 2 * gmax * VEC * sizeof(float);
+    // span length and width class of every pass; the scratch for the row pieces is sized for
+    // the pass that needs most
+    struct Pass { int32_t cb; int w, gf; int64_t span; };
+    std::vector<Pass> passes;
+    size_t need = 0;
+    for (int32_t cb = c0; cb < c1; cb += kMaxTile) {
+        Pass p;
+        p.cb = cb;
+        p.w = (c1 - cb) < kMaxTile ? (c1 - cb) : kMaxTile;
+        p.gf = 4;  // lanes that span the whole pass: fix-up group and partial-slot stride
+        while (p.gf * VEC < p.w) p.gf *= 2;
+        const int lpr = slice_lanes(p.gf);
+        p.span = span_entries(lpr, e1 - e0, (int)ceil_div(p.w, lpr * VEC));
+        const int64_t spans = ceil_div(e1, p.span) - e0 / p.span;
+        const size_t bytes = (size_t)spans * 2 * p.gf * VEC * sizeof(float);
+        need = bytes > need ? bytes : need;
+        passes.push_back(p);
+    }
     if (need > g->partials_bytes) {
         // growing the scratch waits for earlier work that may still read the old one
         MIXGCN_HIP_TRY(hipDeviceSynchronize());
@@ -475,17 +496,17 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, v
         MIXGCN_HIP_TRY(hipMalloc((void**)&g->partials, want));
         g->partials_bytes = want;
     }
-    for (int32_t cb = c0; cb < c1; cb += kMaxTile) {
-        const int w = (c1 - cb) < kMaxTile ? (c1 - cb) : kMaxTile;
-        int GF = 4;  // lanes that span the whole pass: fix-up group and partial-slot stride
-        while (GF * VEC < w) GF *= 2;
-        const int64_t span = (int64_t)kBatchesPerSpan * (kWave / slice_lanes(GF));
+    for (const Pass& p : passes) {
+        const int32_t cb = p.cb;
+        const int w = p.w;
+        const int64_t span = p.span;
         float* P = g->partials;
 #define MIXGCN_AGG_PASS(GG)                                                                      \
     MIXGCN_TRY((launch_main<slice_lanes(GG), GG, DT>(m, (int64_t)g->n, H, ldh, Z, ldz, cb, w, r0,  \
-                                                     r1, e0, e1, P, relu, mask, ldm, s, timer))); \
+                                                     r1, e0, e1, span, P, relu, mask, ldm, s,     \
+                                                     timer)));                                    \
     MIXGCN_TRY((launch_fixup<GG, DT>(m, Z, ldz, cb, w, e0, e1, span, P, relu, mask, ldm, s)))
-        switch (GF) {
+        switch (p.gf) {
         case 4: MIXGCN_AGG_PASS(4); break;
         case 8: MIXGCN_AGG_PASS(8); break;
         case 16: MIXGCN_AGG_PASS(16); break;

@@ -60,22 +60,43 @@ class GCNStep:
         self.dh = [None] + [rows(self.w[l].shape[0]) for l in range(1, L)]
         self.loss = torch.zeros(1, dtype=torch.float64, device=dev)
 
-    def forward(self):
+    def forward(self, pipe=None):
+        pipe = self.pipe if pipe is None else pipe
         L = len(self.w)
         for l in range(L):
-            B.layer_fwd(self.g, self.h[l], self.w[l], self.z[l], self.h[l + 1], self.pipe,
+            B.layer_fwd(self.g, self.h[l], self.w[l], self.z[l], self.h[l + 1], pipe,
                         relu=(l < L - 1), n_chunks=self.n_chunks, order=self.order[l])
-        B.softmax_xent(self.h[L], self.labels, self.dlogits, self.loss, stream=self.pipe.primary)
+        B.softmax_xent(self.h[L], self.labels, self.dlogits, self.loss, stream=pipe.primary)
 
-    def backward(self):
+    def backward(self, pipe=None):
+        pipe = self.pipe if pipe is None else pipe
         L = len(self.w)
         grad = self.dlogits
         for l in range(L - 1, -1, -1):
             B.layer_bwd(self.g, self.z[l], self.h[l + 1], self.w[l], grad, self.dw[l], self.dh[l],
-                        self.pipe, relu=(l < L - 1), n_chunks=self.n_chunks, order=self.order[l],
+                        pipe, relu=(l < L - 1), n_chunks=self.n_chunks, order=self.order[l],
                         H=self.h[l])
             grad = self.dh[l]
 
     def step(self):
         self.forward()
         self.backward()
+
+    def capture(self):
+        """Records one step (single-stream schedule) into a HIP graph; replay() then launches
+        the whole step with one call, which matters when the graph is small and the step is
+        bound by launch overhead.  One eager step runs first so that every scratch buffer has
+        its final size (growing one allocates, which a capture cannot contain)."""
+        assert self.n_chunks == 1, "the captured step uses one stream"
+        self.step()
+        torch.cuda.synchronize()
+        self._graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self._graph):
+            cur = torch.cuda.current_stream()
+            self._graph_pipe = B.Pipeline(primary=cur, secondary=cur)
+            self.forward(self._graph_pipe)
+            self.backward(self._graph_pipe)
+        return self
+
+    def replay(self):
+        self._graph.replay()
