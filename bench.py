@@ -319,9 +319,7 @@ def main():
     del step, calib_src, calib_dst
     torch.cuda.empty_cache()
     try:
-        read_gbs, copy_gbs, f32_tf, bf16_tf = mg.measure_peaks()
-        out["measured_peaks"] = {"read_GBps": read_gbs, "copy_GBps": copy_gbs,
-                                 "mfma_f32_TFLOPs": f32_tf, "mfma_bf16_TFLOPs": bf16_tf}
+        out["measured_peaks"] = mg.measure_peaks()
     except mg.MixGCNError as e:  # needs 8 GiB of free device memory; not part of the result
         out["measured_peaks"] = {"error": str(e)}
     if not args.no_cpu_baseline:

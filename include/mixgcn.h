@@ -263,12 +263,15 @@ int mixgcn_permute_rows(int dtype, const void* X, int64_t ldx, void* Y, int64_t 
 
 /*
  * Measurement aid, not part of the training path: the rates this device sustains on a 4 GiB
- * streaming read and a 4 GiB streaming copy (GB/s; the copy counts read + write) and on
- * register-only MFMA chains in fp32 (32x32x2) and bf16 (32x32x16), in TFLOP/s, for comparison
- * with the published peaks that the roofline fractions are quoted against.  Outputs are host
- * pointers.  Allocates and frees 8 GiB of device memory; synchronises the stream.
+ * streaming read and a 4 GiB streaming copy (GB/s; the copy counts read + write), on random
+ * 128-byte gathers (16 bytes per lane, 8 lanes per line, nothing else in the kernel) from a
+ * 2 MiB buffer that every L2 holds and from a 4 GiB buffer in HBM, and on register-only MFMA
+ * chains in fp32 (32x32x2) and bf16 (32x32x16), in TFLOP/s, for comparison with the published
+ * peaks that the roofline fractions are quoted against.  Outputs are host pointers.  Allocates
+ * and frees 8 GiB of device memory; synchronises the stream.
  */
-int mixgcn_measure_peaks(double* read_gbs, double* copy_gbs, double* mfma_f32_tflops,
+int mixgcn_measure_peaks(double* read_gbs, double* copy_gbs, double* gather_l2_gbs,
+                         double* gather_hbm_gbs, double* mfma_f32_tflops,
                          double* mfma_bf16_tflops, void* stream);
 const char* mixgcn_strerror(int code);
 const char* mixgcn_last_error(void);

@@ -78,7 +78,7 @@ def load_library():
     lib.mixgcn_relabel_edges.argtypes = [vp, vp, u64, vp, u32, vp, vp, vp]
     lib.mixgcn_permute_rows.argtypes = [ctypes.c_int, vp, i64, vp, i64, i64, i32, vp, vp]
     dp = ctypes.POINTER(ctypes.c_double)
-    lib.mixgcn_measure_peaks.argtypes = [dp, dp, dp, dp, vp]
+    lib.mixgcn_measure_peaks.argtypes = [dp, dp, dp, dp, dp, dp, vp]
     lib.mixgcn_update.argtypes = [ctypes.c_int, ctypes.c_int, vp, i64, vp, i64, vp, i64, i64, i32,
                                   i32, vp, i64, f32, vp]
     lib.mixgcn_layer_fwd.argtypes = [vp, ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp]
@@ -109,12 +109,15 @@ def version() -> int:
 
 
 def measure_peaks(stream=None):
-    """(read GB/s, copy GB/s, fp32 MFMA TFLOP/s, bf16 MFMA TFLOP/s) this device sustains on
-    kernels that do nothing else.  A measurement aid for bench.py."""
-    r, c, f, b = ctypes.c_double(), ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
-    _check(load_library().mixgcn_measure_peaks(ctypes.byref(r), ctypes.byref(c), ctypes.byref(f),
-                                               ctypes.byref(b), _stream(stream)), "measure_peaks")
-    return r.value, c.value, f.value, b.value
+    """Rates this device sustains on kernels that do nothing else, as a dict: streaming read and
+    copy, random 128-byte gathers from L2 and from HBM (GB/s), fp32 and bf16 MFMA chains
+    (TFLOP/s).  A measurement aid for bench.py."""
+    v = [ctypes.c_double() for _ in range(6)]
+    _check(load_library().mixgcn_measure_peaks(*[ctypes.byref(x) for x in v], _stream(stream)),
+           "measure_peaks")
+    names = ("read_GBps", "copy_GBps", "gather_l2_GBps", "gather_hbm_GBps", "mfma_f32_TFLOPs",
+             "mfma_bf16_TFLOPs")
+    return {k: x.value for k, x in zip(names, v)}
 
 
 def _check(rc: int, where: str) -> None:

@@ -40,6 +40,37 @@ __global__ __launch_bounds__(kBlock) void read_kernel(const float4* __restrict__
     out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// Random 128-byte gathers: every group of 8 lanes reads one pseudo-random line of the buffer
+// (16 bytes per lane), four independent loads in flight per lane, nothing else.  line_mask + 1
+// lines (a power of two) are addressed.
+__global__ __launch_bounds__(kBlock) void gather_kernel(const uint4* __restrict__ buf,
+                                                        uint32_t line_mask, int iters,
+                                                        uint4* __restrict__ out)
+{
+    const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t grp = t >> 3, lj = t & 7;
+    uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+    for (int it = 0; it < iters; it += 4) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            uint32_t x = (grp * (uint32_t)iters + (uint32_t)(it + u)) * 0x9E3779B1u;
+            x ^= x >> 15;
+            x *= 0x85EBCA77u;
+            x ^= x >> 13;
+            v[u] = buf[(size_t)(x & line_mask) * 8 + lj];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            acc.x ^= v[u].x;
+            acc.y ^= v[u].y;
+            acc.z ^= v[u].z;
+            acc.w ^= v[u].w;
+        }
+    }
+    out[t] = acc;
+}
+
 constexpr int kChains = 4;  // independent accumulators per wavefront
 
 __global__ __launch_bounds__(kBlock) void mfma_f32_loop_kernel(float* out, int iters, float seed)
@@ -111,10 +142,12 @@ struct DevBuf {
 
 using namespace mixgcn;
 
-extern "C" int mixgcn_measure_peaks(double* read_gbs, double* copy_gbs, double* mfma_f32_tflops,
+extern "C" int mixgcn_measure_peaks(double* read_gbs, double* copy_gbs, double* gather_l2_gbs,
+                                    double* gather_hbm_gbs, double* mfma_f32_tflops,
                                     double* mfma_bf16_tflops, void* stream)
 {
-    if (!read_gbs || !copy_gbs || !mfma_f32_tflops || !mfma_bf16_tflops)
+    if (!read_gbs || !copy_gbs || !gather_l2_gbs || !gather_hbm_gbs || !mfma_f32_tflops ||
+        !mfma_bf16_tflops)
         return fail(MIXGCN_EINVAL, "measure_peaks: null output");
     hipStream_t s = (hipStream_t)stream;
     int dev = 0, n_cu = 0;
@@ -153,6 +186,29 @@ extern "C" int mixgcn_measure_peaks(double* read_gbs, double* copy_gbs, double* 
         MIXGCN_HIP_TRY(hipEventElapsedTime(&ms, ev.a, ev.b));
     }
     *read_gbs = (double)bytes / ((double)ms * 1e-3) / 1e9;
+
+    // random 128-byte lines: from 2 MiB (every L2 holds it: the L2 -> L1 fill rate) and from
+    // the whole 4 GiB buffer (every line comes from HBM)
+    {
+        const unsigned ggrid = (unsigned)n_cu * 32;  // 8 workgroups per SIMD row, 4 x 8 waves
+        const int giters = 256;
+        const double gbytes = (double)ggrid * kBlock * giters * 16.0;
+        const uint32_t masks[2] = {(2u << 20) / 128 - 1, (uint32_t)(bytes / 128 - 1)};
+        double* outs[2] = {gather_l2_gbs, gather_hbm_gbs};
+        DevBuf gout;
+        MIXGCN_HIP_TRY(hipMalloc(&gout.p, (size_t)ggrid * kBlock * sizeof(uint4)));
+        for (int k = 0; k < 2; ++k) {
+            for (int rep = 0; rep < 3; ++rep) {
+                MIXGCN_HIP_TRY(hipEventRecord(ev.a, s));
+                hipLaunchKernelGGL(gather_kernel, dim3(ggrid), dim3(kBlock), 0, s,
+                                   (const uint4*)src.p, masks[k], giters, (uint4*)gout.p);
+                MIXGCN_HIP_TRY(hipEventRecord(ev.b, s));
+                MIXGCN_HIP_TRY(hipEventSynchronize(ev.b));
+                MIXGCN_HIP_TRY(hipEventElapsedTime(&ms, ev.a, ev.b));
+            }
+            *outs[k] = gbytes / ((double)ms * 1e-3) / 1e9;
+        }
+    }
 
     // MFMA chains: 2 workgroups of 4 wavefronts per CU, kChains accumulators each
     const unsigned grid = (unsigned)n_cu * 2;
