@@ -29,7 +29,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 def measured_traffic(config, width):
     """HBM bytes per launch of the dominant kernel, taken from the committed rocprofv3 --pmc
     summary of this same command (counters cannot be read from inside the run)."""
-    files = {("c2", 256): "c2_aggregate_pmc.txt", ("c4", 128): "c4_aggregate_pmc.txt"}
+    files = {("c2", 256): "c2_aggregate_pmc.txt", ("c3", 128): "c3_aggregate_pmc.txt",
+             ("c4", 128): "c4_aggregate_pmc.txt"}
     if (config, width) not in files:
         return None
     path = os.path.join(ROOT, "profiles", files[(config, width)])
