@@ -255,6 +255,24 @@ __global__ __launch_bounds__(kBlock) void rowblock_gemm_kernel(
 
     // D layout of the 32x32 MFMA: lane l, register v -> row 8*(v/4) + 4*(l/32) + v%4, col l%32
     const int li = lane & 31, lk = lane >> 5;
+    if (tile_inside) {
+        // no bounds to test: a scalar base per 32 x 32 tile and register, one 32-bit lane offset
+        const int wmu = __builtin_amdgcn_readfirstlane(wm), wnu = __builtin_amdgcn_readfirstlane(wn);
+        const uint32_t lane_off = (uint32_t)(4 * lk) * (uint32_t)ldc + (uint32_t)li;
+#pragma unroll
+        for (int tm = 0; tm < S::TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < S::TN; ++tn) {
+                T* tile = C + (row0 + (wmu * S::TM + tm) * 32) * ldc + col0 + (wnu * S::TN + tn) * 32;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    float x = acc[tm][tn][v];
+                    if (RELU) x = fmaxf(x, 0.f);
+                    store_elem(tile + (int64_t)(8 * (v / 4) + (v % 4)) * ldc + lane_off, x);
+                }
+            }
+        return;
+    }
 #pragma unroll
     for (int tm = 0; tm < S::TM; ++tm)
 #pragma unroll
@@ -359,6 +377,21 @@ __global__ __launch_bounds__(kBlock) void wgrad_slab_kernel(
     }
     float* out = P + (size_t)slab * KD * MD;
     const int li = lane & 31, lk = lane >> 5;
+    if (tile_inside) {
+        const int wmu = __builtin_amdgcn_readfirstlane(wm), wnu = __builtin_amdgcn_readfirstlane(wn);
+        const uint32_t lane_off = (uint32_t)(4 * lk) * (uint32_t)MD + (uint32_t)li;
+#pragma unroll
+        for (int tm = 0; tm < S::TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < S::TN; ++tn) {
+                float* tile = out + (size_t)(i0 + (wmu * S::TM + tm) * 32) * MD + j0 +
+                              (wnu * S::TN + tn) * 32;
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    tile[(size_t)(8 * (v / 4) + (v % 4)) * MD + lane_off] = acc[tm][tn][v];
+            }
+        return;
+    }
 #pragma unroll
     for (int tm = 0; tm < S::TM; ++tm)
 #pragma unroll
