@@ -195,6 +195,43 @@ int mixgcn_layer_bwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, const vo
                      mixgcn_pipeline* p);
 
 /*
+ * Sec. 3.2.2, Proposition 3.5: several layers as one fine-grain pipeline.  The nodes are processed
+ * in s = n_chunks batches of consecutive rows (the same s, dtype and graph for every layer; batch
+ * boundaries are multiples of 128 rows, see mixgcn_pipeline_window).  With bandwidth b of the
+ * graph as numbered, batch c of an aggregation reads only rows [r0 - b, r1 + b) of its input, so
+ * it is started as soon as the dense operation before it has written those batches, while that
+ * operation is still working on later ones; aggregations are issued on the pipeline's primary
+ * stream, updates on its secondary stream.  With b >= n - 1 every aggregation waits for the whole
+ * operation before it and the schedule is the layer-by-layer one.  By Proposition 3.5 the first
+ * batch of the next aggregation never waits for the last batch of the update before it once
+ * s >= mixgcn_pipeline_stages(n, b).
+ *   d[l]     : descriptor of layer l; d[l].f_in == d[l-1].f_out and d[l].ld_h == d[l-1].ld_out.
+ *   H0       : input of layer 0; the input of layer l > 0 is Hout[l-1].
+ *   W, Z, Hout, G, dW : host arrays of n_layers device pointers, used per layer exactly as by
+ *              mixgcn_layer_fwd / mixgcn_layer_bwd.  G[n_layers-1] holds the loss gradient on
+ *              entry; G[l-1] receives the input gradient of layer l (the dH of
+ *              mixgcn_layer_bwd); dH0 (may be NULL: not computed) that of layer 0.
+ *   bandwidth: b; a value below the stored graph's own bandwidth (computed once per graph, which
+ *              synchronises the primary stream on the first call) is MIXGCN_EINVAL.
+ * The weight gradient of a layer is accumulated batch by batch (beta = 1 after the first), so it
+ * agrees with mixgcn_layer_bwd up to the order of summation.  On return the work is enqueued and
+ * the primary stream is ordered after all of it.
+ *
+ * mixgcn_pipeline_window (host arithmetic): rows [*row_begin, *row_end) of batch `chunk`, and the
+ * batches [*first, *last] of its input that a windowed operation on that batch reads.  Any
+ * output pointer may be NULL.
+ */
+int mixgcn_forward_pipelined(const mixgcn_graph* g, int32_t n_layers, const mixgcn_layer_desc* d,
+                             const void* H0, const float* const* W, void* const* Z,
+                             void* const* Hout, int64_t bandwidth, mixgcn_pipeline* p);
+int mixgcn_backward_pipelined(const mixgcn_graph* g, int32_t n_layers, const mixgcn_layer_desc* d,
+                              const void* H0, void* const* Z, const void* const* Hout,
+                              const float* const* W, void* const* G, float* const* dW, void* dH0,
+                              int64_t bandwidth, mixgcn_pipeline* p);
+int mixgcn_pipeline_window(int64_t n_nodes, int32_t n_chunks, int64_t bandwidth, int32_t chunk,
+                           int64_t* row_begin, int64_t* row_end, int32_t* first, int32_t* last);
+
+/*
  * Loss glue (Algorithm 2, loss line): mean softmax cross-entropy over n nodes and its gradient
  * dlogits = (softmax - onehot) / n (may alias logits).  logits and dlogits are stored as
  * `dtype` (the arithmetic is fp32, the loss sum fp64).  loss: one device double.

@@ -83,6 +83,13 @@ def load_library():
                                   i32, vp, i64, f32, vp]
     lib.mixgcn_layer_fwd.argtypes = [vp, ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp]
     lib.mixgcn_layer_bwd.argtypes = [vp, ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.mixgcn_forward_pipelined.argtypes = [vp, i32, ctypes.POINTER(LayerDesc), vp, vp, vp, vp, i64, vp]
+    lib.mixgcn_backward_pipelined.argtypes = [vp, i32, ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp,
+                                              vp, vp, i64, vp]
+    lib.mixgcn_pipeline_window.argtypes = [i64, i32, i64, i32, ctypes.POINTER(ctypes.c_int64),
+                                           ctypes.POINTER(ctypes.c_int64),
+                                           ctypes.POINTER(ctypes.c_int32),
+                                           ctypes.POINTER(ctypes.c_int32)]
     lib.mixgcn_softmax_xent.argtypes = [ctypes.c_int, vp, i64, vp, i64, i32, vp, i64, vp, vp]
     lib.mixgcn_graph_info.argtypes = [vp, ctypes.POINTER(_GraphView)]
     lib.mixgcn_graph_free.argtypes = [vp]
@@ -383,6 +390,54 @@ def layer_bwd(g: Graph, Z, Hout, W, G, dW, dH, pipe: Pipeline, relu: bool = True
     _check(load_library().mixgcn_layer_bwd(g._h, ctypes.byref(d), _ptr(H), _ptr(Z), _ptr(Hout),
                                            _ptr(W), _ptr(G), _ptr(dW), _ptr(dH), pipe._h),
            "layer_bwd")
+
+
+def _ptr_array(tensors):
+    return (ctypes.c_void_p * len(tensors))(*[None if t is None else t.data_ptr() for t in tensors])
+
+
+def forward_pipelined(g: Graph, H0, Ws, Zs, Houts, pipe: Pipeline, bandwidth: int, n_chunks: int,
+                      orders=None, last_relu: bool = False) -> None:
+    """All layers as one cross-layer pipeline (ReLU on every layer but the last unless
+    last_relu)."""
+    L = len(Ws)
+    orders = orders or [AGG_FIRST] * L
+    ins = [H0] + list(Houts[:-1])
+    descs = (LayerDesc * L)(*[_desc(ins[l], Zs[l], Houts[l], Ws[l], l < L - 1 or last_relu,
+                                    n_chunks, orders[l]) for l in range(L)])
+    _check(load_library().mixgcn_forward_pipelined(g._h, L, descs, _ptr(H0), _ptr_array(Ws),
+                                                   _ptr_array(Zs), _ptr_array(Houts), bandwidth,
+                                                   pipe._h), "forward_pipelined")
+
+
+def backward_pipelined(g: Graph, H0, Zs, Houts, Ws, Gs, dWs, dH0, pipe: Pipeline, bandwidth: int,
+                       n_chunks: int, orders=None, last_relu: bool = False) -> None:
+    """Gs[l]: gradient with respect to Houts[l]; Gs[-1] is the loss gradient on entry, the others
+    are written (Gs[l-1] = input gradient of layer l)."""
+    L = len(Ws)
+    orders = orders or [AGG_FIRST] * L
+    ins = [H0] + list(Houts[:-1])
+    for l in range(L):
+        assert _ld(dWs[l]) == _ld(Ws[l]), "dW must have the leading dimension of W"
+        assert _ld(Gs[l]) == _ld(Houts[l]), "G must have the leading dimension of Hout"
+    descs = (LayerDesc * L)(*[_desc(ins[l], Zs[l], Houts[l], Ws[l], l < L - 1 or last_relu,
+                                    n_chunks, orders[l]) for l in range(L)])
+    _check(load_library().mixgcn_backward_pipelined(g._h, L, descs, _ptr(H0), _ptr_array(Zs),
+                                                    _ptr_array(Houts), _ptr_array(Ws),
+                                                    _ptr_array(Gs), _ptr_array(dWs), _ptr(dH0),
+                                                    bandwidth, pipe._h), "backward_pipelined")
+
+
+def pipeline_window(n_nodes: int, n_chunks: int, bandwidth: int, chunk: int):
+    """(row_begin, row_end, first, last): the rows of batch `chunk` and the batches of its input
+    that an aggregation of that batch reads.  Host arithmetic, no GPU needed."""
+    r0, r1 = ctypes.c_int64(), ctypes.c_int64()
+    f, l = ctypes.c_int32(), ctypes.c_int32()
+    _check(load_library().mixgcn_pipeline_window(n_nodes, n_chunks, bandwidth, chunk,
+                                                 ctypes.byref(r0), ctypes.byref(r1),
+                                                 ctypes.byref(f), ctypes.byref(l)),
+           "pipeline_window")
+    return r0.value, r1.value, f.value, l.value
 
 
 def softmax_xent(logits, labels, dlogits, loss, stream=None) -> None:

@@ -1,7 +1,10 @@
-// C ABI entry points: argument validation, object lifetime, and the two-stream row-chunk
-// pipeline that overlaps the aggregation of chunk k with the update of chunk k-1
+// C ABI entry points: argument validation, object lifetime, the two-stream row-chunk
+// pipeline that overlaps the aggregation of chunk k with the update of chunk k-1, and its
+// cross-layer form
 // (paper Sec. 3.2.2, fine-grain pipeline between the sparse and the dense half of a layer).
 #include <cstring>
+#include <functional>
+#include <memory>
 #include <mutex>
 #include <new>
 
@@ -566,6 +569,248 @@ int mixgcn_layer_bwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, const vo
         MIXGCN_HIP_TRY(hipStreamWaitEvent(p->primary, p->ev_done, 0));
     }
     return MIXGCN_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+// One operation of a chain of layers, applied to the row chunks in order.  A windowed operation
+// (an aggregation) reads rows [r0 - b, r1 + b) of what the operation before it wrote, any other
+// only its own rows [r0, r1).
+struct ChainOp {
+    bool sparse;    // issued on the primary (sparse) stream, else on the secondary (dense) one
+    bool windowed;
+    std::function<int(int64_t r0, int64_t r1, hipStream_t s)> run;
+};
+
+// Chunks [first, last] of the producer that chunk c of a windowed consumer reads.
+void chunk_window(int64_t n, int nc, int64_t b, int c, int* first, int* last)
+{
+    const int64_t r0 = chunk_bound(n, nc, c), r1 = chunk_bound(n, nc, c + 1);
+    const int64_t lo = r0 - b > 0 ? r0 - b : 0;
+    const int64_t hi = r1 + b < n ? r1 + b : n;  // exclusive
+    int f = c, l = c;
+    while (f > 0 && chunk_bound(n, nc, f) > lo) --f;
+    while (l + 1 < nc && chunk_bound(n, nc, l + 1) < hi) ++l;
+    *first = f;
+    *last = l;
+}
+
+// Issues the chain operation by operation, chunk by chunk.  Both streams run their work in
+// issue order, so a chunk only has to wait for the LAST chunk it reads of the operation before
+// it, and only when that one runs on the other stream (Sec. 3.2.2: the first batch of the next
+// aggregation starts as soon as the batches it depends on are there, not when the layer is).
+int run_chain(const mixgcn_graph* g, mixgcn_pipeline* p, int nc, int64_t b,
+              const std::vector<ChainOp>& ops)
+{
+    const int64_t n = g->n;
+    const bool two = p->secondary != p->primary;
+    MIXGCN_TRY(ensure_events(p, ops.size() * (size_t)nc));
+    if (two) {
+        MIXGCN_HIP_TRY(hipEventRecord(p->ev_start, p->primary));
+        MIXGCN_HIP_TRY(hipStreamWaitEvent(p->secondary, p->ev_start, 0));
+    }
+    for (size_t k = 0; k < ops.size(); ++k) {
+        const ChainOp& op = ops[k];
+        hipStream_t s = (op.sparse || !two) ? p->primary : p->secondary;
+        const bool cross = two && k > 0 && ops[k - 1].sparse != op.sparse;
+        int waited = -1;  // highest chunk of the producer this stream already waits for
+        for (int c = 0; c < nc; ++c) {
+            const int64_t r0 = chunk_bound(n, nc, c), r1 = chunk_bound(n, nc, c + 1);
+            if (cross) {
+                int first = c, last = c;
+                if (op.windowed) chunk_window(n, nc, b, c, &first, &last);
+                if (last > waited) {
+                    MIXGCN_HIP_TRY(hipStreamWaitEvent(s, p->events[(k - 1) * (size_t)nc + (size_t)last], 0));
+                    waited = last;
+                }
+            }
+            if (r1 > r0) MIXGCN_TRY(op.run(r0, r1, s));
+            if (two) MIXGCN_HIP_TRY(hipEventRecord(p->events[k * (size_t)nc + (size_t)c], s));
+        }
+    }
+    if (two) {
+        MIXGCN_HIP_TRY(hipEventRecord(p->ev_done, p->secondary));
+        MIXGCN_HIP_TRY(hipStreamWaitEvent(p->primary, p->ev_done, 0));
+    }
+    return MIXGCN_OK;
+}
+
+int check_chain(const char* who, const mixgcn_graph* g, int32_t n_layers,
+                const mixgcn_layer_desc* d, int64_t bandwidth, const mixgcn_pipeline* p)
+{
+    if (n_layers <= 0 || n_layers > 1024) return fail(MIXGCN_EINVAL, std::string(who) + ": n_layers");
+    for (int l = 0; l < n_layers; ++l) {
+        MIXGCN_TRY(check_layer(who, g, d ? d + l : nullptr, p));
+        if (d[l].n_chunks != d[0].n_chunks || d[l].dtype != d[0].dtype)
+            return fail(MIXGCN_EINVAL, std::string(who) + ": layers differ in n_chunks or dtype");
+        if (l > 0 && (d[l].f_in != d[l - 1].f_out || d[l].ld_h != d[l - 1].ld_out))
+            return fail(MIXGCN_EINVAL, std::string(who) + ": layer input does not match the output before it");
+    }
+    if (bandwidth < 0) return fail(MIXGCN_EINVAL, std::string(who) + ": bandwidth");
+    // the window must cover the graph as stored: a smaller one would let an aggregation read
+    // rows that are not written yet
+    if (g->bandwidth < 0) {
+        int64_t bw = 0;
+        MIXGCN_TRY(mixgcn_bandwidth(g, nullptr, &bw, p->primary));
+        g->bandwidth = bw;
+    }
+    if (bandwidth < g->bandwidth)
+        return fail(MIXGCN_EINVAL, std::string(who) + ": bandwidth is smaller than the graph's (" +
+                                       std::to_string(g->bandwidth) + ")");
+    return MIXGCN_OK;
+}
+
+inline const char* row_ptr(const void* base, int64_t r, int64_t ld, int es)
+{
+    return (const char*)base + (size_t)r * (size_t)ld * (size_t)es;
+}
+inline char* row_ptr(void* base, int64_t r, int64_t ld, int es)
+{
+    return (char*)base + (size_t)r * (size_t)ld * (size_t)es;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mixgcn_pipeline_window(int64_t n_nodes, int32_t n_chunks, int64_t bandwidth, int32_t chunk,
+                           int64_t* row_begin, int64_t* row_end, int32_t* first, int32_t* last)
+{
+    if (n_nodes < 0 || n_chunks <= 0 || bandwidth < 0 || chunk < 0 || chunk >= n_chunks)
+        return fail(MIXGCN_EINVAL, "pipeline_window: arguments");
+    if (row_begin) *row_begin = chunk_bound(n_nodes, n_chunks, chunk);
+    if (row_end) *row_end = chunk_bound(n_nodes, n_chunks, chunk + 1);
+    int f = chunk, l = chunk;
+    chunk_window(n_nodes, n_chunks, bandwidth, chunk, &f, &l);
+    if (first) *first = f;
+    if (last) *last = l;
+    return MIXGCN_OK;
+}
+
+int mixgcn_forward_pipelined(const mixgcn_graph* g, int32_t n_layers, const mixgcn_layer_desc* d,
+                             const void* H0, const float* const* W, void* const* Z,
+                             void* const* Hout, int64_t bandwidth, mixgcn_pipeline* p)
+{
+    MIXGCN_TRY(check_chain("forward_pipelined", g, n_layers, d, bandwidth, p));
+    if (!H0 || !W || !Z || !Hout) return fail(MIXGCN_EINVAL, "forward_pipelined: null argument");
+    for (int l = 0; l < n_layers; ++l)
+        if (!W[l] || !Z[l] || !Hout[l]) return fail(MIXGCN_EINVAL, "forward_pipelined: null tensor");
+    Timer* tm = p->timer.enabled ? &p->timer : nullptr;
+    const int es = elem_size(d[0].dtype);
+    std::vector<ChainOp> ops;
+    for (int l = 0; l < n_layers; ++l) {
+        const mixgcn_layer_desc L = d[l];
+        const void* in = l == 0 ? H0 : Hout[l - 1];
+        const float* w = W[l];
+        void* z = Z[l];
+        void* out = Hout[l];
+        const int op = L.relu ? MIXGCN_OP_FWD_RELU : MIXGCN_OP_FWD;
+        if (L.order == MIXGCN_AGG_FIRST) {
+            ops.push_back({true, true, [=](int64_t r0, int64_t r1, hipStream_t s) {
+                               return aggregate_impl(g, 0, L.dtype, in, L.ld_h, z, L.ld_z, 0, L.f_in,
+                                                     r0, r1, 0, s, tm);
+                           }});
+            ops.push_back({false, false, [=](int64_t r0, int64_t r1, hipStream_t s) {
+                               return update_impl(op, L.dtype, row_ptr(z, r0, L.ld_z, es), L.ld_z, w,
+                                                  L.ld_w, row_ptr(out, r0, L.ld_out, es), L.ld_out,
+                                                  r1 - r0, L.f_in, L.f_out, nullptr, 0, 0.f, s, tm);
+                           }});
+        } else {
+            ops.push_back({false, false, [=](int64_t r0, int64_t r1, hipStream_t s) {
+                               return update_impl(MIXGCN_OP_FWD, L.dtype, row_ptr(in, r0, L.ld_h, es),
+                                                  L.ld_h, w, L.ld_w, row_ptr(z, r0, L.ld_z, es),
+                                                  L.ld_z, r1 - r0, L.f_in, L.f_out, nullptr, 0, 0.f,
+                                                  s, tm);
+                           }});
+            ops.push_back({true, true, [=](int64_t r0, int64_t r1, hipStream_t s) {
+                               return aggregate_impl(g, 0, L.dtype, z, L.ld_z, out, L.ld_out, 0,
+                                                     L.f_out, r0, r1, L.relu, s, tm);
+                           }});
+        }
+    }
+    return run_chain(g, p, d[0].n_chunks, bandwidth, ops);
+}
+
+int mixgcn_backward_pipelined(const mixgcn_graph* g, int32_t n_layers, const mixgcn_layer_desc* d,
+                              const void* H0, void* const* Z, const void* const* Hout,
+                              const float* const* W, void* const* G, float* const* dW, void* dH0,
+                              int64_t bandwidth, mixgcn_pipeline* p)
+{
+    MIXGCN_TRY(check_chain("backward_pipelined", g, n_layers, d, bandwidth, p));
+    if (!Z || !Hout || !W || !G || !dW) return fail(MIXGCN_EINVAL, "backward_pipelined: null argument");
+    for (int l = 0; l < n_layers; ++l) {
+        if (!Z[l] || !W[l] || !G[l] || !dW[l])
+            return fail(MIXGCN_EINVAL, "backward_pipelined: null tensor");
+        if (d[l].relu && !Hout[l]) return fail(MIXGCN_EINVAL, "backward_pipelined: relu layer needs Hout");
+        if (d[l].order == MIXGCN_UPDATE_FIRST && !(l == 0 ? H0 : Hout[l - 1]))
+            return fail(MIXGCN_EINVAL, "backward_pipelined: update-first layer needs its input");
+    }
+    Timer* tm = p->timer.enabled ? &p->timer : nullptr;
+    const int es = elem_size(d[0].dtype);
+    std::vector<ChainOp> ops;
+    // first = 1 until the weight gradient of a layer has been started (beta = 0), one per layer
+    auto started = std::make_shared<std::vector<char>>((size_t)n_layers, 0);
+    for (int l = n_layers - 1; l >= 0; --l) {
+        const mixgcn_layer_desc L = d[l];
+        const void* in = l == 0 ? H0 : Hout[l - 1];
+        const void* R = L.relu ? Hout[l] : nullptr;
+        const float* w = W[l];
+        void* z = Z[l];
+        void* grad = G[l];
+        float* dw = dW[l];
+        void* dh = l == 0 ? dH0 : G[l - 1];
+        if (L.order == MIXGCN_AGG_FIRST) {
+            // dW += Z^T dP and dZ = dP W^T for the chunk (dZ over Z, after dW has read it)
+            ops.push_back({false, false, [=](int64_t r0, int64_t r1, hipStream_t s) {
+                               const float beta = (*started)[(size_t)l] ? 1.f : 0.f;
+                               (*started)[(size_t)l] = 1;
+                               const void* rc = R ? row_ptr(R, r0, L.ld_out, es) : nullptr;
+                               MIXGCN_TRY(update_impl(MIXGCN_OP_WGRAD, L.dtype,
+                                                      row_ptr(z, r0, L.ld_z, es), L.ld_z,
+                                                      row_ptr(grad, r0, L.ld_out, es), L.ld_out, dw,
+                                                      L.ld_w, r1 - r0, L.f_in, L.f_out, rc, L.ld_out,
+                                                      beta, s, tm));
+                               if (!dh) return (int)MIXGCN_OK;
+                               return update_impl(MIXGCN_OP_DGRAD, L.dtype,
+                                                  row_ptr(grad, r0, L.ld_out, es), L.ld_out, w, L.ld_w,
+                                                  row_ptr(z, r0, L.ld_z, es), L.ld_z, r1 - r0, L.f_in,
+                                                  L.f_out, rc, L.ld_out, 0.f, s, tm);
+                           }});
+            if (dh)
+                ops.push_back({true, true, [=](int64_t r0, int64_t r1, hipStream_t s) {
+                                   return aggregate_impl(g, 1, L.dtype, z, L.ld_z, dh, L.ld_h, 0,
+                                                         L.f_in, r0, r1, 0, s, tm);
+                               }});
+        } else {
+            if (R)
+                ops.push_back({false, false, [=](int64_t r0, int64_t r1, hipStream_t s) {
+                                   return launch_relu_mask(L.dtype, row_ptr(grad, r0, L.ld_out, es),
+                                                           L.ld_out, row_ptr(R, r0, L.ld_out, es),
+                                                           L.ld_out, r1 - r0, L.f_out, s);
+                               }});
+            ops.push_back({true, true, [=](int64_t r0, int64_t r1, hipStream_t s) {
+                               return aggregate_impl(g, 1, L.dtype, grad, L.ld_out, z, L.ld_z, 0,
+                                                     L.f_out, r0, r1, 0, s, tm);
+                           }});
+            ops.push_back({false, false, [=](int64_t r0, int64_t r1, hipStream_t s) {
+                               const float beta = (*started)[(size_t)l] ? 1.f : 0.f;
+                               (*started)[(size_t)l] = 1;
+                               MIXGCN_TRY(update_impl(MIXGCN_OP_WGRAD, L.dtype,
+                                                      row_ptr(in, r0, L.ld_h, es), L.ld_h,
+                                                      row_ptr(z, r0, L.ld_z, es), L.ld_z, dw, L.ld_w,
+                                                      r1 - r0, L.f_in, L.f_out, nullptr, 0, beta, s,
+                                                      tm));
+                               if (!dh) return (int)MIXGCN_OK;
+                               return update_impl(MIXGCN_OP_DGRAD, L.dtype, row_ptr(z, r0, L.ld_z, es),
+                                                  L.ld_z, w, L.ld_w, row_ptr(dh, r0, L.ld_h, es),
+                                                  L.ld_h, r1 - r0, L.f_in, L.f_out, nullptr, 0, 0.f,
+                                                  s, tm);
+                           }});
+        }
+    }
+    return run_chain(g, p, d[0].n_chunks, bandwidth, ops);
 }
 
 }  // extern "C"

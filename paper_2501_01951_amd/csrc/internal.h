@@ -71,6 +71,8 @@ struct mixgcn_graph {
     // grown on demand, so aggregate calls on one graph must be ordered on one stream.
     mutable float* partials = nullptr;
     mutable size_t partials_bytes = 0;
+    // max |u - v| over the stored entries, computed on first use by the cross-layer pipeline
+    mutable int64_t bandwidth = -1;
 };
 
 namespace mixgcn {

@@ -31,13 +31,16 @@ class GCNStep:
     for training)."""
 
     def __init__(self, g: B.Graph, x, weights, labels, n_chunks: int = 1, pipe: B.Pipeline = None,
-                 reorder: bool = True):
+                 reorder: bool = True, bandwidth: int = None):
         self.g = g
         self.n = x.shape[0]
         self.x = x
         self.w = list(weights)
         self.labels = labels
         self.n_chunks = n_chunks
+        # bandwidth of the graph as numbered: the layers then run as one cross-layer pipeline of
+        # n_chunks batches instead of layer by layer
+        self.bandwidth = bandwidth
         self.pipe = pipe if pipe is not None else B.Pipeline()
         dev = x.device
         L = len(self.w)
@@ -63,6 +66,11 @@ class GCNStep:
     def forward(self, pipe=None):
         pipe = self.pipe if pipe is None else pipe
         L = len(self.w)
+        if self.bandwidth is not None:
+            B.forward_pipelined(self.g, self.h[0], self.w, self.z, self.h[1:], pipe, self.bandwidth,
+                                self.n_chunks, orders=self.order)
+            B.softmax_xent(self.h[L], self.labels, self.dlogits, self.loss, stream=pipe.primary)
+            return
         for l in range(L):
             B.layer_fwd(self.g, self.h[l], self.w[l], self.z[l], self.h[l + 1], pipe,
                         relu=(l < L - 1), n_chunks=self.n_chunks, order=self.order[l])
@@ -71,6 +79,11 @@ class GCNStep:
     def backward(self, pipe=None):
         pipe = self.pipe if pipe is None else pipe
         L = len(self.w)
+        if self.bandwidth is not None:
+            B.backward_pipelined(self.g, self.h[0], self.z, self.h[1:], self.w,
+                                 self.dh[1:] + [self.dlogits], self.dw, None, pipe, self.bandwidth,
+                                 self.n_chunks, orders=self.order)
+            return
         grad = self.dlogits
         for l in range(L - 1, -1, -1):
             B.layer_bwd(self.g, self.z[l], self.h[l + 1], self.w[l], grad, self.dw[l], self.dh[l],

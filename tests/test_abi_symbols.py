@@ -58,3 +58,93 @@ def test_argument_errors_need_no_gpu():
     assert lib.mixgcn_graph_free(None) == 0
     assert lib.mixgcn_update(9, 0, None, 0, None, 0, None, 0, 1, 1, 1, None, 0, 0.0, None) == -1
     assert lib.mixgcn_update(0, 0, None, 4, None, 4, None, 4, 1, 4, 4, None, 0, 0.0, None) == -1
+
+
+# ---- host arithmetic of the cross-layer pipeline (Sec. 3.2.2) -------------------------------
+
+def _windows(m, n, s, b):
+    return [m.pipeline_window(n, s, b, c) for c in range(s)]
+
+
+@pytest.mark.parametrize("n,s,b", [(1000, 8, 130), (1000, 8, 0), (100, 20, 7), (5000, 3, 4999),
+                                   (1 << 20, 5, 549_127), (77, 1, 5), (4096, 32, 1)])
+def test_pipeline_window_covers_exactly_the_rows_within_b(n, s, b):
+    """The batches tile [0, n) in order; every row within b of a batch lies in a batch of
+    [first, last], and first / last are not wider than needed."""
+    import numpy as np
+    import paper_2501_01951_amd as m
+
+    w = _windows(m, n, s, b)
+    assert w[0][0] == 0 and w[-1][1] == n
+    for c in range(s - 1):
+        assert w[c][1] == w[c + 1][0] and w[c][0] <= w[c][1]
+    batch_of = np.empty(n, dtype=np.int64)
+    for c, (r0, r1, _, _) in enumerate(w):
+        batch_of[r0:r1] = c
+    for c, (r0, r1, first, last) in enumerate(w):
+        assert first <= c <= last
+        if r1 == r0:
+            continue
+        rows = np.arange(max(0, r0 - b), min(n, r1 + b))
+        used = batch_of[rows]
+        assert used.min() >= first and used.max() <= last
+        if w[first][1] > w[first][0]:
+            assert used.min() == first
+        if w[last][1] > w[last][0]:
+            assert used.max() == last
+
+
+def test_pipeline_window_on_a_graph_holds_every_neighbor():
+    """With b = the graph's bandwidth, every stored neighbor of a row of batch c lies in a batch
+    of [first, last] (the rows an aggregation of that batch gathers)."""
+    import numpy as np
+    import oracle
+    import graphgen as gg
+    import paper_2501_01951_amd as m
+
+    n = 3000
+    s0, d0 = gg.ring_lattice_edges(n, 6)
+    perm = np.random.default_rng(1).permutation(n).astype(np.uint32)
+    g = oracle.build_csr(perm[s0], perm[d0], n)
+    pos = oracle.rcm(g)
+    g2 = oracle.build_csr(pos[perm[s0]], pos[perm[d0]], n)
+    b = oracle.bandwidth(g2)
+    assert b < 20
+    s = 9
+    w = _windows(m, n, s, b)
+    rowptr, col = g2.rowptr, g2.col.astype(np.int64)
+    for c, (r0, r1, first, last) in enumerate(w):
+        nb = col[rowptr[r0]:rowptr[r1]]
+        assert nb.min() >= w[first][0] and nb.max() < w[last][1]
+    # and one less than the bandwidth is not enough for some batch
+    short = _windows(m, n, s, 0)
+    assert any(col[rowptr[r0]:rowptr[r1]].max() >= short[l][1] or
+               col[rowptr[r0]:rowptr[r1]].min() < short[f][0] for (r0, r1, f, l) in short)
+
+
+@pytest.mark.parametrize("n,b", [(128 * 3 * 7 * 40, 1000), (35840, 26880), (10752, 5376),
+                                 (128 * 360, 25)])
+def test_proposition_3_5_is_the_point_where_the_first_batch_stops_waiting_for_the_last(n, b):
+    """With s = ceil(2n / (n - b)) batches of equal size the first batch of an aggregation does
+    not read the last batch of its input; with one batch fewer it does (batch sizes chosen so
+    that n / s is a whole number of 128-row tiles for both)."""
+    import paper_2501_01951_amd as m
+
+    s = m.pipeline_stages(n, b)
+    assert s >= 3 and n % (128 * s) == 0 and n % (128 * (s - 1)) == 0
+    _, _, _, last = m.pipeline_window(n, s, b, 0)
+    assert last <= s - 2
+    _, _, _, last = m.pipeline_window(n, s - 1, b, 0)
+    assert last == s - 2
+
+
+def test_pipelined_calls_reject_bad_arguments_without_a_gpu():
+    import paper_2501_01951_amd as m
+
+    lib = m.load_library()
+    assert lib.mixgcn_pipeline_window(10, 0, 1, 0, None, None, None, None) == -1
+    assert lib.mixgcn_pipeline_window(10, 2, 1, 2, None, None, None, None) == -1
+    assert lib.mixgcn_pipeline_window(10, 2, -1, 0, None, None, None, None) == -1
+    assert lib.mixgcn_forward_pipelined(None, 0, None, None, None, None, None, 0, None) == -1
+    assert lib.mixgcn_backward_pipelined(None, 1, None, None, None, None, None, None, None, None, 0,
+                                         None) == -1

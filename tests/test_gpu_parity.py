@@ -525,10 +525,12 @@ def test_layer_update_first(mg, rmat15, relu):
     pipe.free()
 
 
-def run_model_gpu(mg, g, x, ws, y, n_chunks=1, reorder=True):
+def run_model_gpu(mg, g, x, ws, y, n_chunks=1, reorder=True, bandwidth=None):
     """L-layer GCN forward + backward through the C ABI only, with the same sequencing helper
-    that bench.py times.  Returns loss, logits, dW list and the stored activations."""
-    step = mg.GCNStep(g, dev(x), [dev(w) for w in ws], dev(y), n_chunks=n_chunks, reorder=reorder)
+    that bench.py times.  Returns loss, logits, dW list and the stored activations.  With a
+    bandwidth the layers run as one cross-layer pipeline."""
+    step = mg.GCNStep(g, dev(x), [dev(w) for w in ws], dev(y), n_chunks=n_chunks, reorder=reorder,
+                      bandwidth=bandwidth)
     step.step()
     torch.cuda.synchronize()
     out = (step.loss.item(), step.h[-1].cpu().numpy(), [d.cpu().numpy() for d in step.dw],
@@ -537,11 +539,12 @@ def run_model_gpu(mg, g, x, ws, y, n_chunks=1, reorder=True):
     return out
 
 
-def check_model(mg, name, src, dst, n, x, ws, y, n_chunks, reorder=True):
+def check_model(mg, name, src, dst, n, x, ws, y, n_chunks, reorder=True, cross_layer=False):
     og = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n)))
     ref = oracle.gcn_step(og, x, ws, y)
     g = _gpu_graph(mg, src, dst, n)
-    loss, logits, dws, hs = run_model_gpu(mg, g, x, ws, y, n_chunks, reorder)
+    bandwidth = mg.bandwidth(g) if cross_layer else None
+    loss, logits, dws, hs = run_model_gpu(mg, g, x, ws, y, n_chunks, reorder, bandwidth)
     g.free()
     assert abs(loss - ref["loss"]) <= 1e-5 * abs(ref["loss"]), f"{name}: loss {loss} vs {ref['loss']}"
     assert_close(logits, ref["logits"], RTOL_F32, f"{name}: logits")
@@ -586,6 +589,73 @@ def test_config2_shape_three_layer_gcn_scale17(mg, reorder):
           gg.glorot(gg.MASTER_SEED, 12, 256, 16)]
     y = gg.labels(gg.MASTER_SEED, 5, n, 16)
     check_model(mg, "c2@17", src, dst, n, x, ws, y, 4, reorder)
+
+
+def _banded_case(n, k, seed):
+    """Ring lattice with scrambled ids, renumbered by the ORACLE's reverse Cuthill-McKee
+    sequence (so the expected values do not depend on the GPU's); returns the edge list in the
+    new numbering and its bandwidth."""
+    s0, d0 = gg.ring_lattice_edges(n, k)
+    perm = np.random.default_rng(seed).permutation(n).astype(np.uint32)
+    s1, d1 = perm[s0], perm[d0]
+    og = oracle.build_csr(s1, d1, n)
+    pos = oracle.rcm(og)
+    s2, d2 = pos[s1], pos[d1]
+    return s2, d2, oracle.bandwidth(oracle.build_csr(s2, d2, n))
+
+
+@pytest.mark.parametrize("reorder", [False, True])
+@pytest.mark.parametrize("extra_chunks", [0, 6])
+def test_cross_layer_pipeline_on_a_banded_graph(mg, extra_chunks, reorder):
+    """Sec. 3.2.2: three layers as one pipeline of s batches, s from Proposition 3.5 and above;
+    values against the oracle's layer-by-layer step."""
+    n = 60_000
+    src, dst, b = _banded_case(n, 8, 3)
+    s = mg.pipeline_stages(n, b) + extra_chunks
+    say(f"cross-layer pipeline, ring lattice n={n} b={b} batches={s} reorder={reorder}")
+    assert b < n // 100 and s >= 3
+    x = gg.normal(gg.MASTER_SEED, 1, n, 64)
+    ws = [gg.glorot(gg.MASTER_SEED, 10, 64, 96), gg.glorot(gg.MASTER_SEED, 11, 96, 48),
+          gg.glorot(gg.MASTER_SEED, 12, 48, 8)]
+    y = gg.labels(gg.MASTER_SEED, 5, n, 8)
+    check_model(mg, "ring60k", src, dst, n, x, ws, y, s, reorder, cross_layer=True)
+
+
+def test_cross_layer_pipeline_equals_layer_by_layer_and_rejects_a_small_window(mg):
+    """Same batches, same kernels: the activations of the cross-layer schedule are bit for bit
+    those of the layer-by-layer one, on every one of several runs; a bandwidth below the
+    graph's own is an error, one above it (no overlap across layers) is not."""
+    n = 40_000
+    src, dst, b = _banded_case(n, 6, 9)
+    g = _gpu_graph(mg, src, dst, n)
+    assert mg.bandwidth(g) == b
+    x = gg.normal(gg.MASTER_SEED, 1, n, 32)
+    ws = [gg.glorot(gg.MASTER_SEED, 10, 32, 64), gg.glorot(gg.MASTER_SEED, 11, 64, 16)]
+    y = gg.labels(gg.MASTER_SEED, 5, n, 16)
+    s = 7
+    base = run_model_gpu(mg, g, x, ws, y, s, reorder=False)
+    for bw in (b, b, n):
+        say(f"cross-layer pipeline vs layer by layer, bandwidth argument {bw}")
+        got = run_model_gpu(mg, g, x, ws, y, s, reorder=False, bandwidth=bw)
+        assert got[0] == base[0]
+        for a, c in zip(got[3], base[3]):
+            assert np.array_equal(a, c)
+        for a, c in zip(got[2], base[2]):  # dW: summed batch by batch
+            assert_close(a, c, RTOL_F32, "dW")
+    with pytest.raises(mg.MixGCNError):
+        run_model_gpu(mg, g, x, ws, y, s, reorder=False, bandwidth=b - 1)
+    g.free()
+
+
+def test_cross_layer_pipeline_without_a_band(mg):
+    """An Erdos-Renyi graph has b close to n: every aggregation waits for the whole operation
+    before it, and the result is still the oracle's."""
+    say("cross-layer pipeline on config 1 (no band)")
+    src, dst, n = gg.config_graph("c1")
+    x = gg.uniform(gg.MASTER_SEED, 1, n, 64)
+    ws = [gg.glorot(gg.MASTER_SEED, 10, 64, 32), gg.glorot(gg.MASTER_SEED, 11, 32, 8)]
+    y = gg.labels(gg.MASTER_SEED, 5, n, 8)
+    check_model(mg, "c1", src, dst, n, x, ws, y, 4, True, cross_layer=True)
 
 
 def test_captured_step_replays_match_eager(mg):
