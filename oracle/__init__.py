@@ -271,3 +271,129 @@ def gcn_step(g: Graph, X, Ws, labels, want_dx=False, linear=False, q=Q_NONE, bac
                                    _p(g.t_col), _p(g.t_val), n, L, _p(dims), _p(X), w_arr, _p(labels),
                                    z_arr, h_arr, dw_arr, _p(dX), int(linear), q)
     return {"loss": loss, "logits": Hs[L], "Z": Zs, "H": Hs, "dW": dWs, "dX": dX}
+
+
+# ------------------------------------------------------------------------------------------
+# The two other architectures of the paper's experiments (Sec. 4, "The Model and Datasets":
+# GCN, GraphSAGE, GIN).  The paper prints no equations for them, so these follow the works it
+# cites: GraphSAGE with the mean aggregator and concatenation (Hamilton et al. 2017, Alg. 1,
+# without the optional output normalisation), GIN with a two-layer perceptron (Xu et al. 2019,
+# Eq. 4.1).  Plain numpy in fp64 on top of spmm(); matmul is the library primitive of each
+# update.  No bias, no dropout, ReLU between layers and none after the last, as in gcn_step.
+# ------------------------------------------------------------------------------------------
+def _rows_of_entries(g: Graph):
+    return np.repeat(np.arange(g.n, dtype=np.int64), np.diff(g.rowptr))
+
+
+def normalize_mean(g: Graph) -> Graph:
+    """A_hat = D^-1 A on the stored pattern: every stored entry of row u is 1 / deg(u), deg(u)
+    the number of stored entries of the row (the neighbors of u; u itself only if the graph was
+    built with self-loops).  val_f32 is the fp32 encoding (float)(1 / (double)deg)."""
+    deg = np.diff(g.rowptr).astype(np.uint32)
+    rows = _rows_of_entries(g)
+    g.deg = deg
+    with np.errstate(divide="ignore"):
+        inv = np.where(deg > 0, 1.0 / deg.astype(np.float64), 0.0)
+    g.dinv = inv
+    g.val = inv[rows]
+    g.val_f32 = inv.astype(np.float32)[rows]
+    g.t_rowptr = g.t_col = g.t_val = None
+    return g
+
+
+def normalize_sum(g: Graph, eps: float = 0.0) -> Graph:
+    """A_hat = A + eps I on the stored pattern of A + I: 1 for a neighbor, 1 + eps for the node
+    itself (GIN's (1 + eps) h_v + sum of the neighbors).  val_f32 adds in fp32."""
+    rows = _rows_of_entries(g)
+    diag = rows == g.col.astype(np.int64)
+    g.deg = np.diff(g.rowptr).astype(np.uint32)
+    g.dinv = np.zeros(g.n, dtype=np.float64)
+    g.val = np.where(diag, 1.0 + float(eps), 1.0)
+    g.val_f32 = np.where(diag, np.float32(1.0) + np.float32(eps), np.float32(1.0)).astype(np.float32)
+    g.t_rowptr = g.t_col = g.t_val = None
+    return g
+
+
+def _loss_and_grad(logits, labels, backward):
+    loss, d = softmax_xent(logits, labels, want_grad=backward)
+    return loss, d
+
+
+def sage_step(g: Graph, X, Ws, labels, want_dx=False, backward=True):
+    """L-layer GraphSAGE (mean aggregator).  g: normalize_mean'd graph WITHOUT self-loops.
+    Ws[l] has 2 d_l rows: the first d_l multiply the node's own features, the last d_l the mean
+    of its neighbors' (the concatenation [h_v | mean]).
+        M_l = A_hat H_l;  X_l = [H_l | M_l];  P_l = X_l W_l;  H_{l+1} = relu(P_l), last: P_l.
+    Backward: dW_l = X_l^T dP_l;  dX_l = dP_l W_l^T;  dH_l = dX_l[:, :d] + A_hat^T dX_l[:, d:];
+    dP_{l-1} = dH_l (.) 1[H_l > 0]."""
+    X = _f64(X)
+    Ws = [_f64(w) for w in Ws]
+    L = len(Ws)
+    if g.t_rowptr is None:
+        transpose(g)
+    Hs, Xs = [X], []
+    for l, w in enumerate(Ws):
+        d = Hs[l].shape[1]
+        assert w.shape[0] == 2 * d
+        xc = np.concatenate([Hs[l], spmm(g, Hs[l])], axis=1)
+        p = xc @ w
+        Xs.append(xc)
+        Hs.append(np.maximum(p, 0.0) if l < L - 1 else p)
+    loss, dP = _loss_and_grad(Hs[L], labels, backward)
+    out = {"loss": loss, "logits": Hs[L], "H": Hs, "X": Xs, "dW": None, "dX": None}
+    if not backward:
+        return out
+    dWs = [None] * L
+    for l in range(L - 1, -1, -1):
+        d = Hs[l].shape[1]
+        dWs[l] = Xs[l].T @ dP
+        if l == 0 and not want_dx:
+            break
+        dXc = dP @ Ws[l].T
+        dH = dXc[:, :d] + spmm(g, np.ascontiguousarray(dXc[:, d:]), transposed=True)
+        if l == 0:
+            out["dX"] = dH
+            break
+        dP = dH * (Hs[l] > 0)
+    out["dW"] = dWs
+    return out
+
+
+def gin_step(g: Graph, X, W1s, W2s, labels, want_dx=False, backward=True):
+    """L-layer GIN.  g: normalize_sum'd graph WITH self-loops (their value carries 1 + eps).
+        Z_l = A_hat H_l;  T_l = relu(Z_l W1_l);  P_l = T_l W2_l;  H_{l+1} = relu(P_l), last: P_l.
+    Backward: dW2_l = T_l^T dP_l;  dT_l = dP_l W2_l^T (.) 1[T_l > 0];  dW1_l = Z_l^T dT_l;
+    dZ_l = dT_l W1_l^T;  dH_l = A_hat^T dZ_l;  dP_{l-1} = dH_l (.) 1[H_l > 0]."""
+    X = _f64(X)
+    W1s = [_f64(w) for w in W1s]
+    W2s = [_f64(w) for w in W2s]
+    L = len(W1s)
+    if g.t_rowptr is None:
+        transpose(g)
+    Hs, Zs, Ts = [X], [], []
+    for l in range(L):
+        z = spmm(g, Hs[l])
+        t = np.maximum(z @ W1s[l], 0.0)
+        p = t @ W2s[l]
+        Zs.append(z)
+        Ts.append(t)
+        Hs.append(np.maximum(p, 0.0) if l < L - 1 else p)
+    loss, dP = _loss_and_grad(Hs[L], labels, backward)
+    out = {"loss": loss, "logits": Hs[L], "H": Hs, "Z": Zs, "T": Ts, "dW1": None, "dW2": None,
+           "dX": None}
+    if not backward:
+        return out
+    dW1s, dW2s = [None] * L, [None] * L
+    for l in range(L - 1, -1, -1):
+        dW2s[l] = Ts[l].T @ dP
+        dT = (dP @ W2s[l].T) * (Ts[l] > 0)
+        dW1s[l] = Zs[l].T @ dT
+        if l == 0 and not want_dx:
+            break
+        dH = spmm(g, dT @ W1s[l].T, transposed=True)
+        if l == 0:
+            out["dX"] = dH
+            break
+        dP = dH * (Hs[l] > 0)
+    out["dW1"], out["dW2"] = dW1s, dW2s
+    return out

@@ -568,3 +568,170 @@ def test_bf16_quantiser_rounds_to_nearest_even():
     assert out[0, 3] == np.float32(-0.30078125)
     out32 = oracle.update_fwd(z, w, relu=False, q=oracle.Q_F32)
     assert np.array_equal(out32, z.astype(np.float32).astype(np.float64))
+
+
+# ------------------------------------------------------------------------------------------
+# GraphSAGE (mean) and GIN: the other two architectures of the paper's experiments (Sec. 4).
+# Pins: dense brute force written from the cited definitions, closed forms, special cases that
+# reduce to a perceptron, central finite differences for every gradient.
+# ------------------------------------------------------------------------------------------
+def _tiny_variant_problem(seed, n=11, dims=(4, 3, 2), loops=False):
+    rng = np.random.default_rng(seed)
+    src = rng.integers(0, n, 2 * n)
+    dst = rng.integers(0, n, 2 * n)
+    g = oracle.build_csr(src, dst, n, True, loops)
+    x = rng.normal(size=(n, dims[0]))
+    y = rng.integers(0, dims[-1], n).astype(np.int32)
+    return rng, g, src, dst, x, y
+
+
+def test_mean_weights_row_sums_dense_form_and_transpose():
+    rng, g, src, dst, x, y = _tiny_variant_problem(51, n=40)
+    oracle.normalize_mean(g)
+    a = dense_atilde(src, dst, g.n, True, False).astype(np.float64)
+    deg = a.sum(axis=1)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        am = np.where(deg[:, None] > 0, a / deg[:, None], 0.0)
+    assert np.array_equal(g.deg, deg.astype(np.uint32))
+    np.testing.assert_allclose(csr_to_dense(g, g.val), am, rtol=0, atol=1e-15)
+    # rows with neighbors sum to one; the mean of a constant is the constant
+    ones = oracle.spmm(g, np.ones((g.n, 3)))
+    assert np.allclose(ones[deg > 0], 1.0) and np.all(ones[deg == 0] == 0.0)
+    h = rng.normal(size=(g.n, 5))
+    np.testing.assert_allclose(oracle.spmm(g, h), am @ h, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(oracle.spmm(g, h, transposed=True), am.T @ h, rtol=1e-12, atol=1e-14)
+    # the fp32 encoding is the rounded reciprocal of the row count
+    rows = np.repeat(np.arange(g.n), np.diff(g.rowptr))
+    assert np.array_equal(g.val_f32, (1.0 / deg[rows]).astype(np.float32))
+
+
+@pytest.mark.parametrize("eps", [0.0, 0.25, -1.0])
+def test_sum_weights_dense_form_and_regular_graph(eps):
+    rng, g, src, dst, x, y = _tiny_variant_problem(52, n=30, loops=True)
+    oracle.normalize_sum(g, eps)
+    a = dense_atilde(src, dst, g.n, True, False).astype(np.float64)
+    want = a + (1.0 + eps) * np.eye(g.n)
+    np.testing.assert_allclose(csr_to_dense(g, g.val), want, rtol=0, atol=0)
+    h = rng.normal(size=(g.n, 4))
+    np.testing.assert_allclose(oracle.spmm(g, h), (1 + eps) * h + a @ h, rtol=1e-12, atol=1e-13)
+    # k-regular ring: every row of (A + (1 + eps) I) 1 is k + 1 + eps
+    s, d = gg.ring_lattice_edges(50, 6)
+    r = oracle.normalize_sum(oracle.build_csr(s, d, 50, True, True), eps)
+    np.testing.assert_allclose(oracle.spmm(r, np.ones((50, 2))), 6 + 1 + eps, rtol=1e-14)
+
+
+def test_sage_forward_vs_dense_definition_and_concat_order():
+    rng, g, src, dst, x, y = _tiny_variant_problem(53)
+    oracle.normalize_mean(g)
+    ws = [rng.normal(size=(8, 3)), rng.normal(size=(6, 2))]
+    a = dense_atilde(src, dst, g.n, True, False).astype(np.float64)
+    h = x
+    for l, w in enumerate(ws):
+        d = h.shape[1]
+        mean = np.zeros_like(h)
+        for v in range(g.n):  # the definition, node by node
+            nb = np.nonzero(a[v])[0]
+            if len(nb):
+                mean[v] = h[nb].mean(axis=0)
+        h = h @ w[:d] + mean @ w[d:]  # own features meet the FIRST d rows of W
+        if l < len(ws) - 1:
+            h = np.maximum(h, 0)
+    out = oracle.sage_step(g, x, ws, y, backward=False)
+    np.testing.assert_allclose(out["logits"], h, rtol=1e-11, atol=1e-13)
+
+
+def test_sage_special_cases_reduce_to_a_perceptron():
+    rng, g, src, dst, x, y = _tiny_variant_problem(54)
+    oracle.normalize_mean(g)
+    w0, w1 = rng.normal(size=(8, 3)), rng.normal(size=(6, 2))
+    # neighbor half of every W zero: the graph does not matter
+    w0z, w1z = w0.copy(), w1.copy()
+    w0z[4:] = 0
+    w1z[3:] = 0
+    out = oracle.sage_step(g, x, [w0z, w1z], y, backward=False)
+    np.testing.assert_allclose(out["logits"], np.maximum(x @ w0[:4], 0) @ w1[:3], rtol=1e-12, atol=1e-14)
+    # a graph of self-loops only: the mean is the node itself, so W_self + W_neigh acts on it
+    n = g.n
+    loops = oracle.normalize_mean(oracle.build_csr(np.arange(0), np.arange(0), n, True, True))
+    out = oracle.sage_step(loops, x, [w0, w1], y, backward=False)
+    ref = np.maximum(x @ (w0[:4] + w0[4:]), 0) @ (w1[:3] + w1[3:])
+    np.testing.assert_allclose(out["logits"], ref, rtol=1e-12, atol=1e-14)
+
+
+def test_gin_forward_vs_dense_definition():
+    rng, g, src, dst, x, y = _tiny_variant_problem(55, loops=True)
+    eps = 0.3
+    oracle.normalize_sum(g, eps)
+    w1s = [rng.normal(size=(4, 5)), rng.normal(size=(3, 4))]
+    w2s = [rng.normal(size=(5, 3)), rng.normal(size=(4, 2))]
+    a = dense_atilde(src, dst, g.n, True, False)
+    h = x
+    for l in range(2):
+        agg = np.zeros_like(h)
+        for v in range(g.n):  # (1 + eps) h_v + sum over the neighbors
+            agg[v] = (1 + eps) * h[v] + h[np.nonzero(a[v])[0]].sum(axis=0)
+        h = np.maximum(agg @ w1s[l], 0) @ w2s[l]
+        if l == 0:
+            h = np.maximum(h, 0)
+    out = oracle.gin_step(g, x, w1s, w2s, y, backward=False)
+    np.testing.assert_allclose(out["logits"], h, rtol=1e-11, atol=1e-13)
+
+
+def _fd_check(loss_at, params, grads, hstep=1e-6):
+    for p, gr in zip(params, grads):
+        num = np.zeros_like(p)
+        for idx in np.ndindex(*p.shape):
+            old = p[idx]
+            p[idx] = old + hstep
+            lp = loss_at()
+            p[idx] = old - hstep
+            lm = loss_at()
+            p[idx] = old
+            num[idx] = (lp - lm) / (2 * hstep)
+        np.testing.assert_allclose(gr, num, rtol=5e-6, atol=2e-9)
+
+
+@pytest.mark.parametrize("seed", [61, 62, 63])
+def test_sage_gradients_vs_central_finite_differences(seed):
+    rng, g, src, dst, x, y = _tiny_variant_problem(seed, dims=(4, 3, 3, 2))
+    oracle.normalize_mean(g)
+    ws = [rng.normal(size=(8, 3)), rng.normal(size=(6, 3)), rng.normal(size=(6, 2))]
+    base = oracle.sage_step(g, x, ws, y, want_dx=True)
+    for l in (0, 1):
+        if np.min(np.abs(base["X"][l] @ ws[l])) < 1e-4:
+            pytest.skip("sample too close to a ReLU kink")
+    _fd_check(lambda: oracle.sage_step(g, x, ws, y, backward=False)["loss"], ws + [x],
+              base["dW"] + [base["dX"]])
+
+
+@pytest.mark.parametrize("seed", [71, 74, 75])
+def test_gin_gradients_vs_central_finite_differences(seed):
+    rng, g, src, dst, x, y = _tiny_variant_problem(seed, loops=True)
+    oracle.normalize_sum(g, 0.2)
+    w1s = [rng.normal(size=(4, 3)) * 0.5, rng.normal(size=(3, 3)) * 0.5]
+    w2s = [rng.normal(size=(3, 3)) * 0.5, rng.normal(size=(3, 2)) * 0.5]
+    base = oracle.gin_step(g, x, w1s, w2s, y, want_dx=True)
+    for l in (0, 1):
+        # a row of T that the inner ReLU zeroed gives a pre-activation of exactly 0 that no small
+        # step moves: not a kink for the difference quotient
+        pre2 = np.abs(base["T"][l] @ w2s[l])
+        if np.min(np.abs(base["Z"][l] @ w1s[l])) < 1e-4 or \
+                (l == 0 and np.min(pre2[pre2 > 0]) < 1e-4):
+            pytest.skip("sample too close to a ReLU kink")
+    _fd_check(lambda: oracle.gin_step(g, x, w1s, w2s, y, backward=False)["loss"], w1s + w2s + [x],
+              base["dW1"] + base["dW2"] + [base["dX"]])
+
+
+def test_sage_gradient_fd_on_a_directed_graph_pins_the_transposed_mean():
+    """On a directed graph D^-1 A and its transpose differ in pattern AND values."""
+    rng = np.random.default_rng(81)
+    n = 10
+    src, dst = rng.integers(0, n, 25), rng.integers(0, n, 25)
+    g = oracle.normalize_mean(oracle.build_csr(src, dst, n, False, False))
+    x = rng.normal(size=(n, 3))
+    ws = [rng.normal(size=(6, 3)), rng.normal(size=(6, 2))]
+    y = rng.integers(0, 2, n).astype(np.int32)
+    base = oracle.sage_step(g, x, ws, y, want_dx=True)
+    if np.min(np.abs(base["X"][0] @ ws[0])) < 1e-4:
+        pytest.skip("sample too close to a ReLU kink")
+    _fd_check(lambda: oracle.sage_step(g, x, ws, y, backward=False)["loss"], [x], [base["dX"]])
