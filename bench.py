@@ -183,6 +183,91 @@ def bench_single_layer(args, mg, dev):
     }))
 
 
+def bench_variant(args, mg, dev):
+    """--model sage | gin (not the default line): the paper's two other architectures, three
+    layers with 128 hidden units, on the graph and features of the chosen configuration."""
+    import numpy as np
+    import torch
+
+    import graphgen as gg
+
+    src, dst, n = gg.config_graph(args.config, seed=args.seed, scale_override=args.scale)
+    d0 = model_dims(args.config)[0]
+    classes = model_dims(args.config)[-1]
+    dims = [d0, 128, 128, classes]
+    x = gg.normal(args.seed, 1, n, d0)
+    y = gg.labels(args.seed, 5, n, classes)
+    sage = args.model == "sage"
+    flags = mg.SYMMETRIZE | (0 if sage else mg.ADD_SELF_LOOPS)
+    g = mg.build_csr(dev(src.view(np.int32)), dev(dst.view(np.int32)), n, flags)
+    mg.normalize(g, mg.NORM_MEAN if sage else mg.NORM_SUM, eps=0.0 if sage else 0.1)
+    nnz = g.nnz
+    if sage:
+        ws = [dev(gg.glorot(args.seed, 20 + l, 2 * dims[l], dims[l + 1])) for l in range(3)]
+        step = mg.SAGEStep(g, dev(x), ws, dev(y))
+        agg_in, agg_out = step.xc[1][:, :128], step.xc[1][:, 128:256]
+    else:
+        w1s = [dev(0.02 * gg.glorot(args.seed, 30 + l, dims[l], 128)) for l in range(3)]
+        w2s = [dev(gg.glorot(args.seed, 40 + l, 128, dims[l + 1])) for l in range(3)]
+        step = mg.GINStep(g, dev(x), w1s, w2s, dev(y))
+        agg_in, agg_out = step.h[1], step.z[1]
+    for _ in range(args.warmup):
+        step.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step.step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    loss = step.loss.item()
+    # the aggregation at the hidden width, timed alone with events on the stream it runs on
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * args.steps)]
+    for i in range(args.steps):
+        ev[2 * i].record()
+        mg.aggregate(g, agg_in, agg_out)
+        ev[2 * i + 1].record()
+    torch.cuda.synchronize()
+    agg_ms = sum(ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(args.steps)) / args.steps
+    per_launch = 8.0 * nnz + 2.0 * n * 128 * 4 + 8.0 * n
+    achieved = per_launch / (agg_ms * 1e-3) / 1e9
+    name = "GraphSAGE (mean)" if sage else "GIN (eps = 0.1)"
+    out = {
+        "metric": f"{name} fwd+bwd edges*feat/s", "value": sum(nnz * d for d in dims[:-1]) / dt,
+        "unit": "edges*feat/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.config} graph: 3-layer {name} {'-'.join(map(str, dims))}, one "
+                               f"fwd+bwd epoch, N={n}, nnz(A_hat)={nnz}",
+                   "n_nodes": n, "nnz": nnz, "seed": args.seed},
+        "loss": loss,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "aggregate_kernel<8, 32, 0, false, true> (128 fp32 columns)",
+                     "avg_launch_ms": agg_ms, "algorithmic_bytes_per_launch": per_launch},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+
+        s2, d2, n2 = gg.config_graph(args.config, seed=args.seed, scale_override=args.cpu_scale)
+        og = oracle.build_csr(s2, d2, n2, True, not sage)
+        og = oracle.transpose(oracle.normalize_mean(og) if sage else oracle.normalize_sum(og, 0.1))
+        x2, y2 = gg.normal(args.seed, 1, n2, d0), gg.labels(args.seed, 5, n2, classes)
+        t0 = time.perf_counter()
+        if sage:
+            oracle.sage_step(og, x2, [gg.glorot(args.seed, 20 + l, 2 * dims[l], dims[l + 1])
+                                      for l in range(3)], y2)
+        else:
+            oracle.gin_step(og, x2, [0.02 * gg.glorot(args.seed, 30 + l, dims[l], 128) for l in range(3)],
+                            [gg.glorot(args.seed, 40 + l, 128, dims[l + 1]) for l in range(3)], y2)
+        t = time.perf_counter() - t0
+        out["cpu_baseline"] = {
+            "value": sum(og.nnz * d for d in dims[:-1]) / t, "unit": "edges*feat/s",
+            "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"same generator and model at R-MAT scale {args.cpu_scale} (N={n2}, "
+                      f"nnz={og.nnz}), one fwd+bwd step, {t:.1f} s"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -195,6 +280,9 @@ def main():
     ap.add_argument("--cpu-scale", type=int, default=20, help="R-MAT scale of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-event-timing", action="store_true")
+    ap.add_argument("--model", default="gcn", choices=["gcn", "sage", "gin"],
+                    help="gcn: the benchmark line; sage / gin: the two other architectures of the "
+                         "paper's experiments on the same graph (3 layers, 128 hidden units)")
     ap.add_argument("--hip-graph", action="store_true",
                     help="record the step into a HIP graph and time its replays (one stream, no "
                          "per-kernel events): for small inputs, where launches dominate")
@@ -215,6 +303,9 @@ def main():
     def dev(a):
         return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
+    if args.model != "gcn":
+        assert args.config in ("c1", "c2"), "--model sage/gin run on the graphs of c1 and c2"
+        return bench_variant(args, mg, dev)
     if args.config in ("c3", "c4"):
         return bench_single_layer(args, mg, dev)
     src, dst, n, x, ws, y, dims = make_inputs(args.config, args.scale, args.seed)

@@ -50,7 +50,20 @@ enum {
     MIXGCN_INPUT_ON_HOST = 8    /* src/dst are host pointers (copied synchronously) */
 };
 
-enum { MIXGCN_NORM_SYM = 0 }; /* A_hat = D^-1/2 A_tilde D^-1/2 */
+/* Aggregation matrices (mixgcn_normalize_mode).  SYM is the paper's GCN (Sec. 2.1); MEAN and
+ * SUM are the neighbor aggregations of the two other architectures the paper evaluates (Sec. 4,
+ * experimental setting: GraphSAGE and GIN), taken from the works it cites for them. */
+enum {
+    MIXGCN_NORM_SYM = 0,  /* A_hat = D^-1/2 A_tilde D^-1/2                                      */
+    MIXGCN_NORM_MEAN = 1, /* A_hat = D^-1 A: mean over the stored row (GraphSAGE, mean form)   */
+    MIXGCN_NORM_SUM = 2   /* A_hat = A + eps I on the stored pattern: 1 off the diagonal,
+                             1 + eps on it (GIN; build the graph with self-loops)               */
+};
+/* Epilogue flags of mixgcn_aggregate_ex. */
+enum {
+    MIXGCN_EPI_RELU = 1,      /* Z = max(A_hat H, 0)                                            */
+    MIXGCN_EPI_ACCUMULATE = 2 /* Z = Z + A_hat H (applied before the ReLU if both are set)     */
+};
 enum { MIXGCN_F32 = 0, MIXGCN_BF16 = 1 };
 
 /* mixgcn_update ops */
@@ -119,6 +132,16 @@ int mixgcn_build_csr(const uint32_t* src, const uint32_t* dst, uint64_t n_edges,
  * for the transpose as well if it is stored.  Asynchronous on `stream`.
  */
 int mixgcn_normalize(mixgcn_graph* g, int mode, void* stream);
+/*
+ * The same with the aggregation matrix of another architecture (MIXGCN_NORM_*); mixgcn_normalize
+ * is this call with eps = 0.  deg is always the stored row count.
+ *   MEAN: dinv = (float)(1 / (double)deg) (0 for an empty row), val[e] = dinv[row(e)].  The
+ *         transpose has other values (dinv[col]) on the same pattern; they are kept beside the
+ *         matrix, and transpose = 1 of the aggregate calls uses them.
+ *   SUM:  val[e] = 1, and (float)1 + eps where row == col (entries that are not stored stay
+ *         zero: without self-loops in the graph eps has no effect).  eps must be finite.
+ */
+int mixgcn_normalize_mode(mixgcn_graph* g, int mode, float eps, void* stream);
 
 /*
  * Algorithm 2, aggregation phase (and its adjoint for the backward pass):
@@ -133,6 +156,20 @@ int mixgcn_normalize(mixgcn_graph* g, int mode, void* stream);
 int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void* H, int64_t ldh,
                      void* Z, int64_t ldz, int32_t col_begin, int32_t col_end, int64_t row_begin,
                      int64_t row_end, void* stream);
+
+/*
+ * mixgcn_aggregate with an epilogue (MIXGCN_EPI_* flags, 0 = none), for the layer forms that
+ * combine a node's own features with the aggregate (GraphSAGE's concatenation, whose backward
+ * pass is dH = dX_self + A_hat^T dX_neigh):
+ *   ACCUMULATE adds the row sums to what Z holds (rows without stored entries keep their value);
+ *   RELU clamps the result at zero.
+ * H and Z may be two column blocks of ONE row-major buffer: same ld, and the column ranges
+ * [0, col_end) counted from the H pointer and from the Z pointer do not meet within a row
+ * (H = X, Z = X + F with F >= col_end rounded up to a whole 16-byte group, 2 F <= ld).
+ */
+int mixgcn_aggregate_ex(const mixgcn_graph* g, int transpose, int dtype, const void* H, int64_t ldh,
+                        void* Z, int64_t ldz, int32_t col_begin, int32_t col_end,
+                        int64_t row_begin, int64_t row_end, int epilogue, void* stream);
 
 /*
  * Sec. 3.2.1, Eq. 4 (S-SpMM): Z = (M_op H) (.) mask on the same ranges as mixgcn_aggregate, the

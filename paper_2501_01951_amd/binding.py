@@ -14,6 +14,8 @@ _lib = None
 F32, BF16 = 0, 1
 OP_FWD, OP_FWD_RELU, OP_DGRAD, OP_WGRAD = 0, 1, 2, 3
 SYMMETRIZE, ADD_SELF_LOOPS, BUILD_TRANSPOSE, INPUT_ON_HOST = 1, 2, 4, 8
+NORM_SYM, NORM_MEAN, NORM_SUM = 0, 1, 2
+EPI_RELU, EPI_ACCUMULATE = 1, 2
 AGG_FIRST, UPDATE_FIRST = 0, 1
 
 
@@ -66,6 +68,9 @@ def load_library():
     lib.mixgcn_strerror.argtypes = [ctypes.c_int]
     lib.mixgcn_build_csr.argtypes = [vp, vp, u64, u32, u32, vp, ctypes.POINTER(vp)]
     lib.mixgcn_normalize.argtypes = [vp, ctypes.c_int, vp]
+    lib.mixgcn_normalize_mode.argtypes = [vp, ctypes.c_int, ctypes.c_float, vp]
+    lib.mixgcn_aggregate_ex.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, i64, vp, i64, i32, i32,
+                                        i64, i64, ctypes.c_int, vp]
     lib.mixgcn_aggregate.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, i64, vp, i64, i32, i32,
                                      i64, i64, vp]
     lib.mixgcn_aggregate_masked.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, i64, vp, i64, i32,
@@ -281,14 +286,22 @@ def build_csr(src, dst, n_nodes: int, flags: int = SYMMETRIZE | ADD_SELF_LOOPS, 
     return Graph(h, dev)
 
 
-def normalize(g: Graph, mode: int = 0, stream=None) -> None:
-    _check(load_library().mixgcn_normalize(g._h, mode, _stream(stream)), "normalize")
+def normalize(g: Graph, mode: int = 0, stream=None, eps: float = 0.0) -> None:
+    """mode: NORM_SYM (GCN), NORM_MEAN (GraphSAGE mean), NORM_SUM (GIN; eps on the diagonal)."""
+    _check(load_library().mixgcn_normalize_mode(g._h, mode, eps, _stream(stream)), "normalize")
 
 
 def aggregate(g: Graph, H, Z, col_begin=0, col_end=None, row_begin=0, row_end=None,
-              transpose=False, stream=None) -> None:
+              transpose=False, stream=None, relu=False, accumulate=False) -> None:
     col_end = H.shape[1] if col_end is None else col_end
     row_end = g.n if row_end is None else row_end
+    if relu or accumulate:
+        epi = (EPI_RELU if relu else 0) | (EPI_ACCUMULATE if accumulate else 0)
+        _check(load_library().mixgcn_aggregate_ex(g._h, int(transpose), _dtype_of(H), _ptr(H),
+                                                  _ld(H), _ptr(Z), _ld(Z), col_begin, col_end,
+                                                  row_begin, row_end, epi, _stream(stream)),
+               "aggregate_ex")
+        return
     _check(load_library().mixgcn_aggregate(g._h, int(transpose), _dtype_of(H), _ptr(H), _ld(H),
                                            _ptr(Z), _ld(Z), col_begin, col_end, row_begin, row_end,
                                            _stream(stream)), "aggregate")

@@ -2,6 +2,7 @@
 // pipeline that overlaps the aggregation of chunk k with the update of chunk k-1, and its
 // cross-layer form
 // (paper Sec. 3.2.2, fine-grain pipeline between the sparse and the dense half of a layer).
+#include <cmath>
 #include <cstring>
 #include <functional>
 #include <memory>
@@ -198,8 +199,16 @@ int mixgcn_graph_free(mixgcn_graph* g)
 int mixgcn_normalize(mixgcn_graph* g, int mode, void* stream)
 {
     if (!g) return fail(MIXGCN_EINVAL, "normalize: graph is null");
-    if (mode != MIXGCN_NORM_SYM) return fail(MIXGCN_EINVAL, "normalize: unknown mode");
-    return normalize_sym(g, (hipStream_t)stream);
+    return mixgcn_normalize_mode(g, mode, 0.f, stream);
+}
+
+int mixgcn_normalize_mode(mixgcn_graph* g, int mode, float eps, void* stream)
+{
+    if (!g) return fail(MIXGCN_EINVAL, "normalize: graph is null");
+    if (mode != MIXGCN_NORM_SYM && mode != MIXGCN_NORM_MEAN && mode != MIXGCN_NORM_SUM)
+        return fail(MIXGCN_EINVAL, "normalize: unknown mode");
+    if (!(eps == eps) || fabsf(eps) > 3.0e38f) return fail(MIXGCN_EINVAL, "normalize: eps");
+    return normalize_graph(g, mode, mode == MIXGCN_NORM_SUM ? eps : 0.f, (hipStream_t)stream);
 }
 
 int mixgcn_graph_info(const mixgcn_graph* g, mixgcn_graph_view* out)
@@ -220,19 +229,22 @@ int mixgcn_graph_info(const mixgcn_graph* g, mixgcn_graph_view* out)
     if (t) {
         out->t_rowptr = t->rowptr;
         out->t_col = t->col;
-        out->t_val = g->normalized ? t->val : nullptr;
+        const bool own = t == &g->fwd && g->norm_mode == MIXGCN_NORM_MEAN && t->val_t;
+        out->t_val = g->normalized ? (own ? t->val_t : t->val) : nullptr;
     }
     return MIXGCN_OK;
 }
 
 static int aggregate_impl(const mixgcn_graph* g, int transpose, int dtype, const void* H,
                           int64_t ldh, void* Z, int64_t ldz, int32_t col_begin, int32_t col_end,
-                          int64_t row_begin, int64_t row_end, int relu, hipStream_t stream,
+                          int64_t row_begin, int64_t row_end, int epilogue, hipStream_t stream,
                           Timer* timer, const uint32_t* mask = nullptr, int64_t ld_mask = 0)
 {
     if (!g) return fail(MIXGCN_EINVAL, "aggregate: graph is null");
     if (!g->normalized) return fail(MIXGCN_ESTATE, "aggregate: call mixgcn_normalize first");
     if (dtype != MIXGCN_F32 && dtype != MIXGCN_BF16) return fail(MIXGCN_EINVAL, "aggregate: dtype");
+    if (epilogue & ~(MIXGCN_EPI_RELU | MIXGCN_EPI_ACCUMULATE))
+        return fail(MIXGCN_EINVAL, "aggregate: unknown epilogue flag");
     const int es = elem_size(dtype), vec = 16 / es;
     if (col_begin < 0 || col_end < col_begin) return fail(MIXGCN_EINVAL, "aggregate: column range");
     if (row_begin < 0 || row_end < row_begin || row_end > (int64_t)g->n)
@@ -240,9 +252,9 @@ static int aggregate_impl(const mixgcn_graph* g, int transpose, int dtype, const
     MIXGCN_TRY(check_matrix("aggregate: H", H, ldh, col_end, es));
     MIXGCN_TRY(check_matrix("aggregate: Z", Z, ldz, col_end, es));
     if (col_begin % vec != 0) return fail(MIXGCN_EINVAL, "aggregate: col_begin not vector aligned");
+    const int64_t up = ((int64_t)col_end + vec - 1) / vec * vec;
     if (col_end % vec != 0) {
         // the last vector reaches into the row padding, which must exist in both matrices
-        const int64_t up = (col_end + vec - 1) / vec * vec;
         if (up > ldh || up > ldz)
             return fail(MIXGCN_EINVAL, "aggregate: col_end not vector aligned and no row padding");
     }
@@ -251,19 +263,33 @@ static int aggregate_impl(const mixgcn_graph* g, int transpose, int dtype, const
         const char* h1 = h0 + (size_t)g->n * ldh * es;
         const char* z0 = (const char*)Z;
         const char* z1 = z0 + (size_t)g->n * ldz * es;
-        if (h0 < z1 && z0 < h1) return fail(MIXGCN_EINVAL, "aggregate: H and Z overlap");
+        if (h0 < z1 && z0 < h1) {
+            // Two column blocks of one row-major buffer (same pitch) may interleave: the
+            // columns [0, up) seen from H and from Z must be disjoint within a row.
+            const int64_t pitch = ldh * es;
+            int64_t shift = ((z0 - h0) % pitch + pitch) % pitch;
+            const bool disjoint = ldh == ldz && shift >= up * es && shift + up * es <= pitch;
+            if (!disjoint) return fail(MIXGCN_EINVAL, "aggregate: H and Z overlap");
+        }
     }
     const mixgcn::Csr* m = &g->fwd;
-    if (transpose && !(g->flags & MIXGCN_SYMMETRIZE)) {
-        if (!g->has_transpose)
-            return fail(MIXGCN_ESTATE, "aggregate: transpose needs MIXGCN_BUILD_TRANSPOSE");
-        m = &g->tr;
+    const uint2* cv = g->fwd.cv;
+    if (transpose) {
+        if (g->flags & MIXGCN_SYMMETRIZE) {
+            if (g->norm_mode == MIXGCN_NORM_MEAN) cv = g->fwd.cv_t;
+        } else {
+            if (!g->has_transpose)
+                return fail(MIXGCN_ESTATE, "aggregate: transpose needs MIXGCN_BUILD_TRANSPOSE");
+            m = &g->tr;
+            cv = g->tr.cv;
+        }
     }
+    if (!cv) return fail(MIXGCN_ESTATE, "aggregate: values of the transpose are missing");
     if (mask && ld_mask < ((int64_t)col_end + 31) / 32)
         return fail(MIXGCN_EINVAL, "aggregate: ld_mask shorter than ceil(col_end / 32) words");
     if (row_end == row_begin || col_end == col_begin) return MIXGCN_OK;
-    return launch_aggregate(g, *m, dtype, H, ldh, Z, ldz, col_begin, col_end, row_begin, row_end,
-                            relu, mask, ld_mask, stream, timer);
+    return launch_aggregate(g, *m, cv, dtype, H, ldh, Z, ldz, col_begin, col_end, row_begin,
+                            row_end, epilogue, mask, ld_mask, stream, timer);
 }
 
 int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void* H, int64_t ldh,
@@ -272,6 +298,14 @@ int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void
 {
     return aggregate_impl(g, transpose, dtype, H, ldh, Z, ldz, col_begin, col_end, row_begin,
                           row_end, 0, (hipStream_t)stream, nullptr);
+}
+
+int mixgcn_aggregate_ex(const mixgcn_graph* g, int transpose, int dtype, const void* H, int64_t ldh,
+                        void* Z, int64_t ldz, int32_t col_begin, int32_t col_end,
+                        int64_t row_begin, int64_t row_end, int epilogue, void* stream)
+{
+    return aggregate_impl(g, transpose, dtype, H, ldh, Z, ldz, col_begin, col_end, row_begin,
+                          row_end, epilogue, (hipStream_t)stream, nullptr);
 }
 
 int mixgcn_aggregate_masked(const mixgcn_graph* g, int transpose, int dtype, const void* H,

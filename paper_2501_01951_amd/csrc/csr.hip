@@ -138,23 +138,32 @@ __global__ __launch_bounds__(kBlock) void group_rows_kernel(const int64_t* __res
     grp_row[g] = (uint32_t)(lo - 1);
 }
 
+// Row sums of the binary matrix and the scaling vector of the mode: D^-1/2 (symmetric), D^-1
+// (mean), unused (sum).
 __global__ __launch_bounds__(kBlock) void degree_kernel(const int64_t* __restrict__ rowptr,
-                                                        uint32_t n, uint32_t* __restrict__ deg,
+                                                        uint32_t n, int mode,
+                                                        uint32_t* __restrict__ deg,
                                                         float* __restrict__ dinv)
 {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= n) return;
     const uint32_t d = (uint32_t)(rowptr[r + 1] - rowptr[r]);
     deg[r] = d;
-    dinv[r] = d ? (float)(1.0 / sqrt((double)d)) : 0.0f;
+    if (mode == MIXGCN_NORM_MEAN) dinv[r] = d ? (float)(1.0 / (double)d) : 0.0f;
+    else dinv[r] = d ? (float)(1.0 / sqrt((double)d)) : 0.0f;
 }
 
-// val[e] = dinv[row(e)] * dinv[col[e]]: one thread per stored entry, its row found by binary
-// search in rowptr.  A single fp32 multiply, so val(u,v) == val(v,u) bit for bit.
+// One thread per stored entry (r, c) of the CSR at hand, its row found by binary search in
+// rowptr.  `swapped`: the CSR holds the transpose of the aggregation matrix, so its entry
+// (r, c) carries the value of entry (c, r).
+//   symmetric: dinv[r] * dinv[c] - a single fp32 multiply, so val(u,v) == val(v,u) bit for bit;
+//   mean:      dinv[row of the aggregation matrix] = 1 / deg;
+//   sum:       1, and 1 + eps on the diagonal.
 __global__ __launch_bounds__(kBlock) void values_kernel(const int64_t* __restrict__ rowptr,
                                                         const uint32_t* __restrict__ col,
                                                         const float* __restrict__ dinv,
-                                                        uint32_t n, int64_t nnz,
+                                                        uint32_t n, int64_t nnz, int mode,
+                                                        float eps, int swapped,
                                                         float* __restrict__ val,
                                                         uint2* __restrict__ cv)
 {
@@ -167,9 +176,21 @@ __global__ __launch_bounds__(kBlock) void values_kernel(const int64_t* __restric
         else hi = mid;
     }
     const int64_t row = lo - 1;
-    const float v = dinv[row] * dinv[col[e]];
+    const uint32_t c = col[e];
+    float v;
+    if (mode == MIXGCN_NORM_MEAN) v = swapped ? dinv[c] : dinv[row];
+    else if (mode == MIXGCN_NORM_SUM) v = ((int64_t)c == row) ? 1.0f + eps : 1.0f;
+    else v = dinv[row] * dinv[c];
     val[e] = v;
     cv[e].y = __float_as_uint(v);
+}
+
+// cv_t = cv with the value words left for values_kernel to fill (same columns and row marks)
+__global__ __launch_bounds__(kBlock) void copy_entries_kernel(const uint2* __restrict__ in,
+                                                              uint2* __restrict__ out, int64_t count)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) out[i] = in[i];
 }
 
 template <typename T>
@@ -203,6 +224,8 @@ void csr_free(Csr* c)
     if (c->col) (void)hipFree(c->col);
     if (c->cv) (void)hipFree(c->cv);
     if (c->val) (void)hipFree(c->val);
+    if (c->cv_t) (void)hipFree(c->cv_t);
+    if (c->val_t) (void)hipFree(c->val_t);
     if (c->grp_row) (void)hipFree(c->grp_row);
     *c = Csr();
 }
@@ -303,25 +326,38 @@ int csr_from_edges(const uint32_t* d_src, const uint32_t* d_dst, uint64_t n_edge
     return MIXGCN_OK;
 }
 
-int normalize_sym(mixgcn_graph* g, hipStream_t s)
+int normalize_graph(mixgcn_graph* g, int mode, float eps, hipStream_t s)
 {
     const uint32_t n = g->n;
     if (!g->deg) MIXGCN_TRY(dmalloc(&g->deg, n));
     if (!g->dinv) MIXGCN_TRY(dmalloc(&g->dinv, n));
     if (n > 0)
         hipLaunchKernelGGL(degree_kernel, dim3((unsigned)ceil_div(n, kBlock)), dim3(kBlock), 0, s,
-                           g->fwd.rowptr, n, g->deg, g->dinv);
+                           g->fwd.rowptr, n, mode, g->deg, g->dinv);
     Csr* mats[2] = {&g->fwd, g->has_transpose ? &g->tr : nullptr};
     for (Csr* c : mats) {
         if (!c) continue;
         if (!c->val) MIXGCN_TRY(dmalloc(&c->val, (size_t)c->nnz));
         if (c->nnz > 0)
             hipLaunchKernelGGL(values_kernel, dim3((unsigned)ceil_div(c->nnz, kBlock)),
-                               dim3(kBlock), 0, s, c->rowptr, c->col, g->dinv, n, c->nnz, c->val,
-                               c->cv);
+                               dim3(kBlock), 0, s, c->rowptr, c->col, g->dinv, n, c->nnz, mode, eps,
+                               c == &g->tr ? 1 : 0, c->val, c->cv);
+    }
+    // A symmetrised graph stores one pattern for the matrix and its transpose.  The mean
+    // weights are not symmetric, so the transpose gets value arrays of its own on that pattern.
+    Csr& f = g->fwd;
+    if (mode == MIXGCN_NORM_MEAN && (g->flags & MIXGCN_SYMMETRIZE)) {
+        if (!f.val_t) MIXGCN_TRY(dmalloc(&f.val_t, (size_t)f.nnz));
+        if (!f.cv_t) MIXGCN_TRY(dmalloc(&f.cv_t, (size_t)f.nnz_padded));
+        hipLaunchKernelGGL(copy_entries_kernel, dim3((unsigned)ceil_div(f.nnz_padded, kBlock)),
+                           dim3(kBlock), 0, s, f.cv, f.cv_t, f.nnz_padded);
+        if (f.nnz > 0)
+            hipLaunchKernelGGL(values_kernel, dim3((unsigned)ceil_div(f.nnz, kBlock)), dim3(kBlock), 0,
+                               s, f.rowptr, f.col, g->dinv, n, f.nnz, mode, eps, 1, f.val_t, f.cv_t);
     }
     MIXGCN_HIP_TRY(hipGetLastError());
     g->normalized = true;
+    g->norm_mode = mode;
     return MIXGCN_OK;
 }
 

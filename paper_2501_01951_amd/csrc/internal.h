@@ -50,6 +50,10 @@ struct Csr {
     float* val = nullptr;            // [nnz]  (public form)
     // The aggregation kernel's form: entry e = { col | end-of-row mark, val bits }, zero padded.
     uint2* cv = nullptr;             // [nnz_padded]
+    // Values of the TRANSPOSED matrix on this same pattern (symmetrised graph whose weights are
+    // not symmetric, i.e. the mean mode); null otherwise.
+    uint2* cv_t = nullptr;           // [nnz_padded]
+    float* val_t = nullptr;          // [nnz]
     uint32_t* grp_row = nullptr;     // [n_groups + 1] row that holds entry g * kGroupNnz
     std::vector<int64_t> h_rowptr;   // host copy of rowptr
     bool has_empty_rows = false;
@@ -62,6 +66,7 @@ struct mixgcn_graph {
     uint32_t flags = 0;
     int device = 0;
     bool normalized = false;
+    int norm_mode = 0;           // MIXGCN_NORM_* of the last normalisation
     bool has_transpose = false;  // a separate transpose CSR is stored in `tr`
     mixgcn::Csr fwd;
     mixgcn::Csr tr;
@@ -137,12 +142,15 @@ int get_scratch(int which, size_t bytes, void** out);
 int csr_from_edges(const uint32_t* d_src, const uint32_t* d_dst, uint64_t n_edges, uint32_t n,
                    bool symmetrize, bool self_loops, bool transposed, Csr* out, hipStream_t s);
 void csr_free(Csr* c);
-int normalize_sym(mixgcn_graph* g, hipStream_t s);
+int normalize_graph(mixgcn_graph* g, int mode, float eps, hipStream_t s);
 
 // mask: optional bitmap applied to the written outputs (bit c % 32 of mask[r * ldm + c / 32])
-int launch_aggregate(const mixgcn_graph* g, const Csr& m, int dtype, const void* H, int64_t ldh,
-                     void* Z, int64_t ldz, int32_t c0, int32_t c1, int64_t r0, int64_t r1,
-                     int relu, const uint32_t* mask, int64_t ldm, hipStream_t s, Timer* timer);
+// cv: the entry array to walk (m.cv, or m.cv_t for the transpose of a symmetrised graph with
+// unsymmetric weights); epilogue: MIXGCN_EPI_* flags
+int launch_aggregate(const mixgcn_graph* g, const Csr& m, const uint2* cv, int dtype, const void* H,
+                     int64_t ldh, void* Z, int64_t ldz, int32_t c0, int32_t c1, int64_t r0,
+                     int64_t r1, int epilogue, const uint32_t* mask, int64_t ldm, hipStream_t s,
+                     Timer* timer);
 
 // bits[r * ldb + c / 32] bit c % 32 = X[r, c] > 0; every word of a row up to ldb is written
 int launch_relu_bitmap(int dtype, const void* X, int64_t ldx, int64_t n, int32_t cols,

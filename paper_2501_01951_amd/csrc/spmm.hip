@@ -120,6 +120,20 @@ __device__ inline void apply_mask(float* t, const uint32_t* __restrict__ mask, i
     for (int i = 0; i < VEC; ++i) t[i] = ((bits >> i) & 1u) ? t[i] : 0.f;
 }
 
+// Epilogue flags carried in the kernels' `relu` argument (MIXGCN_EPI_* of the ABI).
+constexpr int kEpiRelu = 1;        // Z = max(., 0)
+constexpr int kEpiAccumulate = 2;  // Z = Z + (.): the finished row sum is added to what Z holds
+
+template <int DT>
+__device__ inline void add_stored(float* t, const void* Z, int64_t elem_off)
+{
+    using F = Feat<DT>;
+    float o[F::VEC];
+    F::widen(*F::ptr(Z, elem_off), o);
+#pragma unroll
+    for (int i = 0; i < F::VEC; ++i) t[i] += o[i];
+}
+
 // Partial-sum slots: [span in call][head = 0 / tail = 1][part_stride] fp32, indexed by the
 // column offset within the pass.
 // GF = lanes that would span the whole pass (its width class: 4 GF fp32 or 8 GF bf16 columns);
@@ -269,7 +283,8 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
 #pragma unroll
                             for (int i = 0; i < VEC; ++i) part[i] = t[i];
                         } else {
-                            if (relu) {
+                            if (relu & kEpiAccumulate) add_stored<DT>(t, Z, r * ldz + coff);
+                            if (relu & kEpiRelu) {
 #pragma unroll
                                 for (int i = 0; i < VEC; ++i) t[i] = fmaxf(t[i], 0.f);
                             }
@@ -359,7 +374,8 @@ __global__ __launch_bounds__(kBlock) void aggregate_fixup_kernel(
     p = partials + (size_t)kk * 2 * PS + (size_t)lg * VEC;  // head of the span where it ends
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] += p[i];
-    if (relu) {
+    if (relu & kEpiAccumulate) add_stored<DT>(acc, Z, r * ldz + (int64_t)c0 + (int64_t)lg * VEC);
+    if (relu & kEpiRelu) {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[i] = fmaxf(acc[i], 0.f);
     }
@@ -393,8 +409,8 @@ inline int64_t span_entries(int lpr, int64_t entries, int n_slices)
 }
 
 template <int LPR, int GF, int DT>
-int launch_main(const Csr& m, int64_t n_nodes, const void* H, int64_t ldh, void* Z, int64_t ldz,
-                int c0, int width,
+int launch_main(const Csr& m, const uint2* cv, int64_t n_nodes, const void* H, int64_t ldh,
+                void* Z, int64_t ldz, int c0, int width,
                 int64_t r0, int64_t r1, int64_t e0, int64_t e1, int64_t SPAN, float* partials,
                 int relu, const uint32_t* mask, int64_t ldm, hipStream_t s, Timer* timer)
 {
@@ -416,7 +432,7 @@ int launch_main(const Csr& m, int64_t n_nodes, const void* H, int64_t ldh, void*
     if (timer) MIXGCN_TRY(timer->begin(kind, s));
 #define MIXGCN_AGG_LAUNCH(EMPTY, O32)                                                            \
     hipLaunchKernelGGL((aggregate_kernel<LPR, GF, DT, EMPTY, O32>), dim3(grid), dim3(kBlock), 0, \
-                       s, m.rowptr, m.cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,  \
+                       s, m.rowptr, cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,  \
                        span_first, n_spans, partials, n_slices, relu, mask, ldm,                 \
                        (int)(SPAN / (kWave / LPR)))
     if (m.has_empty_rows) {
@@ -455,13 +471,13 @@ int launch_fixup(const Csr& m, void* Z, int64_t ldz, int c0, int width, int64_t 
 constexpr int slice_lanes(int gf) { return gf < 8 ? gf : 8; }
 
 template <int DT>
-int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, void* Z,
-              int64_t ldz, int32_t c0, int32_t c1, int64_t r0, int64_t r1, int relu,
+int launch_dt(const mixgcn_graph* g, const Csr& m, const uint2* cv, const void* H, int64_t ldh,
+              void* Z, int64_t ldz, int32_t c0, int32_t c1, int64_t r0, int64_t r1, int relu,
               const uint32_t* mask, int64_t ldm, hipStream_t s, Timer* timer)
 {
     constexpr int VEC = Feat<DT>::VEC;
     constexpr int kMaxTile = 64 * VEC;  // widest pass
-    if (m.has_empty_rows) {
+    if (m.has_empty_rows && !(relu & kEpiAccumulate)) {  // an empty row adds nothing
         const int64_t cells = (r1 - r0) * (int64_t)(c1 - c0);
         hipLaunchKernelGGL((zero_rows_kernel<DT>), dim3((unsigned)ceil_div(cells, kBlock)),
                            dim3(kBlock), 0, s, Z, ldz, c0, c1 - c0, r0, r1);
@@ -502,7 +518,7 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const void* H, int64_t ldh, v
         const int64_t span = p.span;
         float* P = g->partials;
 #define MIXGCN_AGG_PASS(GG)                                                                      \
-    MIXGCN_TRY((launch_main<slice_lanes(GG), GG, DT>(m, (int64_t)g->n, H, ldh, Z, ldz, cb, w, r0,  \
+    MIXGCN_TRY((launch_main<slice_lanes(GG), GG, DT>(m, cv, (int64_t)g->n, H, ldh, Z, ldz, cb, w, r0, \
                                                      r1, e0, e1, span, P, relu, mask, ldm, s,     \
                                                      timer)));                                    \
     MIXGCN_TRY((launch_fixup<GG, DT>(m, Z, ldz, cb, w, e0, e1, span, P, relu, mask, ldm, s)))
@@ -573,14 +589,16 @@ int launch_relu_bitmap(int dtype, const void* X, int64_t ldx, int64_t n, int32_t
     return MIXGCN_OK;
 }
 
-int launch_aggregate(const mixgcn_graph* g, const Csr& m, int dtype, const void* H, int64_t ldh,
-                     void* Z, int64_t ldz, int32_t c0, int32_t c1, int64_t r0, int64_t r1,
-                     int relu, const uint32_t* mask, int64_t ldm, hipStream_t s, Timer* timer)
+int launch_aggregate(const mixgcn_graph* g, const Csr& m, const uint2* cv, int dtype, const void* H,
+                     int64_t ldh, void* Z, int64_t ldz, int32_t c0, int32_t c1, int64_t r0,
+                     int64_t r1, int epilogue, const uint32_t* mask, int64_t ldm, hipStream_t s,
+                     Timer* timer)
 {
     if (dtype == MIXGCN_F32)
-        return launch_dt<MIXGCN_F32>(g, m, H, ldh, Z, ldz, c0, c1, r0, r1, relu, mask, ldm, s,
-                                     timer);
-    return launch_dt<MIXGCN_BF16>(g, m, H, ldh, Z, ldz, c0, c1, r0, r1, relu, mask, ldm, s, timer);
+        return launch_dt<MIXGCN_F32>(g, m, cv, H, ldh, Z, ldz, c0, c1, r0, r1, epilogue, mask, ldm,
+                                     s, timer);
+    return launch_dt<MIXGCN_BF16>(g, m, cv, H, ldh, Z, ldz, c0, c1, r0, r1, epilogue, mask, ldm, s,
+                                  timer);
 }
 
 }  // namespace mixgcn

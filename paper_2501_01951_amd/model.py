@@ -113,3 +113,118 @@ class GCNStep:
 
     def replay(self):
         self._graph.replay()
+
+
+class SAGEStep:
+    """Forward + loss + backward of an L-layer GraphSAGE with the mean aggregator (the graph is
+    normalised with NORM_MEAN, no self-loops).  Layer l keeps X_l = [H_l | mean of the neighbors'
+    H_l] in ONE n x 2 d_l buffer: the aggregation reads its left half and writes its right half,
+    the update of layer l - 1 writes H_l straight into the left half, and W_l (2 d_l x d_{l+1})
+    multiplies the whole buffer.  Backward: dX_l = dP_l W_l^T into a buffer of the same shape,
+    then the transposed aggregation ADDS A_hat^T of its right half onto its left half, which is
+    the gradient with respect to H_l.  Widths must be multiples of 4 (fp32) / 8 (bf16)."""
+
+    def __init__(self, g: B.Graph, x, weights, labels):
+        self.g, self.n, self.labels = g, x.shape[0], labels
+        self.w = list(weights)
+        dev, dt = x.device, x.dtype
+        L = len(self.w)
+        self.dims = [x.shape[1]] + [w.shape[1] for w in self.w]
+        vec = 16 // torch.empty(0, dtype=dt).element_size()
+        for l, w in enumerate(self.w):
+            assert self.dims[l] % vec == 0 and w.shape[0] == 2 * self.dims[l]
+        self.xc = [padded_rows(self.n, 2 * self.dims[l], dt, dev) for l in range(L)]
+        self.xc[0][:, :self.dims[0]].copy_(x)
+        self.logits = padded_rows(self.n, self.dims[L], dt, dev)
+        self.dlogits = padded_rows(self.n, self.dims[L], dt, dev)
+        self.dxc = [None] + [padded_rows(self.n, 2 * self.dims[l], dt, dev) for l in range(1, L)]
+        self.dw = [torch.empty_strided(w.shape, w.stride(), dtype=w.dtype, device=dev) for w in self.w]
+        self.loss = torch.zeros(1, dtype=torch.float64, device=dev)
+
+    def h(self, l):
+        """H_l: the left half of X_l, or the logits."""
+        return self.logits if l == len(self.w) else self.xc[l][:, :self.dims[l]]
+
+    def forward(self):
+        L = len(self.w)
+        for l in range(L):
+            d = self.dims[l]
+            B.aggregate(self.g, self.xc[l][:, :d], self.xc[l][:, d:2 * d])
+            B.update(B.OP_FWD_RELU if l < L - 1 else B.OP_FWD, self.xc[l], self.w[l], self.h(l + 1),
+                     self.n, 2 * d, self.dims[l + 1])
+        B.softmax_xent(self.logits, self.labels, self.dlogits, self.loss)
+
+    def backward(self):
+        L = len(self.w)
+        grad = self.dlogits
+        for l in range(L - 1, -1, -1):
+            d = self.dims[l]
+            ref = self.h(l + 1) if l < L - 1 else None
+            B.update(B.OP_WGRAD, self.xc[l], grad, self.dw[l], self.n, 2 * d, self.dims[l + 1],
+                     relu_ref=ref)
+            if l == 0:
+                break
+            B.update(B.OP_DGRAD, grad, self.w[l], self.dxc[l], self.n, 2 * d, self.dims[l + 1],
+                     relu_ref=ref)
+            B.aggregate(self.g, self.dxc[l][:, d:2 * d], self.dxc[l][:, :d], transpose=True,
+                        accumulate=True)
+            grad = self.dxc[l][:, :d]
+
+    def step(self):
+        self.forward()
+        self.backward()
+
+
+class GINStep:
+    """Forward + loss + backward of an L-layer GIN (the graph is normalised with NORM_SUM and
+    has self-loops, whose value carries 1 + eps).  Layer l: Z_l = A_hat H_l, T_l = relu(Z_l W1_l),
+    H_{l+1} = relu(T_l W2_l) (no ReLU after the last layer)."""
+
+    def __init__(self, g: B.Graph, x, w1s, w2s, labels):
+        self.g, self.n, self.labels = g, x.shape[0], labels
+        self.w1, self.w2 = list(w1s), list(w2s)
+        dev, dt = x.device, x.dtype
+        L = len(self.w1)
+        rows = lambda f: padded_rows(self.n, f, dt, dev)
+        x_p = rows(x.shape[1])
+        x_p.copy_(x)
+        self.h = [x_p] + [rows(w.shape[1]) for w in self.w2]
+        self.z = [rows(w.shape[0]) for w in self.w1]
+        self.t = [rows(w.shape[1]) for w in self.w1]
+        self.dt = [rows(w.shape[1]) for w in self.w1]
+        self.dh = [None] + [rows(self.w1[l].shape[0]) for l in range(1, L)]
+        self.dlogits = rows(self.w2[L - 1].shape[1])
+        like = lambda w: torch.empty_strided(w.shape, w.stride(), dtype=w.dtype, device=dev)
+        self.dw1 = [like(w) for w in self.w1]
+        self.dw2 = [like(w) for w in self.w2]
+        self.loss = torch.zeros(1, dtype=torch.float64, device=dev)
+
+    def forward(self):
+        L = len(self.w1)
+        for l in range(L):
+            k, hd, m = self.w1[l].shape[0], self.w1[l].shape[1], self.w2[l].shape[1]
+            B.aggregate(self.g, self.h[l], self.z[l])
+            B.update(B.OP_FWD_RELU, self.z[l], self.w1[l], self.t[l], self.n, k, hd)
+            B.update(B.OP_FWD_RELU if l < L - 1 else B.OP_FWD, self.t[l], self.w2[l], self.h[l + 1],
+                     self.n, hd, m)
+        B.softmax_xent(self.h[L], self.labels, self.dlogits, self.loss)
+
+    def backward(self):
+        L = len(self.w1)
+        grad = self.dlogits
+        for l in range(L - 1, -1, -1):
+            k, hd, m = self.w1[l].shape[0], self.w1[l].shape[1], self.w2[l].shape[1]
+            ref = self.h[l + 1] if l < L - 1 else None
+            B.update(B.OP_WGRAD, self.t[l], grad, self.dw2[l], self.n, hd, m, relu_ref=ref)
+            B.update(B.OP_DGRAD, grad, self.w2[l], self.dt[l], self.n, hd, m, relu_ref=ref)
+            B.update(B.OP_WGRAD, self.z[l], self.dt[l], self.dw1[l], self.n, k, hd, relu_ref=self.t[l])
+            if l == 0:
+                break
+            # dZ_l over Z_l (the weight gradient above was its last reader), then A_hat^T
+            B.update(B.OP_DGRAD, self.dt[l], self.w1[l], self.z[l], self.n, k, hd, relu_ref=self.t[l])
+            B.aggregate(self.g, self.z[l], self.dh[l], transpose=True)
+            grad = self.dh[l]
+
+    def step(self):
+        self.forward()
+        self.backward()

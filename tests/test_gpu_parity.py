@@ -689,6 +689,217 @@ def test_captured_step_replays_match_eager(mg):
 
 
 # ------------------------------------------------------------------------------------------
+# GraphSAGE (mean) and GIN: the other aggregation weights, the aggregation epilogues they need
+# and the two models end to end (paper Sec. 4, experimental setting)
+# ------------------------------------------------------------------------------------------
+def _variant_graph(mg, src, dst, n, sym, loops, mode, eps=0.0):
+    flags = (mg.SYMMETRIZE if sym else 0) | (mg.ADD_SELF_LOOPS if loops else 0) | mg.BUILD_TRANSPOSE
+    s, d = edges_dev(src, dst)
+    g = mg.build_csr(s, d, n, flags)
+    mg.normalize(g, mode, eps=eps)
+    og = oracle.build_csr(src, dst, n, sym, loops)
+    og = oracle.normalize_mean(og) if mode == mg.NORM_MEAN else oracle.normalize_sum(og, eps)
+    return g, oracle.transpose(og)
+
+
+@pytest.mark.parametrize("sym,loops,mode,eps", [(True, False, 1, 0.0), (True, True, 1, 0.0),
+                                                (False, False, 1, 0.0), (True, True, 2, 0.25),
+                                                (True, True, 2, -1.0), (False, True, 2, 0.5),
+                                                (True, False, 2, 0.25)])
+def test_normalize_mean_and_sum_bit_exact(mg, sym, loops, mode, eps):
+    src, dst, n = gg.config_graph("c2", scale_override=13)
+    say(f"normalize mode={mode} sym={sym} loops={loops} eps={eps}")
+    g, og = _variant_graph(mg, src, dst, n, sym, loops, mode, eps)
+    a = g.arrays()
+    assert np.array_equal(a["deg"].cpu().numpy().view(np.uint32), og.deg)
+    assert np.array_equal(a["val"].cpu().numpy(), og.val_f32)
+    if mode == mg.NORM_MEAN:
+        assert np.array_equal(a["dinv"].cpu().numpy(), og.dinv.astype(np.float32))
+    t = g.arrays(transpose=True)
+    assert np.array_equal(t["rowptr"].cpu().numpy(), og.t_rowptr)
+    assert np.array_equal(t["col"].cpu().numpy().view(np.uint32), og.t_col)
+    # every fp64 value of these two modes is 1, 1 + eps or 1 / deg: its fp32 rounding is the encoding
+    assert np.array_equal(t["val"].cpu().numpy(), og.t_val.astype(np.float32))
+    # the aggregation uses them: forward and adjoint
+    h = gg.normal(91, 1, n, 36, ld=40)
+    hd = dev(h)[:, :36]
+    for tr in (False, True):
+        z = torch.full((n, 40), 2.0, device="cuda")[:, :36]
+        mg.aggregate(g, hd, z, transpose=tr)
+        ref = oracle.spmm(og, h[:, :36].astype(np.float64), transposed=tr)
+        assert_close(z.cpu().numpy(), ref, RTOL_F32, f"mode {mode} transpose={tr}")
+    # back to the symmetric weights on the same graph object
+    mg.normalize(g)
+    og2 = oracle.normalize(oracle.build_csr(src, dst, n, sym, loops))
+    assert np.array_equal(g.arrays()["val"].cpu().numpy(), og2.val_f32)
+    g.free()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_aggregate_epilogues_relu_and_accumulate(mg, rmat15, dtype):
+    og, g = rmat15
+    f, ld = 72, 80
+    h = gg.normal(92, 1, og.n, f, ld=ld)
+    z0 = gg.normal(92, 2, og.n, f, ld=ld)
+    if dtype == "bf16":
+        h, z0 = bf16_round(h), bf16_round(z0)
+        up = lambda a: dev_bf16(a)
+        rtol = RTOL_BF16
+    else:
+        up = dev
+        rtol = RTOL_F32
+    agg = oracle.spmm(og, h[:, :f].astype(np.float64))
+    want = {(False, False): agg, (True, False): np.maximum(agg, 0),
+            (False, True): z0[:, :f] + agg, (True, True): np.maximum(z0[:, :f] + agg, 0)}
+    hd = up(h)
+    for (relu, acc), ref in want.items():
+        say(f"aggregate epilogue relu={relu} accumulate={acc} {dtype}")
+        z = up(z0)
+        mg.aggregate(g, hd[:, :f], z[:, :f], relu=relu, accumulate=acc)
+        assert_close(z[:, :f].float().cpu().numpy(), ref, rtol, f"relu={relu} acc={acc}")
+    # row range x column slice: everything else keeps its value
+    z = up(z0)
+    mg.aggregate(g, hd[:, :f], z[:, :f], col_begin=8, col_end=40, row_begin=1000, row_end=21000,
+                 accumulate=True)
+    zz = z.float().cpu().numpy()
+    assert_close(zz[1000:21000, 8:40], want[(False, True)][1000:21000, 8:40], rtol, "slice x chunk")
+    zz[1000:21000, 8:40] = z0[1000:21000, 8:40]
+    assert np.array_equal(zz, z0.astype(np.float32))
+    from paper_2501_01951_amd import binding as B
+    rc = mg.load_library().mixgcn_aggregate_ex(g._h, 0, 0, B._ptr(hd), ld, B._ptr(z), ld, 0, 8, 0,
+                                               og.n, 4, None)
+    assert rc == -1 and b"epilogue" in mg.load_library().mixgcn_last_error()
+
+
+def test_aggregate_accumulate_with_empty_rows_and_transpose(mg):
+    src, dst = gg.rmat_edges(21, 13, 40_000)
+    n = 1 << 13
+    say("aggregate accumulate, directed graph with empty rows")
+    g, og = _variant_graph(mg, src, dst, n, False, False, mg.NORM_MEAN)
+    assert (np.diff(og.rowptr) == 0).any() and (np.diff(og.t_rowptr) == 0).any()
+    h = gg.normal(93, 1, n, 64)
+    z0 = gg.normal(93, 2, n, 64)
+    for tr in (False, True):
+        z = dev(z0)
+        mg.aggregate(g, dev(h), z, transpose=tr, accumulate=True)
+        ref = z0 + oracle.spmm(og, h.astype(np.float64), transposed=tr)
+        assert_close(z.cpu().numpy(), ref, RTOL_F32, f"accumulate transpose={tr}")
+    g.free()
+
+
+def test_aggregate_between_two_column_blocks_of_one_buffer(mg, rmat15):
+    """X = [H | A_hat H] in one buffer (the concatenation of the GraphSAGE layer), both ways
+    round, and the layouts that would overlap are refused."""
+    og, g = rmat15
+    f = 48
+    h = gg.normal(94, 1, og.n, f)
+    ref = oracle.spmm(og, h.astype(np.float64))
+    for ld in (96, 104, 160):
+        say(f"aggregate inside one buffer ld={ld}")
+        x = torch.full((og.n, ld), 9.0, device="cuda")
+        x[:, :f] = dev(h)
+        mg.aggregate(g, x[:, :f], x[:, f:2 * f])
+        xx = x.cpu().numpy()
+        assert np.array_equal(xx[:, :f], h) and np.all(xx[:, 2 * f:] == 9.0)
+        assert_close(xx[:, f:2 * f], ref, RTOL_F32, "right half")
+        x = torch.full((og.n, ld), 9.0, device="cuda")
+        x[:, f:2 * f] = dev(h)
+        mg.aggregate(g, x[:, f:2 * f], x[:, :f])
+        assert_close(x.cpu().numpy()[:, :f], ref, RTOL_F32, "left half")
+    x = torch.zeros(og.n, 96, device="cuda")
+    for hv, zv in [(x[:, :48], x[:, 44:92]), (x[:, :48], x[:, :48]), (x[:, 4:52], x[:, :48])]:
+        with pytest.raises(mg.MixGCNError):
+            mg.aggregate(g, hv, zv)
+
+
+def _grad_close(name, got, ref, flips):
+    if flips == 0:
+        assert_close(got, ref, RTOL_F32, name)
+    else:
+        assert rel_fro(got, ref) < 2e-3, f"{name} with {flips} ReLU flips"
+
+
+def _flips(gpu_acts, ref_acts, name):
+    """ReLU decisions each side takes from its own stored activations: where they differ the
+    oracle's value must be within rounding of zero."""
+    total = 0
+    for a, r in zip(gpu_acts, ref_acts):
+        diff = (a > 0) != (r > 0)
+        if diff.any():
+            scale = np.sqrt(np.mean(r ** 2))
+            assert np.max(np.abs(r[diff])) <= 1e-4 * scale, f"{name}: ReLU flips away from zero"
+            assert diff.mean() < 1e-5
+        total += int(diff.sum())
+    return total
+
+
+def _sage_case(name):
+    if name == "c1":
+        src, dst, n = gg.config_graph("c1")
+        dims = (64, 32, 8)
+    else:
+        src, dst, n = gg.config_graph("c2", scale_override=16)
+        dims = (128, 128, 128, 16)
+    x = gg.normal(gg.MASTER_SEED, 1, n, dims[0])
+    y = gg.labels(gg.MASTER_SEED, 5, n, dims[-1])
+    return src, dst, n, dims, x, y
+
+
+@pytest.mark.parametrize("name", ["c1", "c2@16"])
+def test_graphsage_mean_model_end_to_end(mg, name):
+    src, dst, n, dims, x, y = _sage_case(name)
+    say(f"GraphSAGE (mean) {name} dims={dims}")
+    ws = [gg.glorot(gg.MASTER_SEED, 20 + l, 2 * dims[l], dims[l + 1]) for l in range(len(dims) - 1)]
+    g, og = _variant_graph(mg, src, dst, n, True, False, mg.NORM_MEAN)
+    ref = oracle.sage_step(og, x, ws, y)
+    st = mg.SAGEStep(g, dev(x), [dev(w) for w in ws], dev(y))
+    st.step()
+    torch.cuda.synchronize()
+    L = len(ws)
+    assert abs(st.loss.item() - ref["loss"]) <= 1e-5 * abs(ref["loss"])
+    assert_close(st.logits.cpu().numpy(), ref["logits"], RTOL_F32, "logits")
+    acts = [st.h(l).cpu().numpy() for l in range(1, L)]
+    for l in range(L):
+        assert_close(st.xc[l].cpu().numpy(), ref["X"][l], RTOL_F32, f"X[{l}]")
+    _grad_close(f"dW[{L - 1}]", st.dw[L - 1].cpu().numpy(), ref["dW"][L - 1], 0)
+    for l in range(L - 1):
+        fl = _flips(acts[l:], ref["H"][l + 1:L], name)
+        _grad_close(f"dW[{l}]", st.dw[l].cpu().numpy(), ref["dW"][l], fl)
+    g.free()
+
+
+@pytest.mark.parametrize("name", ["c1", "c2@16"])
+def test_gin_model_end_to_end(mg, name):
+    src, dst, n, dims, x, y = _sage_case(name)
+    eps = 0.1
+    say(f"GIN {name} dims={dims} eps={eps}")
+    L = len(dims) - 1
+    hidden = [dims[l + 1] if l < L - 1 else dims[l] for l in range(L)]
+    # Glorot weights scaled down: the sum aggregation multiplies magnitudes by the degree
+    w1s = [0.02 * gg.glorot(gg.MASTER_SEED, 30 + l, dims[l], hidden[l]) for l in range(L)]
+    w2s = [gg.glorot(gg.MASTER_SEED, 40 + l, hidden[l], dims[l + 1]) for l in range(L)]
+    g, og = _variant_graph(mg, src, dst, n, True, True, mg.NORM_SUM, eps)
+    ref = oracle.gin_step(og, x, w1s, w2s, y)
+    st = mg.GINStep(g, dev(x), [dev(w) for w in w1s], [dev(w) for w in w2s], dev(y))
+    st.step()
+    torch.cuda.synchronize()
+    assert abs(st.loss.item() - ref["loss"]) <= 1e-5 * abs(ref["loss"])
+    assert_close(st.h[L].cpu().numpy(), ref["logits"], RTOL_F32, "logits")
+    for l in range(L):
+        assert_close(st.t[l].cpu().numpy(), ref["T"][l], RTOL_F32, f"T[{l}]")
+    # ReLU decisions above a gradient, in the order the backward pass meets them
+    t_gpu = [t.cpu().numpy() for t in st.t]
+    h_gpu = [h.cpu().numpy() for h in st.h]
+    for l in range(L - 1, -1, -1):
+        above_w2 = sum(_flips([t_gpu[j]], [ref["T"][j]], name) for j in range(l + 1, L)) + \
+            sum(_flips([h_gpu[j]], [ref["H"][j]], name) for j in range(l + 1, L))
+        above_w1 = above_w2 + _flips([t_gpu[l]], [ref["T"][l]], name)
+        _grad_close(f"dW2[{l}]", st.dw2[l].cpu().numpy(), ref["dW2"][l], above_w2)
+        _grad_close(f"dW1[{l}]", st.dw1[l].cpu().numpy(), ref["dW1"][l], above_w1)
+    g.free()
+
+
+# ------------------------------------------------------------------------------------------
 # bf16 storage (config 5 shape): every n x F tensor is stored in bf16, arithmetic is fp32
 # ------------------------------------------------------------------------------------------
 def bf16_round(a):
