@@ -14,6 +14,9 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 16;          // reduction depth staged per step
+// Workgroups per CU that the register allocation of each kernel is held to (measured best of
+// 2, 3, 4 on the 128 x 128 shapes): the masked row-block kernel keeps more values live.
+constexpr int kRowblockMinBlocks = 3, kRowblockMaskedMinBlocks = 2, kWgradMinBlocks = 4;
 constexpr int kLdsPad = 4;      // row stride of the staged tiles = tile width + 4 floats
 
 // Tile shape: WM x WN waves (4 in total), each owning TM x TN accumulator tiles of 32 x 32.
@@ -135,6 +138,160 @@ struct Piece {
     }
 };
 
+// ---- fast path: tiles that lie wholly inside their matrices, fp32 -------------------------------
+// A vector instruction costs the SIMD four cycles during which its matrix core idles (measured:
+// MFMA and vector work of a SIMD do not overlap on this part), so the inner loop of a tile with
+// nothing to clip is written to need almost none: every global address is a scalar base (stepped
+// with scalar arithmetic) plus a per-thread 32-bit offset that never changes, and every LDS
+// address is a per-thread base plus an immediate.  LDS accesses go through volatile pointers so
+// that the compiler keeps them as single instructions with 16-bit immediates: fused into
+// two-address forms (8-bit offsets) they would need a vector add per pair to rebase.
+typedef __attribute__((address_space(3))) float lds_float;
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) floatx4 lds_floatx4;
+
+// One operand tile of a step: E free indices x BK reduction indices, staged to LDS as [k][e].
+//   TRANSPOSED: memory is [e][k]; an item is 4 consecutive k of one e (4 single-word writes)
+//   DIRECT:     memory is [k][e]; an item is 4 consecutive e of one k (one 16-byte write)
+// Item `tid` of pass p lies a whole number of rows (of memory) after item `tid` of pass 0, so one
+// 32-bit offset per thread serves every pass: the pass only moves the uniform base.
+template <int E, bool TRANSPOSED, bool MASK>
+struct FastTile {
+    static constexpr int LD = E + kLdsPad;
+    static constexpr int ITEMS = TRANSPOSED ? E * (BK / 4) : BK * (E / 4);
+    static constexpr int PASSES = (ITEMS + kBlock - 1) / kBlock;
+    // rows of memory between passes, and floats of LDS between passes
+    static constexpr int PASS_ROWS = TRANSPOSED ? kBlock / (BK / 4) : kBlock / (E / 4);
+    static constexpr int PASS_LDS = TRANSPOSED ? PASS_ROWS : PASS_ROWS * LD;
+    static_assert(PASSES == 1 || ITEMS % kBlock == 0, "whole passes");
+    uint32_t goff, moff;  // byte offset of the thread's item in the operand / the mask reference
+    int lpos;             // float index of the item in the LDS tile
+    bool on;              // the thread has an item (tiles smaller than one pass)
+    float4 v[PASSES], m[PASSES];
+
+    __device__ inline void init(int tid, uint32_t pitch, uint32_t pitch_r)
+    {
+        on = (ITEMS % kBlock == 0) || tid < ITEMS;
+        const int it = on ? tid : 0;
+        if (TRANSPOSED) {
+            const int e = it / (BK / 4), kq = 4 * (it % (BK / 4));
+            goff = (uint32_t)e * pitch + 4u * kq;
+            moff = (uint32_t)e * pitch_r + 4u * kq;
+            lpos = kq * LD + e;
+        } else {
+            const int kk = it / (E / 4), e = 4 * (it % (E / 4));
+            goff = (uint32_t)kk * pitch + 4u * e;
+            moff = (uint32_t)kk * pitch_r + 4u * e;
+            lpos = kk * LD + e;
+        }
+    }
+    // base, base_r: uniform addresses of the step's tile; pitch in bytes
+    __device__ inline void load(const char* base, const char* base_r, size_t pitch, size_t pitch_r)
+    {
+        if (on) {
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p) {
+                v[p] = *reinterpret_cast<const float4*>(base + p * PASS_ROWS * pitch + goff);
+                if (MASK)
+                    m[p] = *reinterpret_cast<const float4*>(base_r + p * PASS_ROWS * pitch_r + moff);
+            }
+        }
+    }
+    __device__ static inline float keep(float x, float r) { return MASK ? (r > 0.f ? x : 0.f) : x; }
+    __device__ inline void store(float* tile) const
+    {
+        if (on) {
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p) {
+                const float x0 = keep(v[p].x, m[p].x), x1 = keep(v[p].y, m[p].y);
+                const float x2 = keep(v[p].z, m[p].z), x3 = keep(v[p].w, m[p].w);
+                if (TRANSPOSED) {
+                    volatile lds_float* o = (volatile lds_float*)(tile + lpos + p * PASS_LDS);
+                    o[0 * LD] = x0;
+                    o[1 * LD] = x1;
+                    o[2 * LD] = x2;
+                    o[3 * LD] = x3;
+                } else {
+                    const floatx4 q = {x0, x1, x2, x3};
+                    *(lds_floatx4*)(tile + lpos + p * PASS_LDS) = q;
+                }
+            }
+        }
+    }
+};
+
+// mma_step with single-word LDS reads at immediate offsets.
+template <class S>
+__device__ inline void mma_step_fast(const float* As, const float* Bs, int wm, int wn, int lane,
+                                     floatx16 (&acc)[S::TM][S::TN])
+{
+    constexpr int LDA = S::BM + kLdsPad, LDB = S::BN + kLdsPad;
+    const int li = lane & 31, lk = lane >> 5;
+    const volatile lds_float* ap = (const volatile lds_float*)(As + lk * LDA + wm * S::TM * 32 + li);
+    const volatile lds_float* bp = (const volatile lds_float*)(Bs + lk * LDB + wn * S::TN * 32 + li);
+    float a[2][S::TM], b[2][S::TN];
+#pragma unroll
+    for (int tm = 0; tm < S::TM; ++tm) a[0][tm] = ap[tm * 32];
+#pragma unroll
+    for (int tn = 0; tn < S::TN; ++tn) b[0][tn] = bp[tn * 32];
+#pragma unroll
+    for (int k2 = 0; k2 < BK; k2 += 2) {
+        const int cur = (k2 >> 1) & 1, nxt = cur ^ 1;
+        if (k2 + 2 < BK) {
+#pragma unroll
+            for (int tm = 0; tm < S::TM; ++tm) a[nxt][tm] = ap[(k2 + 2) * LDA + tm * 32];
+#pragma unroll
+            for (int tn = 0; tn < S::TN; ++tn) b[nxt][tn] = bp[(k2 + 2) * LDB + tn * 32];
+        }
+#pragma unroll
+        for (int tm = 0; tm < S::TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < S::TN; ++tn)
+                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][tm], b[cur][tn],
+                                                                   acc[tm][tn], 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, S::TM + S::TN, 0);  // DS reads of step k2 + 2
+        __builtin_amdgcn_sched_group_barrier(0x008, S::TM * S::TN, 0);  // MFMAs of step k2
+    }
+}
+
+// The reduction loop of the fast path: nk full steps, LDS double buffered with compile-time
+// buffer indices (two steps per trip) so that buffer offsets fold into the immediates.
+template <class S, class TA, class TB, class LoadFn>
+__device__ inline void fast_reduction(float (&As)[2][BK * (S::BM + kLdsPad)],
+                                      float (&Bs)[2][BK * (S::BN + kLdsPad)], TA& ta, TB& tb,
+                                      LoadFn load, int64_t nk, int wm, int wn, int lane,
+                                      floatx16 (&acc)[S::TM][S::TN])
+{
+    load((int64_t)0);
+    ta.store(As[0]);
+    tb.store(Bs[0]);
+    __syncthreads();
+    int64_t s = 0;
+    while (s + 2 < nk) {
+        load(s + 1);
+        mma_step_fast<S>(As[0], Bs[0], wm, wn, lane, acc);
+        ta.store(As[1]);
+        tb.store(Bs[1]);
+        __syncthreads();
+        load(s + 2);
+        mma_step_fast<S>(As[1], Bs[1], wm, wn, lane, acc);
+        ta.store(As[0]);
+        tb.store(Bs[0]);
+        __syncthreads();
+        s += 2;
+    }
+    if (s + 1 < nk) {
+        load(s + 1);
+        mma_step_fast<S>(As[0], Bs[0], wm, wn, lane, acc);
+        ta.store(As[1]);
+        tb.store(Bs[1]);
+        __syncthreads();
+        mma_step_fast<S>(As[1], Bs[1], wm, wn, lane, acc);
+    } else {
+        mma_step_fast<S>(As[0], Bs[0], wm, wn, lane, acc);
+    }
+}
+
 // Workgroups are dealt round-robin to the 8 XCDs.  This maps the hardware block index to a
 // logical one such that consecutive logical indices run on the same XCD, so tiles that share
 // an operand (the column tiles of one row block) find it in that XCD's L2.
@@ -151,7 +308,8 @@ __device__ inline unsigned xcd_local_index(unsigned bid, unsigned grid)
 // A is staged transposed (reduction-major) so that the MFMA operand reads are unit-stride.
 // LDS tiles are double buffered: one barrier per reduction step.
 template <class S, bool B_TRANS, bool RELU, bool MASK, typename T>
-__global__ __launch_bounds__(kBlock) void rowblock_gemm_kernel(
+__global__ __launch_bounds__(kBlock, MASK ? kRowblockMaskedMinBlocks : kRowblockMinBlocks) void
+rowblock_gemm_kernel(
     const T* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb,
     T* __restrict__ C, int64_t ldc, int64_t n, int KD, int MD, const T* __restrict__ R,
     int64_t ldr, int n_col_tiles)
@@ -242,15 +400,35 @@ __global__ __launch_bounds__(kBlock) void rowblock_gemm_kernel(
     };
 
     const int nk = (KD + BK - 1) / BK;
-    issue_tiles(0);
-    store_tiles(As[0], Bs[0], 0);
-    __syncthreads();
-    for (int i = 0; i < nk; ++i) {
-        const int cur = i & 1;
-        if (i + 1 < nk) issue_tiles((i + 1) * BK);
-        mma_step<S>(As[cur], Bs[cur], wm, wn, lane, acc);
-        if (i + 1 < nk) store_tiles(As[cur ^ 1], Bs[cur ^ 1], (i + 1) * BK);
+    // every piece inside its matrix, whole reduction steps, 32-bit offsets within a tile
+    const bool fast = std::is_same<T, float>::value && tile_inside && KD % BK == 0 &&
+                      lda < (1 << 22) && ldb < (1 << 22) && ldr < (1 << 22);
+    if (fast) {
+        FastTile<S::BM, true, MASK> ta;
+        FastTile<S::BN, B_TRANS, false> tb;
+        ta.init(tid, (uint32_t)lda * 4u, (uint32_t)ldr * 4u);
+        tb.init(tid, (uint32_t)ldb * 4u, 0u);
+        const char* a0 = reinterpret_cast<const char*>(A + row0 * lda);
+        const char* r0 = MASK ? reinterpret_cast<const char*>(R + row0 * ldr) : nullptr;
+        const char* b0 = reinterpret_cast<const char*>(B_TRANS ? B + (int64_t)col0 * ldb : B + col0);
+        const size_t b_step = B_TRANS ? (size_t)BK * 4 : (size_t)BK * 4 * (size_t)ldb;
+        auto load = [&](int64_t st) {
+            ta.load(a0 + (size_t)st * (BK * 4), r0 + (size_t)st * (BK * 4), (size_t)lda * 4,
+                    (size_t)ldr * 4);
+            tb.load(b0 + (size_t)st * b_step, nullptr, (size_t)ldb * 4, 0);
+        };
+        fast_reduction<S>(As, Bs, ta, tb, load, (int64_t)nk, wm, wn, lane, acc);
+    } else {
+        issue_tiles(0);
+        store_tiles(As[0], Bs[0], 0);
         __syncthreads();
+        for (int i = 0; i < nk; ++i) {
+            const int cur = i & 1;
+            if (i + 1 < nk) issue_tiles((i + 1) * BK);
+            mma_step<S>(As[cur], Bs[cur], wm, wn, lane, acc);
+            if (i + 1 < nk) store_tiles(As[cur ^ 1], Bs[cur ^ 1], (i + 1) * BK);
+            __syncthreads();
+        }
     }
 
     // D layout of the 32x32 MFMA: lane l, register v -> row 8*(v/4) + 4*(l/32) + v%4, col l%32
@@ -295,7 +473,7 @@ __global__ __launch_bounds__(kBlock) void rowblock_gemm_kernel(
 // Both operands are staged exactly as they lie in memory (node-major), which already is the
 // reduction-major layout the MFMA operand reads want.
 template <class S, bool MASK, typename T>
-__global__ __launch_bounds__(kBlock) void wgrad_slab_kernel(
+__global__ __launch_bounds__(kBlock, kWgradMinBlocks) void wgrad_slab_kernel(
     const T* __restrict__ A, int64_t lda, const T* __restrict__ B, int64_t ldb,
     const T* __restrict__ R, int64_t ldr, float* __restrict__ P, int64_t n, int KD, int MD,
     int64_t rows_per_slab, int n_i_tiles, int n_j_tiles)
@@ -362,7 +540,24 @@ __global__ __launch_bounds__(kBlock) void wgrad_slab_kernel(
         else store_tiles_as(as, bs, std::true_type{});
     };
 
-    if (r_begin < r_end) {
+    const bool fast = std::is_same<T, float>::value && tile_inside && r_begin < r_end &&
+                      (r_end - r_begin) % BK == 0 && lda < (1 << 22) && ldb < (1 << 22) &&
+                      ldr < (1 << 22);
+    if (fast) {
+        FastTile<S::BM, false, false> ta;
+        FastTile<S::BN, false, MASK> tb;
+        ta.init(tid, (uint32_t)lda * 4u, 0u);
+        tb.init(tid, (uint32_t)ldb * 4u, (uint32_t)ldr * 4u);
+        const char* a0 = reinterpret_cast<const char*>(A + r_begin * lda + i0);
+        const char* b0 = reinterpret_cast<const char*>(B + r_begin * ldb + j0);
+        const char* m0 = MASK ? reinterpret_cast<const char*>(R + r_begin * ldr + j0) : nullptr;
+        auto load = [&](int64_t st) {
+            ta.load(a0 + (size_t)st * BK * 4 * (size_t)lda, nullptr, (size_t)lda * 4, 0);
+            tb.load(b0 + (size_t)st * BK * 4 * (size_t)ldb, m0 + (size_t)st * BK * 4 * (size_t)ldr,
+                    (size_t)ldb * 4, (size_t)ldr * 4);
+        };
+        fast_reduction<S>(As, Bs, ta, tb, load, (r_end - r_begin) / BK, wm, wn, lane, acc);
+    } else if (r_begin < r_end) {
         const int64_t nk = (r_end - r_begin + BK - 1) / BK;
         issue_tiles(r_begin);
         store_tiles(As[0], Bs[0], r_begin);

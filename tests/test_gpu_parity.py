@@ -396,7 +396,9 @@ def test_aggregate_regular_graph_row_sums_and_eigenvector(mg):
 
 
 UPDATE_SHAPES = [(1000, 64, 32), (4173, 32, 8), (2048, 128, 256), (3000, 256, 16), (777, 100, 47),
-                 (1500, 128, 172), (130, 256, 256), (1, 16, 4), (5000, 128, 1024)]
+                 (1500, 128, 172), (130, 256, 256), (1, 16, 4), (5000, 128, 1024),
+                 # whole tiles with 1, 3 and 5 reduction steps (the loop takes two per trip)
+                 (256, 16, 128), (384, 48, 160), (640, 80, 64), (1024, 16, 16)]
 
 
 @pytest.mark.parametrize("n,k,m", UPDATE_SHAPES)
