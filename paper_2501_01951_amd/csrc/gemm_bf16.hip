@@ -109,6 +109,93 @@ __device__ inline bf16x8 lds_operand(const uint16_t* p)
     return *reinterpret_cast<const bf16x8*>(p);
 }
 
+// ---- fast path of the row-block kernel ----------------------------------------------------------
+// Vector instructions do not overlap with MFMAs on a SIMD of this part (each costs 4 cycles, an
+// eighth of a 32x32x16 bf16 MFMA), and the generic staging path above spends more cycles on
+// address arithmetic and zero-fill masks than the MFMAs take.  A tile whose rows all exist, with
+// a reduction depth of whole steps, needs none of that: both operands are 16-byte copies from a
+// scalar base plus a fixed per-thread offset to a fixed LDS position (the split weights are
+// padded to whole tiles with zeros).  What is left per step is the ReLU mask, three packed 16-bit
+// integer instructions and an AND per 32-bit word.
+typedef short short2v __attribute__((ext_vector_type(2)));
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) uintx4 lds_uintx4;
+__device__ inline void lds_store16(uint16_t* p, const uint4& v)
+{
+    const uintx4 q = {v.x, v.y, v.z, v.w};
+    *(lds_uintx4*)p = q;
+}
+
+// x with the halves zeroed whose reference half (bf16 bits) is not > 0: as 16-bit integers,
+// max(r, 0) is positive exactly for positive finite values (and +inf), its negation then has
+// the sign bit set, which an arithmetic shift spreads over the half.
+__device__ inline uint32_t keep_positive(uint32_t x, uint32_t r)
+{
+    short2v rr;
+    __builtin_memcpy(&rr, &r, 4);
+    const short2v zero = {0, 0};
+    const short2v keep = (-__builtin_elementwise_max(rr, zero)) >> 15;
+    uint32_t k;
+    __builtin_memcpy(&k, &keep, 4);
+    return x & k;
+}
+
+template <class S, bool MASK>
+struct FastStage {
+    static constexpr int A_PASSES = S::BM / 64;
+    static constexpr int B_PASSES = (S::BN + 63) / 64;
+    uint32_t aoff, roff, boff;  // bytes from the step's scalar bases
+    int lpos;                   // halfword index in a staged tile
+    bool b_on[B_PASSES];
+    uint4 a[A_PASSES], r[A_PASSES], bh[B_PASSES], bl[B_PASSES];
+
+    __device__ inline void init(int tid, uint32_t pitch_a, uint32_t pitch_r, uint32_t pitch_b)
+    {
+        const int prow = tid / 4, pk = 8 * (tid & 3);
+        aoff = (uint32_t)prow * pitch_a + 2u * pk;
+        roff = (uint32_t)prow * pitch_r + 2u * pk;
+        boff = (uint32_t)prow * pitch_b + 2u * pk;
+        lpos = prow * LDT + pk;
+#pragma unroll
+        for (int p = 0; p < B_PASSES; ++p) b_on[p] = p * 64 + prow < S::BN;
+    }
+    __device__ inline void load(const char* a0, const char* r0, const char* bh0, const char* bl0,
+                                size_t pitch_a, size_t pitch_r, size_t pitch_b)
+    {
+#pragma unroll
+        for (int p = 0; p < A_PASSES; ++p) {
+            a[p] = *reinterpret_cast<const uint4*>(a0 + p * 64 * pitch_a + aoff);
+            if (MASK) r[p] = *reinterpret_cast<const uint4*>(r0 + p * 64 * pitch_r + roff);
+        }
+#pragma unroll
+        for (int p = 0; p < B_PASSES; ++p)
+            if (b_on[p]) {
+                bh[p] = *reinterpret_cast<const uint4*>(bh0 + p * 64 * pitch_b + boff);
+                bl[p] = *reinterpret_cast<const uint4*>(bl0 + p * 64 * pitch_b + boff);
+            }
+    }
+    __device__ inline void store(uint16_t* as, uint16_t* bhs, uint16_t* bls) const
+    {
+#pragma unroll
+        for (int p = 0; p < A_PASSES; ++p) {
+            uint4 v = a[p];
+            if (MASK) {
+                v.x = keep_positive(v.x, r[p].x);
+                v.y = keep_positive(v.y, r[p].y);
+                v.z = keep_positive(v.z, r[p].z);
+                v.w = keep_positive(v.w, r[p].w);
+            }
+            lds_store16(as + lpos + p * 64 * LDT, v);
+        }
+#pragma unroll
+        for (int p = 0; p < B_PASSES; ++p)
+            if (b_on[p]) {
+                lds_store16(bhs + lpos + p * 64 * LDT, bh[p]);
+                lds_store16(bls + lpos + p * 64 * LDT, bl[p]);
+            }
+    }
+};
+
 // ---- row-block kernel: C[n x MD] = (A (.) 1[R > 0])[n x KD] * Bop[KD x MD] ---------------------
 // Bop is given split and transposed: Bh/Bl[j][kk], j < n_col_tiles * BN, kk < ldb (a multiple of
 // BKB), zero outside the weights.
@@ -193,15 +280,55 @@ __global__ __launch_bounds__(kBlock) void rowblock_bf16_kernel(
     };
 
     const int nk = (KD + BKB - 1) / BKB;
-    issue_tiles(0);
-    store_tiles(As[0], Bhs[0], Bls[0]);
-    __syncthreads();
-    for (int i = 0; i < nk; ++i) {
-        const int cur = i & 1;
-        if (i + 1 < nk) issue_tiles((i + 1) * BKB);
-        mma_step(As[cur], Bhs[cur], Bls[cur]);
-        if (i + 1 < nk) store_tiles(As[cur ^ 1], Bhs[cur ^ 1], Bls[cur ^ 1]);
+    // every row of the tile exists, whole reduction steps, 32-bit offsets inside a tile
+    const bool fast = row0 + S::BM <= n && KD % BKB == 0 && lda < (1 << 22) && ldr < (1 << 22);
+    if (fast) {
+        FastStage<S, MASK> st;
+        st.init(tid, (uint32_t)lda * 2u, (uint32_t)ldr * 2u, (uint32_t)ldb * 2u);
+        const char* a0 = reinterpret_cast<const char*>(A + row0 * lda);
+        const char* r0 = MASK ? reinterpret_cast<const char*>(R + row0 * ldr) : nullptr;
+        const char* bh0 = reinterpret_cast<const char*>(Bh + (int64_t)col0 * ldb);
+        const char* bl0 = reinterpret_cast<const char*>(Bl + (int64_t)col0 * ldb);
+        auto load = [&](int step) {
+            const size_t o = (size_t)step * (BKB * 2);
+            st.load(a0 + o, r0 + o, bh0 + o, bl0 + o, (size_t)lda * 2, (size_t)ldr * 2, (size_t)ldb * 2);
+        };
+        // two steps per trip, so that the LDS buffer of every access is known at compile time
+        load(0);
+        st.store(As[0], Bhs[0], Bls[0]);
         __syncthreads();
+        int i = 0;
+        while (i + 2 < nk) {
+            load(i + 1);
+            mma_step(As[0], Bhs[0], Bls[0]);
+            st.store(As[1], Bhs[1], Bls[1]);
+            __syncthreads();
+            load(i + 2);
+            mma_step(As[1], Bhs[1], Bls[1]);
+            st.store(As[0], Bhs[0], Bls[0]);
+            __syncthreads();
+            i += 2;
+        }
+        if (i + 1 < nk) {
+            load(i + 1);
+            mma_step(As[0], Bhs[0], Bls[0]);
+            st.store(As[1], Bhs[1], Bls[1]);
+            __syncthreads();
+            mma_step(As[1], Bhs[1], Bls[1]);
+        } else {
+            mma_step(As[0], Bhs[0], Bls[0]);
+        }
+    } else {
+        issue_tiles(0);
+        store_tiles(As[0], Bhs[0], Bls[0]);
+        __syncthreads();
+        for (int i = 0; i < nk; ++i) {
+            const int cur = i & 1;
+            if (i + 1 < nk) issue_tiles((i + 1) * BKB);
+            mma_step(As[cur], Bhs[cur], Bls[cur]);
+            if (i + 1 < nk) store_tiles(As[cur ^ 1], Bhs[cur ^ 1], Bls[cur ^ 1]);
+            __syncthreads();
+        }
     }
 
     // D layout: lane l, register v -> row 8*(v/4) + 4*(l/32) + v%4, col l%32
