@@ -55,6 +55,10 @@ def _load():
         lib.oracle_pipeline_stages.restype = i64
         lib.oracle_relu_bitmap.argtypes = [p, i64, i64, i64, p, i64]
         lib.oracle_relu_bitmap.restype = None
+        lib.oracle_splitmix64.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
+        lib.oracle_splitmix64.restype = ctypes.c_uint64
+        lib.oracle_dropout_bitmap.argtypes = [ctypes.c_uint64, i64, i64, ctypes.c_double, p, i64]
+        lib.oracle_dropout_bitmap.restype = None
         lib.oracle_sspmm.argtypes = [p, p, p, p, i64, p, i64, i64, i64, i64, i64, p, i64, i32]
         lib.oracle_sspmm.restype = None
         lib.oracle_update_fwd.argtypes = [p, i64, p, i64, p, i64, i64, i64, i64, i32, i32]
@@ -178,6 +182,19 @@ def relu_bitmap(X):
     n, m = X.shape
     bits = np.zeros((n, (m + 31) // 32), dtype=np.uint32)
     _load().oracle_relu_bitmap(_p(X), m, n, m, _p(bits), bits.shape[1])
+    return bits
+
+
+def splitmix64(seed: int, i: int) -> int:
+    """Output i (from 0) of SplitMix64 started at `seed`."""
+    return int(_load().oracle_splitmix64(seed & (2 ** 64 - 1), i))
+
+
+def dropout_bitmap(seed: int, n: int, m: int, keep: float):
+    """uint32 bitmap [n, ceil(m / 32)] of the kept elements of an n x m tensor: element (v, j) is
+    kept iff splitmix64(seed, v * m + j) >> 32 < keep * 2^32."""
+    bits = np.zeros((n, (m + 31) // 32), dtype=np.uint32)
+    _load().oracle_dropout_bitmap(seed & (2 ** 64 - 1), n, m, float(keep), _p(bits), bits.shape[1])
     return bits
 
 

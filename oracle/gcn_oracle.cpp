@@ -190,6 +190,39 @@ void oracle_relu_bitmap(const double* X, int64_t ldx, int64_t n, int64_t m, uint
 }
 
 /*
+ * The forward use of the output mask (Sec. 3.2.1: about half of the aggregation's outputs are
+ * dropped by dropout in the forward pass).  The paper gives no random-number specification, so the
+ * mask is defined here: element (v, j) of an n x m tensor is KEPT iff the upper 32 bits of
+ * splitmix64(seed, v * m + j) are below keep * 2^32, where splitmix64(seed, i) is output i
+ * (counting from 0) of the SplitMix64 generator (Steele, Lea, Flood, OOPSLA 2014) started at
+ * `seed`: z = seed + (i + 1) * 0x9E3779B97F4A7C15, then two xor-shift-multiply rounds and a final
+ * xor-shift.  A pure function of (seed, index), so any number of threads produce the same mask.
+ */
+uint64_t oracle_splitmix64(uint64_t seed, uint64_t i)
+{
+    uint64_t z = seed + (i + 1) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+/* keep in [0, 1]; bitmap layout as oracle_relu_bitmap (bits past column m are clear). */
+void oracle_dropout_bitmap(uint64_t seed, int64_t n, int64_t m, double keep, uint32_t* bits,
+                           int64_t ldb)
+{
+    double t = keep * 4294967296.0;
+    if (t < 0.0) t = 0.0;
+    if (t > 4294967296.0) t = 4294967296.0;
+    const uint64_t threshold = (uint64_t)t;
+    for (int64_t v = 0; v < n; ++v) {
+        for (int64_t w = 0; w < ldb; ++w) bits[v * ldb + w] = 0u;
+        for (int64_t j = 0; j < m; ++j)
+            if ((oracle_splitmix64(seed, (uint64_t)(v * m + j)) >> 32) < threshold)
+                bits[v * ldb + j / 32] |= 1u << (j % 32);
+    }
+}
+
+/*
  * S-SpMM (Sec. 3.2.1, Eq. 4):  Z = (A H) (.) M  with the mask M given as a bitmap (layout as
  * above).  Every output is the full neighbor sum of the plain aggregation, kept where the mask
  * bit is set and zero elsewhere.

@@ -735,3 +735,56 @@ def test_sage_gradient_fd_on_a_directed_graph_pins_the_transposed_mean():
     if np.min(np.abs(base["X"][0] @ ws[0])) < 1e-4:
         pytest.skip("sample too close to a ReLU kink")
     _fd_check(lambda: oracle.sage_step(g, x, ws, y, backward=False)["loss"], [x], [base["dX"]])
+
+
+# ------------------------------------------------------------------------------------------
+# dropout mask of the S-SpMM's forward use (Sec. 3.2.1): the generator and the bitmap
+# ------------------------------------------------------------------------------------------
+def test_splitmix64_published_test_vector():
+    want = [int(l, 16) for l in open(os.path.join(GOLD, "splitmix64_seed0.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert [oracle.splitmix64(0, i) for i in range(len(want))] == want
+    # a seed shifts the sequence: output i of seed s + k * gamma is output i + k of seed s
+    gamma = 0x9E3779B97F4A7C15
+    assert oracle.splitmix64((5 * gamma) % 2 ** 64, 2) == oracle.splitmix64(0, 7)
+
+
+def test_dropout_bitmap_is_the_thresholded_generator_and_has_the_right_density():
+    n, m, seed = 257, 70, 12345
+    for keep in (0.0, 0.25, 0.5, 0.9, 1.0):
+        bits = oracle.dropout_bitmap(seed, n, m, keep)
+        got = unpack_bits(bits, m)
+        # bits past the last column are clear
+        assert np.all(unpack_bits(bits, 32 * bits.shape[1])[:, m:] == 0)
+        # element by element from the generator (python integers), on a sample of the rows
+        thr = int(keep * 2 ** 32)
+        for v in (0, 1, 100, n - 1):
+            ref = [(oracle.splitmix64(seed, v * m + j) >> 32) < thr for j in range(m)]
+            assert list(got[v].astype(bool)) == ref
+        if keep in (0.0, 1.0):
+            assert got.sum() == (0 if keep == 0.0 else n * m)
+        else:  # binomial: 5 standard deviations
+            sd = math.sqrt(n * m * keep * (1 - keep))
+            assert abs(got.sum() - n * m * keep) < 5 * sd
+    # another seed gives another mask; the same seed the same one
+    a = oracle.dropout_bitmap(1, n, m, 0.5)
+    assert np.array_equal(a, oracle.dropout_bitmap(1, n, m, 0.5))
+    b = unpack_bits(oracle.dropout_bitmap(2, n, m, 0.5), m)
+    agree = (unpack_bits(a, m) == b).mean()
+    assert 0.45 < agree < 0.55
+    # rows are not copies of each other, columns neither (index = v * m + j, not v or j alone)
+    g = unpack_bits(a, m).astype(np.float64)
+    assert abs(np.corrcoef(g[0::2].ravel()[:8000], g[1::2].ravel()[:8000])[0, 1]) < 0.05
+
+
+def test_dropout_mask_in_the_sspmm_keeps_about_half_of_the_outputs():
+    rng = np.random.default_rng(7)
+    n = 50
+    g = oracle.normalize(oracle.build_csr(rng.integers(0, n, 200), rng.integers(0, n, 200), n))
+    h = rng.normal(size=(n, 40))
+    bits = oracle.dropout_bitmap(99, n, 40, 0.5)
+    z = oracle.sspmm(g, h, bits)
+    full = oracle.spmm(g, h)
+    keep = unpack_bits(bits, 40).astype(bool)
+    np.testing.assert_allclose(z, np.where(keep, full, 0.0), rtol=0, atol=0)
+    assert 0.4 < keep.mean() < 0.6
