@@ -194,6 +194,19 @@ int mixgcn_relu_bitmap(int dtype, const void* X, int64_t ldx, int64_t n_rows, in
                        uint32_t* mask, int64_t ld_mask, void* stream);
 
 /*
+ * The mask of the S-SpMM's forward use (Sec. 3.2.1: dropout drops about half of the outputs of
+ * the aggregation), as a bitmap for mixgcn_aggregate_masked.  The paper specifies no random
+ * numbers, so the mask is defined here: element (r, c) of the n_rows x n_cols tensor is kept
+ * (bit set) iff the upper 32 bits of output number r * n_cols + c (counting from 0) of the
+ * SplitMix64 generator started at `seed` are below keep_probability * 2^32.  A pure function of
+ * (seed, r, c): the same call gives the same mask, and the backward pass can regenerate it
+ * instead of storing it.  Every word of a row up to ld_mask is written; bits past n_cols are
+ * clear.  No scaling by 1 / keep_probability is implied: Eq. 4 multiplies by the 0/1 mask.
+ */
+int mixgcn_dropout_bitmap(uint64_t seed, int64_t n_rows, int32_t n_cols, double keep_probability,
+                          uint32_t* mask, int64_t ld_mask, void* stream);
+
+/*
  * Algorithm 2, update phase, and the two products of its backward pass (see MIXGCN_OP_*).
  *   A, B, C    : operands as listed per op; n_rows = n, k = d^(l), m = d^(l+1).
  *   relu_ref   : R, the stored layer output H' whose sign gives the ReLU derivative

@@ -76,6 +76,7 @@ def load_library():
     lib.mixgcn_aggregate_masked.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, i64, vp, i64, i32,
                                             i32, i64, i64, vp, i64, vp]
     lib.mixgcn_relu_bitmap.argtypes = [ctypes.c_int, vp, i64, i64, i32, vp, i64, vp]
+    lib.mixgcn_dropout_bitmap.argtypes = [u64, i64, i32, ctypes.c_double, vp, i64, vp]
     lib.mixgcn_reorder_rcm.argtypes = [vp, vp, vp]
     lib.mixgcn_bandwidth.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int64), vp]
     lib.mixgcn_pipeline_stages.argtypes = [i64, i64]
@@ -317,6 +318,16 @@ def aggregate_masked(g: Graph, H, Z, mask, col_begin=0, col_end=None, row_begin=
                                                   _ptr(Z), _ld(Z), col_begin, col_end, row_begin,
                                                   row_end, _ptr(mask), mask.stride(0),
                                                   _stream(stream)), "aggregate_masked")
+
+
+def dropout_bitmap(seed: int, n_rows: int, n_cols: int, keep_probability: float, stream=None):
+    """Bitmap [n_rows, ceil(n_cols / 32)] (int32 device tensor) of the elements a dropout with
+    this seed keeps; see mixgcn_dropout_bitmap for the generator."""
+    mask = torch.empty(n_rows, (n_cols + 31) // 32, dtype=torch.int32, device="cuda")
+    _check(load_library().mixgcn_dropout_bitmap(seed & (2 ** 64 - 1), n_rows, n_cols,
+                                                float(keep_probability), _ptr(mask), mask.stride(0),
+                                                _stream(stream)), "dropout_bitmap")
+    return mask
 
 
 def reorder_rcm(g: Graph, stream=None):

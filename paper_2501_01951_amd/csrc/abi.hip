@@ -365,6 +365,22 @@ static int update_impl(int op, int dtype, const void* A, int64_t lda, const void
                          ldr, beta, stream, timer);
 }
 
+int mixgcn_dropout_bitmap(uint64_t seed, int64_t n_rows, int32_t n_cols, double keep_probability,
+                          uint32_t* mask, int64_t ld_mask, void* stream)
+{
+    if (n_rows < 0 || n_cols <= 0) return fail(MIXGCN_EINVAL, "dropout_bitmap: sizes");
+    if (!mask) return fail(MIXGCN_EINVAL, "dropout_bitmap: null pointer");
+    if (!(keep_probability >= 0.0 && keep_probability <= 1.0))
+        return fail(MIXGCN_EINVAL, "dropout_bitmap: keep_probability outside [0, 1]");
+    if (ld_mask < ((int64_t)n_cols + 31) / 32)
+        return fail(MIXGCN_EINVAL, "dropout_bitmap: ld_mask shorter than ceil(n_cols / 32) words");
+    if (n_rows > 0 && (uint64_t)n_rows > (1ull << 62) / (uint64_t)n_cols)
+        return fail(MIXGCN_EINVAL, "dropout_bitmap: n_rows * n_cols too large");
+    const uint64_t threshold = (uint64_t)(keep_probability * 4294967296.0);
+    return launch_dropout_bitmap(seed, n_rows, n_cols, threshold, mask, ld_mask,
+                                 (hipStream_t)stream);
+}
+
 int mixgcn_update(int op, int dtype, const void* A, int64_t lda, const void* B, int64_t ldb,
                   void* C, int64_t ldc, int64_t n_rows, int32_t k, int32_t m,
                   const void* relu_ref, int64_t ldr, float beta, void* stream)

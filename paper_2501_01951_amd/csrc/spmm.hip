@@ -566,7 +566,49 @@ __global__ __launch_bounds__(kBlock) void relu_bitmap_kernel(const void* __restr
     if (q % LPW == 0 && r < n) bits[r * ldb + q / LPW] = w;
 }
 
+// Dropout mask as a bitmap (forward use of the S-SpMM, Sec. 3.2.1).  Element (r, c) of the
+// n x cols tensor is kept iff the upper half of output number r * cols + c of the SplitMix64
+// generator started at `seed` is below `threshold` (= keep probability * 2^32).  One thread per
+// word; every word of a row up to ldb is written, bits past `cols` are clear.
+__device__ inline uint64_t splitmix64_at(uint64_t seed, uint64_t i)
+{
+    uint64_t z = seed + (i + 1) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+__global__ __launch_bounds__(kBlock) void dropout_bitmap_kernel(uint64_t seed, int64_t n, int cols,
+                                                                uint64_t threshold,
+                                                                uint32_t* __restrict__ bits,
+                                                                int64_t ldb)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n * ldb) return;
+    const int64_t r = i / ldb;
+    const int c0 = (int)(i % ldb) * 32;
+    uint32_t w = 0;
+#pragma unroll 8
+    for (int b = 0; b < 32; ++b) {
+        const int c = c0 + b;
+        if (c < cols && (splitmix64_at(seed, (uint64_t)(r * cols + c)) >> 32) < threshold)
+            w |= 1u << b;
+    }
+    bits[i] = w;
+}
+
 }  // namespace
+
+int launch_dropout_bitmap(uint64_t seed, int64_t n, int32_t cols, uint64_t threshold,
+                          uint32_t* bits, int64_t ldb, hipStream_t s)
+{
+    const int64_t total = n * ldb;
+    if (total == 0) return MIXGCN_OK;
+    hipLaunchKernelGGL(dropout_bitmap_kernel, dim3((unsigned)ceil_div(total, kBlock)), dim3(kBlock),
+                       0, s, seed, n, cols, threshold, bits, ldb);
+    MIXGCN_HIP_TRY(hipGetLastError());
+    return MIXGCN_OK;
+}
 
 int launch_relu_bitmap(int dtype, const void* X, int64_t ldx, int64_t n, int32_t cols,
                        uint32_t* bits, int64_t ldb, hipStream_t s)

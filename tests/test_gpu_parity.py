@@ -246,6 +246,41 @@ def test_aggregate_masked_slices_rows_transpose_bf16(mg, rmat15):
         mg.aggregate_masked(g, hd, z, bits[:, :2].contiguous())
 
 
+@pytest.mark.parametrize("n,c,keep", [(1, 1, 0.5), (1000, 32, 0.5), (513, 33, 0.25), (4099, 100, 0.9),
+                                      (300, 256, 0.0), (300, 256, 1.0), (70001, 47, 0.5)])
+def test_dropout_bitmap_bit_exact(mg, n, c, keep):
+    say(f"dropout_bitmap n={n} c={c} keep={keep}")
+    seed = 0xC0FFEE123456789
+    got = mg.dropout_bitmap(seed, n, c, keep).cpu().numpy().view(np.uint32)
+    assert np.array_equal(got, oracle.dropout_bitmap(seed, n, c, keep))
+    # a wider row pitch: the extra words are written as zero
+    import paper_2501_01951_amd.binding as B
+    wide = torch.full((n, (c + 31) // 32 + 2), -1, dtype=torch.int32, device="cuda")
+    B._check(mg.load_library().mixgcn_dropout_bitmap(seed, n, c, keep, B._ptr(wide), wide.stride(0),
+                                                     None), "dropout_bitmap")
+    torch.cuda.synchronize()
+    w = wide.cpu().numpy().view(np.uint32)
+    assert np.array_equal(w[:, :got.shape[1]], got) and np.all(w[:, got.shape[1]:] == 0)
+    lib = mg.load_library()
+    assert lib.mixgcn_dropout_bitmap(seed, n, c, 1.5, B._ptr(wide), wide.stride(0), None) == -1
+    assert lib.mixgcn_dropout_bitmap(seed, n, c, keep, B._ptr(wide), 0, None) == -1
+
+
+def test_aggregate_with_the_dropout_mask(mg, rmat15):
+    """Forward use of the S-SpMM (Eq. 4): Z = (A_hat H) (.) M with M from the dropout generator."""
+    og, g = rmat15
+    f = 100
+    h = gg.normal(61, 1, og.n, f, ld=104)
+    mask = mg.dropout_bitmap(2024, og.n, f, 0.5)
+    z = torch.full((og.n, 104), 3.0, device="cuda")[:, :f]
+    mg.aggregate_masked(g, dev(h)[:, :f], z, mask)
+    ref = oracle.sspmm(og, h[:, :f].astype(np.float64), oracle.dropout_bitmap(2024, og.n, f, 0.5))
+    got = z.cpu().numpy()
+    assert_close(got, ref, RTOL_F32, "dropout-masked aggregation")
+    assert np.array_equal(got == 0, ref == 0)  # exactly the dropped outputs are zero
+    assert 0.45 < (got == 0).mean() < 0.55
+
+
 def test_aggregate_masked_backward_use_matches_mask_after_aggregate(mg, rmat15):
     """The backward use: dP = (A_hat^T dZ) (.) 1[H > 0] in one pass equals the plain aggregation
     followed by the ReLU-derivative mask, bit for bit."""
