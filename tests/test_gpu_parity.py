@@ -470,6 +470,28 @@ def test_update_ops(mg, n, k, m):
         assert np.all(o[:, m:] == 9.0)
         mg.update(mg.OP_WGRAD, zd, gd, dw, n, k, m, relu_ref=ref_t, beta=1.0)
         assert_close(dw.cpu().numpy()[:, :m], 2 * refw, RTOL_F32, "wgrad beta=1")
+    # every operand a column block of a wider buffer, each with a pitch of its own: same bits
+    def wide(t, width, extra):
+        buf = torch.ones(n, extra + (width + 3) // 4 * 4 + 4, device="cuda")
+        buf[:, extra:extra + width] = t[:, :width]
+        return buf[:, extra:extra + width]
+
+    g2, h2, z2 = wide(gd, m, 8), wide(hd, m, 20), wide(zd, k, 4)
+    dz0 = torch.zeros(n, ldk, device="cuda")[:, :k]
+    mg.update(mg.OP_DGRAD, gd[:, :m], wd[:, :m], dz0, n, k, m, relu_ref=hd[:, :m])
+    dz2 = torch.zeros(n, ldk + 12, device="cuda")[:, 8:8 + k]
+    mg.update(mg.OP_DGRAD, g2, wd[:, :m], dz2, n, k, m, relu_ref=h2)
+    assert torch.equal(dz2, dz0)
+    out0 = torch.zeros(n, ldm, device="cuda")[:, :m]
+    mg.update(mg.OP_FWD_RELU, zd[:, :k], wd[:, :m], out0, n, k, m)
+    out2 = torch.zeros(n, ldm + 8, device="cuda")[:, 4:4 + m]
+    mg.update(mg.OP_FWD_RELU, z2, wd[:, :m], out2, n, k, m)
+    assert torch.equal(out2, out0)
+    dw0 = torch.zeros(k, ldm, device="cuda")[:, :m]
+    mg.update(mg.OP_WGRAD, zd[:, :k], gd[:, :m], dw0, n, k, m, relu_ref=hd[:, :m])
+    dw2 = torch.zeros(k, ldm, device="cuda")[:, :m]
+    mg.update(mg.OP_WGRAD, z2, g2, dw2, n, k, m, relu_ref=h2)
+    assert torch.equal(dw2, dw0)
 
 
 @pytest.mark.parametrize("n,c", [(4096, 8), (10000, 16), (3000, 172), (999, 47), (5, 3), (1, 2),
@@ -988,6 +1010,19 @@ def test_update_ops_bf16(mg, n, k, m):
     dw = torch.zeros(k, wd.stride(0), device="cuda")[:, :m]
     mg.update(mg.OP_WGRAD, zd, gd, dw, n, k, m, relu_ref=hd)
     assert_close(dw.cpu().numpy(), oracle.update_wgrad(z64, dp), 1e-3, "wgrad bf16 inputs, fp32 sum")
+    # every operand a column block of a wider buffer, each with a pitch of its own
+    def wide(t, extra):
+        buf = torch.ones(n, extra + (t.shape[1] + 7) // 8 * 8 + 8, dtype=t.dtype, device="cuda")
+        buf[:, extra:extra + t.shape[1]] = t
+        return buf[:, extra:extra + t.shape[1]]
+
+    g2, h2 = wide(gd, 16), wide(hd, 40)
+    dz2 = torch.zeros(n, ldk + 24, dtype=torch.bfloat16, device="cuda")[:, 8:8 + k]
+    mg.update(mg.OP_DGRAD, g2, wd, dz2, n, k, m, relu_ref=h2)
+    assert torch.equal(dz2, dz)
+    dw2 = torch.zeros(k, wd.stride(0), device="cuda")[:, :m]
+    mg.update(mg.OP_WGRAD, wide(zd, 8), g2, dw2, n, k, m, relu_ref=h2)
+    assert torch.equal(dw2, dw)
 
 
 def test_softmax_xent_bf16(mg):
