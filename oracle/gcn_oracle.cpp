@@ -15,7 +15,13 @@
  * against dense brute force and adjoint identities; the loss against ln C at W = 0; the whole
  * forward+backward against central finite differences and the linear-activation closed form;
  * the masked aggregation (S-SpMM) against a dense masked product, the complement identity
- * Z(M) + Z(not M) = A_hat H, and Z = M on regular graphs with H = 1; the bitmap against numpy.
+ * Z(M) + Z(not M) = A_hat H, and Z = M on regular graphs with H = 1; the bitmap against numpy;
+ * the reverse Cuthill-McKee sequence against a hand-worked example, closed forms (path, cycle,
+ * star, complete graph, grid) and the brute-force optimum on 7-node graphs; the dropout mask
+ * against the generator's published test vector and its density.  The GraphSAGE and GIN steps
+ * (numpy, in the Python module beside this file) are pinned by node-by-node definitions,
+ * special cases that reduce to a perceptron and finite differences.  No function here is
+ * "parity unpinned".
  */
 #include <algorithm>
 #include <cmath>
