@@ -896,6 +896,9 @@ def _sage_case(name):
     if name == "c1":
         src, dst, n = gg.config_graph("c1")
         dims = (64, 32, 8)
+    elif name == "c2":  # the graph of config 2 at its full size, as bench.py --model runs it
+        src, dst, n = gg.config_graph("c2")
+        dims = (128, 128, 128, 16)
     else:
         src, dst, n = gg.config_graph("c2", scale_override=16)
         dims = (128, 128, 128, 16)
@@ -904,7 +907,7 @@ def _sage_case(name):
     return src, dst, n, dims, x, y
 
 
-@pytest.mark.parametrize("name", ["c1", "c2@16"])
+@pytest.mark.parametrize("name", ["c1", "c2@16", "c2"])
 def test_graphsage_mean_model_end_to_end(mg, name):
     src, dst, n, dims, x, y = _sage_case(name)
     say(f"GraphSAGE (mean) {name} dims={dims}")
@@ -927,7 +930,7 @@ def test_graphsage_mean_model_end_to_end(mg, name):
     g.free()
 
 
-@pytest.mark.parametrize("name", ["c1", "c2@16"])
+@pytest.mark.parametrize("name", ["c1", "c2@16", "c2"])
 def test_gin_model_end_to_end(mg, name):
     src, dst, n, dims, x, y = _sage_case(name)
     eps = 0.1
