@@ -414,3 +414,46 @@ def gin_step(g: Graph, X, W1s, W2s, labels, want_dx=False, backward=True):
         dP = dH * (Hs[l] > 0)
     out["dW1"], out["dW2"] = dW1s, dW2s
     return out
+
+
+def gcn_dropout_step(g: Graph, X, Ws, labels, seed: int, keep: float, want_dx=False, backward=True):
+    """L-layer GCN in the order of Algorithm 2 with the output mask of Sec. 3.2.1 / Eq. 4 on every
+    aggregation: Z_l = (A_hat H_l) (.) M_l, M_l = dropout_bitmap(seed + l, n, d_l, keep), P_l =
+    Z_l W_l, H_{l+1} = relu(P_l) (none after the last).  The mask is a constant of the step, so
+    the backward pass multiplies by it where the forward pass did:
+    dW_l = Z_l^T dP_l;  dZ_l = dP_l W_l^T;  dH_l = A_hat^T (dZ_l (.) M_l);  dP_{l-1} = dH_l (.) 1[H_l > 0].
+    No rescaling by 1 / keep (Eq. 4 multiplies by the 0/1 mask)."""
+    X = _f64(X)
+    Ws = [_f64(w) for w in Ws]
+    L = len(Ws)
+    n = g.n
+    if g.t_rowptr is None:
+        transpose(g)
+    bits = [dropout_bitmap(seed + l, n, Ws[l].shape[0], keep) for l in range(L)]
+    masks = []
+    for l in range(L):
+        d = Ws[l].shape[0]
+        cols = np.arange(d)
+        masks.append(((bits[l][:, cols // 32] >> (cols % 32).astype(np.uint32)) & 1).astype(np.float64))
+    Hs, Zs = [X], []
+    for l, w in enumerate(Ws):
+        z = sspmm(g, Hs[l], bits[l])
+        p = z @ w
+        Zs.append(z)
+        Hs.append(np.maximum(p, 0.0) if l < L - 1 else p)
+    loss, dP = _loss_and_grad(Hs[L], labels, backward)
+    out = {"loss": loss, "logits": Hs[L], "H": Hs, "Z": Zs, "M": masks, "dW": None, "dX": None}
+    if not backward:
+        return out
+    dWs = [None] * L
+    for l in range(L - 1, -1, -1):
+        dWs[l] = Zs[l].T @ dP
+        if l == 0 and not want_dx:
+            break
+        dH = spmm(g, (dP @ Ws[l].T) * masks[l], transposed=True)
+        if l == 0:
+            out["dX"] = dH
+            break
+        dP = dH * (Hs[l] > 0)
+    out["dW"] = dWs
+    return out

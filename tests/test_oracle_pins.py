@@ -788,3 +788,31 @@ def test_dropout_mask_in_the_sspmm_keeps_about_half_of_the_outputs():
     keep = unpack_bits(bits, 40).astype(bool)
     np.testing.assert_allclose(z, np.where(keep, full, 0.0), rtol=0, atol=0)
     assert 0.4 < keep.mean() < 0.6
+
+
+def test_dropout_gcn_forward_vs_dense_and_gradients_vs_finite_differences():
+    """The masked step: forward against the dense definition with the mask read back bit by bit,
+    gradients against central differences (the mask is a constant of the step)."""
+    g, src, dst, x, ws, y = _tiny_problem(91)
+    seed, keep = 777, 0.6
+    base = oracle.gcn_dropout_step(g, x, ws, y, seed, keep, want_dx=True)
+    ah = dense_ahat(dense_atilde(src, dst, g.n))
+    h = x
+    for l, w in enumerate(ws):
+        m = unpack_bits(oracle.dropout_bitmap(seed + l, g.n, w.shape[0], keep), w.shape[0])
+        h = ((ah @ h) * m) @ w
+        if l < len(ws) - 1:
+            h = np.maximum(h, 0)
+    np.testing.assert_allclose(base["logits"], h, rtol=1e-11, atol=1e-13)
+    for l in (1, 2):
+        pre = base["Z"][l - 1] @ ws[l - 1]
+        if np.min(np.abs(pre[pre != 0])) < 1e-4:
+            pytest.skip("sample too close to a ReLU kink")
+    _fd_check(lambda: oracle.gcn_dropout_step(g, x, ws, y, seed, keep, backward=False)["loss"],
+              ws + [x], base["dW"] + [base["dX"]])
+    # keep = 1 is the plain step
+    plain = oracle.gcn_step(g, x, ws, y)
+    full = oracle.gcn_dropout_step(g, x, ws, y, seed, 1.0)
+    np.testing.assert_allclose(full["logits"], plain["logits"], rtol=1e-12, atol=1e-14)
+    for a, b in zip(full["dW"], plain["dW"]):
+        np.testing.assert_allclose(a, b, rtol=1e-10, atol=1e-14)
