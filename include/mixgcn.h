@@ -207,6 +207,16 @@ int mixgcn_dropout_bitmap(uint64_t seed, int64_t n_rows, int32_t n_cols, double 
                           uint32_t* mask, int64_t ld_mask, void* stream);
 
 /*
+ * X <- X (.) M in place for a bitmap M (layout as above): the backward pass of an aggregation
+ * whose output was masked multiplies the gradient by the same mask before A_hat^T (Eq. 4; the
+ * mask is a constant of the step).  X: n_rows x n_cols, 16-byte aligned rows.  A masked-off
+ * element becomes +0; the elements of the row padding up to the next 16 bytes are rewritten too
+ * (zero where the mask bit past n_cols is clear, as the two mask generators leave it).
+ */
+int mixgcn_apply_bitmap(int dtype, void* X, int64_t ldx, int64_t n_rows, int32_t n_cols,
+                        const uint32_t* mask, int64_t ld_mask, void* stream);
+
+/*
  * Algorithm 2, update phase, and the two products of its backward pass (see MIXGCN_OP_*).
  *   A, B, C    : operands as listed per op; n_rows = n, k = d^(l), m = d^(l+1).
  *   relu_ref   : R, the stored layer output H' whose sign gives the ReLU derivative

@@ -77,6 +77,7 @@ def load_library():
                                             i32, i64, i64, vp, i64, vp]
     lib.mixgcn_relu_bitmap.argtypes = [ctypes.c_int, vp, i64, i64, i32, vp, i64, vp]
     lib.mixgcn_dropout_bitmap.argtypes = [u64, i64, i32, ctypes.c_double, vp, i64, vp]
+    lib.mixgcn_apply_bitmap.argtypes = [ctypes.c_int, vp, i64, i64, i32, vp, i64, vp]
     lib.mixgcn_reorder_rcm.argtypes = [vp, vp, vp]
     lib.mixgcn_bandwidth.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int64), vp]
     lib.mixgcn_pipeline_stages.argtypes = [i64, i64]
@@ -328,6 +329,13 @@ def dropout_bitmap(seed: int, n_rows: int, n_cols: int, keep_probability: float,
                                                 float(keep_probability), _ptr(mask), mask.stride(0),
                                                 _stream(stream)), "dropout_bitmap")
     return mask
+
+
+def apply_bitmap(X, mask, stream=None) -> None:
+    """X <- X (.) M in place."""
+    n, cols = X.shape
+    _check(load_library().mixgcn_apply_bitmap(_dtype_of(X), _ptr(X), _ld(X), n, cols, _ptr(mask),
+                                              mask.stride(0), _stream(stream)), "apply_bitmap")
 
 
 def reorder_rcm(g: Graph, stream=None):

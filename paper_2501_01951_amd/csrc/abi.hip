@@ -365,6 +365,19 @@ static int update_impl(int op, int dtype, const void* A, int64_t lda, const void
                          ldr, beta, stream, timer);
 }
 
+int mixgcn_apply_bitmap(int dtype, void* X, int64_t ldx, int64_t n_rows, int32_t n_cols,
+                        const uint32_t* mask, int64_t ld_mask, void* stream)
+{
+    if (dtype != MIXGCN_F32 && dtype != MIXGCN_BF16)
+        return fail(MIXGCN_EINVAL, "apply_bitmap: dtype");
+    if (n_rows < 0 || n_cols <= 0) return fail(MIXGCN_EINVAL, "apply_bitmap: sizes");
+    if (!mask) return fail(MIXGCN_EINVAL, "apply_bitmap: null pointer");
+    MIXGCN_TRY(check_matrix("apply_bitmap: X", X, ldx, n_cols, elem_size(dtype)));
+    if (ld_mask < ((int64_t)n_cols + 31) / 32)
+        return fail(MIXGCN_EINVAL, "apply_bitmap: ld_mask shorter than ceil(n_cols / 32) words");
+    return launch_apply_bitmap(dtype, X, ldx, n_rows, n_cols, mask, ld_mask, (hipStream_t)stream);
+}
+
 int mixgcn_dropout_bitmap(uint64_t seed, int64_t n_rows, int32_t n_cols, double keep_probability,
                           uint32_t* mask, int64_t ld_mask, void* stream)
 {

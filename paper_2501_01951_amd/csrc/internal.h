@@ -155,6 +155,9 @@ int launch_aggregate(const mixgcn_graph* g, const Csr& m, const uint2* cv, int d
 // bits[r * ldb + c / 32] bit c % 32 = X[r, c] > 0; every word of a row up to ldb is written
 int launch_relu_bitmap(int dtype, const void* X, int64_t ldx, int64_t n, int32_t cols,
                        uint32_t* bits, int64_t ldb, hipStream_t s);
+// X <- X (.) M (bitmap M); rows are padded to 16 bytes, so the last vector is in bounds
+int launch_apply_bitmap(int dtype, void* X, int64_t ldx, int64_t n, int32_t cols,
+                        const uint32_t* bits, int64_t ldb, hipStream_t s);
 // bit of (r, c) = upper half of SplitMix64 output r * cols + c (seed) < threshold
 int launch_dropout_bitmap(uint64_t seed, int64_t n, int32_t cols, uint64_t threshold,
                           uint32_t* bits, int64_t ldb, hipStream_t s);

@@ -597,7 +597,45 @@ __global__ __launch_bounds__(kBlock) void dropout_bitmap_kernel(uint64_t seed, i
     bits[i] = w;
 }
 
+// X <- X (.) M for a bitmap M: a lane owns 16 bytes of a row (VEC columns, which lie in one
+// mask word because VEC divides 32).
+template <int DT>
+__global__ __launch_bounds__(kBlock) void apply_bitmap_kernel(void* __restrict__ X, int64_t ldx,
+                                                              int64_t n, int cols,
+                                                              const uint32_t* __restrict__ bits,
+                                                              int64_t ldb)
+{
+    using F = Feat<DT>;
+    constexpr int VEC = F::VEC;
+    const int vpr = (cols + VEC - 1) / VEC;  // vectors per row (the last may reach into the padding)
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n * vpr) return;
+    const int64_t r = i / vpr;
+    const int c = (int)(i % vpr) * VEC;
+    float x[VEC];
+    F::widen(*F::ptr(X, r * ldx + c), x);
+    apply_mask<VEC>(x, bits, ldb, r, c);
+    F::store(X, r * ldx + c, x);
+}
+
 }  // namespace
+
+int launch_apply_bitmap(int dtype, void* X, int64_t ldx, int64_t n, int32_t cols,
+                        const uint32_t* bits, int64_t ldb, hipStream_t s)
+{
+    const int vec = dtype == MIXGCN_F32 ? 4 : 8;
+    const int64_t total = n * ((cols + vec - 1) / vec);
+    if (total == 0) return MIXGCN_OK;
+    const dim3 grid((unsigned)ceil_div(total, kBlock));
+    if (dtype == MIXGCN_F32)
+        hipLaunchKernelGGL(apply_bitmap_kernel<MIXGCN_F32>, grid, dim3(kBlock), 0, s, X, ldx, n, cols,
+                           bits, ldb);
+    else
+        hipLaunchKernelGGL(apply_bitmap_kernel<MIXGCN_BF16>, grid, dim3(kBlock), 0, s, X, ldx, n, cols,
+                           bits, ldb);
+    MIXGCN_HIP_TRY(hipGetLastError());
+    return MIXGCN_OK;
+}
 
 int launch_dropout_bitmap(uint64_t seed, int64_t n, int32_t cols, uint64_t threshold,
                           uint32_t* bits, int64_t ldb, hipStream_t s)

@@ -228,3 +228,56 @@ class GINStep:
     def step(self):
         self.forward()
         self.backward()
+
+
+class GCNDropoutStep:
+    """GCNStep in the order of Algorithm 2 with the output mask of Eq. 4 on every aggregation
+    (forward use of the S-SpMM): Z_l = (A_hat H_l) (.) M_l with M_l the dropout bitmap of seed
+    `seed + l`, regenerated where the backward pass needs it instead of being kept.  Backward:
+    dZ_l (.) M_l before the transposed aggregation."""
+
+    def __init__(self, g: B.Graph, x, weights, labels, seed: int, keep: float):
+        self.g, self.n, self.labels = g, x.shape[0], labels
+        self.w = list(weights)
+        self.seed, self.keep = seed, keep
+        dev, dt = x.device, x.dtype
+        L = len(self.w)
+        rows = lambda f: padded_rows(self.n, f, dt, dev)
+        x_p = rows(x.shape[1])
+        x_p.copy_(x)
+        self.h = [x_p] + [rows(w.shape[1]) for w in self.w]
+        self.z = [rows(w.shape[0]) for w in self.w]
+        self.dw = [torch.empty_strided(w.shape, w.stride(), dtype=w.dtype, device=dev) for w in self.w]
+        self.dlogits = rows(self.w[L - 1].shape[1])
+        self.dh = [None] + [rows(self.w[l].shape[0]) for l in range(1, L)]
+        self.loss = torch.zeros(1, dtype=torch.float64, device=dev)
+
+    def mask(self, l):
+        return B.dropout_bitmap(self.seed + l, self.n, self.w[l].shape[0], self.keep)
+
+    def forward(self):
+        L = len(self.w)
+        for l in range(L):
+            k, m = self.w[l].shape
+            B.aggregate_masked(self.g, self.h[l], self.z[l], self.mask(l))
+            B.update(B.OP_FWD_RELU if l < L - 1 else B.OP_FWD, self.z[l], self.w[l], self.h[l + 1],
+                     self.n, k, m)
+        B.softmax_xent(self.h[L], self.labels, self.dlogits, self.loss)
+
+    def backward(self):
+        L = len(self.w)
+        grad = self.dlogits
+        for l in range(L - 1, -1, -1):
+            k, m = self.w[l].shape
+            ref = self.h[l + 1] if l < L - 1 else None
+            B.update(B.OP_WGRAD, self.z[l], grad, self.dw[l], self.n, k, m, relu_ref=ref)
+            if l == 0:
+                break
+            B.update(B.OP_DGRAD, grad, self.w[l], self.z[l], self.n, k, m, relu_ref=ref)
+            B.apply_bitmap(self.z[l], self.mask(l))
+            B.aggregate(self.g, self.z[l], self.dh[l], transpose=True)
+            grad = self.dh[l]
+
+    def step(self):
+        self.forward()
+        self.backward()

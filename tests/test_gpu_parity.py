@@ -281,6 +281,47 @@ def test_aggregate_with_the_dropout_mask(mg, rmat15):
     assert 0.45 < (got == 0).mean() < 0.55
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_apply_bitmap(mg, dtype):
+    n, c = 3001, 100
+    say(f"apply_bitmap {dtype}")
+    x = gg.normal(62, 1, n, c, ld=104)
+    bits = oracle.dropout_bitmap(5, n, c, 0.5)
+    keep = ((bits[:, np.arange(c) // 32] >> (np.arange(c) % 32).astype(np.uint32)) & 1).astype(bool)
+    if dtype == "bf16":
+        x = bf16_round(x)
+        xd = dev_bf16(x)
+    else:
+        xd = dev(x)
+    mg.apply_bitmap(xd[:, :c], dev(bits.view(np.int32)))
+    got = xd.float().cpu().numpy()
+    assert np.array_equal(got[:, :c], np.where(keep, x[:, :c], 0.0).astype(np.float32))
+
+
+@pytest.mark.parametrize("name", ["c1", "c2@16"])
+def test_gcn_with_dropout_masks_end_to_end(mg, name):
+    """Forward use of the S-SpMM in a whole step (Eq. 4 on every aggregation), against the oracle."""
+    src, dst, n, dims, x, y = _sage_case(name)
+    say(f"GCN with dropout masks {name} dims={dims}")
+    seed, keep = 4242, 0.5
+    L = len(dims) - 1
+    ws = [gg.glorot(gg.MASTER_SEED, 10 + l, dims[l], dims[l + 1]) for l in range(L)]
+    og = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n)))
+    ref = oracle.gcn_dropout_step(og, x, ws, y, seed, keep)
+    g = _gpu_graph(mg, src, dst, n)
+    st = mg.GCNDropoutStep(g, dev(x), [dev(w) for w in ws], dev(y), seed, keep)
+    st.step()
+    torch.cuda.synchronize()
+    assert abs(st.loss.item() - ref["loss"]) <= 1e-5 * abs(ref["loss"])
+    assert_close(st.h[L].cpu().numpy(), ref["logits"], RTOL_F32, "logits")
+    hs = [h.cpu().numpy() for h in st.h]
+    _grad_close(f"dW[{L - 1}]", st.dw[L - 1].cpu().numpy(), ref["dW"][L - 1], 0)
+    for l in range(L - 1):
+        fl = _flips(hs[l + 1:L], ref["H"][l + 1:L], name)
+        _grad_close(f"dW[{l}]", st.dw[l].cpu().numpy(), ref["dW"][l], fl)
+    g.free()
+
+
 def test_aggregate_masked_backward_use_matches_mask_after_aggregate(mg, rmat15):
     """The backward use: dP = (A_hat^T dZ) (.) 1[H > 0] in one pass equals the plain aggregation
     followed by the ReLU-derivative mask, bit for bit."""
