@@ -161,8 +161,8 @@ int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void
  * mixgcn_aggregate with an epilogue (MIXGCN_EPI_* flags, 0 = none), for the layer forms that
  * combine a node's own features with the aggregate (GraphSAGE's concatenation, whose backward
  * pass is dH = dX_self + A_hat^T dX_neigh):
- *   ACCUMULATE adds the row sums to what Z holds (rows without stored entries keep their value);
- *   RELU clamps the result at zero.
+ *   ACCUMULATE adds the row sums to what Z holds (a row without stored entries adds nothing);
+ *   RELU clamps the result at zero, also on the rows without entries.
  * H and Z may be two column blocks of ONE row-major buffer: same ld, and the column ranges
  * [0, col_end) counted from the H pointer and from the Z pointer do not meet within a row
  * (H = X, Z = X + F with F >= col_end rounded up to a whole 16-byte group, 2 F <= ld).

@@ -884,6 +884,13 @@ def test_aggregate_accumulate_with_empty_rows_and_transpose(mg):
         mg.aggregate(g, dev(h), z, transpose=tr, accumulate=True)
         ref = z0 + oracle.spmm(og, h.astype(np.float64), transposed=tr)
         assert_close(z.cpu().numpy(), ref, RTOL_F32, f"accumulate transpose={tr}")
+        # with the ReLU as well: a row without entries still has its own value clamped
+        z = dev(z0)
+        mg.aggregate(g, dev(h), z, transpose=tr, accumulate=True, relu=True)
+        got = z.cpu().numpy()
+        assert_close(got, np.maximum(ref, 0), RTOL_F32, f"accumulate + relu transpose={tr}")
+        empty = np.diff(og.t_rowptr if tr else og.rowptr) == 0
+        assert np.array_equal(got[empty], np.maximum(z0[empty], 0))
     g.free()
 
 
