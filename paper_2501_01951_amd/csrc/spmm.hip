@@ -383,34 +383,36 @@ __global__ __launch_bounds__(kBlock) void aggregate_fixup_kernel(
     F::store(Z, r * ldz + (int64_t)c0 + (int64_t)lg * VEC, acc);
 }
 
-// Rows without stored entries get no visit from the main kernel.  clamp_only = 0: every cell of
-// the range is zeroed first (rows with entries are overwritten afterwards).  clamp_only = 1
-// (accumulate with ReLU): Z = max(Z + 0, 0) on the rows that have no entries, nothing else.
+// Rows without stored entries get no visit from the main kernel: they are set here, to zero, or
+// (clamp_only, the accumulating call with ReLU) to max(Z, 0).  A thread looks at one row; the
+// wavefront then writes each of its empty rows together, 64 columns at a time, so a graph with
+// few empty rows costs one pass over the row pointers and a graph of mostly empty rows is
+// written with whole lines.
 template <int DT>
-__global__ __launch_bounds__(kBlock) void zero_rows_kernel(const int64_t* __restrict__ rowptr,
-                                                           void* Z, int64_t ldz, int c0, int width,
-                                                           int64_t row_begin, int64_t row_end,
-                                                           int clamp_only)
+__global__ __launch_bounds__(kBlock) void empty_rows_kernel(const int64_t* __restrict__ rowptr,
+                                                            void* Z, int64_t ldz, int c0, int width,
+                                                            int64_t row_begin, int64_t row_end,
+                                                            int clamp_only)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t rows = row_end - row_begin;
-    if (i >= rows * width) return;
-    const int64_t r = row_begin + i / width;
-    const int c = c0 + (int)(i % width);
-    if (clamp_only) {
-        if (rowptr[r + 1] != rowptr[r]) return;
-        if (DT == MIXGCN_F32) {
-            float* p = reinterpret_cast<float*>(Z) + r * ldz + c;
-            *p = fmaxf(*p, 0.f);
-        } else {
-            uint16_t* p = reinterpret_cast<uint16_t*>(Z) + r * ldz + c;
-            const float x = __uint_as_float((uint32_t)*p << 16);
-            if (!(x > 0.f)) *p = 0;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t r = row_begin + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool empty = r < row_end && rowptr[r + 1] == rowptr[r];
+    uint64_t m = __ballot(empty);
+    const int64_t wave_row0 = r - lane;
+    while (m) {
+        const int b = (int)__ffsll((unsigned long long)m) - 1;
+        m &= m - 1;
+        const int64_t rr = wave_row0 + b;
+        for (int c = c0 + lane; c < c0 + width; c += kWave) {
+            if (DT == MIXGCN_F32) {
+                float* p = reinterpret_cast<float*>(Z) + rr * ldz + c;
+                *p = clamp_only ? fmaxf(*p, 0.f) : 0.f;
+            } else {
+                uint16_t* p = reinterpret_cast<uint16_t*>(Z) + rr * ldz + c;
+                if (!clamp_only || !(__uint_as_float((uint32_t)*p << 16) > 0.f)) *p = 0;
+            }
         }
-        return;
     }
-    if (DT == MIXGCN_F32) reinterpret_cast<float*>(Z)[r * ldz + c] = 0.f;
-    else reinterpret_cast<uint16_t*>(Z)[r * ldz + c] = 0;
 }
 
 // Entries per span of a pass: kBatchesPerSpan batches, halved while the launch would have fewer
@@ -496,12 +498,10 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const uint2* cv, const void* 
     constexpr int kMaxTile = 64 * VEC;  // widest pass
     // an empty row adds nothing to an accumulating call, but a ReLU still clamps what it holds
     const bool acc_only = (relu & kEpiAccumulate) && !(relu & kEpiRelu);
-    if (m.has_empty_rows && !acc_only) {
-        const int64_t cells = (r1 - r0) * (int64_t)(c1 - c0);
-        hipLaunchKernelGGL((zero_rows_kernel<DT>), dim3((unsigned)ceil_div(cells, kBlock)),
+    if (m.has_empty_rows && !acc_only && r1 > r0)
+        hipLaunchKernelGGL((empty_rows_kernel<DT>), dim3((unsigned)ceil_div(r1 - r0, kBlock)),
                            dim3(kBlock), 0, s, m.rowptr, Z, ldz, c0, c1 - c0, r0, r1,
                            (relu & kEpiAccumulate) ? 1 : 0);
-    }
     const int64_t e0 = m.h_rowptr[(size_t)r0], e1 = m.h_rowptr[(size_t)r1];
     if (e1 <= e0) return MIXGCN_OK;
     // span length and width class of every pass; the scratch for the row pieces is sized for
