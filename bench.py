@@ -399,7 +399,8 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": f"{args.config}: {len(dims) - 1}-layer GCN {'-'.join(map(str, dims))}, one "
-                        f"fwd+bwd epoch, R-MAT graph N={n}, nnz(A_hat)={nnz}",
+                        f"fwd+bwd epoch, {'Erdos-Renyi' if args.config == 'c1' else 'R-MAT'} graph "
+                        f"N={n}, nnz(A_hat)={nnz}",
             "n_nodes": n, "nnz": nnz, "row_chunks": args.chunks, "seed": args.seed,
             "hip_graph": bool(args.hip_graph),
         },
