@@ -148,3 +148,14 @@ def test_pipelined_calls_reject_bad_arguments_without_a_gpu():
     assert lib.mixgcn_forward_pipelined(None, 0, None, None, None, None, None, 0, None) == -1
     assert lib.mixgcn_backward_pipelined(None, 1, None, None, None, None, None, None, None, None, 0,
                                          None) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: bench.py --gpus 2 exits with a message (before touching torch)."""
+    import subprocess
+    import sys
+
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=60)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
