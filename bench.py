@@ -172,7 +172,8 @@ def bench_single_layer(args, mg, dev):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"{what}, N={n}, nnz(A_hat)={nnz}", "n_nodes": n, "nnz": nnz},
+        "config": {"workload": f"{what}, N={n}, nnz(A_hat)={nnz}", "n_nodes": n, "nnz": nnz,
+                   "update_arith": args.update_arith},
         "kernels": kinds,
         "roofline": {"bound": "hbm", "achieved": algo / (agg_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": algo / (agg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -238,7 +239,7 @@ def bench_variant(args, mg, dev):
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.config} graph: 3-layer {name} {'-'.join(map(str, dims))}, one "
                                f"fwd+bwd epoch, N={n}, nnz(A_hat)={nnz}",
-                   "n_nodes": n, "nnz": nnz, "seed": args.seed},
+                   "n_nodes": n, "nnz": nnz, "seed": args.seed, "update_arith": args.update_arith},
         "loss": loss,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
@@ -286,6 +287,10 @@ def main():
     ap.add_argument("--hip-graph", action="store_true",
                     help="record the step into a HIP graph and time its replays (one stream, no "
                          "per-kernel events): for small inputs, where launches dominate")
+    ap.add_argument("--update-arith", default="fp32", choices=["fp32", "bf16x3"],
+                    help="matrix-core arithmetic of the update products of fp32 features: fp32 MFMA "
+                         "(the benchmark line) or three bf16 terms per operand, six bf16 MFMAs per "
+                         "product (forward and data gradient of wide layers)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no collectives are part of it); "
@@ -299,6 +304,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     mg.load_library()
     torch.cuda.set_device(0)
+    mg.set_update_arith(mg.ARITH_BF16X3 if args.update_arith == "bf16x3" else mg.ARITH_FP32)
 
     def dev(a):
         return torch.from_numpy(np.ascontiguousarray(a)).cuda()
@@ -402,7 +408,7 @@ def main():
                         f"fwd+bwd epoch, {'Erdos-Renyi' if args.config == 'c1' else 'R-MAT'} graph "
                         f"N={n}, nnz(A_hat)={nnz}",
             "n_nodes": n, "nnz": nnz, "row_chunks": args.chunks, "seed": args.seed,
-            "hip_graph": bool(args.hip_graph),
+            "hip_graph": bool(args.hip_graph), "update_arith": args.update_arith,
         },
         "loss": loss, "build_csr_normalize_ms": t_build * 1e3, "kernels": kinds,
         "roofline": roofline,

@@ -74,6 +74,13 @@ enum {
     MIXGCN_OP_WGRAD = 3     /* C[k x m] = beta C + A[n x k]^T (B (.) 1[R > 0])[n x m]        */
 };
 
+/* mixgcn_set_update_arith: how the update products of fp32 features use the matrix cores */
+enum {
+    MIXGCN_ARITH_FP32 = 0,  /* fp32 MFMA (the default)                                        */
+    MIXGCN_ARITH_BF16X3 = 1 /* every fp32 operand as the exact sum of three bf16 terms, six   */
+                            /* bf16 MFMAs per product, fp32 accumulation                      */
+};
+
 typedef struct mixgcn_graph mixgcn_graph;
 typedef struct mixgcn_pipeline mixgcn_pipeline;
 
@@ -228,6 +235,18 @@ int mixgcn_apply_bitmap(int dtype, void* X, int64_t ldx, int64_t n_rows, int32_t
 int mixgcn_update(int op, int dtype, const void* A, int64_t lda, const void* B, int64_t ldb,
                   void* C, int64_t ldc, int64_t n_rows, int32_t k, int32_t m,
                   const void* relu_ref, int64_t ldr, float beta, void* stream);
+
+/*
+ * Chooses the arithmetic of the update products (Algorithm 2, update phase) for fp32 features in
+ * every later call of this process, whichever entry point launches them; bf16 features are not
+ * affected.  MIXGCN_ARITH_BF16X3 applies to the forward product and the data gradient when the
+ * reduction depth (k forward, m backward) is a multiple of 16 and the pitches are below 2^22
+ * elements; every other product keeps the fp32 MFMA.  Its error per product term is bounded by
+ * 2^-23 |a| |b| (the three dropped partial products), the size of an fp32 rounding; non-finite
+ * inputs give NaN where the fp32 path gives an infinity.  Not thread safe: set it before
+ * launching work.  MIXGCN_EINVAL for an unknown mode.
+ */
+int mixgcn_set_update_arith(int mode);
 
 /*
  * One layer forward, Eq. 3.

@@ -5,12 +5,12 @@ is computed in Python: the wrappers only marshal pointers, sizes and streams.  t
 for device memory and streams.  There is no CPU fallback: a missing library is an error.
 """
 from .binding import (  # noqa: F401
-    AGG_FIRST, UPDATE_FIRST, BF16, F32, NORM_SYM, NORM_MEAN, NORM_SUM, EPI_RELU, EPI_ACCUMULATE, OP_DGRAD, OP_FWD, OP_FWD_RELU, OP_WGRAD, SYMMETRIZE, ADD_SELF_LOOPS,
+    AGG_FIRST, UPDATE_FIRST, BF16, F32, NORM_SYM, NORM_MEAN, NORM_SUM, EPI_RELU, EPI_ACCUMULATE, ARITH_FP32, ARITH_BF16X3, OP_DGRAD, OP_FWD, OP_FWD_RELU, OP_WGRAD, SYMMETRIZE, ADD_SELF_LOOPS,
     BUILD_TRANSPOSE, INPUT_ON_HOST, Graph, LayerDesc, MixGCNError, Pipeline, aggregate, aggregate_masked,
     apply_bitmap,
     backward_pipelined, bandwidth, build_csr, dropout_bitmap, forward_pipelined, pipeline_window,
     cu_subset_stream,
     layer_bwd, layer_fwd, lib_path, load_library, measure_peaks, normalize, permute_rows, pipeline_stages, relabel_edges,
-    relu_bitmap, reorder_rcm, softmax_xent, update, version,
+    relu_bitmap, reorder_rcm, set_update_arith, softmax_xent, update, version,
 )
 from .model import GCNDropoutStep, GCNStep, GINStep, SAGEStep  # noqa: F401

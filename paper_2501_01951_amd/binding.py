@@ -16,6 +16,7 @@ OP_FWD, OP_FWD_RELU, OP_DGRAD, OP_WGRAD = 0, 1, 2, 3
 SYMMETRIZE, ADD_SELF_LOOPS, BUILD_TRANSPOSE, INPUT_ON_HOST = 1, 2, 4, 8
 NORM_SYM, NORM_MEAN, NORM_SUM = 0, 1, 2
 EPI_RELU, EPI_ACCUMULATE = 1, 2
+ARITH_FP32, ARITH_BF16X3 = 0, 1
 AGG_FIRST, UPDATE_FIRST = 0, 1
 
 
@@ -98,6 +99,8 @@ def load_library():
                                            ctypes.POINTER(ctypes.c_int32),
                                            ctypes.POINTER(ctypes.c_int32)]
     lib.mixgcn_softmax_xent.argtypes = [ctypes.c_int, vp, i64, vp, i64, i32, vp, i64, vp, vp]
+    lib.mixgcn_set_update_arith.argtypes = [ctypes.c_int]
+    lib.mixgcn_set_update_arith.restype = ctypes.c_int
     lib.mixgcn_graph_info.argtypes = [vp, ctypes.POINTER(_GraphView)]
     lib.mixgcn_graph_free.argtypes = [vp]
     lib.mixgcn_pipeline_create.argtypes = [vp, vp, ctypes.POINTER(vp)]
@@ -470,6 +473,11 @@ def pipeline_window(n_nodes: int, n_chunks: int, bandwidth: int, chunk: int):
                                                  ctypes.byref(f), ctypes.byref(l)),
            "pipeline_window")
     return r0.value, r1.value, f.value, l.value
+
+
+def set_update_arith(mode: int) -> None:
+    """ARITH_FP32 (default) or ARITH_BF16X3 for the update products of fp32 features."""
+    _check(load_library().mixgcn_set_update_arith(mode), "set_update_arith")
 
 
 def softmax_xent(logits, labels, dlogits, loss, stream=None) -> None:

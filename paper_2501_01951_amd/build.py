@@ -13,7 +13,7 @@ CSRC = os.path.join(_HERE, "csrc")
 BUILD_DIR = os.path.join(_HERE, "_build")
 LIB_PATH = os.path.join(_HERE, "libmixgcn.so")
 
-SOURCES = ["abi.hip", "scan.hip", "sort.hip", "csr.hip", "spmm.hip", "gemm.hip", "gemm_bf16.hip",
+SOURCES = ["abi.hip", "scan.hip", "sort.hip", "csr.hip", "spmm.hip", "gemm.hip", "gemm_bf16.hip", "gemm_split.hip",
            "loss.hip", "peaks.hip", "reorder.hip"]
 
 HIPCC_FLAGS = [

@@ -15,6 +15,8 @@ namespace mixgcn {
 
 static thread_local std::string g_last_error;
 
+int g_update_arith = MIXGCN_ARITH_FP32;
+
 void set_error(const std::string& msg) { g_last_error = msg; }
 int fail(int code, const std::string& msg)
 {
@@ -400,6 +402,14 @@ int mixgcn_update(int op, int dtype, const void* A, int64_t lda, const void* B, 
 {
     return update_impl(op, dtype, A, lda, B, ldb, C, ldc, n_rows, k, m, relu_ref, ldr, beta,
                        (hipStream_t)stream, nullptr);
+}
+
+int mixgcn_set_update_arith(int mode)
+{
+    if (mode != MIXGCN_ARITH_FP32 && mode != MIXGCN_ARITH_BF16X3)
+        return fail(MIXGCN_EINVAL, "set_update_arith: unknown mode");
+    g_update_arith = mode;
+    return MIXGCN_OK;
 }
 
 int mixgcn_softmax_xent(int dtype, const void* logits, int64_t ldl, const int32_t* labels,

@@ -767,6 +767,10 @@ int launch_update(int op, int dtype, const void* A, int64_t lda, const void* B, 
                   void* C, int64_t ldc, int64_t n, int32_t k, int32_t m, const void* R,
                   int64_t ldr, float beta, hipStream_t s, Timer* timer)
 {
+    if (dtype == MIXGCN_F32 && g_update_arith == MIXGCN_ARITH_BF16X3 &&
+        update_split_applies(op, lda, ldr, n, k, m))
+        return launch_update_split(op, (const float*)A, lda, (const float*)B, ldb, (float*)C, ldc, n,
+                                   k, m, (const float*)R, ldr, s, timer);
     if (dtype == MIXGCN_F32)
         return update_typed<float>(op, (const float*)A, lda, B, ldb, C, ldc, n, k, m,
                                    (const float*)R, ldr, beta, s, timer);

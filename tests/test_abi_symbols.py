@@ -58,6 +58,9 @@ def test_argument_errors_need_no_gpu():
     assert lib.mixgcn_graph_free(None) == 0
     assert lib.mixgcn_update(9, 0, None, 0, None, 0, None, 0, 1, 1, 1, None, 0, 0.0, None) == -1
     assert lib.mixgcn_update(0, 0, None, 4, None, 4, None, 4, 1, 4, 4, None, 0, 0.0, None) == -1
+    assert lib.mixgcn_set_update_arith(2) == -1 and b"set_update_arith" in lib.mixgcn_last_error()
+    assert lib.mixgcn_set_update_arith(m.ARITH_BF16X3) == 0
+    assert lib.mixgcn_set_update_arith(m.ARITH_FP32) == 0
 
 
 # ---- host arithmetic of the cross-layer pipeline (Sec. 3.2.2) -------------------------------
