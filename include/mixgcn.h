@@ -240,8 +240,9 @@ int mixgcn_update(int op, int dtype, const void* A, int64_t lda, const void* B, 
  * Chooses the arithmetic of the update products (Algorithm 2, update phase) for fp32 features in
  * every later call of this process, whichever entry point launches them; bf16 features are not
  * affected.  MIXGCN_ARITH_BF16X3 applies to the forward product and the data gradient when the
- * reduction depth (k forward, m backward) is a multiple of 16 and the pitches are below 2^22
- * elements; every other product keeps the fp32 MFMA.  Its error per product term is bounded by
+ * output is wider than 64 columns, the reduction depth (k forward, m backward) is a multiple of
+ * 16 and at least 64, and the pitches are below 2^22 elements; every other product keeps the
+ * fp32 MFMA.  Its error per product term is bounded by
  * 2^-23 |a| |b| (the three dropped partial products), the size of an fp32 rounding; non-finite
  * inputs give NaN where the fp32 path gives an infinity.  Not thread safe: set it before
  * launching work.  MIXGCN_EINVAL for an unknown mode.

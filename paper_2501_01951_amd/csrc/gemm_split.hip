@@ -355,9 +355,10 @@ bool update_split_applies(int op, int64_t lda, int64_t ldr, int64_t n, int32_t k
 {
     if (n <= 0) return false;
     if (lda >= (1 << 22) || ldr >= (1 << 22)) return false;  // 32-bit offsets inside a tile
-    // outputs of at most 64 columns are bound by their memory traffic on either path
-    if (op == MIXGCN_OP_FWD || op == MIXGCN_OP_FWD_RELU) return m > 64 && k % BKS == 0;
-    if (op == MIXGCN_OP_DGRAD) return k > 64 && m % BKS == 0;
+    // outputs of at most 64 columns and reductions of fewer than four steps are bound by their
+    // memory traffic on either path
+    if (op == MIXGCN_OP_FWD || op == MIXGCN_OP_FWD_RELU) return m > 64 && k >= 64 && k % BKS == 0;
+    if (op == MIXGCN_OP_DGRAD) return k > 64 && m >= 64 && m % BKS == 0;
     return false;
 }
 

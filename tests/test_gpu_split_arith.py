@@ -32,10 +32,11 @@ def split(mg):
         mg.set_update_arith(mg.ARITH_FP32)
 
 
-# (n, k, m): forward needs m > 64 and k % 16 == 0, the data gradient k > 64 and m % 16 == 0;
-# ragged row counts, one to many reduction steps, several column tiles, a ragged last column tile
+# (n, k, m): forward needs m > 64 and k a multiple of 16 from 64 up, the data gradient k > 64 and
+# the same of m; ragged row counts, 4 to 17 reduction steps (the loop takes two per trip and
+# finishes with one to three), several column tiles, a ragged last column tile
 SPLIT_SHAPES = [(1000, 64, 128), (2048, 128, 256), (4133, 256, 256), (130, 256, 256), (1, 128, 128),
-                (5000, 128, 1024), (777, 48, 160), (256, 16, 128), (384, 80, 144), (1500, 128, 172),
+                (5000, 128, 1024), (777, 96, 160), (256, 112, 128), (384, 80, 144), (1500, 128, 172),
                 (640, 176, 96), (129, 272, 80)]
 
 
@@ -133,7 +134,7 @@ def test_split_error_is_not_above_the_fp32_path(mg):
     assert errs["bf16x3"] <= 1.5 * errs["fp32"]
 
 
-@pytest.mark.parametrize("n,k,m", [(1000, 100, 128), (1000, 64, 32), (900, 128, 200)])
+@pytest.mark.parametrize("n,k,m", [(1000, 100, 128), (1000, 64, 32), (900, 128, 200), (500, 48, 128)])
 def test_products_outside_the_split_path_do_not_change(mg, n, k, m):
     """Reduction depths that are not whole steps, narrow outputs and the weight gradient keep the
     fp32 MFMA kernels: bit-identical results in both modes."""
@@ -146,11 +147,11 @@ def test_products_outside_the_split_path_do_not_change(mg, n, k, m):
             out = torch.empty(n, m, device="cuda")
             dz = torch.empty(n, k, device="cuda")
             dw = torch.empty(k, m, device="cuda")
-            if k % 16 or m <= 64:
+            if k % 16 or k < 64 or m <= 64:
                 mg.update(mg.OP_FWD_RELU, z, w, out, n, k, m)
             else:
                 out.zero_()
-            if m % 16 or k <= 64:
+            if m % 16 or m < 64 or k <= 64:
                 mg.update(mg.OP_DGRAD, gr, w, dz, n, k, m)
             else:
                 dz.zero_()
