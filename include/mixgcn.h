@@ -231,6 +231,10 @@ int mixgcn_apply_bitmap(int dtype, void* X, int64_t ldx, int64_t n_rows, int32_t
  *   beta       : WGRAD only, 0 or 1.
  * FWD, FWD_RELU, DGRAD: B is the weight matrix W[k x m], fp32, row-major.  WGRAD: A = Z
  * [n x k], B = the upstream gradient [n x m], C = dW [k x m] fp32.
+ * Two per-device work buffers are shared by all calls: the slab partials of WGRAD, and the weight
+ * terms of the products with W for bf16 features and under MIXGCN_ARITH_BF16X3.  Calls that use
+ * the same one must not overlap: issue them on one stream, or order the streams with events (the
+ * layer and pipeline entry points do).
  */
 int mixgcn_update(int op, int dtype, const void* A, int64_t lda, const void* B, int64_t ldb,
                   void* C, int64_t ldc, int64_t n_rows, int32_t k, int32_t m,
