@@ -105,8 +105,18 @@ def test_random_aggregations(mg, seed):
         g.free()
 
 
-@pytest.mark.parametrize("seed", [1, 2])
-def test_random_update_products(mg, seed):
+@pytest.mark.parametrize("seed,arith", [(1, "fp32"), (2, "fp32"), (3, "bf16x3"), (4, "bf16x3")])
+def test_random_update_products(mg, seed, arith):
+    """arith = bf16x3: the same sweep with the three-term bf16 arithmetic switched on, which the
+    wide fp32 products with whole reduction steps then take (the others must not care)."""
+    mg.set_update_arith(mg.ARITH_BF16X3 if arith == "bf16x3" else mg.ARITH_FP32)
+    try:
+        _random_update_products(mg, seed)
+    finally:
+        mg.set_update_arith(mg.ARITH_FP32)
+
+
+def _random_update_products(mg, seed):
     rng = np.random.default_rng(seed)
     ncase = 80
     for case in range(ncase):
