@@ -413,6 +413,23 @@ def main():
         "loss": loss, "build_csr_normalize_ms": t_build * 1e3, "kernels": kinds,
         "roofline": roofline,
     }
+    # the same steps with the opt-in update arithmetic (fp32 operands as three bf16 terms on the
+    # bf16 matrix cores), after and outside the timed region above: reported beside the result
+    if args.update_arith == "fp32" and not bf16 and not args.hip_graph:
+        mg.set_update_arith(mg.ARITH_BF16X3)
+        try:
+            for _ in range(2):
+                run_step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                run_step()
+            torch.cuda.synchronize()
+            dt3 = (time.perf_counter() - t0) / args.steps
+            out["with_update_arith_bf16x3"] = {"ms_per_step": dt3 * 1e3, "value": work / dt3,
+                                               "loss": step.loss.item()}
+        finally:
+            mg.set_update_arith(mg.ARITH_FP32)
     # what this device sustains on a plain copy and on register-only MFMA chains (outside the
     # timed region): context for the published peaks the fractions above are quoted against
     del step, calib_src, calib_dst
