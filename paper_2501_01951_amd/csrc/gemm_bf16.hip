@@ -4,7 +4,8 @@
 // Activations and gradients are bf16 in memory and enter the MFMA as they are.  Weights are
 // fp32: every call first splits W = hi + lo into two bf16 terms (|W - hi - lo| < 2^-16 |W|) in
 // the layout the B operand wants (output index major, reduction index contiguous, zero padded
-// to whole tiles), so a product with W is two MFMAs and keeps fp32-class weights.  The weight
+// to whole tiles, and tile by tile in the order the kernel walks them, so that a step's weights
+// are one dense block), so a product with W is two MFMAs and keeps fp32-class weights.  The weight
 // gradient multiplies two bf16 tensors and needs no split.
 //
 // MFMA 32x32x16 operand layout: lane l supplies A[i = l % 32][k = 8 (l / 32) + 0..7] and
@@ -46,10 +47,16 @@ __device__ inline unsigned xcd_local_index(unsigned bid, unsigned grid)
     return x * q + (x < rem ? x : rem) + bid / 8;
 }
 
-// out[j][kk] = transpose ? W[kk][j] : W[j][kk], zero outside W, as bf16 hi and lo parts.
+// Operand element (j, kk) = transpose ? W[kk][j] : W[j][kk], zero outside W, as bf16 hi and lo
+// parts, in the order the row-block kernel walks them: [column tile j / bn][step kk / BKB]
+// [j % bn][kk % BKB], so that the weights of one step of one tile are bn * 64 contiguous bytes.
+__device__ __host__ inline size_t split_weight_index(int j, int kk, int bn, int n_steps)
+{
+    return (((size_t)(j / bn) * n_steps + kk / BKB) * bn + j % bn) * BKB + kk % BKB;
+}
 __global__ __launch_bounds__(kBlock) void split_weights_kernel(
     const float* __restrict__ W, int64_t ldw, int rows_w, int cols_w, int transpose,
-    uint16_t* __restrict__ hi, uint16_t* __restrict__ lo, int out_rows, int out_cols)
+    uint16_t* __restrict__ hi, uint16_t* __restrict__ lo, int out_rows, int out_cols, int bn)
 {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= out_rows * out_cols) return;
@@ -58,8 +65,9 @@ __global__ __launch_bounds__(kBlock) void split_weights_kernel(
     const float x = (r < rows_w && c < cols_w) ? W[(int64_t)r * ldw + c] : 0.f;
     const uint16_t h = bf16_rne(x);
     const float rest = x - __uint_as_float((uint32_t)h << 16);
-    hi[idx] = h;
-    lo[idx] = (rest == rest && fabsf(rest) <= 3.0e38f) ? bf16_rne(rest) : (uint16_t)0;
+    const size_t o = split_weight_index(j, kk, bn, out_cols / BKB);
+    hi[o] = h;
+    lo[o] = (rest == rest && fabsf(rest) <= 3.0e38f) ? bf16_rne(rest) : (uint16_t)0;
 }
 
 // Eight bf16 of a feature tile on their way from global memory to LDS: issue() starts the
@@ -149,18 +157,19 @@ struct FastStage {
     bool b_on[B_PASSES];
     uint4 a[A_PASSES], r[A_PASSES], bh[B_PASSES], bl[B_PASSES];
 
-    __device__ inline void init(int tid, uint32_t pitch_a, uint32_t pitch_r, uint32_t pitch_b)
+    static constexpr uint32_t kPitchB = BKB * 2;  // a weight tile of one step is dense
+    __device__ inline void init(int tid, uint32_t pitch_a, uint32_t pitch_r)
     {
         const int prow = tid / 4, pk = 8 * (tid & 3);
         aoff = (uint32_t)prow * pitch_a + 2u * pk;
         roff = (uint32_t)prow * pitch_r + 2u * pk;
-        boff = (uint32_t)prow * pitch_b + 2u * pk;
+        boff = (uint32_t)prow * kPitchB + 2u * pk;
         lpos = prow * LDT + pk;
 #pragma unroll
         for (int p = 0; p < B_PASSES; ++p) b_on[p] = p * 64 + prow < S::BN;
     }
     __device__ inline void load(const char* a0, const char* r0, const char* bh0, const char* bl0,
-                                size_t pitch_a, size_t pitch_r, size_t pitch_b)
+                                size_t pitch_a, size_t pitch_r)
     {
 #pragma unroll
         for (int p = 0; p < A_PASSES; ++p) {
@@ -170,8 +179,8 @@ struct FastStage {
 #pragma unroll
         for (int p = 0; p < B_PASSES; ++p)
             if (b_on[p]) {
-                bh[p] = *reinterpret_cast<const uint4*>(bh0 + p * 64 * pitch_b + boff);
-                bl[p] = *reinterpret_cast<const uint4*>(bl0 + p * 64 * pitch_b + boff);
+                bh[p] = *reinterpret_cast<const uint4*>(bh0 + p * 64 * kPitchB + boff);
+                bl[p] = *reinterpret_cast<const uint4*>(bl0 + p * 64 * kPitchB + boff);
             }
     }
     __device__ inline void store(uint16_t* as, uint16_t* bhs, uint16_t* bls) const
@@ -197,8 +206,8 @@ struct FastStage {
 };
 
 // ---- row-block kernel: C[n x MD] = (A (.) 1[R > 0])[n x KD] * Bop[KD x MD] ---------------------
-// Bop is given split and transposed: Bh/Bl[j][kk], j < n_col_tiles * BN, kk < ldb (a multiple of
-// BKB), zero outside the weights.
+// Bop is given split, in the order of split_weights_kernel (bn = BN): j < n_col_tiles * BN,
+// kk < ldb (a multiple of BKB), zero outside the weights.
 template <class S, bool RELU, bool MASK>
 __global__ __launch_bounds__(kBlock) void rowblock_bf16_kernel(
     const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ Bh,
@@ -236,7 +245,7 @@ __global__ __launch_bounds__(kBlock) void rowblock_bf16_kernel(
 #pragma unroll
         for (int p = 0; p < B_PASSES; ++p) {
             const int j = p * 64 + prow;
-            const int64_t off = (int64_t)(col0 + (j < S::BN ? j : 0)) * ldb + k0 + pk;
+            const size_t off = split_weight_index(col0 + (j < S::BN ? j : 0), k0 + pk, S::BN, ldb / BKB);
             rbh[p] = *reinterpret_cast<const uint4*>(Bh + off);
             rbl[p] = *reinterpret_cast<const uint4*>(Bl + off);
         }
@@ -284,14 +293,15 @@ __global__ __launch_bounds__(kBlock) void rowblock_bf16_kernel(
     const bool fast = row0 + S::BM <= n && KD % BKB == 0 && lda < (1 << 22) && ldr < (1 << 22);
     if (fast) {
         FastStage<S, MASK> st;
-        st.init(tid, (uint32_t)lda * 2u, (uint32_t)ldr * 2u, (uint32_t)ldb * 2u);
+        st.init(tid, (uint32_t)lda * 2u, (uint32_t)ldr * 2u);
         const char* a0 = reinterpret_cast<const char*>(A + row0 * lda);
         const char* r0 = MASK ? reinterpret_cast<const char*>(R + row0 * ldr) : nullptr;
-        const char* bh0 = reinterpret_cast<const char*>(Bh + (int64_t)col0 * ldb);
-        const char* bl0 = reinterpret_cast<const char*>(Bl + (int64_t)col0 * ldb);
+        const size_t tile0 = split_weight_index(col0, 0, S::BN, ldb / BKB);
+        const char* bh0 = reinterpret_cast<const char*>(Bh + tile0);
+        const char* bl0 = reinterpret_cast<const char*>(Bl + tile0);
         auto load = [&](int step) {
-            const size_t o = (size_t)step * (BKB * 2);
-            st.load(a0 + o, r0 + o, bh0 + o, bl0 + o, (size_t)lda * 2, (size_t)ldr * 2, (size_t)ldb * 2);
+            const size_t o = (size_t)step * (BKB * 2), ob = (size_t)step * (S::BN * BKB * 2);
+            st.load(a0 + o, r0 + o, bh0 + ob, bl0 + ob, (size_t)lda * 2, (size_t)ldr * 2);
         };
         // two steps per trip, so that the LDS buffer of every access is known at compile time
         load(0);
@@ -492,7 +502,7 @@ int launch_rowblock_bf16(bool relu, const uint16_t* A, int64_t lda, const float*
     uint16_t* lo = hi + (size_t)out_rows * out_cols;
     hipLaunchKernelGGL(split_weights_kernel, dim3((unsigned)ceil_div(out_rows * out_cols, kBlock)),
                        dim3(kBlock), 0, s, W, ldw, w_rows, w_cols, transpose_w ? 1 : 0, hi, lo,
-                       out_rows, out_cols);
+                       out_rows, out_cols, S::BN);
 #define MIXGCN_ROWBLOCK(RELU, MASK)                                                              \
     hipLaunchKernelGGL((rowblock_bf16_kernel<S, RELU, MASK>), dim3((unsigned)grid), dim3(kBlock), \
                        0, s, A, lda, hi, lo, out_cols, C, ldc, n, red_dim, out_dim, R, ldr, nct)
