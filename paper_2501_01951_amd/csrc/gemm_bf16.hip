@@ -163,7 +163,8 @@ struct FastStage {
         const int prow = tid / 4, pk = 8 * (tid & 3);
         aoff = (uint32_t)prow * pitch_a + 2u * pk;
         roff = (uint32_t)prow * pitch_r + 2u * pk;
-        boff = (uint32_t)prow * kPitchB + 2u * pk;
+        // threads beyond a narrow weight tile load a row of it again and store nothing
+        boff = (uint32_t)(prow % S::BN) * kPitchB + 2u * pk;
         lpos = prow * LDT + pk;
 #pragma unroll
         for (int p = 0; p < B_PASSES; ++p) b_on[p] = p * 64 + prow < S::BN;
@@ -177,11 +178,10 @@ struct FastStage {
             if (MASK) r[p] = *reinterpret_cast<const uint4*>(r0 + p * 64 * pitch_r + roff);
         }
 #pragma unroll
-        for (int p = 0; p < B_PASSES; ++p)
-            if (b_on[p]) {
-                bh[p] = *reinterpret_cast<const uint4*>(bh0 + p * 64 * kPitchB + boff);
-                bl[p] = *reinterpret_cast<const uint4*>(bl0 + p * 64 * kPitchB + boff);
-            }
+        for (int p = 0; p < B_PASSES; ++p) {
+            bh[p] = *reinterpret_cast<const uint4*>(bh0 + p * 64 * kPitchB + boff);
+            bl[p] = *reinterpret_cast<const uint4*>(bl0 + p * 64 * kPitchB + boff);
+        }
     }
     __device__ inline void store(uint16_t* as, uint16_t* bhs, uint16_t* bls) const
     {
@@ -292,41 +292,73 @@ __global__ __launch_bounds__(kBlock) void rowblock_bf16_kernel(
     // every row of the tile exists, whole reduction steps, 32-bit offsets inside a tile
     const bool fast = row0 + S::BM <= n && KD % BKB == 0 && lda < (1 << 22) && ldr < (1 << 22);
     if (fast) {
-        FastStage<S, MASK> st;
-        st.init(tid, (uint32_t)lda * 2u, (uint32_t)ldr * 2u);
+        // Global loads run two steps ahead of their LDS writes, in two register sets: at eight or
+        // fewer steps per tile the kernel lives on the bytes it keeps in flight.  Loads beyond the
+        // last step repeat it (never stored), so that no load is conditional and the wait for one
+        // set can leave the other set's loads in flight.  Two steps per trip keep the LDS buffer
+        // and the register set of every access known at compile time.
+        FastStage<S, MASK> st0, st1;
+        st0.init(tid, (uint32_t)lda * 2u, (uint32_t)ldr * 2u);
+        st1.init(tid, (uint32_t)lda * 2u, (uint32_t)ldr * 2u);
         const char* a0 = reinterpret_cast<const char*>(A + row0 * lda);
         const char* r0 = MASK ? reinterpret_cast<const char*>(R + row0 * ldr) : nullptr;
         const size_t tile0 = split_weight_index(col0, 0, S::BN, ldb / BKB);
         const char* bh0 = reinterpret_cast<const char*>(Bh + tile0);
         const char* bl0 = reinterpret_cast<const char*>(Bl + tile0);
-        auto load = [&](int step) {
-            const size_t o = (size_t)step * (BKB * 2), ob = (size_t)step * (S::BN * BKB * 2);
+        auto load = [&](FastStage<S, MASK>& st, int step) {
+            const size_t sc = (size_t)(step < nk ? step : nk - 1);
+            const size_t o = sc * (BKB * 2), ob = sc * (S::BN * BKB * 2);
             st.load(a0 + o, r0 + o, bh0 + ob, bl0 + ob, (size_t)lda * 2, (size_t)ldr * 2);
         };
-        // two steps per trip, so that the LDS buffer of every access is known at compile time
-        load(0);
-        st.store(As[0], Bhs[0], Bls[0]);
-        __syncthreads();
-        int i = 0;
-        while (i + 2 < nk) {
-            load(i + 1);
+        if constexpr (S::BN >= 128) {
+            load(st0, 0);
+            load(st1, 1);
+            st0.store(As[0], Bhs[0], Bls[0]);
+            load(st0, 2);
+            __syncthreads();
+            int i = 0;
+            for (; i + 2 < nk; i += 2) {
+                mma_step(As[0], Bhs[0], Bls[0]);
+                st1.store(As[1], Bhs[1], Bls[1]);
+                load(st1, i + 3);
+                __syncthreads();
+                mma_step(As[1], Bhs[1], Bls[1]);
+                st0.store(As[0], Bhs[0], Bls[0]);
+                load(st0, i + 4);
+                __syncthreads();
+            }
             mma_step(As[0], Bhs[0], Bls[0]);
-            st.store(As[1], Bhs[1], Bls[1]);
-            __syncthreads();
-            load(i + 2);
-            mma_step(As[1], Bhs[1], Bls[1]);
-            st.store(As[0], Bhs[0], Bls[0]);
-            __syncthreads();
-            i += 2;
-        }
-        if (i + 1 < nk) {
-            load(i + 1);
-            mma_step(As[0], Bhs[0], Bls[0]);
-            st.store(As[1], Bhs[1], Bls[1]);
-            __syncthreads();
-            mma_step(As[1], Bhs[1], Bls[1]);
+            if (nk - i == 2) {
+                st1.store(As[1], Bhs[1], Bls[1]);
+                __syncthreads();
+                mma_step(As[1], Bhs[1], Bls[1]);
+            }
         } else {
-            mma_step(As[0], Bhs[0], Bls[0]);
+            // narrow outputs are bound by their memory traffic and run faster with the wavefronts
+            // that the second register set would cost: one step ahead, one set
+            load(st0, 0);
+            st0.store(As[0], Bhs[0], Bls[0]);
+            __syncthreads();
+            int i = 0;
+            for (; i + 2 < nk; i += 2) {
+                load(st0, i + 1);
+                mma_step(As[0], Bhs[0], Bls[0]);
+                st0.store(As[1], Bhs[1], Bls[1]);
+                __syncthreads();
+                load(st0, i + 2);
+                mma_step(As[1], Bhs[1], Bls[1]);
+                st0.store(As[0], Bhs[0], Bls[0]);
+                __syncthreads();
+            }
+            if (nk - i == 2) {
+                load(st0, i + 1);
+                mma_step(As[0], Bhs[0], Bls[0]);
+                st0.store(As[1], Bhs[1], Bls[1]);
+                __syncthreads();
+                mma_step(As[1], Bhs[1], Bls[1]);
+            } else {
+                mma_step(As[0], Bhs[0], Bls[0]);
+            }
         }
     } else {
         issue_tiles(0);
