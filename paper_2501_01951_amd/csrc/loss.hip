@@ -57,6 +57,21 @@ __global__ __launch_bounds__(kBlock) void xent_rows_kernel(const T* logits, int6
         const bool live = r < r_end;
         const int64_t rr = live ? r : r_end - 1;  // idle groups redo the last row, write nothing
         const T* x = logits + rr * ldl;
+        if (c <= G) {
+            // one class per lane: the row is read once and stays in registers
+            const bool has = gl < c;
+            const float v = has ? ld_elem(x + gl) : -INFINITY;
+            const float mx = group_max<G>(v);
+            const float se = group_sum<G>(has ? expf(v - mx) : 0.f);
+            const float lse = mx + logf(se);
+            const int y = labels[rr];
+            const float xy = __shfl(v, gi * G + y, kWave);
+            if (live) {
+                if (has) st_elem(dlogits + r * ldd + gl, (expf(v - lse) - (gl == y ? 1.f : 0.f)) * inv_n);
+                if (gl == 0) acc += (double)(lse - xy);
+            }
+            continue;
+        }
         float mx = -INFINITY;
         for (int j = gl; j < c; j += G) mx = fmaxf(mx, ld_elem(x + j));
         mx = group_max<G>(mx);
