@@ -1296,3 +1296,47 @@ def test_config4_full_size_graph_and_aggregation(mg):
     mg.aggregate(g, dev(r4), z4)
     np.testing.assert_allclose(z4.cpu().numpy(), r4, rtol=3e-5)
     g.free()
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_update_with_pitches_beyond_32_bit_tile_offsets(mg, bf16):
+    """The fast paths of the update kernels address a tile with 32-bit offsets from a scalar base
+    and therefore only take pitches below 2^22 elements; beyond that the generic paths must give
+    the same bits as the packed case (the arithmetic does not depend on the pitch).  The
+    three-term bf16 arithmetic has the same limit and hands such operands to the fp32 MFMA
+    kernels: switched on, it must give the fp32 path's bits here."""
+    n, k, m = 300, 64, 128
+    big = (1 << 22) + 8
+    say(f"update with pitch {big}, bf16={bf16}")
+    dt = torch.bfloat16 if bf16 else torch.float32
+    w = dev(gg.glorot(91, 2, k, m))
+    zp, gp = dev(gg.normal(91, 1, n, k)).to(dt), dev(gg.normal(91, 3, n, m)).to(dt)
+
+    def pitched(t):
+        buf = torch.empty(n, big, dtype=dt, device="cuda")
+        buf[:, :t.shape[1]] = t
+        return buf[:, :t.shape[1]]
+
+    h = torch.empty(n, m, dtype=dt, device="cuda")
+    mg.update(mg.OP_FWD_RELU, zp, w, h, n, k, m)
+    dz = torch.empty(n, k, dtype=dt, device="cuda")
+    mg.update(mg.OP_DGRAD, gp, w, dz, n, k, m, relu_ref=h)
+    dw = torch.empty(k, m, device="cuda")
+    mg.update(mg.OP_WGRAD, zp, gp, dw, n, k, m, relu_ref=h)
+    zb, gb, hb = pitched(zp), pitched(gp), pitched(h)
+    try:
+        for arith in (mg.ARITH_FP32, mg.ARITH_BF16X3):
+            mg.set_update_arith(arith)
+            h2 = pitched(torch.zeros(n, m, dtype=dt, device="cuda"))
+            mg.update(mg.OP_FWD_RELU, zb, w, h2, n, k, m)
+            assert torch.equal(h2, h), f"forward, arith {arith}"
+            dz2 = pitched(torch.zeros(n, k, dtype=dt, device="cuda"))
+            mg.update(mg.OP_DGRAD, gb, w, dz2, n, k, m, relu_ref=hb)
+            assert torch.equal(dz2, dz), f"dgrad, arith {arith}"
+            dw2 = torch.empty(k, m, device="cuda")
+            mg.update(mg.OP_WGRAD, zb, gb, dw2, n, k, m, relu_ref=hb)
+            assert torch.equal(dw2, dw), f"wgrad, arith {arith}"
+            del h2, dz2
+            torch.cuda.empty_cache()
+    finally:
+        mg.set_update_arith(mg.ARITH_FP32)
