@@ -613,8 +613,19 @@ __global__ __launch_bounds__(kBlock) void wgrad_reduce_kernel(const float* __res
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int64_t i = (int64_t)blockIdx.x * kWave + lane;
     double s = 0.0;
-    if (i < cells)
-        for (int64_t b = w; b < n_slabs; b += kBlock / kWave) s += (double)P[(size_t)b * cells + i];
+    if (i < cells) {
+        // eight loads in flight, added in the order of the plain loop
+        constexpr int kStep = kBlock / kWave;
+        int64_t b = w;
+        for (; b + 7 * kStep < n_slabs; b += 8 * kStep) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = P[(size_t)(b + u * kStep) * cells + i];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += (double)v[u];
+        }
+        for (; b < n_slabs; b += kStep) s += (double)P[(size_t)b * cells + i];
+    }
     part[w][lane] = s;
     __syncthreads();
     if (w == 0 && i < cells) {
