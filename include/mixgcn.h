@@ -248,7 +248,8 @@ int mixgcn_update(int op, int dtype, const void* A, int64_t lda, const void* B, 
  * 16 and at least 64, and the pitches are below 2^22 elements; every other product keeps the
  * fp32 MFMA.  Its error per product term is bounded by
  * 2^-23 |a| |b| (the three dropped partial products), the size of an fp32 rounding; non-finite
- * inputs give NaN where the fp32 path gives an infinity.  Not thread safe: set it before
+ * inputs, and magnitudes that round to infinity as bf16 (above 3.39e38), give NaN where the fp32
+ * path gives an infinity or a finite value.  Not thread safe: set it before
  * launching work.  MIXGCN_EINVAL for an unknown mode.
  */
 int mixgcn_set_update_arith(int mode);
