@@ -779,9 +779,21 @@ int launch_update(int op, int dtype, const void* A, int64_t lda, const void* B, 
                   int64_t ldr, float beta, hipStream_t s, Timer* timer)
 {
     if (dtype == MIXGCN_F32 && g_update_arith == MIXGCN_ARITH_BF16X3 &&
-        update_split_applies(op, lda, ldr, n, k, m))
-        return launch_update_split(op, (const float*)A, lda, (const float*)B, ldb, (float*)C, ldc, n,
-                                   k, m, (const float*)R, ldr, s, timer);
+        update_split_applies(op, lda, ldb, ldr, n, k, m)) {
+        const float* a = (const float*)A;
+        const float* b = (const float*)B;
+        const float* r = (const float*)R;
+        if (op != MIXGCN_OP_WGRAD)
+            return launch_update_split(op, a, lda, b, ldb, (float*)C, ldc, n, k, m, r, ldr, beta, s,
+                                       timer);
+        // whole steps of 16 node rows on the bf16 matrix cores, the last few rows on the fp32 ones
+        const int64_t n16 = n - n % 16;
+        MIXGCN_TRY(launch_update_split(op, a, lda, b, ldb, (float*)C, ldc, n16, k, m, r, ldr, beta, s,
+                                       timer));
+        if (n16 == n) return MIXGCN_OK;
+        return update_typed<float>(op, a + n16 * lda, lda, b + n16 * ldb, ldb, C, ldc, n - n16, k, m,
+                                   r ? r + n16 * ldr : nullptr, ldr, 1.f, s, nullptr);
+    }
     if (dtype == MIXGCN_F32)
         return update_typed<float>(op, (const float*)A, lda, B, ldb, C, ldc, n, k, m,
                                    (const float*)R, ldr, beta, s, timer);

@@ -321,6 +321,183 @@ __global__ __launch_bounds__(kBlock, 2) void rowblock_split_kernel(
         }
 }
 
+// ---- weight gradient: P[slab][KD x MD] = A[rows of slab][KD]^T * (B (.) 1[R > 0])[rows][MD] -----
+// The reduction runs over node rows, the slow index of both operands in memory, while the bf16
+// MFMA wants eight consecutive reduction indices per lane.  The tiles are therefore staged as
+// they lie (row-major [node row][feature], three bf16 planes each, plain 8-byte writes) and the
+// transposition is done by the LDS read: ds_read_b64_tr_b16 hands lane i of a group of 16 lanes
+// element i % 4 of the 8 bytes addressed by lanes i / 4, i / 4 + 4, i / 4 + 8 and i / 4 + 12, so
+// with lane s of the group pointing at row s / 4, features 4 (s % 4) .. + 3, every lane receives
+// its own feature at four consecutive rows; two such reads are one MFMA operand.
+// LDS rows are 288 bytes (128 features + pad): the four rows of a group fall on distinct banks.
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef short shortx8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
+constexpr int LDW = 128 + 16;            // halfwords per staged row
+constexpr int kWPlane = BKS * LDW;       // halfwords per plane of a tile
+
+__device__ inline bf16x8 read_transposed(const uint16_t* p)
+{
+    const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4*)p);
+    const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4*)(p + 4 * LDW));
+    const shortx8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    bf16x8 o;
+    __builtin_memcpy(&o, &v, 16);
+    return o;
+}
+
+template <bool MASK>
+__global__ __launch_bounds__(kBlock, 2) void wgrad_split_kernel(
+    const float* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb,
+    const float* __restrict__ R, int64_t ldr, float* __restrict__ P, int KD, int MD,
+    int64_t rows_per_slab, int64_t n_rows, int n_i_tiles, int n_j_tiles)
+{
+    constexpr int TM = 2, TN = 2;
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][kPlanes * kWPlane];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][kPlanes * kWPlane];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int tiles = n_i_tiles * n_j_tiles;
+    const unsigned lid = xcd_local_index(blockIdx.x, gridDim.x);
+    const int64_t slab = lid / tiles;
+    const int t = (int)(lid % tiles);
+    const int i0 = (t / n_j_tiles) * 128, j0 = (t % n_j_tiles) * 128;
+    const int64_t r_begin = slab * rows_per_slab;
+    const int64_t r_end = (r_begin + rows_per_slab) < n_rows ? (r_begin + rows_per_slab) : n_rows;
+    const int nk = (int)((r_end - r_begin) / BKS);  // whole steps: the caller sees to it
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
+
+    // staging: thread -> rows tid / 32 and tid / 32 + 8 of the step, features 4 (tid % 32) .. + 3
+    const int srow = tid >> 5, scol = 4 * (tid & 31);
+    uint32_t aoff[2], boff[2], roff[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        aoff[p] = (uint32_t)(srow + 8 * p) * (uint32_t)lda * 4u + 4u * scol;
+        boff[p] = (uint32_t)(srow + 8 * p) * (uint32_t)ldb * 4u + 4u * scol;
+        roff[p] = MASK ? (uint32_t)(srow + 8 * p) * (uint32_t)ldr * 4u + 4u * scol : 0u;
+    }
+    const int spos = srow * LDW + scol;
+    const char* a0 = reinterpret_cast<const char*>(A + r_begin * lda + i0);
+    const char* b0 = reinterpret_cast<const char*>(B + r_begin * ldb + j0);
+    const char* m0 = MASK ? reinterpret_cast<const char*>(R + r_begin * ldr + j0) : nullptr;
+    const size_t step_a = (size_t)BKS * 4 * (size_t)lda, step_b = (size_t)BKS * 4 * (size_t)ldb,
+                 step_r = (size_t)BKS * 4 * (size_t)ldr;
+
+    struct Regs {
+        float4 a[2], b[2], r[2];
+    };
+    // a step beyond the last one loads the last one again (never stored): no branch around loads
+    auto load = [&](Regs& g, int step) {
+        const size_t sc = (size_t)(step < nk ? step : nk - 1);
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            g.a[p] = *reinterpret_cast<const float4*>(a0 + sc * step_a + aoff[p]);
+            g.b[p] = *reinterpret_cast<const float4*>(b0 + sc * step_b + boff[p]);
+            if (MASK) g.r[p] = *reinterpret_cast<const float4*>(m0 + sc * step_r + roff[p]);
+        }
+    };
+    auto store = [&](const Regs& g, uint16_t* as, uint16_t* bs) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            uint16_t* qa = as + spos + p * 8 * LDW;
+            split_store<false>(g.a[p], g.a[p], qa, qa + kWPlane, qa + 2 * kWPlane);
+            uint16_t* qb = bs + spos + p * 8 * LDW;
+            split_store<MASK>(g.b[p], g.r[p], qb, qb + kWPlane, qb + 2 * kWPlane);
+        }
+    };
+    // operand reads: lane -> 16-lane group (feature block, reduction half), place in the group
+    const int grp = lane >> 4, gs = lane & 15;
+    const int rpos = (8 * (grp >> 1) + (gs >> 2)) * LDW + 16 * (grp & 1) + 4 * (gs & 3);
+    struct Operands {
+        bf16x8 a[kPlanes][TM], b[kPlanes][TN];
+    };
+    auto read_operands = [&](Operands& o, const uint16_t* as, const uint16_t* bs) {
+#pragma unroll
+        for (int p = 0; p < kPlanes; ++p) {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+                o.a[p][tm] = read_transposed(as + p * kWPlane + rpos + (wm * TM + tm) * 32);
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+                o.b[p][tn] = read_transposed(bs + p * kWPlane + rpos + (wn * TN + tn) * 32);
+        }
+    };
+    auto mma = [&](const Operands& o) {
+        constexpr int pa[6] = {2, 0, 1, 1, 0, 0};
+        constexpr int pb[6] = {0, 2, 1, 0, 1, 0};
+#pragma unroll
+        for (int q = 0; q < 6; ++q)
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        o.a[pa[q]][tm], o.b[pb[q]][tn], acc[tm][tn], 0, 0, 0);
+    };
+
+    if (nk > 0) {
+        // the pipeline of the row-block kernel: MFMAs of step i on operands read during step
+        // i - 1, operands of step i + 1 read, tiles of step i + 2 split and written, loads two
+        // more steps ahead
+        Regs g0, g1;
+        Operands o0, o1;
+        load(g0, 0);
+        load(g1, 1);
+        store(g0, As[0], Bs[0]);
+        load(g0, 2);
+        if (nk > 1) store(g1, As[1], Bs[1]);
+        load(g1, 3);
+        __syncthreads();
+        read_operands(o0, As[0], Bs[0]);
+        __syncthreads();
+        int i = 0;
+        for (; i + 3 < nk; i += 2) {
+            read_operands(o1, As[1], Bs[1]);
+            mma(o0);
+            store(g0, As[0], Bs[0]);
+            load(g0, i + 4);
+            __syncthreads();
+            read_operands(o0, As[0], Bs[0]);
+            mma(o1);
+            store(g1, As[1], Bs[1]);
+            load(g1, i + 5);
+            __syncthreads();
+        }
+        const int rem = nk - i;
+        if (rem >= 2) read_operands(o1, As[1], Bs[1]);
+        mma(o0);
+        if (rem >= 3) store(g0, As[0], Bs[0]);
+        if (rem >= 2) {
+            __syncthreads();
+            if (rem >= 3) read_operands(o0, As[0], Bs[0]);
+            mma(o1);
+            if (rem >= 3) mma(o0);
+        }
+    }
+
+    // D layout: lane l, register v -> row 8 (v / 4) + 4 (l / 32) + v % 4, col l % 32
+    const int li = lane & 31, lk = lane >> 5;
+    float* out = P + (size_t)slab * KD * MD;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const int j = j0 + (wn * TN + tn) * 32 + li;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = i0 + (wm * TM + tm) * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
+                out[(size_t)i * MD + j] = acc[tm][tn][v];
+            }
+        }
+}
+
 // C[n x out_dim] = (A (.) mask)[n x red_dim] * Wop, Wop[kk][j] = transpose_w ? W[kk][j] : W[j][kk]
 template <class S>
 int launch_rowblock_split(bool relu, const float* A, int64_t lda, const float* W, int64_t ldw,
@@ -351,21 +528,61 @@ int launch_rowblock_split(bool relu, const float* A, int64_t lda, const float* W
 
 }  // namespace
 
-bool update_split_applies(int op, int64_t lda, int64_t ldr, int64_t n, int32_t k, int32_t m)
+bool update_split_applies(int op, int64_t lda, int64_t ldb, int64_t ldr, int64_t n, int32_t k,
+                          int32_t m)
 {
     if (n <= 0) return false;
     if (lda >= (1 << 22) || ldr >= (1 << 22)) return false;  // 32-bit offsets inside a tile
+    if (op == MIXGCN_OP_WGRAD && ldb >= (1 << 22)) return false;
     // outputs of at most 64 columns and reductions of fewer than four steps are bound by their
     // memory traffic on either path
     if (op == MIXGCN_OP_FWD || op == MIXGCN_OP_FWD_RELU) return m > 64 && k >= 64 && k % BKS == 0;
     if (op == MIXGCN_OP_DGRAD) return k > 64 && m >= 64 && m % BKS == 0;
+    // the weight gradient: whole 128 x 128 tiles, and at least one whole step of rows (a remainder
+    // of fewer than 16 rows goes to the fp32 MFMA kernel)
+    if (op == MIXGCN_OP_WGRAD) return k % 128 == 0 && m % 128 == 0 && n >= BKS;
     return false;
+}
+
+// dW[k x m] = beta dW + A[n x k]^T (B (.) mask)[n x m] for whole 128 x 128 tiles and a row count of
+// whole steps
+static int launch_wgrad_split(const float* A, int64_t lda, const float* B, int64_t ldb, float* C,
+                              int64_t ldc, int64_t n, int32_t k, int32_t m, const float* R,
+                              int64_t ldr, float beta, hipStream_t s, Timer* timer)
+{
+    const int nit = k / 128, njt = m / 128, tiles = nit * njt;
+    int64_t n_slabs = ceil_div(n, 1024);
+    const int64_t cap = tiles >= 1024 ? 1 : 1024 / tiles;
+    if (n_slabs > cap) n_slabs = cap;
+    if (n_slabs < 1) n_slabs = 1;
+    const int64_t rows_per_slab = ceil_div(ceil_div(n, n_slabs), BKS) * BKS;
+    n_slabs = ceil_div(n, rows_per_slab);
+    const int64_t cells = (int64_t)k * m;
+    void* scratch = nullptr;
+    MIXGCN_TRY(get_scratch(0, (size_t)n_slabs * cells * sizeof(float), &scratch));
+    float* P = (float*)scratch;
+    const unsigned grid = (unsigned)(n_slabs * tiles);
+    if (timer) MIXGCN_TRY(timer->begin(kTimeUpdateWgrad, s));
+    if (R)
+        hipLaunchKernelGGL((wgrad_split_kernel<true>), dim3(grid), dim3(kBlock), 0, s, A, lda, B, ldb, R,
+                           ldr, P, k, m, rows_per_slab, n, nit, njt);
+    else
+        hipLaunchKernelGGL((wgrad_split_kernel<false>), dim3(grid), dim3(kBlock), 0, s, A, lda, B, ldb,
+                           R, ldr, P, k, m, rows_per_slab, n, nit, njt);
+    if (timer) MIXGCN_TRY(timer->end(s));
+    return launch_wgrad_reduce(P, n_slabs, cells, m, C, ldc, beta, s);
 }
 
 int launch_update_split(int op, const float* A, int64_t lda, const float* W, int64_t ldw, float* C,
                         int64_t ldc, int64_t n, int32_t k, int32_t m, const float* R, int64_t ldr,
-                        hipStream_t s, Timer* timer)
+                        float beta, hipStream_t s, Timer* timer)
 {
+    if (op == MIXGCN_OP_WGRAD) {
+        // here W is the upstream gradient [n x m]; n must be a multiple of 16
+        MIXGCN_TRY(launch_wgrad_split(A, lda, W, ldw, C, ldc, n, k, m, R, ldr, beta, s, timer));
+        MIXGCN_HIP_TRY(hipGetLastError());
+        return MIXGCN_OK;
+    }
     if (op == MIXGCN_OP_FWD || op == MIXGCN_OP_FWD_RELU) {
         // C[n x m] = A[n x k] W, W stored k x m: operand rows = output columns -> transposed split
         const bool relu = op == MIXGCN_OP_FWD_RELU;

@@ -178,10 +178,13 @@ int launch_update_bf16(int op, const uint16_t* A, int64_t lda, const void* B, in
 // fp32 features on the bf16 matrix cores (every operand as three bf16 terms, six partial products);
 // chosen by mixgcn_set_update_arith, and only where update_split_applies says so
 extern int g_update_arith;
-bool update_split_applies(int op, int64_t lda, int64_t ldr, int64_t n, int32_t k, int32_t m);
+bool update_split_applies(int op, int64_t lda, int64_t ldb, int64_t ldr, int64_t n, int32_t k,
+                          int32_t m);
+// W: the weights (forward, data gradient) or the upstream gradient (weight gradient, whose row
+// count must be a multiple of 16)
 int launch_update_split(int op, const float* A, int64_t lda, const float* W, int64_t ldw, float* C,
                         int64_t ldc, int64_t n, int32_t k, int32_t m, const float* R, int64_t ldr,
-                        hipStream_t s, Timer* timer);
+                        float beta, hipStream_t s, Timer* timer);
 
 // dW = beta dW + sum of the slab partials P[slab][cells], in slab order in fp64
 int launch_wgrad_reduce(const float* P, int64_t n_slabs, int64_t cells, int32_t m, float* dW,

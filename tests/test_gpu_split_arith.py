@@ -1,5 +1,6 @@
 """GPU parity of the opt-in update arithmetic MIXGCN_ARITH_BF16X3 (fp32 operands as three bf16
-terms, six bf16 MFMAs per product): the same oracle and the same tolerance as the fp32 MFMA path,
+terms, six bf16 MFMAs per product; forward, data gradient and weight gradient): the same oracle
+and the same tolerance as the fp32 MFMA path,
 two exactness pins (inputs whose terms and sums are exact must come out bit-exact), a check that
 its error is not above the fp32 path's, and the products that must not change with the mode."""
 import numpy as np
@@ -37,7 +38,7 @@ def split(mg):
 # finishes with one to three), several column tiles, a ragged last column tile
 SPLIT_SHAPES = [(1000, 64, 128), (2048, 128, 256), (4133, 256, 256), (130, 256, 256), (1, 128, 128),
                 (5000, 128, 1024), (777, 96, 160), (256, 112, 128), (384, 80, 144), (1500, 128, 172),
-                (640, 176, 96), (129, 272, 80)]
+                (640, 176, 96), (129, 272, 80), (16, 128, 128), (47, 256, 128), (20000, 384, 128)]
 
 
 @pytest.mark.parametrize("n,k,m", SPLIT_SHAPES)
@@ -67,6 +68,14 @@ def test_split_forward_and_data_gradient(split, n, k, m):
         o = dz.cpu().numpy()
         assert_close(o[:, :k], oracle.update_dgrad(dp, w64), RTOL_F32, "dgrad")
         assert np.all(o[:, k:] == 9.0)
+        # the weight gradient takes the path for whole 128 x 128 tiles (rows beyond the last
+        # multiple of 16 go to the fp32 kernel and are added)
+        for beta in (0.0, 1.0):
+            dw = torch.full((k, ldm), 2.0, device="cuda")
+            mg.update(mg.OP_WGRAD, zd, gd, dw, n, k, m, relu_ref=ref_t, beta=beta)
+            o = dw.cpu().numpy()
+            assert_close(o[:, :m], oracle.update_wgrad(z64, dp) + 2.0 * beta, RTOL_F32, f"wgrad beta={beta}")
+            assert np.all(o[:, m:] == 2.0)
 
 
 def test_split_is_exact_where_fp32_is(split):
@@ -93,6 +102,15 @@ def test_split_is_exact_where_fp32_is(split):
     mg.update(mg.OP_FWD, dev(a), dev(w), out, n, k, m)
     assert np.array_equal(out.cpu().numpy().astype(np.float64),
                           oracle.update_fwd(a.astype(np.float64), w.astype(np.float64), False))
+    say("bf16x3 exactness, weight gradient with two-term features")
+    kk, mm = 128, 256
+    p, q = rng.integers(-127, 128, size=(n, kk)), rng.integers(-127, 128, size=(n, kk))
+    a = (p + q / 256.0).astype(np.float32)
+    g = rng.integers(-1, 3, size=(n, mm)).astype(np.float32)
+    dw = torch.empty(kk, mm, device="cuda")
+    mg.update(mg.OP_WGRAD, dev(a), dev(g), dw, n, kk, mm)
+    assert np.array_equal(dw.cpu().numpy().astype(np.float64),
+                          oracle.update_wgrad(a.astype(np.float64), g.astype(np.float64)))
     say("bf16x3 exactness, two-term weights in the data gradient")
     kk, mm = 128, 64  # dZ[n x kk] = G[n x mm] W[kk x mm]^T
     g = rng.integers(-1, 3, size=(n, mm)).astype(np.float32)
