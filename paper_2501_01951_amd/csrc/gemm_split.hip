@@ -1,5 +1,5 @@
-// Node update and data gradient of fp32 features (paper Algorithm 2, update phase) on the bf16
-// matrix cores; opt-in (mixgcn_set_update_arith), wide outputs only.  Every fp32 operand is
+// Node update, data gradient and weight gradient of fp32 features (paper Algorithm 2, update
+// phase) on the bf16 matrix cores; opt-in (mixgcn_set_update_arith), wide layers only.  Every fp32 operand is
 // written as the exact sum of three bf16 terms (round to nearest at each stage),
 //     x = x0 + x1 + x2,   |x1| <= 2^-8 |x|,   |x2| <= 2^-16 |x|,
 // and a product a b is accumulated in fp32 from the six partial products of order 2^-16 and
