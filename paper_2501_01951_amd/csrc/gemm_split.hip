@@ -329,11 +329,13 @@ __global__ __launch_bounds__(kBlock, 2) void rowblock_split_kernel(
 // element i % 4 of the 8 bytes addressed by lanes i / 4, i / 4 + 4, i / 4 + 8 and i / 4 + 12, so
 // with lane s of the group pointing at row s / 4, features 4 (s % 4) .. + 3, every lane receives
 // its own feature at four consecutive rows; two such reads are one MFMA operand.
-// LDS rows are 288 bytes (128 features + pad): the four rows of a group fall on distinct banks.
+// LDS rows are 320 bytes (128 features + pad): two groups of 16 lanes are served together (64
+// banks), that is four rows of 64 bytes, which a pitch of 16 banks modulo 64 keeps apart (with
+// 288-byte rows a third of the LDS cycles were bank conflicts).
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef short shortx8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
-constexpr int LDW = 128 + 16;            // halfwords per staged row
+constexpr int LDW = 128 + 32;            // halfwords per staged row
 constexpr int kWPlane = BKS * LDW;       // halfwords per plane of a tile
 
 __device__ inline bf16x8 read_transposed(const uint16_t* p)
