@@ -516,6 +516,208 @@ __global__ __launch_bounds__(kBlock) void wgrad_bf16_kernel(
         }
 }
 
+// ---- the same product without the scattered LDS writes -------------------------------------------
+// (In the kernel above the transposing 4-byte writes keep the LDS busy 80 % of the time, seven
+// eighths of it with bank conflicts.)  Here the tiles are staged as they lie, row-major
+// [node row][feature] with 16-byte copies, and the LDS read transposes: ds_read_b64_tr_b16 hands
+// lane i of a group of 16 lanes element i % 4 of the 8 bytes addressed by lanes i / 4, i / 4 + 4,
+// i / 4 + 8 and i / 4 + 12, so with lane s of the group pointing at row s / 4, features
+// 4 (s % 4) .. + 3, every lane receives its own feature at four consecutive rows, and two such
+// reads are one MFMA operand.  Two groups are served per cycle from 64 banks (four rows of 64
+// bytes): a row pitch of 64 bytes modulo 256 keeps them apart.  Rows come in whole steps of 32
+// (the caller gives the last n % 32 rows to the kernel above); features beyond the matrices are
+// zeroed with per-thread masks that do not change from step to step.
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef short shortx8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
+
+template <int PITCH>
+__device__ inline bf16x8 read_transposed(const uint16_t* p)
+{
+    const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4*)p);
+    const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4*)(p + 4 * PITCH));
+    const shortx8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    bf16x8 o;
+    __builtin_memcpy(&o, &v, 16);
+    return o;
+}
+
+template <class S, bool MASK>
+__global__ __launch_bounds__(kBlock) void wgrad_bf16_tr_kernel(
+    const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ B, int64_t ldb,
+    const uint16_t* __restrict__ R, int64_t ldr, float* __restrict__ P, int64_t n, int KD, int MD,
+    int64_t rows_per_slab, int n_i_tiles, int n_j_tiles)
+{
+    static_assert(S::BM == 128 && (S::BN == 128 || S::BN == 32), "tile shapes of the staging");
+    constexpr int PA = 128 + 32;                         // halfwords per staged row of A
+    constexpr int PB = S::BN == 128 ? 128 + 32 : 32;     // ... of B
+    constexpr int B_PPR = S::BN / 8;                     // 16-byte pieces per row of B
+    constexpr int B_RPP = kBlock / B_PPR;                // rows per pass of the block
+    constexpr int B_PASSES = B_RPP >= BKB ? 1 : BKB / B_RPP;
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][BKB * PA];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BKB * PB];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / S::WN, wn = wave % S::WN;
+    const int tiles = n_i_tiles * n_j_tiles;
+    const unsigned lid = xcd_local_index(blockIdx.x, gridDim.x);
+    const int64_t slab = lid / tiles;
+    const int t = (int)(lid % tiles);
+    const int i0 = (t / n_j_tiles) * S::BM, j0 = (t % n_j_tiles) * S::BN;
+    const int64_t r_begin = slab * rows_per_slab;
+    const int64_t r_end = (r_begin + rows_per_slab) < n ? (r_begin + rows_per_slab) : n;
+    const int nk = (int)((r_end - r_begin) / BKB);  // whole steps: the caller sees to it
+
+    floatx16 acc[S::TM][S::TN];
+#pragma unroll
+    for (int tm = 0; tm < S::TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < S::TN; ++tn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
+
+    // staging: A rows tid / 16 and tid / 16 + 16, features 8 (tid % 16) .. + 7; B alike with its
+    // own pieces per row.  A piece beyond the matrix is loaded from column 0 and masked to zero.
+    auto keep_words = [](int nvalid, uint32_t* kw) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            kw[w] = (nvalid > 2 * w ? 0x0000FFFFu : 0u) | (nvalid > 2 * w + 1 ? 0xFFFF0000u : 0u);
+    };
+    const int arow = tid >> 4, acol = i0 + 8 * (tid & 15);
+    const int a_valid = acol < KD ? (KD - acol < 8 ? KD - acol : 8) : 0;
+    uint32_t a_keep[4];
+    keep_words(a_valid, a_keep);
+    const uint32_t a_off = ((uint32_t)arow * (uint32_t)lda + (uint32_t)(a_valid ? acol : 0)) * 2u;
+    const int a_pos = arow * PA + 8 * (tid & 15);
+    const int brow = tid / B_PPR, bcol = j0 + 8 * (tid % B_PPR);
+    const bool b_on = brow < BKB;
+    const int b_valid = bcol < MD ? (MD - bcol < 8 ? MD - bcol : 8) : 0;
+    uint32_t b_keep[4];
+    keep_words(b_valid, b_keep);
+    const int brow_c = b_on ? brow : 0;  // idle threads of a narrow tile load row 0 again
+    const uint32_t b_off = ((uint32_t)brow_c * (uint32_t)ldb + (uint32_t)(b_valid ? bcol : 0)) * 2u;
+    const uint32_t r_off = MASK ? ((uint32_t)brow_c * (uint32_t)ldr + (uint32_t)(b_valid ? bcol : 0)) * 2u : 0u;
+    const int b_pos = brow_c * PB + 8 * (tid % B_PPR);
+    const bool inside = i0 + S::BM <= KD && j0 + S::BN <= MD;
+
+    const char* a0 = reinterpret_cast<const char*>(A + r_begin * lda);
+    const char* b0 = reinterpret_cast<const char*>(B + r_begin * ldb);
+    const char* m0 = MASK ? reinterpret_cast<const char*>(R + r_begin * ldr) : nullptr;
+    const size_t step_a = (size_t)BKB * 2 * (size_t)lda, step_b = (size_t)BKB * 2 * (size_t)ldb,
+                 step_r = (size_t)BKB * 2 * (size_t)ldr;
+
+    struct Regs {
+        uint4 a[2], b[B_PASSES], r[B_PASSES];
+    };
+    // a step beyond the last one loads the last one again (never stored): no branch around loads
+    auto load = [&](Regs& g, int step) {
+        const size_t sc = (size_t)(step < nk ? step : nk - 1);
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+            g.a[p] = *reinterpret_cast<const uint4*>(a0 + sc * step_a + (size_t)p * 16 * 2 * (size_t)lda + a_off);
+#pragma unroll
+        for (int p = 0; p < B_PASSES; ++p) {
+            g.b[p] = *reinterpret_cast<const uint4*>(b0 + sc * step_b + (size_t)p * B_RPP * 2 * (size_t)ldb + b_off);
+            if (MASK)
+                g.r[p] = *reinterpret_cast<const uint4*>(m0 + sc * step_r + (size_t)p * B_RPP * 2 * (size_t)ldr + r_off);
+        }
+    };
+    auto store = [&](const Regs& g, uint16_t* as, uint16_t* bs) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            uint4 v = g.a[p];
+            if (!inside) {
+                v.x &= a_keep[0];
+                v.y &= a_keep[1];
+                v.z &= a_keep[2];
+                v.w &= a_keep[3];
+            }
+            lds_store16(as + a_pos + p * 16 * PA, v);
+        }
+        if (b_on) {
+#pragma unroll
+            for (int p = 0; p < B_PASSES; ++p) {
+                uint4 v = g.b[p];
+                if (MASK) {
+                    v.x = keep_positive(v.x, g.r[p].x);
+                    v.y = keep_positive(v.y, g.r[p].y);
+                    v.z = keep_positive(v.z, g.r[p].z);
+                    v.w = keep_positive(v.w, g.r[p].w);
+                }
+                if (!inside) {
+                    v.x &= b_keep[0];
+                    v.y &= b_keep[1];
+                    v.z &= b_keep[2];
+                    v.w &= b_keep[3];
+                }
+                lds_store16(bs + b_pos + p * B_RPP * PB, v);
+            }
+        }
+    };
+    // operand reads: lane -> 16-lane group (feature block, reduction half), place in the group
+    const int grp = lane >> 4, gs = lane & 15;
+    const int rrow = 8 * (grp >> 1) + (gs >> 2), rcol = 16 * (grp & 1) + 4 * (gs & 3);
+    auto step_mma = [&](const uint16_t* as, const uint16_t* bs) {
+#pragma unroll
+        for (int kc = 0; kc < BKB; kc += 16) {
+            bf16x8 a[S::TM], b[S::TN];
+#pragma unroll
+            for (int tm = 0; tm < S::TM; ++tm)
+                a[tm] = read_transposed<PA>(as + (kc + rrow) * PA + (wm * S::TM + tm) * 32 + rcol);
+#pragma unroll
+            for (int tn = 0; tn < S::TN; ++tn)
+                b[tn] = read_transposed<PB>(bs + (kc + rrow) * PB + (wn * S::TN + tn) * 32 + rcol);
+#pragma unroll
+            for (int tm = 0; tm < S::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < S::TN; ++tn)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], b[tn], acc[tm][tn],
+                                                                          0, 0, 0);
+        }
+    };
+
+    if (nk > 0) {
+        // LDS double buffered one step ahead, global loads two steps ahead in two register sets
+        Regs g0, g1;
+        load(g0, 0);
+        load(g1, 1);
+        store(g0, As[0], Bs[0]);
+        load(g0, 2);
+        __syncthreads();
+        int i = 0;
+        for (; i + 2 < nk; i += 2) {
+            step_mma(As[0], Bs[0]);
+            store(g1, As[1], Bs[1]);
+            load(g1, i + 3);
+            __syncthreads();
+            step_mma(As[1], Bs[1]);
+            store(g0, As[0], Bs[0]);
+            load(g0, i + 4);
+            __syncthreads();
+        }
+        step_mma(As[0], Bs[0]);
+        if (nk - i == 2) {
+            store(g1, As[1], Bs[1]);
+            __syncthreads();
+            step_mma(As[1], Bs[1]);
+        }
+    }
+
+    const int li = lane & 31, lk = lane >> 5;
+    float* out = P + (size_t)slab * KD * MD;
+#pragma unroll
+    for (int tm = 0; tm < S::TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < S::TN; ++tn) {
+            const int j = j0 + (wn * S::TN + tn) * 32 + li;
+            if (j >= MD) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = i0 + (wm * S::TM + tm) * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
+                if (i < KD) out[(size_t)i * MD + j] = acc[tm][tn][v];
+            }
+        }
+}
+
 // C[n x out_dim] = (A (.) mask)[n x red_dim] * Wop, Wop[kk][j] = transpose_w ? W[kk][j] : W[j][kk]
 template <class S>
 int launch_rowblock_bf16(bool relu, const uint16_t* A, int64_t lda, const float* W, int64_t ldw,
@@ -577,39 +779,55 @@ int launch_update_bf16(int op, const uint16_t* A, int64_t lda, const void* B_, i
                                                          s)));
         if (timer) MIXGCN_TRY(timer->end(s));
     } else if (op == MIXGCN_OP_WGRAD) {
-        // C[k x m] = beta C + A[n x k]^T (B (.) mask)[n x m]
+        // C[k x m] = beta C + A[n x k]^T (B (.) mask)[n x m]: whole steps of 32 rows with the
+        // transposing LDS reads, the last n % 32 rows with the scattering kernel, added on top
         const uint16_t* B = (const uint16_t*)B_;
         float* C = (float*)C_;
         const bool wide = m > 64;
         const int bm = 128, bn = wide ? 128 : 32;
         const int nit = (int)ceil_div(k, bm), njt = (int)ceil_div(m, bn);
         const int tiles = nit * njt;
-        int64_t n_slabs = ceil_div(n, 2048);
-        const int64_t cap = tiles >= 1024 ? 1 : 1024 / tiles;
-        if (n_slabs > cap) n_slabs = cap;
-        if (n_slabs < 1) n_slabs = 1;
-        int64_t rows_per_slab = ceil_div(ceil_div(n, n_slabs), BKB) * BKB;
-        if (rows_per_slab < BKB) rows_per_slab = BKB;
-        n_slabs = n > 0 ? ceil_div(n, rows_per_slab) : 1;
         const int64_t cells = (int64_t)k * m;
-        void* scratch = nullptr;
-        MIXGCN_TRY(get_scratch(0, (size_t)n_slabs * cells * sizeof(float), &scratch));
-        float* P = (float*)scratch;
-        const unsigned grid = (unsigned)(n_slabs * tiles);
+        const bool pitches_ok = lda < (1 << 25) && ldb < (1 << 25) && ldr < (1 << 25);
+        const int64_t n_main = pitches_ok ? n - n % BKB : 0;
         if (timer) MIXGCN_TRY(timer->begin(kTimeUpdateWgrad, s));
-#define MIXGCN_WGRAD(SHAPE, MASK)                                                                \
-    hipLaunchKernelGGL((wgrad_bf16_kernel<SHAPE, MASK>), dim3(grid), dim3(kBlock), 0, s, A, lda, B, \
-                       ldb, R, ldr, P, n, k, m, rows_per_slab, nit, njt)
-        if (wide) {
-            if (R) MIXGCN_WGRAD(Shape128x128, true);
-            else MIXGCN_WGRAD(Shape128x128, false);
-        } else {
-            if (R) MIXGCN_WGRAD(Shape128x32, true);
-            else MIXGCN_WGRAD(Shape128x32, false);
-        }
+        auto part = [&](bool transposing_reads, int64_t row0, int64_t rows, float beta_part) -> int {
+            int64_t n_slabs = ceil_div(rows, 2048);
+            const int64_t cap = tiles >= 1024 ? 1 : 1024 / tiles;
+            if (n_slabs > cap) n_slabs = cap;
+            if (n_slabs < 1) n_slabs = 1;
+            int64_t rows_per_slab = ceil_div(ceil_div(rows, n_slabs), BKB) * BKB;
+            if (rows_per_slab < BKB) rows_per_slab = BKB;
+            n_slabs = rows > 0 ? ceil_div(rows, rows_per_slab) : 1;
+            void* scratch = nullptr;
+            MIXGCN_TRY(get_scratch(0, (size_t)n_slabs * cells * sizeof(float), &scratch));
+            float* P = (float*)scratch;
+            const unsigned grid = (unsigned)(n_slabs * tiles);
+            const uint16_t* a = A + row0 * lda;
+            const uint16_t* b = B + row0 * ldb;
+            const uint16_t* r = R ? R + row0 * ldr : nullptr;
+#define MIXGCN_WGRAD(KERNEL, SHAPE, MASK)                                                        \
+    hipLaunchKernelGGL((KERNEL<SHAPE, MASK>), dim3(grid), dim3(kBlock), 0, s, a, lda, b, ldb, r,  \
+                       ldr, P, rows, k, m, rows_per_slab, nit, njt)
+#define MIXGCN_WGRAD_SHAPES(KERNEL)                                                              \
+    do {                                                                                         \
+        if (wide) {                                                                              \
+            if (r) MIXGCN_WGRAD(KERNEL, Shape128x128, true);                                     \
+            else MIXGCN_WGRAD(KERNEL, Shape128x128, false);                                      \
+        } else {                                                                                 \
+            if (r) MIXGCN_WGRAD(KERNEL, Shape128x32, true);                                      \
+            else MIXGCN_WGRAD(KERNEL, Shape128x32, false);                                       \
+        }                                                                                        \
+    } while (0)
+            if (transposing_reads) MIXGCN_WGRAD_SHAPES(wgrad_bf16_tr_kernel);
+            else MIXGCN_WGRAD_SHAPES(wgrad_bf16_kernel);
+#undef MIXGCN_WGRAD_SHAPES
 #undef MIXGCN_WGRAD
+            return launch_wgrad_reduce(P, n_slabs, cells, m, C, ldc, beta_part, s);
+        };
+        if (n_main > 0) MIXGCN_TRY(part(true, 0, n_main, beta));
+        if (n_main < n || n == 0) MIXGCN_TRY(part(false, n_main, n - n_main, n_main > 0 ? 1.f : beta));
         if (timer) MIXGCN_TRY(timer->end(s));
-        MIXGCN_TRY(launch_wgrad_reduce(P, n_slabs, cells, m, C, ldc, beta, s));
     } else {
         return fail(MIXGCN_EINVAL, "update: unknown op");
     }
