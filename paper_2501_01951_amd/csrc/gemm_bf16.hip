@@ -148,6 +148,21 @@ __device__ inline uint32_t keep_positive(uint32_t x, uint32_t r)
     return x & k;
 }
 
+// two fp32 -> two bf16 (round to nearest even, the conversion instruction of this part), first
+// argument in the low half
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) uintx2 lds_uintx2;
+__device__ inline uint32_t pack_bf16_pair(float a, float b)
+{
+    const floatx2 v = {a, b};
+    const bf16x2 h = __builtin_convertvector(v, bf16x2);
+    uint32_t u;
+    __builtin_memcpy(&u, &h, 4);
+    return u;
+}
+
 template <class S, bool MASK>
 struct FastStage {
     static constexpr int A_PASSES = S::BM / 64;
@@ -214,9 +229,18 @@ __global__ __launch_bounds__(kBlock) void rowblock_bf16_kernel(
     const uint16_t* __restrict__ Bl, int ldb, uint16_t* __restrict__ C, int64_t ldc, int64_t n,
     int KD, int MD, const uint16_t* __restrict__ R, int64_t ldr, int n_col_tiles)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t As[2][S::BM * LDT];
-    __shared__ __attribute__((aligned(16))) uint16_t Bhs[2][S::BN * LDT];
-    __shared__ __attribute__((aligned(16))) uint16_t Bls[2][S::BN * LDT];
+    // one buffer: the double-buffered operand tiles, and after the last step the output tile
+    constexpr int kTileA = S::BM * LDT, kTileB = S::BN * LDT;
+    constexpr int LDC = S::BN + 4;  // output tile rows: 66 or 18 banks, 8-byte aligned
+    static_assert(S::BM * LDC <= 2 * (kTileA + 2 * kTileB), "the output tile fits the operand buffers");
+    __shared__ __attribute__((aligned(16))) uint16_t smem[2 * (kTileA + 2 * kTileB)];
+    uint16_t *As[2], *Bhs[2], *Bls[2];
+    As[0] = smem;
+    As[1] = smem + kTileA;
+    Bhs[0] = smem + 2 * kTileA;
+    Bhs[1] = smem + 2 * kTileA + kTileB;
+    Bls[0] = smem + 2 * kTileA + 2 * kTileB;
+    Bls[1] = smem + 2 * kTileA + 3 * kTileB;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / S::WN, wn = wave % S::WN;
     const unsigned lid = xcd_local_index(blockIdx.x, gridDim.x);
@@ -280,9 +304,11 @@ __global__ __launch_bounds__(kBlock) void rowblock_bf16_kernel(
             for (int tm = 0; tm < S::TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < S::TN; ++tn) {
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], l[tn],
+                    // weights as the first operand: the accumulators hold the tile transposed,
+                    // a lane then owns one node row and four consecutive columns per register quad
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(l[tn], a[tm],
                                                                           acc[tm][tn], 0, 0, 0);
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], h[tn],
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(h[tn], a[tm],
                                                                           acc[tm][tn], 0, 0, 0);
                 }
         }
@@ -373,23 +399,51 @@ __global__ __launch_bounds__(kBlock) void rowblock_bf16_kernel(
         }
     }
 
-    // D layout: lane l, register v -> row 8*(v/4) + 4*(l/32) + v%4, col l%32
+    // Accumulator layout (transposed product): lane l, register v -> node row l % 32, column
+    // 8 (v / 4) + 4 (l / 32) + v % 4 of the 32 x 32 tile.
+    // Converted in pairs by the hardware, collected in LDS and written as 8-byte pieces of whole
+    // rows (a lane's own elements lie in 32 different rows: written directly they would be
+    // 2-byte stores scattered over as many lines).
+    __syncthreads();  // every wave is done with the operand tiles
 #pragma unroll
     for (int tm = 0; tm < S::TM; ++tm)
 #pragma unroll
-        for (int tn = 0; tn < S::TN; ++tn) {
-            const int c = col0 + (wn * S::TN + tn) * 32 + li;
-            if (c >= MD) continue;
+        for (int tn = 0; tn < S::TN; ++tn)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t r = row0 + (wm * S::TM + tm) * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
-                if (r < n) {
-                    float x = acc[tm][tn][v];
-                    if (RELU) x = x > 0.f ? x : 0.f;
-                    C[r * ldc + c] = bf16_rne(x);
+            for (int g = 0; g < 4; ++g) {
+                uint32_t w0 = pack_bf16_pair(acc[tm][tn][4 * g], acc[tm][tn][4 * g + 1]);
+                uint32_t w1 = pack_bf16_pair(acc[tm][tn][4 * g + 2], acc[tm][tn][4 * g + 3]);
+                if (RELU) {
+                    w0 = keep_positive(w0, w0);
+                    w1 = keep_positive(w1, w1);
                 }
+                const uintx2 v = {w0, w1};
+                *(lds_uintx2*)(smem + ((wm * S::TM + tm) * 32 + li) * LDC + (wn * S::TN + tn) * 32 +
+                               8 * g + 4 * lk) = v;
             }
+    __syncthreads();
+    constexpr int CPR = S::BN / 4;     // 8-byte pieces per row
+    constexpr int RPP = kBlock / CPR;  // rows per pass of the block
+    const int crow = tid / CPR, cpiece = tid % CPR;
+    const int c = col0 + 4 * cpiece;
+    const int c_valid = c < MD ? (MD - c < 4 ? MD - c : 4) : 0;  // columns of the piece inside C
+    if (c_valid == 0) return;
+    uint16_t* cbase = C + row0 * ldc + c;
+    const int64_t rows_left = n - row0;
+#pragma unroll
+    for (int p = 0; p < S::BM / RPP; ++p) {
+        const int r = p * RPP + crow;
+        if (r >= rows_left) break;
+        const uintx2 v = *(const lds_uintx2*)(smem + r * LDC + 4 * cpiece);
+        uint16_t* dst = cbase + (int64_t)r * ldc;
+        if (c_valid == 4) {
+            *reinterpret_cast<uint2*>(dst) = make_uint2(v.x, v.y);
+        } else {
+            dst[0] = (uint16_t)v.x;
+            if (c_valid > 1) dst[1] = (uint16_t)(v.x >> 16);
+            if (c_valid > 2) dst[2] = (uint16_t)v.y;
         }
+    }
 }
 
 // ---- slab kernel: P[slab][KD x MD] = A[rows of slab][KD]^T * (B (.) 1[R > 0])[rows][MD] --------
