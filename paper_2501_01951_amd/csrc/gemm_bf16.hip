@@ -163,6 +163,15 @@ __device__ inline uint32_t pack_bf16_pair(float a, float b)
     return u;
 }
 
+// Tile row of a thread's 16-byte pieces: rows are dealt so that the 16 lanes of one LDS write
+// cycle (four rows of 64 bytes) take rows q, q + 4, q + 8, q + 12 of a group of 16, which at 20
+// banks per row start 16 banks apart (0, 16, 32, 48 of 64) and do not collide.
+__device__ inline int staged_row(int tid)
+{
+    const int x = tid >> 2;
+    return (x & ~15) | ((x & 3) << 2) | ((x >> 2) & 3);
+}
+
 template <class S, bool MASK>
 struct FastStage {
     static constexpr int A_PASSES = S::BM / 64;
@@ -175,7 +184,7 @@ struct FastStage {
     static constexpr uint32_t kPitchB = BKB * 2;  // a weight tile of one step is dense
     __device__ inline void init(int tid, uint32_t pitch_a, uint32_t pitch_r)
     {
-        const int prow = tid / 4, pk = 8 * (tid & 3);
+        const int prow = staged_row(tid), pk = 8 * (tid & 3);
         aoff = (uint32_t)prow * pitch_a + 2u * pk;
         roff = (uint32_t)prow * pitch_r + 2u * pk;
         // threads beyond a narrow weight tile load a row of it again and store nothing
@@ -260,7 +269,7 @@ __global__ __launch_bounds__(kBlock) void rowblock_bf16_kernel(
     constexpr int B_PASSES = (S::BN + 63) / 64;
     Piece8<MASK> ra[A_PASSES];
     uint4 rbh[B_PASSES], rbl[B_PASSES];
-    const int prow = tid / 4, pk = 8 * (tid & 3);
+    const int prow = staged_row(tid), pk = 8 * (tid & 3);
 
     auto issue_tiles = [&](int k0) {
 #pragma unroll
