@@ -54,13 +54,6 @@ struct Feat<MIXGCN_F32> {
     }
 };
 
-__device__ inline uint32_t f32_to_bf16_rne(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7F800000u) != 0x7F800000u) u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
-}
-
 template <>
 struct Feat<MIXGCN_BF16> {
     static constexpr int VEC = 8;
@@ -74,13 +67,25 @@ struct Feat<MIXGCN_BF16> {
             o[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
         }
     }
+    // two fp32 -> two bf16, round to nearest even, by the conversion instruction of this part
+    // (rounding in software made a row's end a third of the vector work of this kernel at bf16)
+    __device__ static inline uint32_t pack2(float lo, float hi)
+    {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        typedef float floatx2 __attribute__((ext_vector_type(2)));
+        const floatx2 v = {lo, hi};
+        const bf16x2 h = __builtin_convertvector(v, bf16x2);
+        uint32_t u;
+        __builtin_memcpy(&u, &h, 4);
+        return u;
+    }
     __device__ static inline void store(void* base, int64_t elem_off, const float* a)
     {
         uint4 r;
-        r.x = f32_to_bf16_rne(a[0]) | (f32_to_bf16_rne(a[1]) << 16);
-        r.y = f32_to_bf16_rne(a[2]) | (f32_to_bf16_rne(a[3]) << 16);
-        r.z = f32_to_bf16_rne(a[4]) | (f32_to_bf16_rne(a[5]) << 16);
-        r.w = f32_to_bf16_rne(a[6]) | (f32_to_bf16_rne(a[7]) << 16);
+        r.x = pack2(a[0], a[1]);
+        r.y = pack2(a[2], a[3]);
+        r.z = pack2(a[4], a[5]);
+        r.w = pack2(a[6], a[7]);
         *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(base) + elem_off) = r;
     }
     __device__ static inline const Raw* ptr(const void* base, int64_t elem_off)
