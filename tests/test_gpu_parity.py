@@ -552,6 +552,27 @@ def test_softmax_xent(mg, n, c):
     assert abs(loss.item() - np.log(c)) < 1e-6
 
 
+@pytest.mark.parametrize("n,c,ld", [(999, 47, 48), (5, 3, 4), (50, 65, 68), (300, 127, 128), (2000, 16, 20),
+                                    (64, 129, 132), (777, 1, 4), (4097, 7, 8)])
+def test_softmax_xent_padded_rows(mg, n, c, ld):
+    """Rows with a pitch of their own: an even pitch lets the kernel take two classes per lane,
+    also when the class count is odd (the last pair then reaches into the padding, which must
+    stay untouched)."""
+    say(f"softmax_xent n={n} c={c} ld={ld}")
+    x = gg.normal(45, c, n, c) * 3
+    y = gg.labels(45, 5, n, c)
+    loss_ref, d_ref = oracle.softmax_xent(x.astype(np.float64), y)
+    xd = torch.full((n, ld), 50.0, device="cuda")  # a large value where no class is
+    xd[:, :c] = dev(x)
+    d = torch.full((n, ld), 7.0, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    mg.softmax_xent(xd[:, :c], dev(y), d[:, :c], loss)
+    assert abs(loss.item() - loss_ref) <= 1e-5 * abs(loss_ref)
+    o = d.cpu().numpy()
+    assert_close(o[:, :c], d_ref, RTOL_F32, "dlogits")
+    assert np.all(o[:, c:] == 7.0)
+
+
 @pytest.mark.parametrize("n_chunks", [1, 5])
 def test_layer_fwd_bwd(mg, rmat15, n_chunks):
     og, g = rmat15
