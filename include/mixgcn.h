@@ -16,8 +16,10 @@
  *  - Base pointers must be 16-byte aligned and ld * sizeof(element) a multiple of 16.
  *  - Every call returns 0 on success or a negative MIXGCN_E* code; mixgcn_last_error() gives a
  *    thread-local message.  Bad arguments are rejected before anything is launched.
- *  - dtype: MIXGCN_F32 = fp32 storage and arithmetic; MIXGCN_BF16 = bf16 storage of feature
- *    tensors with fp32 accumulation (weights, A_hat values, logits and dW stay fp32).
+ *  - dtype: MIXGCN_F32 = fp32 storage and arithmetic; MIXGCN_BF16 = bf16 storage of every
+ *    n x F feature tensor (inputs, aggregates, layer outputs including the logits, and the
+ *    gradients of all of these) with fp32 accumulation; the weights, the A_hat values, the loss
+ *    and dW stay fp32.
  */
 #ifndef MIXGCN_H
 #define MIXGCN_H
@@ -157,12 +159,43 @@ int mixgcn_normalize_mode(mixgcn_graph* g, int mode, float eps, void* stream);
  *   A_hat^T (transpose = 1).
  * [col_begin, col_end) is the worker's feature slice [floor(d i/m), floor(d (i+1)/m));
  * [row_begin, row_end) is a pipeline chunk.  H and Z are indexed with absolute columns; entries
- * of Z outside the ranges are not touched.  H and Z must not overlap.  col_begin and col_end
- * must be multiples of 4 (fp32) or 8 (bf16) unless col_end equals the row width given by ld.
+ * of Z outside the ranges are not touched, with one exception: the kernel writes whole 16-byte
+ * groups, so when col_end is not a multiple of 4 (fp32) or 8 (bf16) the columns from col_end up
+ * to the next such multiple are overwritten as well (with the sums of whatever H holds there);
+ * they must exist in both matrices (ld at least that multiple), i.e. lie in the row padding or
+ * belong to nobody else.  col_begin must be a multiple of 4 (fp32) or 8 (bf16).  A slice bound
+ * floor(d i/m) of Algorithm 2 that is not such a multiple is therefore not accepted as a
+ * col_begin: split at multiples of the group instead (Proposition 3.4 does not depend on where
+ * the cuts fall).  H and Z must not overlap.
+ *
+ * Concurrency.  Rows that are cut by the kernel's work split are completed through a scratch
+ * buffer that belongs to the graph and to the stream of the call: calls on one stream share it
+ * in stream order, calls on different streams use different buffers, so the column slices of one
+ * graph may be aggregated on several streams at once.  The buffer of the first stream is
+ * allocated by mixgcn_normalize; each further stream that aggregates the graph gets its own on
+ * its first call (one hipMalloc of mixgcn_aggregate_scratch_bytes(nnz), no synchronisation), or
+ * ahead of time through mixgcn_graph_reserve_streams.  Up to 16 streams per graph are served
+ * this way; a 17th takes over the least recently used buffer after a device synchronisation.
+ * Otherwise the call allocates nothing and does not synchronise.
  */
 int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void* H, int64_t ldh,
                      void* Z, int64_t ldz, int32_t col_begin, int32_t col_end, int64_t row_begin,
                      int64_t row_end, void* stream);
+
+/*
+ * Makes sure that `n_streams` (1..16) scratch buffers of the aggregation are allocated and not
+ * yet owned by a stream, so that the next n_streams streams that aggregate this graph for the
+ * first time allocate nothing (a stream keeps its buffer, so later calls on it never do).
+ * After mixgcn_normalize; MIXGCN_EINVAL if fewer than n_streams of the 16 slots are unowned.
+ * mixgcn_aggregate_scratch_bytes: size of one such buffer for a graph with nnz stored entries
+ * (host arithmetic): enough for any row and column range of any call.
+ * mixgcn_aggregate_scratch_need: what one call over n_cols columns actually uses when its rows
+ * hold the stored entries [entry_begin, entry_end) (host arithmetic; -1 for bad arguments).
+ */
+int mixgcn_graph_reserve_streams(mixgcn_graph* g, int32_t n_streams);
+int64_t mixgcn_aggregate_scratch_bytes(int64_t nnz);
+int64_t mixgcn_aggregate_scratch_need(int dtype, int32_t n_cols, int64_t entry_begin,
+                                      int64_t entry_end);
 
 /*
  * mixgcn_aggregate with an epilogue (MIXGCN_EPI_* flags, 0 = none), for the layer forms that
@@ -271,13 +304,18 @@ int mixgcn_layer_fwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, const vo
                      const float* W, void* Z, void* Hout, mixgcn_pipeline* p);
 
 /*
- * One layer backward.  With dP = G (.) 1[Hout > 0] (d->relu) or dP = G:
+ * One layer backward: the chain rule of Eq. 3 in the order of Algorithm 2's backward line
+ * ("perform backward propagation", which Sec. 3.1.2 describes as the forward workflow run in
+ * reverse).  With dP = G (.) 1[Hout > 0] (d->relu) or dP = G:
  *   MIXGCN_AGG_FIRST:     dW = Z^T dP;   dZ = dP W^T (written over Z);   dH = A_hat^T dZ.
  *                         H is not read (may be NULL).
  *   MIXGCN_UPDATE_FIRST:  dQ = A_hat^T dP [n x f_out] (written to the workspace Z);
  *                         dW = H^T dQ;   dH = dQ W^T.  H is the layer's input [n x f_in, ld_h].
  * G may be overwritten.  dH == NULL skips the input gradient (first layer when none is wanted).
  * dW is fp32 [f_in x f_out] with leading dimension d->ld_w.
+ * The backward pass is not cut into row chunks: with d->n_chunks > 1 and two streams the two
+ * dense products run on the secondary stream and the transposed aggregation, which needs all
+ * of dZ, follows on the primary one.
  */
 int mixgcn_layer_bwd(const mixgcn_graph* g, const mixgcn_layer_desc* d, const void* H, void* Z,
                      const void* Hout, const float* W, void* G, float* dW, void* dH,

@@ -7,8 +7,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# MIXGCN_LIB points at another build of the same library (kernel experiments)
-_LIB_PATH = os.environ.get("MIXGCN_LIB") or os.path.join(_HERE, "libmixgcn.so")
+_LIB_PATH = os.path.join(_HERE, "libmixgcn.so")
 _lib = None
 
 F32, BF16 = 0, 1
@@ -74,6 +73,12 @@ def load_library():
                                         i64, i64, ctypes.c_int, vp]
     lib.mixgcn_aggregate.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, i64, vp, i64, i32, i32,
                                      i64, i64, vp]
+    lib.mixgcn_graph_reserve_streams.argtypes = [vp, i32]
+    lib.mixgcn_graph_reserve_streams.restype = ctypes.c_int
+    lib.mixgcn_aggregate_scratch_bytes.argtypes = [i64]
+    lib.mixgcn_aggregate_scratch_bytes.restype = i64
+    lib.mixgcn_aggregate_scratch_need.argtypes = [ctypes.c_int, i32, i64, i64]
+    lib.mixgcn_aggregate_scratch_need.restype = i64
     lib.mixgcn_aggregate_masked.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, i64, vp, i64, i32,
                                             i32, i64, i64, vp, i64, vp]
     lib.mixgcn_relu_bitmap.argtypes = [ctypes.c_int, vp, i64, i64, i32, vp, i64, vp]
@@ -310,6 +315,15 @@ def aggregate(g: Graph, H, Z, col_begin=0, col_end=None, row_begin=0, row_end=No
     _check(load_library().mixgcn_aggregate(g._h, int(transpose), _dtype_of(H), _ptr(H), _ld(H),
                                            _ptr(Z), _ld(Z), col_begin, col_end, row_begin, row_end,
                                            _stream(stream)), "aggregate")
+
+
+def graph_reserve_streams(g: Graph, n_streams: int) -> None:
+    """Allocates the aggregation scratch of n_streams streams ahead of their first use."""
+    _check(load_library().mixgcn_graph_reserve_streams(g._h, n_streams), "graph_reserve_streams")
+
+
+def aggregate_scratch_bytes(nnz: int) -> int:
+    return load_library().mixgcn_aggregate_scratch_bytes(nnz)
 
 
 def aggregate_masked(g: Graph, H, Z, mask, col_begin=0, col_end=None, row_begin=0, row_end=None,

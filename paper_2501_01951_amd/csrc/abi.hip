@@ -46,15 +46,62 @@ int get_scratch(int which, size_t bytes, void** out)
     std::lock_guard<std::mutex> lock(g_scratch_mu);
     Scratch& sc = g_scratch[dev][which];
     if (bytes > sc.bytes) {
-        MIXGCN_HIP_TRY(hipDeviceSynchronize());  // earlier kernels may still use the old buffer
-        if (sc.p) (void)hipFree(sc.p);
+        if (sc.p) {
+            MIXGCN_HIP_TRY(hipDeviceSynchronize());  // earlier kernels may still use the old buffer
+            (void)hipFree(sc.p);
+        }
         sc.p = nullptr;
         sc.bytes = 0;
-        const size_t want = bytes + bytes / 4 + 256;
+        // The first allocation is large enough for the usual case, so that a later call (one
+        // recorded into a HIP graph, say) does not have to grow it: the slab partials of the
+        // weight gradient never exceed 1024 tiles of 128 x 128 fp32.
+        const size_t floor_bytes = which == 0 ? ((size_t)64 << 20) : ((size_t)1 << 20);
+        size_t want = bytes + bytes / 4 + 256;
+        if (want < floor_bytes) want = floor_bytes;
         MIXGCN_HIP_TRY(hipMalloc(&sc.p, want));
         sc.bytes = want;
     }
     *out = sc.p;
+    return MIXGCN_OK;
+}
+
+// Creates the per-device work buffers at their default sizes (a no-op once they exist).
+static int reserve_default_scratch()
+{
+    void* unused = nullptr;
+    for (int which = 0; which < kScratchKinds; ++which) MIXGCN_TRY(get_scratch(which, 1, &unused));
+    return MIXGCN_OK;
+}
+
+// The row-piece scratch of graph g for work on `stream` (see mixgcn_graph::agg_slots).  The
+// usual call finds the stream's slot and touches no HIP API.
+static int acquire_agg_slot(const mixgcn_graph* g, hipStream_t stream, float** out)
+{
+    std::lock_guard<std::mutex> lock(g->agg_mu);
+    AggSlot* slots = g->agg_slots;
+    AggSlot* pick = nullptr;
+    for (int i = 0; i < kAggSlots && !pick; ++i)
+        if (slots[i].bound && slots[i].stream == stream) pick = &slots[i];
+    if (!pick) {
+        // a free slot, one that is already allocated first
+        for (int i = 0; i < kAggSlots && !pick; ++i)
+            if (!slots[i].bound && slots[i].p) pick = &slots[i];
+        for (int i = 0; i < kAggSlots && !pick; ++i)
+            if (!slots[i].bound) pick = &slots[i];
+        if (!pick) {
+            // every slot belongs to another stream: take over the one unused for longest, after
+            // its work has finished (more streams than slots is not a case worth an event pool)
+            pick = &slots[0];
+            for (int i = 1; i < kAggSlots; ++i)
+                if (slots[i].last_use < pick->last_use) pick = &slots[i];
+            MIXGCN_HIP_TRY(hipDeviceSynchronize());
+        }
+        if (!pick->p) MIXGCN_HIP_TRY(hipMalloc((void**)&pick->p, g->agg_slot_bytes));
+        pick->stream = stream;
+        pick->bound = true;
+    }
+    pick->last_use = ++g->agg_tick;
+    *out = pick->p;
     return MIXGCN_OK;
 }
 
@@ -193,7 +240,8 @@ int mixgcn_graph_free(mixgcn_graph* g)
     csr_free(&g->tr);
     if (g->deg) (void)hipFree(g->deg);
     if (g->dinv) (void)hipFree(g->dinv);
-    if (g->partials) (void)hipFree(g->partials);
+    for (AggSlot& slot : g->agg_slots)
+        if (slot.p) (void)hipFree(slot.p);
     delete g;
     return MIXGCN_OK;
 }
@@ -210,7 +258,51 @@ int mixgcn_normalize_mode(mixgcn_graph* g, int mode, float eps, void* stream)
     if (mode != MIXGCN_NORM_SYM && mode != MIXGCN_NORM_MEAN && mode != MIXGCN_NORM_SUM)
         return fail(MIXGCN_EINVAL, "normalize: unknown mode");
     if (!(eps == eps) || fabsf(eps) > 3.0e38f) return fail(MIXGCN_EINVAL, "normalize: eps");
-    return normalize_graph(g, mode, mode == MIXGCN_NORM_SUM ? eps : 0.f, (hipStream_t)stream);
+    MIXGCN_TRY(normalize_graph(g, mode, mode == MIXGCN_NORM_SUM ? eps : 0.f, (hipStream_t)stream));
+    // the row-piece scratch of the aggregation: sized once from the entry count, first slot here
+    if (!g->agg_slot_bytes) g->agg_slot_bytes = agg_scratch_bound(g->fwd.nnz);
+    if (!g->agg_slots[0].p)
+        MIXGCN_HIP_TRY(hipMalloc((void**)&g->agg_slots[0].p, g->agg_slot_bytes));
+    return MIXGCN_OK;
+}
+
+int mixgcn_graph_reserve_streams(mixgcn_graph* g, int32_t n_streams)
+{
+    if (!g) return fail(MIXGCN_EINVAL, "graph_reserve_streams: graph is null");
+    if (!g->normalized) return fail(MIXGCN_ESTATE, "graph_reserve_streams: call mixgcn_normalize first");
+    if (n_streams < 1 || n_streams > kAggSlots)
+        return fail(MIXGCN_EINVAL, "graph_reserve_streams: between 1 and 16 streams");
+    std::lock_guard<std::mutex> lock(g->agg_mu);
+    int ready = 0, free_slots = 0;
+    for (const AggSlot& slot : g->agg_slots) {
+        if (slot.bound) continue;
+        ++free_slots;
+        if (slot.p) ++ready;
+    }
+    if (free_slots < n_streams)
+        return fail(MIXGCN_EINVAL, "graph_reserve_streams: fewer slots than that are unowned");
+    for (int i = 0; i < kAggSlots && ready < n_streams; ++i) {
+        AggSlot& slot = g->agg_slots[i];
+        if (slot.bound || slot.p) continue;
+        MIXGCN_HIP_TRY(hipMalloc((void**)&slot.p, g->agg_slot_bytes));
+        ++ready;
+    }
+    return MIXGCN_OK;
+}
+
+int64_t mixgcn_aggregate_scratch_bytes(int64_t nnz)
+{
+    if (nnz < 0) return 0;
+    return (int64_t)agg_scratch_bound(nnz);
+}
+
+int64_t mixgcn_aggregate_scratch_need(int dtype, int32_t n_cols, int64_t entry_begin,
+                                      int64_t entry_end)
+{
+    if ((dtype != MIXGCN_F32 && dtype != MIXGCN_BF16) || n_cols < 0 || entry_begin < 0 ||
+        entry_end < entry_begin)
+        return -1;
+    return (int64_t)agg_scratch_need(dtype, n_cols, entry_begin, entry_end);
 }
 
 int mixgcn_graph_info(const mixgcn_graph* g, mixgcn_graph_view* out)
@@ -290,8 +382,12 @@ static int aggregate_impl(const mixgcn_graph* g, int transpose, int dtype, const
     if (mask && ld_mask < ((int64_t)col_end + 31) / 32)
         return fail(MIXGCN_EINVAL, "aggregate: ld_mask shorter than ceil(col_end / 32) words");
     if (row_end == row_begin || col_end == col_begin) return MIXGCN_OK;
+    float* partials = nullptr;
+    size_t partials_bytes = g->agg_slot_bytes;
+    MIXGCN_TRY(acquire_agg_slot(g, stream, &partials));
     return launch_aggregate(g, *m, cv, dtype, H, ldh, Z, ldz, col_begin, col_end, row_begin,
-                            row_end, epilogue, mask, ld_mask, stream, timer);
+                            row_end, epilogue, mask, ld_mask, partials, partials_bytes, stream,
+                            timer);
 }
 
 int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void* H, int64_t ldh,
@@ -462,6 +558,15 @@ int mixgcn_pipeline_create(void* primary_stream, void* secondary_stream, mixgcn_
     if (!p) return fail(MIXGCN_ENOMEM, "pipeline_create: host allocation failed");
     p->primary = (hipStream_t)primary_stream;
     p->secondary = (hipStream_t)secondary_stream;
+    // the work buffers of the update products and of the loss exist from here on, so that the
+    // first step of a pipeline allocates nothing
+    {
+        const int rc = reserve_default_scratch();
+        if (rc != MIXGCN_OK) {
+            delete p;
+            return rc;
+        }
+    }
     if (hipEventCreateWithFlags(&p->ev_start, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&p->ev_done, hipEventDisableTiming) != hipSuccess) {
         mixgcn_pipeline_destroy(p);

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -41,6 +42,20 @@ constexpr int kEntryPad = 8192;
 constexpr uint32_t kEntryEndBit = 0x80000000u;  // last stored entry of its row
 constexpr uint32_t kEntryColMask = 0x3FFFFFFFu;
 
+// Widest pass of the aggregation kernel in columns (fp32 and bf16 alike), and the bytes of row
+// pieces one call can need on a graph with `nnz` stored entries, whatever its ranges.
+constexpr int kAggMaxPassCols = 256;
+size_t agg_scratch_bound(int64_t nnz);
+size_t agg_scratch_need(int dtype, int32_t n_cols, int64_t e0, int64_t e1);
+
+constexpr int kAggSlots = 16;
+struct AggSlot {
+    float* p = nullptr;
+    hipStream_t stream = nullptr;
+    bool bound = false;      // `stream` is meaningful (the null stream is a valid owner)
+    uint64_t last_use = 0;
+};
+
 struct Csr {
     int64_t nnz = 0;
     int64_t nnz_padded = 0;          // allocation length of cv
@@ -72,10 +87,16 @@ struct mixgcn_graph {
     mixgcn::Csr tr;
     uint32_t* deg = nullptr;
     float* dinv = nullptr;
-    // scratch of the aggregation kernels (row pieces that cross lane-group boundaries);
-    // grown on demand, so aggregate calls on one graph must be ordered on one stream.
-    mutable float* partials = nullptr;
-    mutable size_t partials_bytes = 0;
+    // Scratch of the aggregation kernels (pieces of the rows that cross span boundaries).  A
+    // slot is bound to the stream that first asks for one and stays with it, so calls on one
+    // stream share a slot (stream order keeps them apart) and calls on different streams never
+    // do.  Every slot has the same size, fixed by mixgcn_normalize from the entry count (enough
+    // for any row and column range); slot 0 is allocated there, further slots when a further
+    // stream first aggregates this graph or ahead of time by mixgcn_graph_reserve_streams.
+    mutable mixgcn::AggSlot agg_slots[mixgcn::kAggSlots];
+    mutable std::mutex agg_mu;
+    mutable uint64_t agg_tick = 0;
+    size_t agg_slot_bytes = 0;
     // max |u - v| over the stored entries, computed on first use by the cross-layer pipeline
     mutable int64_t bandwidth = -1;
 };
@@ -147,11 +168,12 @@ int normalize_graph(mixgcn_graph* g, int mode, float eps, hipStream_t s);
 // mask: optional bitmap applied to the written outputs (bit c % 32 of mask[r * ldm + c / 32])
 // cv: the entry array to walk (m.cv, or m.cv_t for the transpose of a symmetrised graph with
 // unsymmetric weights); epilogue: MIXGCN_EPI_* flags
+// partials / partials_bytes: scratch for the row pieces (device); a call that would need more is
+// refused with MIXGCN_EINVAL before anything is launched
 int launch_aggregate(const mixgcn_graph* g, const Csr& m, const uint2* cv, int dtype, const void* H,
                      int64_t ldh, void* Z, int64_t ldz, int32_t c0, int32_t c1, int64_t r0,
-                     int64_t r1, int epilogue, const uint32_t* mask, int64_t ldm, hipStream_t s,
-                     Timer* timer);
-
+                     int64_t r1, int epilogue, const uint32_t* mask, int64_t ldm, float* partials,
+                     size_t partials_bytes, hipStream_t s, Timer* timer);
 // bits[r * ldb + c / 32] bit c % 32 = X[r, c] > 0; every word of a row up to ldb is written
 int launch_relu_bitmap(int dtype, const void* X, int64_t ldx, int64_t n, int32_t cols,
                        uint32_t* bits, int64_t ldb, hipStream_t s);

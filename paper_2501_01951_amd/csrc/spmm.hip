@@ -20,8 +20,6 @@
 // XCD mapping.  The slice index is taken from the low bits of the workgroup index.  Workgroups
 // are dealt round-robin to the 8 XCDs, so every slice is pinned to a fixed subset of the XCDs
 // and each private L2 caches only its own part of the hot feature rows.
-#include <vector>
-
 #include "device_utils.h"
 #include "internal.h"
 
@@ -494,54 +492,70 @@ int launch_fixup(const Csr& m, void* Z, int64_t ldz, int c0, int width, int64_t 
 // of 128-byte lines; with a power-of-two pitch a slice's lines fall on few L2 channels.)
 constexpr int slice_lanes(int gf) { return gf < 8 ? gf : 8; }
 
+// One pass: column block, width class and span length.
+struct Pass { int32_t cb; int w, gf; int64_t span; };
+
+// Width class of a pass of w columns (lanes that would span it), and its span length for a
+// range of `entries` stored entries.
+inline void plan_pass(int vec, int32_t cb, int w, int64_t entries, Pass* p)
+{
+    p->cb = cb;
+    p->w = w;
+    p->gf = 4;  // lanes that span the whole pass: fix-up group and partial-slot stride
+    while (p->gf * vec < w) p->gf *= 2;
+    const int lpr = slice_lanes(p->gf);
+    p->span = span_entries(lpr, entries, (int)ceil_div(w, lpr * vec));
+}
+
+}  // namespace
+
+// Bytes of row-piece scratch a call over n_cols columns and the stored entries [e0, e1) needs:
+// the widest of its passes, two slots of the pass's width class per span.
+size_t agg_scratch_need(int dtype, int32_t n_cols, int64_t e0, int64_t e1)
+{
+    const int vec = dtype == MIXGCN_F32 ? 4 : 8;
+    size_t need = 0;
+    for (int32_t cb = 0; cb < n_cols && e1 > e0; cb += kAggMaxPassCols) {
+        Pass p;
+        plan_pass(vec, cb, (n_cols - cb) < kAggMaxPassCols ? (n_cols - cb) : kAggMaxPassCols,
+                  e1 - e0, &p);
+        const int64_t spans = ceil_div(e1, p.span) - e0 / p.span;
+        const size_t bytes = (size_t)spans * 2 * p.gf * vec * sizeof(float);
+        need = bytes > need ? bytes : need;
+    }
+    return need;
+}
+
+namespace {
+
 template <int DT>
 int launch_dt(const mixgcn_graph* g, const Csr& m, const uint2* cv, const void* H, int64_t ldh,
               void* Z, int64_t ldz, int32_t c0, int32_t c1, int64_t r0, int64_t r1, int relu,
-              const uint32_t* mask, int64_t ldm, hipStream_t s, Timer* timer)
+              const uint32_t* mask, int64_t ldm, float* P, size_t P_bytes, hipStream_t s,
+              Timer* timer)
 {
     constexpr int VEC = Feat<DT>::VEC;
-    constexpr int kMaxTile = 64 * VEC;  // widest pass
+    const int64_t e0 = m.h_rowptr[(size_t)r0], e1 = m.h_rowptr[(size_t)r1];
+    // the row pieces of every pass must fit the scratch: checked before anything is launched
+    const size_t need = agg_scratch_need(DT, c1 - c0, e0, e1);
+    if (need > P_bytes)
+        return fail(MIXGCN_EINVAL, "aggregate: " + std::to_string(e1 - e0) + " stored entries at " +
+                                       std::to_string(c1 - c0) + " columns need " +
+                                       std::to_string(need) + " bytes of scratch for row pieces, " +
+                                       std::to_string(P_bytes) + " are there");
     // an empty row adds nothing to an accumulating call, but a ReLU still clamps what it holds
     const bool acc_only = (relu & kEpiAccumulate) && !(relu & kEpiRelu);
     if (m.has_empty_rows && !acc_only && r1 > r0)
         hipLaunchKernelGGL((empty_rows_kernel<DT>), dim3((unsigned)ceil_div(r1 - r0, kBlock)),
                            dim3(kBlock), 0, s, m.rowptr, Z, ldz, c0, c1 - c0, r0, r1,
                            (relu & kEpiAccumulate) ? 1 : 0);
-    const int64_t e0 = m.h_rowptr[(size_t)r0], e1 = m.h_rowptr[(size_t)r1];
     if (e1 <= e0) return MIXGCN_OK;
-    // span length and width class of every pass; the scratch for the row pieces is sized for
-    // the pass that needs most
-    struct Pass { int32_t cb; int w, gf; int64_t span; };
-    std::vector<Pass> passes;
-    size_t need = 0;
-    for (int32_t cb = c0; cb < c1; cb += kMaxTile) {
+    for (int32_t cbk = c0; cbk < c1; cbk += kAggMaxPassCols) {
         Pass p;
-        p.cb = cb;
-        p.w = (c1 - cb) < kMaxTile ? (c1 - cb) : kMaxTile;
-        p.gf = 4;  // lanes that span the whole pass: fix-up group and partial-slot stride
-        while (p.gf * VEC < p.w) p.gf *= 2;
-        const int lpr = slice_lanes(p.gf);
-        p.span = span_entries(lpr, e1 - e0, (int)ceil_div(p.w, lpr * VEC));
-        const int64_t spans = ceil_div(e1, p.span) - e0 / p.span;
-        const size_t bytes = (size_t)spans * 2 * p.gf * VEC * sizeof(float);
-        need = bytes > need ? bytes : need;
-        passes.push_back(p);
-    }
-    if (need > g->partials_bytes) {
-        // growing the scratch waits for earlier work that may still read the old one
-        MIXGCN_HIP_TRY(hipDeviceSynchronize());
-        if (g->partials) (void)hipFree(g->partials);
-        g->partials = nullptr;
-        g->partials_bytes = 0;
-        const size_t want = need + need / 4;
-        MIXGCN_HIP_TRY(hipMalloc((void**)&g->partials, want));
-        g->partials_bytes = want;
-    }
-    for (const Pass& p : passes) {
+        plan_pass(VEC, cbk, (c1 - cbk) < kAggMaxPassCols ? (c1 - cbk) : kAggMaxPassCols, e1 - e0, &p);
         const int32_t cb = p.cb;
         const int w = p.w;
         const int64_t span = p.span;
-        float* P = g->partials;
 #define MIXGCN_AGG_PASS(GG)                                                                      \
     MIXGCN_TRY((launch_main<slice_lanes(GG), GG, DT>(m, cv, (int64_t)g->n, H, ldh, Z, ldz, cb, w, r0, \
                                                      r1, e0, e1, span, P, relu, mask, ldm, s,     \
@@ -696,14 +710,41 @@ int launch_relu_bitmap(int dtype, const void* X, int64_t ldx, int64_t n, int32_t
 
 int launch_aggregate(const mixgcn_graph* g, const Csr& m, const uint2* cv, int dtype, const void* H,
                      int64_t ldh, void* Z, int64_t ldz, int32_t c0, int32_t c1, int64_t r0,
-                     int64_t r1, int epilogue, const uint32_t* mask, int64_t ldm, hipStream_t s,
-                     Timer* timer)
+                     int64_t r1, int epilogue, const uint32_t* mask, int64_t ldm, float* partials,
+                     size_t partials_bytes, hipStream_t s, Timer* timer)
 {
     if (dtype == MIXGCN_F32)
         return launch_dt<MIXGCN_F32>(g, m, cv, H, ldh, Z, ldz, c0, c1, r0, r1, epilogue, mask, ldm,
-                                     s, timer);
-    return launch_dt<MIXGCN_BF16>(g, m, cv, H, ldh, Z, ldz, c0, c1, r0, r1, epilogue, mask, ldm, s,
-                                  timer);
+                                     partials, partials_bytes, s, timer);
+    return launch_dt<MIXGCN_BF16>(g, m, cv, H, ldh, Z, ldz, c0, c1, r0, r1, epilogue, mask, ldm,
+                                  partials, partials_bytes, s, timer);
+}
+
+// Upper bound of the row-piece scratch of one call on a graph with nnz stored entries: over
+// both storage types and every pass width, the spans of the longest possible entry range times
+// the two slots of a span.  A range is cut into spans of span_entries(); when that rule has
+// halved the span at least once, the span count stays below 2 * 8192 / slices + 1.
+size_t agg_scratch_bound(int64_t nnz)
+{
+    size_t best = 0;
+    for (int vec = 4; vec <= 8; vec *= 2) {
+        for (int w = 1; w <= kAggMaxPassCols; ++w) {
+            Pass p;
+            plan_pass(vec, 0, w, nnz, &p);
+            const int lpr = slice_lanes(p.gf);
+            const int n_slices = (int)ceil_div(w, lpr * vec);
+            const int64_t full = (int64_t)kBatchesPerSpan * (kWave / lpr);
+            int64_t spans = ceil_div(nnz, full) + 1;  // a range need not start on a span boundary
+            int64_t small = 2 * 8192 / n_slices + 2;
+            // and no span is shorter than the kGroupNnz entries the span-start table resolves
+            const int64_t most = ceil_div(nnz, kGroupNnz) + 1;
+            if (small > most) small = most;
+            if (small > spans) spans = small;
+            const size_t bytes = (size_t)spans * 2 * p.gf * vec * sizeof(float);
+            best = bytes > best ? bytes : best;
+        }
+    }
+    return best;
 }
 
 }  // namespace mixgcn

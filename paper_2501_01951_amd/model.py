@@ -98,10 +98,11 @@ class GCNStep:
     def capture(self):
         """Records one step (single-stream schedule) into a HIP graph; replay() then launches
         the whole step with one call, which matters when the graph is small and the step is
-        bound by launch overhead.  One eager step runs first so that every scratch buffer has
-        its final size (growing one allocates, which a capture cannot contain)."""
+        bound by launch overhead.  No warm-up step is needed: the library's work buffers exist
+        once a pipeline has been created, and the aggregation scratch of the stream that the
+        capture runs on is reserved here, before the capture starts."""
         assert self.n_chunks == 1, "the captured step uses one stream"
-        self.step()
+        B.graph_reserve_streams(self.g, 1)
         torch.cuda.synchronize()
         self._graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(self._graph):

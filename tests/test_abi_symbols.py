@@ -55,12 +55,48 @@ def test_argument_errors_need_no_gpu():
     assert lib.mixgcn_build_csr(None, None, 5, 10, 3, None, ctypes.byref(out)) == -1  # null edges
     assert lib.mixgcn_build_csr(None, None, 0, 10, 1 << 9, None, ctypes.byref(out)) == -1  # flag
     assert lib.mixgcn_normalize(None, 0, None) == -1
+    assert lib.mixgcn_graph_reserve_streams(None, 1) == -1
     assert lib.mixgcn_graph_free(None) == 0
     assert lib.mixgcn_update(9, 0, None, 0, None, 0, None, 0, 1, 1, 1, None, 0, 0.0, None) == -1
     assert lib.mixgcn_update(0, 0, None, 4, None, 4, None, 4, 1, 4, 4, None, 0, 0.0, None) == -1
     assert lib.mixgcn_set_update_arith(2) == -1 and b"set_update_arith" in lib.mixgcn_last_error()
     assert lib.mixgcn_set_update_arith(m.ARITH_BF16X3) == 0
     assert lib.mixgcn_set_update_arith(m.ARITH_FP32) == 0
+
+
+# ---- sizing rule of the aggregation scratch ---------------------------------------------------
+
+@pytest.mark.parametrize("nnz", [1, 255, 4096, 45_056, 1_000_003, 32_450_196, 3_310_441_142])
+def test_aggregation_scratch_bound_covers_every_call(nnz):
+    """mixgcn_aggregate_scratch_bytes(nnz), the size fixed when a graph is normalised, is at
+    least what any call on that graph uses: every column count, both storage types, entry
+    ranges of every length and alignment (the span length, and with it the number of row
+    pieces per entry, depends on the range)."""
+    import numpy as np
+    import paper_2501_01951_amd as m
+
+    lib = m.load_library()
+    bound = lib.mixgcn_aggregate_scratch_bytes(nnz)
+    assert bound > 0
+    rng = np.random.default_rng(nnz)
+    widths = [1, 3, 4, 8, 16, 17, 32, 47, 64, 100, 128, 129, 172, 255, 256, 257, 300, 512, 1024]
+    lengths = {nnz, max(1, nnz // 2), min(nnz, 256), min(nnz, 257), min(nnz, 8192 * 256),
+               min(nnz, 8192 * 2048), min(nnz, 8192 * 2048 - 1), min(nnz, 8191 * 4096 + 1)}
+    lengths |= {int(x) for x in np.minimum(nnz, rng.integers(1, 1 << 34, size=40) >>
+                                           rng.integers(0, 34, size=40)) if x > 0}
+    worst = 0
+    for dtype in (m.F32, m.BF16):
+        for w in widths:
+            for ln in sorted(lengths):
+                for e0 in {0, nnz - ln, int(rng.integers(0, nnz - ln + 1))}:
+                    need = lib.mixgcn_aggregate_scratch_need(dtype, w, e0, e0 + ln)
+                    assert 0 <= need <= bound, (dtype, w, e0, ln, need, bound)
+                    worst = max(worst, need)
+    # and the bound is not wildly generous: at most twice the largest need seen
+    assert bound <= 2 * worst + 4096, (bound, worst)
+    assert lib.mixgcn_aggregate_scratch_need(7, 4, 0, 1) == -1
+    assert lib.mixgcn_aggregate_scratch_need(m.F32, 4, 5, 1) == -1
+    assert lib.mixgcn_aggregate_scratch_bytes(-1) == 0
 
 
 # ---- host arithmetic of the cross-layer pipeline (Sec. 3.2.2) -------------------------------

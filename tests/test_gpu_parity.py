@@ -164,6 +164,70 @@ def test_aggregate_slices_and_row_ranges(mg, rmat15):
 
 
 # S-SpMM (Sec. 3.2.1, Eq. 4): masked aggregation with the mask in bitmap form
+@pytest.mark.parametrize("reserve", [True, False])
+def test_aggregate_column_slices_on_eight_streams_at_once(mg, reserve):
+    """The m = 8 column slices of Algorithm 2's aggregation phase, each on a stream of its own
+    with no ordering between them: every stream has its own scratch for the rows cut by the
+    work split, so the slices may overlap in time.  Several rounds, also mixed with row chunks
+    and the transposed matrix, each compared with the oracle."""
+    src, dst, n = gg.config_graph("c2", scale_override=16)
+    og = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n)))
+    g = _gpu_graph(mg, src, dst, n)
+    if reserve:
+        mg.graph_reserve_streams(g, 8)
+    f, m = 1024, 8
+    h = gg.normal(31, 1, n, f)
+    ref = oracle.spmm(og, h.astype(np.float64))
+    hd = dev(h)
+    streams = [torch.cuda.Stream() for _ in range(m)]
+    torch.cuda.synchronize()
+    for rnd in range(3):
+        z = torch.full((n, f), float("nan"), device="cuda")
+        torch.cuda.synchronize()
+        say(f"eight streams round {rnd} reserve={reserve}")
+        for i, st in enumerate(streams):
+            p, q = f * i // m, f * (i + 1) // m
+            if rnd == 1:  # two row chunks per slice
+                mg.aggregate(g, hd, z, col_begin=p, col_end=q, row_end=n // 3, stream=st)
+                mg.aggregate(g, hd, z, col_begin=p, col_end=q, row_begin=n // 3, stream=st)
+            else:
+                mg.aggregate(g, hd, z, col_begin=p, col_end=q, transpose=(rnd == 2), stream=st)
+        torch.cuda.synchronize()
+        assert_close(z.cpu().numpy(), ref, RTOL_F32, f"eight streams, round {rnd}")
+    # a ninth stream, and the default stream, get buffers of their own as well
+    z = torch.full((n, f), float("nan"), device="cuda")
+    extra = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    mg.aggregate(g, hd, z, col_end=512, stream=extra)
+    mg.aggregate(g, hd, z, col_begin=512, col_end=f)
+    torch.cuda.synchronize()
+    assert_close(z.cpu().numpy(), ref, RTOL_F32, "ninth stream + default stream")
+    g.free()
+
+
+def test_aggregate_more_streams_than_scratch_slots(mg):
+    """A graph keeps 16 scratch buffers; a 17th and 18th stream take over the least recently
+    used ones (after a device synchronisation) and still give the right result."""
+    src, dst, n = gg.config_graph("c2", scale_override=13)
+    og = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n)))
+    g = _gpu_graph(mg, src, dst, n)
+    f = 18 * 16
+    h = gg.normal(32, 1, n, f)
+    ref = oracle.spmm(og, h.astype(np.float64))
+    hd = dev(h)
+    z = torch.full((n, f), float("nan"), device="cuda")
+    streams = [torch.cuda.Stream() for _ in range(18)]
+    torch.cuda.synchronize()
+    say("eighteen streams on one graph")
+    for i, st in enumerate(streams):
+        mg.aggregate(g, hd, z, col_begin=16 * i, col_end=16 * (i + 1), stream=st)
+    torch.cuda.synchronize()
+    assert_close(z.cpu().numpy(), ref, RTOL_F32, "eighteen streams")
+    with pytest.raises(mg.MixGCNError):
+        mg.graph_reserve_streams(g, 1)  # every slot is owned by now
+    g.free()
+
+
 @pytest.mark.parametrize("n,c", [(1, 1), (77, 31), (1000, 32), (513, 33), (300, 64), (2049, 100),
                                  (999, 256), (64, 300)])
 def test_relu_bitmap_bit_exact(mg, n, c):
@@ -787,8 +851,9 @@ def test_captured_step_replays_match_eager(mg):
     ws = [gg.glorot(gg.MASTER_SEED, 10, 64, 32), gg.glorot(gg.MASTER_SEED, 11, 32, 8)]
     y = gg.labels(gg.MASTER_SEED, 5, n, 8)
     g = _gpu_graph(mg, src, dst, n)
-    eager = mg.GCNStep(g, dev(x), [dev(w) for w in ws], dev(y))
+    # captured first, with no step run on this graph before: the capture needs no warm-up
     graph = mg.GCNStep(g, dev(x), [dev(w) for w in ws], dev(y)).capture()
+    eager = mg.GCNStep(g, dev(x), [dev(w) for w in ws], dev(y))
     for rep in range(4):
         say(f"captured step replay {rep}")
         if rep == 2:  # new weights in place: the graph reads the same buffers
