@@ -71,7 +71,7 @@ def _load():
         lib.oracle_update_wgrad.restype = None
         lib.oracle_softmax_xent.argtypes = [p, i64, p, i64, i64, p, i64]
         lib.oracle_softmax_xent.restype = ctypes.c_double
-        lib.oracle_gcn_step.argtypes = [p, p, p, p, p, p, i64, i32, p, p, p, p, p, p, p, p, i32, i32]
+        lib.oracle_gcn_step.argtypes = [p, p, p, p, p, p, i64, i32, p, p, p, p, p, p, p, p, i32, i32, p]
         lib.oracle_gcn_step.restype = ctypes.c_double
         _lib = lib
     return _lib
@@ -261,9 +261,12 @@ def softmax_xent(logits, labels, want_grad=True):
     return loss, d
 
 
-def gcn_step(g: Graph, X, Ws, labels, want_dx=False, linear=False, q=Q_NONE, backward=True):
+def gcn_step(g: Graph, X, Ws, labels, want_dx=False, linear=False, q=Q_NONE, backward=True,
+             relu_sign=None):
     """One forward(+backward) pass of an L-layer GCN.  Returns a dict with loss, logits,
-    Z (list), H (list, H[0] = X), dW (list) and dX."""
+    Z (list), H (list, H[0] = X), dW (list) and dX.  relu_sign: optional list of L + 1 entries
+    (None or an n x dims[l] array for l = 1..L-1) whose signs replace those of H_l in the
+    backward pass's ReLU derivative (see oracle_gcn_step)."""
     X = _f64(X)
     Ws = [_f64(w) for w in Ws]
     labels = np.ascontiguousarray(labels, dtype=np.int32)
@@ -284,9 +287,16 @@ def gcn_step(g: Graph, X, Ws, labels, want_dx=False, linear=False, q=Q_NONE, bac
     z_arr = PtrArr(*[z.ctypes.data for z in Zs])
     h_arr = PtrArr1(*[h.ctypes.data for h in Hs])
     dw_arr = PtrArr(*[d.ctypes.data for d in dWs]) if backward else None
+    sign_arr = None
+    if relu_sign is not None:
+        assert len(relu_sign) == L + 1
+        signs = [None if a is None else _f64(a) for a in relu_sign]
+        for l, a in enumerate(signs):
+            assert a is None or (0 < l < L and a.shape == (n, int(dims[l])))
+        sign_arr = PtrArr1(*[None if a is None else a.ctypes.data for a in signs])
     loss = _load().oracle_gcn_step(_p(g.rowptr), _p(g.col), _p(g.val), _p(g.t_rowptr),
                                    _p(g.t_col), _p(g.t_val), n, L, _p(dims), _p(X), w_arr, _p(labels),
-                                   z_arr, h_arr, dw_arr, _p(dX), int(linear), q)
+                                   z_arr, h_arr, dw_arr, _p(dX), int(linear), q, sign_arr)
     return {"loss": loss, "logits": Hs[L], "Z": Zs, "H": Hs, "dW": dWs, "dX": dX}
 
 
@@ -336,13 +346,27 @@ def _loss_and_grad(logits, labels, backward):
     return loss, d
 
 
-def sage_step(g: Graph, X, Ws, labels, want_dx=False, backward=True):
+def _sign_of(relu_sign, key, l, own):
+    """The array whose signs decide a ReLU derivative: the caller's stand-in (see
+    oracle_gcn_step: relu_sign) when there is one for layer l, else the oracle's own activation."""
+    if relu_sign is None:
+        return own
+    a = relu_sign.get(key, None) if isinstance(relu_sign, dict) else relu_sign
+    if a is None or a[l] is None:
+        return own
+    a = np.asarray(a[l], dtype=np.float64)
+    assert a.shape == own.shape
+    return a
+
+
+def sage_step(g: Graph, X, Ws, labels, want_dx=False, backward=True, relu_sign=None):
     """L-layer GraphSAGE (mean aggregator).  g: normalize_mean'd graph WITHOUT self-loops.
     Ws[l] has 2 d_l rows: the first d_l multiply the node's own features, the last d_l the mean
     of its neighbors' (the concatenation [h_v | mean]).
         M_l = A_hat H_l;  X_l = [H_l | M_l];  P_l = X_l W_l;  H_{l+1} = relu(P_l), last: P_l.
     Backward: dW_l = X_l^T dP_l;  dX_l = dP_l W_l^T;  dH_l = dX_l[:, :d] + A_hat^T dX_l[:, d:];
-    dP_{l-1} = dH_l (.) 1[H_l > 0]."""
+    dP_{l-1} = dH_l (.) 1[H_l > 0].  relu_sign: optional list indexed like H whose entries stand
+    in for H_l in that derivative."""
     X = _f64(X)
     Ws = [_f64(w) for w in Ws]
     L = len(Ws)
@@ -371,16 +395,17 @@ def sage_step(g: Graph, X, Ws, labels, want_dx=False, backward=True):
         if l == 0:
             out["dX"] = dH
             break
-        dP = dH * (Hs[l] > 0)
+        dP = dH * (_sign_of(relu_sign, "H", l, Hs[l]) > 0)
     out["dW"] = dWs
     return out
 
 
-def gin_step(g: Graph, X, W1s, W2s, labels, want_dx=False, backward=True):
+def gin_step(g: Graph, X, W1s, W2s, labels, want_dx=False, backward=True, relu_sign=None):
     """L-layer GIN.  g: normalize_sum'd graph WITH self-loops (their value carries 1 + eps).
         Z_l = A_hat H_l;  T_l = relu(Z_l W1_l);  P_l = T_l W2_l;  H_{l+1} = relu(P_l), last: P_l.
     Backward: dW2_l = T_l^T dP_l;  dT_l = dP_l W2_l^T (.) 1[T_l > 0];  dW1_l = Z_l^T dT_l;
-    dZ_l = dT_l W1_l^T;  dH_l = A_hat^T dZ_l;  dP_{l-1} = dH_l (.) 1[H_l > 0]."""
+    dZ_l = dT_l W1_l^T;  dH_l = A_hat^T dZ_l;  dP_{l-1} = dH_l (.) 1[H_l > 0].  relu_sign: optional
+    dict {"H": list indexed like H, "T": list indexed like T} of stand-ins for the two derivatives."""
     X = _f64(X)
     W1s = [_f64(w) for w in W1s]
     W2s = [_f64(w) for w in W2s]
@@ -403,7 +428,7 @@ def gin_step(g: Graph, X, W1s, W2s, labels, want_dx=False, backward=True):
     dW1s, dW2s = [None] * L, [None] * L
     for l in range(L - 1, -1, -1):
         dW2s[l] = Ts[l].T @ dP
-        dT = (dP @ W2s[l].T) * (Ts[l] > 0)
+        dT = (dP @ W2s[l].T) * (_sign_of(relu_sign, "T", l, Ts[l]) > 0)
         dW1s[l] = Zs[l].T @ dT
         if l == 0 and not want_dx:
             break
@@ -411,12 +436,13 @@ def gin_step(g: Graph, X, W1s, W2s, labels, want_dx=False, backward=True):
         if l == 0:
             out["dX"] = dH
             break
-        dP = dH * (Hs[l] > 0)
+        dP = dH * (_sign_of(relu_sign, "H", l, Hs[l]) > 0)
     out["dW1"], out["dW2"] = dW1s, dW2s
     return out
 
 
-def gcn_dropout_step(g: Graph, X, Ws, labels, seed: int, keep: float, want_dx=False, backward=True):
+def gcn_dropout_step(g: Graph, X, Ws, labels, seed: int, keep: float, want_dx=False, backward=True,
+                     relu_sign=None):
     """L-layer GCN in the order of Algorithm 2 with the output mask of Sec. 3.2.1 / Eq. 4 on every
     aggregation: Z_l = (A_hat H_l) (.) M_l, M_l = dropout_bitmap(seed + l, n, d_l, keep), P_l =
     Z_l W_l, H_{l+1} = relu(P_l) (none after the last).  The mask is a constant of the step, so
@@ -454,6 +480,6 @@ def gcn_dropout_step(g: Graph, X, Ws, labels, seed: int, keep: float, want_dx=Fa
         if l == 0:
             out["dX"] = dH
             break
-        dP = dH * (Hs[l] > 0)
+        dP = dH * (_sign_of(relu_sign, "H", l, Hs[l]) > 0)
     out["dW"] = dWs
     return out

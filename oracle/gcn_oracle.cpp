@@ -429,12 +429,20 @@ double oracle_softmax_xent(const double* logits, int64_t ldl, const int32_t* lab
  * linear != 0 replaces every ReLU by the identity.  q != 0 rounds every stored n x F tensor
  * (Z_l, H_l including the logits, the loss gradient, dZ_l, dH_l, dP_l) to fp32 / bf16 where it
  * is written; weights, A_hat, the loss and dW stay in double.  Returns the loss.
+ * relu_sign (may be NULL, and so may any entry): relu_sign[l], l = 1..L-1, is an n x dims[l]
+ * array that stands in for H_l where the backward pass takes the ReLU derivative,
+ * dP_{l-1} = dH_l (.) 1[relu_sign[l] > 0].  The derivative is a 0/1 decision taken from a
+ * floating-point value; a caller that compares another implementation's gradients passes that
+ * implementation's stored activations here, so that both sides take every decision from the
+ * same numbers (an activation within rounding error of zero is a coin toss that neither side
+ * gets wrong).  The forward pass is not affected.
  */
 double oracle_gcn_step(const int64_t* rowptr, const uint32_t* col, const double* val,
                        const int64_t* t_rowptr, const uint32_t* t_col, const double* t_val,
                        int64_t n, int n_layers, const int64_t* dims, const double* X,
                        const double* const* W, const int32_t* labels, double* const* Zs,
-                       double* const* Hs, double* const* dW, double* dX, int linear, int q)
+                       double* const* Hs, double* const* dW, double* dX, int linear, int q,
+                       const double* const* relu_sign)
 {
     const int L = n_layers;
     const double* Hin = X;
@@ -464,7 +472,8 @@ double oracle_gcn_step(const int64_t* rowptr, const uint32_t* col, const double*
             break;
         }
         dP.assign((size_t)n * k, 0.0);
-        oracle_relu_grad(dH.data(), k, linear ? nullptr : Hs[l], k, dP.data(), k, n, k, q);
+        const double* sign = (relu_sign && relu_sign[l]) ? relu_sign[l] : Hs[l];
+        oracle_relu_grad(dH.data(), k, linear ? nullptr : sign, k, dP.data(), k, n, k, q);
     }
     return loss;
 }

@@ -559,6 +559,153 @@ def test_step_matches_composition_of_calls():
                                   oracle.spmm(g, oracle.update_dgrad(dp0, ws[0]), transposed=True))
 
 
+def _round_bf16(a):
+    """bf16 (8 exponent bits, 7 fraction bits) round-to-nearest-even of doubles, written from
+    the format: go through fp32 and round its low 16 bits away with numpy integer arithmetic."""
+    u = np.asarray(a, dtype=np.float64).astype(np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+def _is_bf16(a):
+    return np.array_equal(_round_bf16(a), np.asarray(a, dtype=np.float64))
+
+
+def _round_as(q):
+    if q == oracle.Q_BF16:
+        return _round_bf16
+    return lambda a: np.asarray(a, dtype=np.float64).astype(np.float32).astype(np.float64)
+
+
+@pytest.mark.parametrize("q", [oracle.Q_F32, oracle.Q_BF16])
+def test_every_call_with_storage_rounding_is_the_unrounded_call_rounded_once(q):
+    """q rounds a result where it is stored and nowhere else: each single call with q equals
+    the same call without q, rounded by an independent implementation of the format."""
+    g, src, dst, x, ws, y = _tiny_problem(43, n=40, dims=(6, 5, 4))
+    rnd = _round_as(q)
+    rng = np.random.default_rng(5)
+    bits = oracle.relu_bitmap(rng.normal(size=(g.n, 6)))
+    np.testing.assert_array_equal(oracle.spmm(g, x, q=q), rnd(oracle.spmm(g, x)))
+    np.testing.assert_array_equal(oracle.spmm(g, x, transposed=True, q=q),
+                                  rnd(oracle.spmm(g, x, transposed=True)))
+    np.testing.assert_array_equal(oracle.sspmm(g, x, bits, q=q), rnd(oracle.sspmm(g, x, bits)))
+    for relu in (True, False):
+        np.testing.assert_array_equal(oracle.update_fwd(x, ws[0], relu, q=q),
+                                      rnd(oracle.update_fwd(x, ws[0], relu)))
+    dp = rng.normal(size=(g.n, 5))
+    np.testing.assert_array_equal(oracle.update_dgrad(dp, ws[0], q=q),
+                                  rnd(oracle.update_dgrad(dp, ws[0])))
+    href = rng.normal(size=(g.n, 5))
+    np.testing.assert_array_equal(oracle.relu_grad(dp, href, q=q), rnd(oracle.relu_grad(dp, href)))
+    assert not _is_bf16(oracle.spmm(g, x)) and _is_bf16(oracle.spmm(g, x, q=oracle.Q_BF16))
+
+
+def _composed_step(g, x, ws, y, q, skip=None):
+    """The 3-layer step as a sequence of the single calls, every stored n x F tensor rounded
+    with q where it is written -- except the one named by `skip` (to show that leaving any one
+    rounding out changes the result)."""
+    skip = set((skip or "").split("+"))
+
+    def qq(name):
+        return oracle.Q_NONE if name in skip else q
+
+    rnd = _round_as(q)
+    L = len(ws)
+    hs, zs = [x], []
+    for l in range(L):
+        zs.append(oracle.spmm(g, hs[l], q=qq(f"Z{l}")))
+        hs.append(oracle.update_fwd(zs[l], ws[l], relu=l < L - 1, q=qq(f"H{l + 1}")))
+    loss, dp = oracle.softmax_xent(hs[L], y)
+    if "dlogits" not in skip:
+        dp = rnd(dp)
+    dws = [None] * L
+    dx = None
+    for l in range(L - 1, -1, -1):
+        dws[l] = oracle.update_wgrad(zs[l], dp)
+        dz = oracle.update_dgrad(dp, ws[l], q=qq(f"dZ{l}"))
+        dh = oracle.spmm(g, dz, transposed=True, q=qq(f"dH{l}"))
+        if l == 0:
+            dx = dh
+            break
+        dp = oracle.relu_grad(dh, hs[l], q=qq(f"dP{l - 1}"))
+    return {"loss": loss, "Z": zs, "H": hs, "dW": dws, "dX": dx}
+
+
+# dP_{l-1} = dH_l (.) mask is rounded like dH_l, and rounding twice is rounding once: the two
+# are one rounding point, left out together
+ROUNDING_POINTS = (["Z0", "Z1", "Z2", "H1", "H2", "H3", "dlogits"] +
+                   ["dZ2", "dZ1", "dZ0", "dH2+dP1", "dH1+dP0", "dH0"])
+
+
+@pytest.mark.parametrize("q", [oracle.Q_F32, oracle.Q_BF16])
+def test_rounded_step_is_the_composition_of_the_rounded_calls(q):
+    """The bf16 (and fp32) storage mode of the whole step: exactly the tensors that are stored as
+    n x F arrays -- Z_l, H_l including the logits, the loss gradient, dZ_l, dH_l, dP_l -- are
+    rounded where they are written; the loss and dW are not."""
+    g, src, dst, x, ws, y = _tiny_problem(44, n=48, dims=(6, 7, 5, 4))
+    x = _round_as(q)(x)
+    out = oracle.gcn_step(g, x, ws, y, want_dx=True, q=q)
+    ref = _composed_step(g, x, ws, y, q)
+    assert out["loss"] == ref["loss"]
+    for l in range(3):
+        np.testing.assert_array_equal(out["Z"][l], ref["Z"][l])
+        np.testing.assert_array_equal(out["H"][l + 1], ref["H"][l + 1])
+        np.testing.assert_array_equal(out["dW"][l], ref["dW"][l])
+    np.testing.assert_array_equal(out["dX"], ref["dX"])
+    if q == oracle.Q_BF16:
+        for l in range(3):
+            assert _is_bf16(out["Z"][l]) and _is_bf16(out["H"][l + 1])
+            assert not _is_bf16(out["dW"][l])
+        assert _is_bf16(out["dX"]) and _is_bf16(out["logits"])
+        assert not _is_bf16(np.array([out["loss"]]))
+
+
+@pytest.mark.parametrize("skip", ROUNDING_POINTS)
+def test_leaving_out_any_one_rounding_point_changes_the_bf16_step(skip):
+    """Sensitivity of the pin above: the composition with one rounding left out no longer
+    equals the step, so a rounding dropped from (or moved inside) the step would be seen."""
+    g, src, dst, x, ws, y = _tiny_problem(44, n=48, dims=(6, 7, 5, 4))
+    x = _round_bf16(x)
+    out = oracle.gcn_step(g, x, ws, y, want_dx=True, q=oracle.Q_BF16)
+    ref = _composed_step(g, x, ws, y, oracle.Q_BF16, skip=skip)
+    same = all(np.array_equal(out["dW"][l], ref["dW"][l]) for l in range(3))
+    same = same and np.array_equal(out["dX"], ref["dX"]) and out["loss"] == ref["loss"]
+    same = same and all(np.array_equal(out["H"][l + 1], ref["H"][l + 1]) for l in range(3))
+    assert not same
+
+
+def test_relu_sign_input_replaces_only_the_derivative_decision():
+    """relu_sign stands in for H_l in dP_{l-1} = dH_l (.) 1[. > 0] and in nothing else: the
+    oracle's own activations give the step unchanged; a stand-in with planted flips gives the
+    composition of the single calls with relu_grad taken from the stand-in; the forward pass,
+    the loss and the gradients of the layers at and above the stand-in do not move."""
+    g, src, dst, x, ws, y = _tiny_problem(45, n=50, dims=(5, 6, 6, 3))
+    base = oracle.gcn_step(g, x, ws, y, want_dx=True)
+    again = oracle.gcn_step(g, x, ws, y, want_dx=True,
+                            relu_sign=[None, base["H"][1], base["H"][2], None])
+    for l in range(3):
+        np.testing.assert_array_equal(base["dW"][l], again["dW"][l])
+    np.testing.assert_array_equal(base["dX"], again["dX"])
+    rng = np.random.default_rng(9)
+    s2 = base["H"][2].copy()
+    flip = rng.random(s2.shape) < 0.2
+    s2[flip] = np.where(s2[flip] > 0, 0.0, 1.0)  # a zero becomes "positive" and the reverse
+    got = oracle.gcn_step(g, x, ws, y, want_dx=True, relu_sign=[None, None, s2, None])
+    assert got["loss"] == base["loss"]
+    for l in range(3):
+        np.testing.assert_array_equal(got["H"][l + 1], base["H"][l + 1])
+    np.testing.assert_array_equal(got["dW"][2], base["dW"][2])
+    _, dp2 = oracle.softmax_xent(base["logits"], y)
+    dh2 = oracle.spmm(g, oracle.update_dgrad(dp2, ws[2]), transposed=True)
+    dp1 = oracle.relu_grad(dh2, s2)
+    np.testing.assert_array_equal(got["dW"][1], oracle.update_wgrad(base["Z"][1], dp1))
+    dh1 = oracle.spmm(g, oracle.update_dgrad(dp1, ws[1]), transposed=True)
+    dp0 = oracle.relu_grad(dh1, base["H"][1])
+    np.testing.assert_array_equal(got["dW"][0], oracle.update_wgrad(base["Z"][0], dp0))
+    assert not np.array_equal(got["dW"][1], base["dW"][1])
+    assert not np.array_equal(got["dW"][0], base["dW"][0])
+
+
 def test_bf16_quantiser_rounds_to_nearest_even():
     # 1 + 2^-8 is a tie between 1 and 1 + 2^-7 -> even mantissa (1.0); 1 + 3*2^-8 ties up.
     z = np.array([[1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, -0.3]])
