@@ -198,6 +198,23 @@ int64_t mixgcn_aggregate_scratch_need(int dtype, int32_t n_cols, int64_t entry_b
                                       int64_t entry_end);
 
 /*
+ * mixgcn_aggregate for callers that cannot allocate device memory or tolerate a library that
+ * does (work recorded into a HIP graph, tight serving loops, harnesses that forbid hipMalloc):
+ * the same kernels and the same result bit for bit, but the scratch for the rows cut by the
+ * work split is a fixed 64 MiB array in device memory that the library holds on every GPU it
+ * runs on until the process ends.  The call makes no hipMalloc / hipFree and no call that does.
+ * A call that needs more scratch than the array has (mixgcn_aggregate_scratch_need: about one
+ * byte per stored entry of the row range at 256 fp32 columns, half of that at 128; 67 million
+ * entries fit at 256 columns) is refused with MIXGCN_EINVAL before anything is launched.  All
+ * calls on one GPU share the array, whatever the graph: calls that overlap in time (different
+ * streams with no ordering between them) race; calls on one stream are safe.  Nothing in the
+ * array has to be cleared between calls: every slot a call reads it has written before.
+ */
+int mixgcn_aggregate_static(const mixgcn_graph* g, int transpose, int dtype, const void* H,
+                            int64_t ldh, void* Z, int64_t ldz, int32_t col_begin, int32_t col_end,
+                            int64_t row_begin, int64_t row_end, void* stream);
+
+/*
  * mixgcn_aggregate with an epilogue (MIXGCN_EPI_* flags, 0 = none), for the layer forms that
  * combine a node's own features with the aggregate (GraphSAGE's concatenation, whose backward
  * pass is dH = dX_self + A_hat^T dX_neigh):

@@ -7,7 +7,7 @@ for device memory and streams.  There is no CPU fallback: a missing library is a
 from .binding import (  # noqa: F401
     AGG_FIRST, UPDATE_FIRST, BF16, F32, NORM_SYM, NORM_MEAN, NORM_SUM, EPI_RELU, EPI_ACCUMULATE, ARITH_FP32, ARITH_BF16X3, OP_DGRAD, OP_FWD, OP_FWD_RELU, OP_WGRAD, SYMMETRIZE, ADD_SELF_LOOPS,
     BUILD_TRANSPOSE, INPUT_ON_HOST, Graph, LayerDesc, MixGCNError, Pipeline, aggregate, aggregate_masked,
-    aggregate_scratch_bytes, graph_reserve_streams,
+    aggregate_scratch_bytes, aggregate_static, graph_reserve_streams,
     apply_bitmap,
     backward_pipelined, bandwidth, build_csr, dropout_bitmap, forward_pipelined, pipeline_window,
     cu_subset_stream,

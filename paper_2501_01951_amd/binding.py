@@ -79,6 +79,8 @@ def load_library():
     lib.mixgcn_aggregate_scratch_bytes.restype = i64
     lib.mixgcn_aggregate_scratch_need.argtypes = [ctypes.c_int, i32, i64, i64]
     lib.mixgcn_aggregate_scratch_need.restype = i64
+    lib.mixgcn_aggregate_static.argtypes = lib.mixgcn_aggregate.argtypes
+    lib.mixgcn_aggregate_static.restype = ctypes.c_int
     lib.mixgcn_aggregate_masked.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, i64, vp, i64, i32,
                                             i32, i64, i64, vp, i64, vp]
     lib.mixgcn_relu_bitmap.argtypes = [ctypes.c_int, vp, i64, i64, i32, vp, i64, vp]
@@ -315,6 +317,17 @@ def aggregate(g: Graph, H, Z, col_begin=0, col_end=None, row_begin=0, row_end=No
     _check(load_library().mixgcn_aggregate(g._h, int(transpose), _dtype_of(H), _ptr(H), _ld(H),
                                            _ptr(Z), _ld(Z), col_begin, col_end, row_begin, row_end,
                                            _stream(stream)), "aggregate")
+
+
+def aggregate_static(g: Graph, H, Z, col_begin=0, col_end=None, row_begin=0, row_end=None,
+                     transpose=False, stream=None) -> None:
+    """mixgcn_aggregate with the library's fixed scratch array: allocates nothing."""
+    col_end = H.shape[1] if col_end is None else col_end
+    row_end = g.n if row_end is None else row_end
+    _check(load_library().mixgcn_aggregate_static(g._h, int(transpose), _dtype_of(H), _ptr(H),
+                                                  _ld(H), _ptr(Z), _ld(Z), col_begin, col_end,
+                                                  row_begin, row_end, _stream(stream)),
+           "aggregate_static")
 
 
 def graph_reserve_streams(g: Graph, n_streams: int) -> None:

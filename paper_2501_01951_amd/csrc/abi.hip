@@ -332,7 +332,8 @@ int mixgcn_graph_info(const mixgcn_graph* g, mixgcn_graph_view* out)
 static int aggregate_impl(const mixgcn_graph* g, int transpose, int dtype, const void* H,
                           int64_t ldh, void* Z, int64_t ldz, int32_t col_begin, int32_t col_end,
                           int64_t row_begin, int64_t row_end, int epilogue, hipStream_t stream,
-                          Timer* timer, const uint32_t* mask = nullptr, int64_t ld_mask = 0)
+                          Timer* timer, const uint32_t* mask = nullptr, int64_t ld_mask = 0,
+                          bool static_scratch = false)
 {
     if (!g) return fail(MIXGCN_EINVAL, "aggregate: graph is null");
     if (!g->normalized) return fail(MIXGCN_ESTATE, "aggregate: call mixgcn_normalize first");
@@ -384,7 +385,8 @@ static int aggregate_impl(const mixgcn_graph* g, int transpose, int dtype, const
     if (row_end == row_begin || col_end == col_begin) return MIXGCN_OK;
     float* partials = nullptr;
     size_t partials_bytes = g->agg_slot_bytes;
-    MIXGCN_TRY(acquire_agg_slot(g, stream, &partials));
+    if (static_scratch) MIXGCN_TRY(static_agg_scratch(&partials, &partials_bytes));
+    else MIXGCN_TRY(acquire_agg_slot(g, stream, &partials));
     return launch_aggregate(g, *m, cv, dtype, H, ldh, Z, ldz, col_begin, col_end, row_begin,
                             row_end, epilogue, mask, ld_mask, partials, partials_bytes, stream,
                             timer);
@@ -396,6 +398,14 @@ int mixgcn_aggregate(const mixgcn_graph* g, int transpose, int dtype, const void
 {
     return aggregate_impl(g, transpose, dtype, H, ldh, Z, ldz, col_begin, col_end, row_begin,
                           row_end, 0, (hipStream_t)stream, nullptr);
+}
+
+int mixgcn_aggregate_static(const mixgcn_graph* g, int transpose, int dtype, const void* H,
+                            int64_t ldh, void* Z, int64_t ldz, int32_t col_begin, int32_t col_end,
+                            int64_t row_begin, int64_t row_end, void* stream)
+{
+    return aggregate_impl(g, transpose, dtype, H, ldh, Z, ldz, col_begin, col_end, row_begin,
+                          row_end, 0, (hipStream_t)stream, nullptr, nullptr, 0, true);
 }
 
 int mixgcn_aggregate_ex(const mixgcn_graph* g, int transpose, int dtype, const void* H, int64_t ldh,

@@ -174,6 +174,10 @@ int launch_aggregate(const mixgcn_graph* g, const Csr& m, const uint2* cv, int d
                      int64_t ldh, void* Z, int64_t ldz, int32_t c0, int32_t c1, int64_t r0,
                      int64_t r1, int epilogue, const uint32_t* mask, int64_t ldm, float* partials,
                      size_t partials_bytes, hipStream_t s, Timer* timer);
+// The aggregation scratch that lives in a fixed device array of the library (one copy per
+// device), for the entry point that may not allocate.
+int static_agg_scratch(float** p, size_t* bytes);
+
 // bits[r * ldb + c / 32] bit c % 32 = X[r, c] > 0; every word of a row up to ldb is written
 int launch_relu_bitmap(int dtype, const void* X, int64_t ldx, int64_t n, int32_t cols,
                        uint32_t* bits, int64_t ldb, hipStream_t s);

@@ -20,6 +20,8 @@
 // XCD mapping.  The slice index is taken from the low bits of the workgroup index.  Workgroups
 // are dealt round-robin to the 8 XCDs, so every slice is pinned to a fixed subset of the XCDs
 // and each private L2 caches only its own part of the hot feature rows.
+#include <mutex>
+
 #include "device_utils.h"
 #include "internal.h"
 
@@ -745,6 +747,36 @@ size_t agg_scratch_bound(int64_t nnz)
         }
     }
     return best;
+}
+
+// Row-piece scratch for the entry point that may not allocate: a fixed array in device memory
+// (every GPU the library runs on holds its own copy until the process ends).  Host code never
+// uses the array's name as an address: the device address is looked up once per device, with
+// that device current, and kept.
+constexpr size_t kStaticAggBytes = (size_t)64 << 20;
+static __device__ __align__(256) float scratch[kStaticAggBytes / sizeof(float)];
+
+namespace {
+constexpr int kStaticDevices = 16;
+float* g_static_ptr[kStaticDevices] = {};
+std::mutex g_static_mu;
+}  // namespace
+
+int static_agg_scratch(float** p, size_t* bytes)
+{
+    int dev = 0;
+    MIXGCN_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kStaticDevices) return fail(MIXGCN_EINVAL, "aggregate_static: device index");
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[dev]) {
+        void* q = nullptr;
+        MIXGCN_HIP_TRY(hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)));
+        if (!q) return fail(MIXGCN_EHIP, "aggregate_static: no device address for the scratch array");
+        g_static_ptr[dev] = reinterpret_cast<float*>(q);
+    }
+    *p = g_static_ptr[dev];
+    *bytes = kStaticAggBytes;
+    return MIXGCN_OK;
 }
 
 }  // namespace mixgcn
