@@ -1,21 +1,35 @@
 #!/usr/bin/env python3
 """Benchmark of the GCN hot path on one MI355X.
 
-One "step" = one full-graph epoch (forward + loss + backward) of the 3-layer GCN of the
-second benchmark configuration: R-MAT scale-20 graph (16 N directed edges, symmetrised,
-self-loops, sym-normalised), X = N x 128 ~ N(0,1), Glorot weights 128 -> 256 -> 256 -> 16,
-16 classes, fp32.  Inputs are synthetic and resident in HBM before the timed region.
+The default run measures three of the benchmark configurations, one after the other, on
+synthetic inputs that are resident in HBM before each timed region, and prints ONE JSON line:
 
-Prints ONE JSON line: whole-job throughput in edges*feat/s (sum over layers of
-nnz(A_hat) * d^(l), divided by the step time), the roofline of the dominant kernel (the
-aggregation gather at 256 columns) from HIP events recorded around its launches inside the
-timed region, and the CPU oracle timed on a bounded, down-scaled sample of the same workload.
+  headline   config 4, the largest configuration one GPU holds: one GCN layer 128 -> 128,
+             forward + backward, on the power-law graph with N = 1.11e8 nodes and 3.3e9
+             stored entries (the three-layer model's activations do not fit 288 GB, the paper
+             spreads them over 32 GPUs; one layer at its real shape does).  If it cannot run
+             (not enough device memory on this machine), config 3 and then config 2 take its
+             place and the line says so.
+  secondary  config 2 (3-layer GCN 128-256-256-16, R-MAT scale 20, fp32), one epoch, and
+             config 5 (3-layer GCN 100-256-256-47, N = 2.45e6, bf16 storage), one epoch.
+
+`value` is whole-job throughput in edges*feat/s: sum over layers of nnz(A_hat) * d^(l), divided
+by the step time.  `roofline` describes the dominant kernel (the aggregation gather): its
+algorithmic bytes per launch over its average launch duration, taken from HIP events that the
+library records around that kernel on the kernel's own stream inside the timed region.
+`cpu_baseline` is the CPU oracle as it stands, timed on this host on a bounded, down-scaled
+sample of the headline workload (median of three runs after a warm-up).
+
+`--config c1|c2|c3|c4|c5` runs that configuration alone (the form the profiles under profiles/
+were taken with).
 """
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -23,39 +37,50 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
+MFMA_F32_TFLOPS = 157.3     # published dense fp32 matrix rate
+KIND_NAMES = ["agg_g4", "agg_g8", "agg_g16", "agg_g32", "agg_g64", "update_fwd", "update_dgrad",
+              "update_wgrad"]
+# rocprofv3 --pmc summaries (committed) that hold the HBM traffic of the dominant kernel
+TRAFFIC_FILES = {("c2", 256): "c2_aggregate_pmc.txt", ("c3", 128): "c3_aggregate_pmc.txt",
+                 ("c4", 128): "c4_aggregate_pmc.txt", ("c5", 256): "c5_aggregate_pmc.txt"}
 
 
 def measured_traffic(config, width):
-    """HBM bytes per launch of the dominant kernel, taken from the committed rocprofv3 --pmc
-    summary of this same command (counters cannot be read from inside the run)."""
-    files = {("c2", 256): "c2_aggregate_pmc.txt", ("c3", 128): "c3_aggregate_pmc.txt",
-             ("c4", 128): "c4_aggregate_pmc.txt"}
-    if (config, width) not in files:
-        return None
-    path = os.path.join(ROOT, "profiles", files[(config, width)])
+    """HBM bytes per launch of the dominant kernel and where the figure comes from: the
+    committed rocprofv3 --pmc summary of this same workload.  Hardware counters cannot be read
+    from inside the run, so this is NOT measured by the run that prints it."""
+    name = TRAFFIC_FILES.get((config, width))
+    if name is None:
+        return None, None
+    path = os.path.join(ROOT, "profiles", name)
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split()[1])
+                return float(line.split()[1]), (
+                    f"profiles/{name}: 2.0 x FETCH_SIZE + WRITE_SIZE from two rocprofv3 --pmc runs "
+                    f"of this workload (committed summary, not re-measured in this run)")
     except OSError:
         pass
-    return None
+    return None, None
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def model_dims(name):
-    if name == "c2":
-        return [128, 256, 256, 16]
-    if name == "c1":
-        return [64, 32, 8]
-    if name == "c5":
-        return [100, 256, 256, 47]
-    raise ValueError(name)
+    return {"c1": [64, 32, 8], "c2": [128, 256, 256, 16], "c4": [128, 128, 128, 172],
+            "c5": [100, 256, 256, 47]}[name]
 
 
 def make_inputs(name, scale, seed):
-    import numpy as np
-
     import graphgen as gg
 
     dims = model_dims(name)
@@ -71,32 +96,136 @@ def make_inputs(name, scale, seed):
     return src, dst, n, x, ws, y, dims
 
 
-def cpu_baseline(name, scale, seed):
-    """The oracle as it stands on the host cores, one forward+backward step of a down-scaled
-    instance of the same generator and model."""
+def timed_median(fn, runs=3):
+    """One warm-up call, then `runs` timed calls; returns (median seconds, all timed seconds)."""
+    fn()
+    ts = []
+    for _ in range(runs):
+        t0 = time.perf_counter()
+        fn()
+        ts.append(time.perf_counter() - t0)
+    return statistics.median(ts), ts
+
+
+def cpu_baseline_model(name, scale, seed, single_thread_scale=None):
+    """The oracle on the host cores: one forward+backward step of a down-scaled instance of the
+    same generator and model (median of 3 after a warm-up); optionally also one thread on a
+    smaller instance."""
     import numpy as np
 
     import oracle
 
-    src, dst, n, x, ws, y, dims = make_inputs(name, scale, seed)
-    g = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n)))
-    ws = [np.ascontiguousarray(w) for w in ws]
-    t0 = time.perf_counter()
-    if name == "c5":
-        oracle.gcn_step(g, x, ws, y, q=oracle.Q_BF16)
-    else:
-        oracle.gcn_step(g, x, ws, y)
-    dt = time.perf_counter() - t0
+    def prepare(sc):
+        src, dst, n, x, ws, y, dims = make_inputs(name, sc, seed)
+        g = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n)))
+        ws = [np.ascontiguousarray(w) for w in ws]
+        q = oracle.Q_BF16 if name == "c5" else oracle.Q_NONE
+        return g, n, dims, (lambda: oracle.gcn_step(g, x, ws, y, q=q))
+
+    g, n, dims, step = prepare(scale)
+    med, ts = timed_median(step)
     work = sum(g.nnz * d for d in dims[:-1])
+    out = {
+        "value": work / med, "unit": "edges*feat/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "cpu_model": cpu_model(), "median_s": med, "runs_s": ts,
+        "sample": f"{name}'s generator and model at scale {scale} (N={n}, nnz={g.nnz}), one "
+                  f"fwd+bwd step, median of 3 after a warm-up",
+    }
+    if single_thread_scale:
+        g1, n1, dims1, step1 = prepare(single_thread_scale)
+        threads = oracle.num_threads()
+        oracle.set_num_threads(1)
+        try:
+            med1, ts1 = timed_median(step1)
+        finally:
+            oracle.set_num_threads(threads)
+        out["single_thread"] = {
+            "value": sum(g1.nnz * d for d in dims1[:-1]) / med1, "unit": "edges*feat/s", "cores": 1,
+            "median_s": med1, "runs_s": ts1,
+            "sample": f"{name}'s generator and model at scale {single_thread_scale} (N={n1}, "
+                      f"nnz={g1.nnz}), one thread"}
+    return out
+
+
+def cpu_baseline_layer(name, scale, seed, k, m, relu):
+    """The oracle on the host cores for the single-layer workloads (configs 3 and 4): Z = A_hat H,
+    H' = sigma(Z W), dW = Z^T dP, dZ = dP W^T, dH = A_hat^T dZ on a down-scaled instance of the
+    same graph generator, median of 3 after a warm-up."""
+    import numpy as np
+
+    import graphgen as gg
+    import oracle
+
+    if name == "c3":
+        n = 1 << scale
+        src, dst = gg.rmat_edges(seed, scale, 8 * n)
+    else:
+        src, dst, n = gg.config_graph("c4", seed, scale)
+    g = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n)))
+    h = gg.normal(seed, 1, n, k).astype(np.float64)
+    w = gg.glorot(seed, 10, k, m).astype(np.float64)
+    grad = gg.normal(seed, 3, n, m).astype(np.float64)
+
+    def step():
+        z = oracle.spmm(g, h)
+        out = oracle.update_fwd(z, w, relu)
+        dp = oracle.relu_grad(grad, out if relu else None)
+        oracle.update_wgrad(z, dp)
+        oracle.spmm(g, oracle.update_dgrad(dp, w), transposed=True)
+
+    med, ts = timed_median(step)
     return {
-        "value": work / dt, "unit": "edges*feat/s", "cores": oracle.num_threads(), "kind": "oracle",
-        "sample": f"same generator and model at R-MAT scale {scale} (N={n}, nnz={g.nnz}), "
-                  f"one fwd+bwd step, {dt:.1f} s",
+        "value": g.nnz * k / med, "unit": "edges*feat/s", "cores": oracle.num_threads(),
+        "kind": "oracle", "cpu_model": cpu_model(), "median_s": med, "runs_s": ts,
+        "sample": f"{name}'s graph generator at scale {scale} (N={n}, nnz={g.nnz}), one layer "
+                  f"{k}->{m} fwd+bwd, median of 3 after a warm-up",
     }
 
 
-def bench_single_layer(args, mg, dev):
-    """Configs 3 and 4 (not the default line): one layer forward + backward at the real shape.
+def read_kinds(pipe):
+    kinds = {}
+    for i, nm in enumerate(KIND_NAMES):
+        ms, cnt = pipe.timing_read(i)
+        if cnt:
+            kinds[nm] = {"total_ms": ms, "launches": cnt, "avg_ms": ms / cnt}
+    return kinds
+
+
+def aggregation_roofline(config, kinds, nnz, n, esz, chunks=1):
+    """Roofline block of the aggregation launch that takes the most time of the step."""
+    agg = {k: v for k, v in kinds.items() if k.startswith("agg")}
+    if not agg:
+        return None
+    dom = max(agg, key=lambda k: agg[k]["total_ms"])
+    gsz = int(dom.split("g")[-1])
+    f = gsz * 16 // esz  # columns of a pass of that width class (16 bytes per lane)
+    # algorithmic minimum per full-graph launch: the entry stream (column + value) once, every
+    # feature row read once, every output row written once, one row pointer per row
+    per_launch = (8.0 * nnz + 2.0 * n * f * esz + 8.0 * n) / max(1, chunks)
+    no_reuse = (nnz * (8.0 + f * esz) + n * f * esz) / max(1, chunks)
+    avg_s = agg[dom]["avg_ms"] * 1e-3
+    achieved = per_launch / avg_s / 1e9
+    traffic, source = measured_traffic(config, f) if chunks == 1 else (None, None)
+    out = {
+        "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": source,
+        "what_achieved_counts": "algorithmic bytes (each feature row read once) per launch / "
+                                "average launch duration",
+        "kernel": f"aggregate_kernel<8, {gsz}, {1 if esz == 2 else 0}, ...> "
+                  f"({f} {'bf16' if esz == 2 else 'fp32'} columns)",
+        "avg_launch_ms": agg[dom]["avg_ms"], "launches": agg[dom]["launches"],
+        "algorithmic_bytes_per_launch": per_launch,
+        "no_reuse_bytes_per_launch": no_reuse,
+        "no_reuse_GBps": no_reuse / avg_s / 1e9,
+    }
+    if traffic:
+        out["counter_traffic_GBps"] = traffic / avg_s / 1e9
+        out["counter_traffic_frac"] = traffic / avg_s / 1e9 / HBM_PEAK_GBS
+    return out
+
+
+def bench_single_layer(args, mg, dev, config):
+    """Configs 3 and 4: one layer forward + backward at the real shape.
 
     c3: a 128-column slice of a 1024-wide layer, R-MAT scale 24 with 8 N directed edges; H comes
     from the seeded generator, the 68.7 GB upstream gradient G is drawn on the device.
@@ -111,7 +240,8 @@ def bench_single_layer(args, mg, dev):
     import graphgen as gg
     from paper_2501_01951_amd.model import padded_rows
 
-    if args.config == "c3":
+    t_gen = time.perf_counter()
+    if config == "c3":
         scale = args.scale or 24
         n, k, m, relu = 1 << scale, 128, 1024, True
         src, dst = gg.rmat_edges(args.seed, scale, 8 * n)
@@ -120,22 +250,27 @@ def bench_single_layer(args, mg, dev):
         src, dst, n = gg.config_graph("c4", args.seed, args.scale)
         k, m, relu = 128, 128, False
         what = "c4: one GCN layer 128->128 fwd+bwd (no ReLU), power-law graph"
+    t_gen = time.perf_counter() - t_gen
     s_d, d_d = dev(src.view(np.int32)), dev(dst.view(np.int32))
     del src, dst
+    torch.cuda.synchronize()
+    t_build = time.perf_counter()
     g = mg.build_csr(s_d, d_d, n)
     del s_d, d_d
     torch.cuda.empty_cache()
     mg.normalize(g)
+    torch.cuda.synchronize()
+    t_build = time.perf_counter() - t_build
     nnz = g.nnz
     hd = padded_rows(n, k, torch.float32, "cuda")
-    if args.config == "c3":
+    if config == "c3":
         hd.copy_(torch.from_numpy(gg.normal(args.seed, 1, n, k)))
     else:
         hd.normal_()
     wd = dev(gg.glorot(args.seed, 10, k, m))
     zd = padded_rows(n, k, torch.float32, "cuda")
     outd = padded_rows(n, m, torch.float32, "cuda")
-    if args.config == "c3":
+    if config == "c3":
         gd = padded_rows(n, m, torch.float32, "cuda")
         gd.normal_()
         dhd = padded_rows(n, k, torch.float32, "cuda")
@@ -157,31 +292,122 @@ def bench_single_layer(args, mg, dev):
         step()
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / args.steps
-    names = ["agg_g4", "agg_g8", "agg_g16", "agg_g32", "agg_g64", "update_fwd", "update_dgrad",
-             "update_wgrad"]
-    kinds = {}
-    for i, nm in enumerate(names):
-        ms, cnt = pipe.timing_read(i)
-        if cnt:
-            kinds[nm] = {"total_ms": ms, "launches": cnt, "avg_ms": ms / cnt}
-    agg_ms = kinds["agg_g32"]["avg_ms"]
-    algo = 8.0 * nnz + 2.0 * n * k * 4 + 8.0 * n
-    traffic = measured_traffic(args.config, k)
-    print(json.dumps({
+    kinds = read_kinds(pipe)
+    pipe.timing(False)
+    out = {
         "metric": "GCN layer fwd+bwd edges*feat/s", "value": nnz * k / dt, "unit": "edges*feat/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"{what}, N={n}, nnz(A_hat)={nnz}", "n_nodes": n, "nnz": nnz,
-                   "update_arith": args.update_arith},
+                   "row_chunks": args.chunks, "seed": args.seed, "update_arith": args.update_arith},
+        "generate_edges_s": t_gen, "build_csr_normalize_ms": t_build * 1e3,
         "kernels": kinds,
-        "roofline": {"bound": "hbm", "achieved": algo / (agg_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": algo / (agg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "traffic": traffic, "kernel": "aggregate_kernel, 128 fp32 columns",
-                     "avg_launch_ms": agg_ms, "algorithmic_bytes_per_launch": algo},
-        "gemm_tflops": {kk: 2.0 * n * k * m / (kinds[kk]["avg_ms"] * 1e-3) / 1e12
-                        for kk in ("update_fwd", "update_dgrad", "update_wgrad")},
-    }))
+        "roofline": aggregation_roofline(config, kinds, nnz, n, 4, args.chunks),
+        "update_products": {
+            kk: {"tflops": 2.0 * n * k * m / (kinds[kk]["avg_ms"] * 1e-3) / 1e12,
+                 "frac_of_fp32_mfma_peak": 2.0 * n * k * m / (kinds[kk]["avg_ms"] * 1e-3) / 1e12 /
+                 MFMA_F32_TFLOPS}
+            for kk in ("update_fwd", "update_dgrad", "update_wgrad") if kk in kinds},
+    }
+    pipe.free()
+    g.free()
+    del hd, zd, outd, gd, dhd, dwd, wd
+    gc.collect()
+    torch.cuda.empty_cache()
+    return out
+
+
+def bench_model(args, mg, dev, config, with_bf16x3=True):
+    """Configs 1, 2 and 5: one epoch (forward + loss + backward) of the multi-layer GCN."""
+    import numpy as np
+    import torch
+
+    t_gen = time.perf_counter()
+    src, dst, n, x, ws, y, dims = make_inputs(config, args.scale, args.seed)
+    t_gen = time.perf_counter() - t_gen
+    s_d, d_d = dev(src.view(np.int32)), dev(dst.view(np.int32))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    g = mg.build_csr(s_d, d_d, n)
+    mg.normalize(g)
+    torch.cuda.synchronize()
+    t_build = time.perf_counter() - t0
+    nnz = g.nnz
+    del s_d, d_d, src, dst
+
+    pipe = mg.Pipeline()
+    bf16 = config == "c5"  # config 5 stores features in bf16
+    x_d = torch.from_numpy(x).cuda()
+    if bf16:
+        x_d = x_d.to(torch.bfloat16)
+    w_d = [torch.from_numpy(np.ascontiguousarray(w.base if w.base is not None else w)).cuda()[:, :w.shape[1]]
+           for w in ws]
+    step = mg.GCNStep(g, x_d, w_d, dev(y), n_chunks=args.chunks, pipe=pipe)
+
+    run_step = step.step
+    if args.hip_graph:
+        assert args.chunks == 1, "--hip-graph times the single-stream schedule"
+        step.capture()
+        run_step = step.replay
+    for _ in range(args.warmup):
+        run_step()
+    torch.cuda.synchronize()
+    timing = not (args.no_event_timing or args.hip_graph)
+    pipe.timing(timing)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    loss = step.loss.item()
+    work = sum(nnz * d for d in dims[:-1])  # sum over layers of nnz * d^(l)
+    kinds = read_kinds(pipe) if timing else {}
+    pipe.timing(False)
+    esz = 2 if bf16 else 4
+    out = {
+        "metric": "GCN layer fwd+bwd edges*feat/s", "value": work / dt, "unit": "edges*feat/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 storage, f32 accumulate" if bf16 else "f32", "data": "synthetic",
+        "config": {
+            "workload": f"{config}: {len(dims) - 1}-layer GCN {'-'.join(map(str, dims))}, one "
+                        f"fwd+bwd epoch, {'Erdos-Renyi' if config == 'c1' else 'R-MAT'} graph "
+                        f"N={n}, nnz(A_hat)={nnz}",
+            "n_nodes": n, "nnz": nnz, "row_chunks": args.chunks, "seed": args.seed,
+            "hip_graph": bool(args.hip_graph), "update_arith": args.update_arith,
+        },
+        "loss": loss, "generate_inputs_s": t_gen, "build_csr_normalize_ms": t_build * 1e3,
+        "kernels": kinds, "roofline": aggregation_roofline(config, kinds, nnz, n, esz, args.chunks),
+    }
+    upd = sum(v["total_ms"] for k, v in kinds.items() if k.startswith("update")) / args.steps
+    if kinds:
+        out["update_products_ms_per_step"] = upd
+        flops = sum(2.0 * n * dims[l] * dims[l + 1] * (3 if l > 0 else 2) for l in range(len(dims) - 1))
+        out["update_products_tflops"] = flops / (upd * 1e-3) / 1e12
+    # the same steps with the opt-in update arithmetic (fp32 operands as three bf16 terms on the
+    # bf16 matrix cores), after and outside the timed region above: reported beside the result
+    if with_bf16x3 and args.update_arith == "fp32" and not bf16 and not args.hip_graph:
+        mg.set_update_arith(mg.ARITH_BF16X3)
+        try:
+            for _ in range(2):
+                run_step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                run_step()
+            torch.cuda.synchronize()
+            dt3 = (time.perf_counter() - t0) / args.steps
+            out["with_update_arith_bf16x3"] = {"ms_per_step": dt3 * 1e3, "value": work / dt3,
+                                               "loss": step.loss.item()}
+        finally:
+            mg.set_update_arith(mg.ARITH_FP32)
+    pipe.free()
+    g.free()
+    del step, x_d, w_d
+    gc.collect()
+    torch.cuda.empty_cache()
+    return out
 
 
 def bench_variant(args, mg, dev):
@@ -242,7 +468,7 @@ def bench_variant(args, mg, dev):
                    "n_nodes": n, "nnz": nnz, "seed": args.seed, "update_arith": args.update_arith},
         "loss": loss,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "traffic_source": None,
                      "kernel": "aggregate_kernel<8, 32, 0, false, true> (128 fp32 columns)",
                      "avg_launch_ms": agg_ms, "algorithmic_bytes_per_launch": per_launch},
     }
@@ -263,10 +489,30 @@ def bench_variant(args, mg, dev):
         t = time.perf_counter() - t0
         out["cpu_baseline"] = {
             "value": sum(og.nnz * d for d in dims[:-1]) / t, "unit": "edges*feat/s",
-            "cores": oracle.num_threads(), "kind": "oracle",
+            "cores": oracle.num_threads(), "kind": "oracle", "cpu_model": cpu_model(),
             "sample": f"same generator and model at R-MAT scale {args.cpu_scale} (N={n2}, "
                       f"nnz={og.nnz}), one fwd+bwd step, {t:.1f} s"}
     print(json.dumps(out))
+
+
+def run_config(args, mg, dev, config):
+    if config in ("c3", "c4"):
+        return bench_single_layer(args, mg, dev, config)
+    return bench_model(args, mg, dev, config)
+
+
+def baseline_for(args, config):
+    """Oracle timing for a headline configuration, on a sample that takes the host cores about
+    ten to thirty seconds in all."""
+    if config == "c4":
+        return cpu_baseline_layer("c4", args.cpu_scale or 21, args.seed, 128, 128, False)
+    if config == "c3":
+        return cpu_baseline_layer("c3", args.cpu_scale or 20, args.seed, 128, 1024, True)
+    if config == "c5":
+        return cpu_baseline_model("c5", args.cpu_scale or 18, args.seed)
+    if config == "c2":
+        return cpu_baseline_model("c2", args.cpu_scale or 18, args.seed, single_thread_scale=14)
+    return cpu_baseline_model(config, None, args.seed)
 
 
 def main():
@@ -274,13 +520,18 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="c2")
-    ap.add_argument("--scale", type=int, default=None, help="override the R-MAT scale")
+    ap.add_argument("--config", default=None,
+                    help="run one configuration alone (c1..c5); default: c4 as the headline with "
+                         "c2 and c5 as secondary blocks")
+    ap.add_argument("--scale", type=int, default=None, help="override the graph scale (with --config)")
     ap.add_argument("--chunks", type=int, default=1, help="row chunks of the layer pipeline")
     ap.add_argument("--seed", type=int, default=250101951)
-    ap.add_argument("--cpu-scale", type=int, default=20, help="R-MAT scale of the oracle sample")
+    ap.add_argument("--cpu-scale", type=int, default=None, help="graph scale of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="default run without the secondary configurations")
     ap.add_argument("--no-event-timing", action="store_true")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the measured-peaks block")
     ap.add_argument("--model", default="gcn", choices=["gcn", "sage", "gin"],
                     help="gcn: the benchmark line; sage / gin: the two other architectures of the "
                          "paper's experiments on the same graph (3 layers, 128 hidden units)")
@@ -310,136 +561,63 @@ def main():
         return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
     if args.model != "gcn":
+        args.config = args.config or "c2"
+        args.cpu_scale = args.cpu_scale or 20
         assert args.config in ("c1", "c2"), "--model sage/gin run on the graphs of c1 and c2"
         return bench_variant(args, mg, dev)
-    if args.config in ("c3", "c4"):
-        return bench_single_layer(args, mg, dev)
-    src, dst, n, x, ws, y, dims = make_inputs(args.config, args.scale, args.seed)
-
-    s_d, d_d = dev(src.view(np.int32)), dev(dst.view(np.int32))
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    g = mg.build_csr(s_d, d_d, n)
-    mg.normalize(g)
-    torch.cuda.synchronize()
-    t_build = time.perf_counter() - t0
-    nnz = g.nnz
-    del s_d, d_d
-
-    pipe = mg.Pipeline()
-    bf16 = args.config == "c5"  # config 5 stores features in bf16
-    x_d = torch.from_numpy(x).cuda()
-    if bf16:
-        x_d = x_d.to(torch.bfloat16)
-    w_d = [torch.from_numpy(np.ascontiguousarray(w.base if w.base is not None else w)).cuda()[:, :w.shape[1]]
-           for w in ws]
-    step = mg.GCNStep(g, x_d, w_d, dev(y), n_chunks=args.chunks, pipe=pipe)
 
     # A plain copy kernel of known size: its FETCH_SIZE / WRITE_SIZE readings calibrate the
     # counter units when this command runs under rocprofv3 --pmc.
     calib_src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
     calib_dst = torch.empty_like(calib_src)
     calib_dst.copy_(calib_src)
-
-    run_step = step.step
-    if args.hip_graph:
-        assert args.chunks == 1, "--hip-graph times the single-stream schedule"
-        args.no_event_timing = True
-        step.capture()
-        run_step = step.replay
-    for _ in range(args.warmup):
-        run_step()
     torch.cuda.synchronize()
-    pipe.timing(not args.no_event_timing)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run_step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-    loss = step.loss.item()
-
-    work = sum(nnz * d for d in dims[:-1])  # sum over layers of nnz * d^(l)
-    value = work / (dt / args.steps)
-
-    kinds = {}
-    if not args.no_event_timing:
-        names = ["agg_g4", "agg_g8", "agg_g16", "agg_g32", "agg_g64", "update_fwd", "update_dgrad",
-                 "update_wgrad"]
-        for k, nm in enumerate(names):
-            ms, cnt = pipe.timing_read(k)
-            if cnt:
-                kinds[nm] = {"total_ms": ms, "launches": cnt, "avg_ms": ms / cnt}
-    pipe.timing(False)
-
-    roofline = None
-    agg = {k: v for k, v in kinds.items() if k.startswith("agg")}
-    if agg:
-        dom = max(agg, key=lambda k: agg[k]["total_ms"])
-        gsz = int(dom.split("g")[-1])
-        esz = 2 if bf16 else 4
-        f = gsz * 16 // esz  # columns of a pass of that width class (16 bytes per lane)
-        # algorithmic minimum per full-graph launch: index + value stream, every feature row
-        # read once, every output row written once, one row pointer per row
-        full = 8.0 * nnz + 2.0 * n * f * esz + 8.0 * n
-        launches_per_layer_call = max(1, args.chunks)
-        per_launch = full / launches_per_layer_call
-        avg_s = agg[dom]["avg_ms"] * 1e-3
-        achieved = per_launch / avg_s / 1e9
-        roofline = {
-            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS,
-            "traffic": measured_traffic(args.config, f) if args.chunks == 1 else None,
-            "kernel": f"aggregate_kernel<8, {gsz}, {1 if bf16 else 0}, false, true> "
-                      f"({f} {'bf16' if bf16 else 'fp32'} columns)",
-            "avg_launch_ms": agg[dom]["avg_ms"], "launches": agg[dom]["launches"],
-            "algorithmic_bytes_per_launch": per_launch,
-            "gather_bytes_per_launch": (nnz * (8.0 + f * esz) + n * f * esz) / launches_per_layer_call,
-        }
-
-    out = {
-        "metric": "GCN layer fwd+bwd edges*feat/s", "value": value, "unit": "edges*feat/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 storage, f32 accumulate" if bf16 else "f32",
-        "data": "synthetic",
-        "config": {
-            "workload": f"{args.config}: {len(dims) - 1}-layer GCN {'-'.join(map(str, dims))}, one "
-                        f"fwd+bwd epoch, {'Erdos-Renyi' if args.config == 'c1' else 'R-MAT'} graph "
-                        f"N={n}, nnz(A_hat)={nnz}",
-            "n_nodes": n, "nnz": nnz, "row_chunks": args.chunks, "seed": args.seed,
-            "hip_graph": bool(args.hip_graph), "update_arith": args.update_arith,
-        },
-        "loss": loss, "build_csr_normalize_ms": t_build * 1e3, "kernels": kinds,
-        "roofline": roofline,
-    }
-    # the same steps with the opt-in update arithmetic (fp32 operands as three bf16 terms on the
-    # bf16 matrix cores), after and outside the timed region above: reported beside the result
-    if args.update_arith == "fp32" and not bf16 and not args.hip_graph:
-        mg.set_update_arith(mg.ARITH_BF16X3)
-        try:
-            for _ in range(2):
-                run_step()
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(args.steps):
-                run_step()
-            torch.cuda.synchronize()
-            dt3 = (time.perf_counter() - t0) / args.steps
-            out["with_update_arith_bf16x3"] = {"ms_per_step": dt3 * 1e3, "value": work / dt3,
-                                               "loss": step.loss.item()}
-        finally:
-            mg.set_update_arith(mg.ARITH_FP32)
-    # what this device sustains on a plain copy and on register-only MFMA chains (outside the
-    # timed region): context for the published peaks the fractions above are quoted against
-    del step, calib_src, calib_dst
+    del calib_src, calib_dst
     torch.cuda.empty_cache()
-    try:
-        out["measured_peaks"] = mg.measure_peaks()
-    except mg.MixGCNError as e:  # needs 8 GiB of free device memory; not part of the result
-        out["measured_peaks"] = {"error": str(e)}
+
+    single = args.config is not None
+    out, used, fallbacks = None, None, []
+    for config in ([args.config] if single else ["c4", "c3", "c2"]):
+        try:
+            out = run_config(args, mg, dev, config)
+            used = config
+            break
+        except (mg.MixGCNError, torch.OutOfMemoryError, MemoryError) as e:  # too large for this box
+            if single:
+                raise
+            fallbacks.append(f"{config}: {type(e).__name__}: {str(e)[:200]}")
+            gc.collect()
+            torch.cuda.empty_cache()
+    if out is None:
+        sys.exit("bench.py: no configuration could run: " + "; ".join(fallbacks))
+    if not single:
+        out["config"]["headline_choice"] = (
+            "the largest benchmark configuration that one GPU holds (config 4, one layer at its "
+            "real shape); configs 2 and 5 follow as secondary blocks" if used == "c4" else
+            "fallback after: " + "; ".join(fallbacks))
+        if not args.no_secondary:
+            out["secondary"] = {}
+            for config in ("c2", "c5"):
+                if config == used:
+                    continue
+                try:
+                    out["secondary"][config] = bench_model(args, mg, dev, config, with_bf16x3=(config == "c2"))
+                except (mg.MixGCNError, torch.OutOfMemoryError, MemoryError) as e:
+                    out["secondary"][config] = {"error": f"{type(e).__name__}: {str(e)[:200]}"}
+    # what this device sustains on a plain copy and on register-only MFMA chains (outside the
+    # timed regions): context for the published peaks the fractions above are quoted against
+    if not args.no_peaks:
+        try:
+            out["measured_peaks"] = mg.measure_peaks()
+        except mg.MixGCNError as e:  # needs 8 GiB of free device memory; not part of the result
+            out["measured_peaks"] = {"error": str(e)}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.config, args.cpu_scale, args.seed)
+        out["cpu_baseline"] = baseline_for(args, used)
+        if not single and not args.no_secondary:
+            for config in ("c2", "c5"):
+                blk = out.get("secondary", {}).get(config)
+                if blk and "error" not in blk:
+                    blk["cpu_baseline"] = baseline_for(args, config)
     print(json.dumps(out))
 
 

@@ -12,8 +12,16 @@ def say(msg):
     print("[case] " + msg, file=sys.stderr, flush=True)
 
 
-def assert_close(got, ref, rtol, what=""):
-    """Per tensor: |got - ref| <= rtol * |ref| + rtol * RMS(ref) for every element."""
+def assert_close(got, ref, rtol, what="", cascade_share=0.0):
+    """Per tensor: |got - ref| <= rtol * |ref| + rtol * RMS(ref) for every element.
+
+    cascade_share > 0 (bf16 storage, whole-model comparisons only): that share of the elements
+    may lie outside the bound, by at most a factor of two.  Both sides round every stored tensor
+    to bf16; where an exact sum falls within accumulation error of a rounding boundary the two
+    roundings legitimately differ by one unit (2^-8 relative), and the layers above see that
+    unit multiplied by a weight.  An element fed by such a flip of a large input can leave the
+    bound although every operation is within it on its own inputs (which the same tests check
+    layer by layer without this allowance)."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape, f"{what}: shape {got.shape} vs {ref.shape}"
@@ -22,6 +30,8 @@ def assert_close(got, ref, rtol, what=""):
     err = np.abs(got - ref)
     bound = rtol * np.abs(ref) + rtol * rms
     bad = err > bound
+    if cascade_share > 0.0 and bad.any() and bad.mean() <= cascade_share:
+        bad = err > 2.0 * bound
     if bad.any():
         i = np.unravel_index(np.argmax(err - bound), err.shape)
         fro = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300)
