@@ -419,8 +419,9 @@ int mixgcn_pipeline_timing_read(mixgcn_pipeline* p, int kind, double* total_ms, 
  * form).  The rule is deterministic: degree = stored entries of the row; a component starts
  * from the unvisited node of smallest (degree, id); nodes are visited in queue order and the
  * unvisited neighbors of the visited node join the queue in increasing (degree, id); the
- * sequence is the visiting order reversed.  Synchronises the stream (one small read-back per
- * breadth-first level, so the time grows with the number of levels).
+ * sequence is the visiting order reversed.  Synchronises the stream.  Levels with a small
+ * frontier (up to 1024 nodes holding up to 4096 stored entries) are walked on the device by one
+ * resident workgroup, a few microseconds each; only wider levels cost a launch and a read-back.
  *
  * mixgcn_bandwidth: b = max over stored entries (u, v) of |p_v - p_u| (the paper's graph
  * bandwidth); pos == NULL takes the identity sequence.  *bandwidth is a host pointer.

@@ -10,7 +10,11 @@
 // offer also appends the neighbor to the next level's list, and that list is sorted by
 // (winning index, rank of the node in the global (degree, id) order).  Components start from
 // the unvisited node of smallest (degree, id); runs of single-node components are appended in
-// one pass.  The host reads one counter per level, so the time grows with the number of levels.
+// one pass.  Wide levels run as grid-wide kernels with one counter read back per level; levels
+// whose frontier is small (at most kNarrowFrontier nodes with kNarrowEdges stored entries) are
+// walked by ONE workgroup that stays on the device from level to level, and from component to
+// component, until it meets a level too wide for it - a banded graph with tens of thousands of
+// levels costs a few microseconds per level instead of a launch and a host round trip.
 #include <vector>
 
 #include "device_utils.h"
@@ -69,56 +73,262 @@ __global__ __launch_bounds__(kBlock) void rank_kernel(const uint64_t* __restrict
     parent[i] = kNone;
 }
 
-// result = smallest position i >= cursor in bydeg whose node is unvisited and not single
-__global__ __launch_bounds__(kBlock) void next_root_kernel(const uint32_t* __restrict__ bydeg,
-                                                           const uint32_t* __restrict__ cm_idx,
-                                                           const uint32_t* __restrict__ single,
-                                                           uint32_t cursor, uint32_t n,
-                                                           uint32_t* __restrict__ result)
+// ---- narrow levels: one resident workgroup --------------------------------------------------
+constexpr int kNarrowFrontier = 1024;  // frontier nodes the workgroup takes on
+constexpr int kNarrowEdges = 4096;     // stored entries of such a frontier (bounds the next level)
+
+// Progress shared between the host loop and the resident workgroup.
+struct RcmState {
+    uint32_t count;    // nodes placed so far
+    uint32_t cursor;   // position in bydeg from which the next root is searched
+    uint32_t f_begin;  // the current frontier is order[f_begin, f_begin + f_count)
+    uint32_t f_count;  // 0: no component is open
+    uint32_t done;     // every node is placed
+    uint32_t levels;   // levels walked on the device (statistics)
+};
+
+__device__ inline uint32_t load_coherent(const uint32_t* p)
 {
-    const uint32_t stride = gridDim.x * blockDim.x;
-    uint32_t best = kNone;
-    for (uint32_t i = cursor + blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
-        const uint32_t v = bydeg[i];
-        if (cm_idx[v] == kNone && !single[v]) {
-            best = i;
-            break;  // positions grow along this thread's walk
-        }
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void store_coherent(uint32_t* p, uint32_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Exclusive prefix sum of one value per thread over the 256 threads of the block; *total gets
+// the block sum.  lds: 4 words.  Two barriers.
+__device__ inline uint32_t block_scan_u32(uint32_t v, uint32_t* total, uint32_t* lds)
+{
+    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const uint32_t t = (uint32_t)__shfl_up((int)inc, o, kWave);
+        if (lane >= o) inc += t;
     }
-    if (best != kNone) atomicMin(result, best);
+    if (lane == kWave - 1) lds[w] = inc;
+    __syncthreads();
+    uint32_t woff = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < kBlock / kWave; ++i) {
+        const uint32_t x = lds[i];
+        if (i < w) woff += x;
+        tot += x;
+    }
+    __syncthreads();
+    *total = tot;
+    return woff + inc - v;
 }
 
-// flags[i] = node bydeg[cursor + i] is unvisited (it is then a single-node component)
-__global__ __launch_bounds__(kBlock) void single_flags_kernel(const uint32_t* __restrict__ bydeg,
-                                                              const uint32_t* __restrict__ cm_idx,
-                                                              uint32_t cursor, uint32_t count,
-                                                              uint32_t* __restrict__ flags)
+// Walks breadth-first levels, and the search for the next component's root (with the runs of
+// single-node components before it), for as long as the frontier stays narrow.  Same rule and
+// same keys as the grid-wide kernels below, so the sequence does not depend on which path a
+// level takes.  Invariant used here: a placed node has parent != kNone (roots and single-node
+// components carry their own queue index), so one atomic minimum per stored entry both tests
+// "unvisited" and makes the offer - a placed node's parent is smaller than any current queue
+// index and stays as it is.  Launched with one workgroup; leaves when every node is placed or
+// the next level is too wide (st->f_count then names that frontier).
+__global__ __launch_bounds__(kBlock) void narrow_levels_kernel(
+    const int64_t* __restrict__ rowptr, const uint32_t* __restrict__ col,
+    const uint32_t* __restrict__ bydeg, const uint32_t* __restrict__ degrank,
+    const uint32_t* __restrict__ single, uint32_t* __restrict__ cm_idx,
+    uint32_t* __restrict__ parent, uint32_t* __restrict__ order, uint32_t n, RcmState* st)
 {
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= count) return;
-    flags[i] = cm_idx[bydeg[cursor + i]] == kNone ? 1u : 0u;
-}
-
-__global__ __launch_bounds__(kBlock) void single_append_kernel(
-    const uint32_t* __restrict__ bydeg, const uint32_t* __restrict__ flags,
-    const uint64_t* __restrict__ offs, uint32_t cursor, uint32_t count, uint32_t base,
-    uint32_t* __restrict__ cm_idx, uint32_t* __restrict__ order)
-{
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= count || !flags[i]) return;
-    const uint32_t v = bydeg[cursor + i];
-    const uint32_t at = base + (uint32_t)offs[i];
-    cm_idx[v] = at;
-    order[at] = v;
-}
-
-__global__ void start_component_kernel(const uint32_t* __restrict__ bydeg, uint32_t pos_in_bydeg,
-                                       uint32_t base, uint32_t* __restrict__ cm_idx,
-                                       uint32_t* __restrict__ order)
-{
-    const uint32_t v = bydeg[pos_in_bydeg];
-    cm_idx[v] = base;
-    order[base] = v;
+    __shared__ uint64_t keys[kNarrowEdges];
+    __shared__ uint32_t vals[kNarrowEdges];
+    __shared__ uint32_t nextl[kNarrowEdges];
+    __shared__ uint32_t f_node[kNarrowFrontier];
+    __shared__ uint32_t f_pre[kNarrowFrontier + 1];  // entries before frontier node i
+    __shared__ int64_t f_row[kNarrowFrontier];       // rowptr of frontier node i
+    __shared__ uint32_t s_scan[4];
+    __shared__ uint32_t s_cnt, s_min;
+    const uint32_t tid = threadIdx.x;
+    uint32_t count = st->count, cursor = st->cursor, f_begin = st->f_begin, f_count = st->f_count;
+    uint32_t levels = 0, done = 0;
+    bool have = false;  // f_node holds the current frontier
+    for (;;) {
+        if (f_count == 0) {
+            // next root: the unvisited node of smallest (degree, id) that has neighbors; every
+            // unvisited node passed on the way is a single-node component and is placed in order
+            bool found = false;
+            while (!found) {
+                if (cursor >= n || count >= n) {
+                    done = 1;
+                    break;
+                }
+                if (tid == 0) s_min = kBlock;
+                __syncthreads();
+                const uint32_t i = cursor + tid;
+                uint32_t v = 0;
+                bool fresh = false;
+                if (i < n) {
+                    v = bydeg[i];
+                    fresh = load_coherent(&cm_idx[v]) == kNone;
+                }
+                const bool is_root = fresh && !single[v];
+                if (is_root) atomicMin(&s_min, tid);
+                __syncthreads();
+                const uint32_t r = s_min;
+                const uint32_t flag = (fresh && !is_root && tid < r) ? 1u : 0u;
+                uint32_t total = 0;
+                const uint32_t off = block_scan_u32(flag, &total, s_scan);
+                if (flag) {
+                    store_coherent(&cm_idx[v], count + off);
+                    store_coherent(&parent[v], count + off);
+                    order[count + off] = v;
+                }
+                count += total;
+                if (r < (uint32_t)kBlock) {
+                    if (tid == r) {
+                        store_coherent(&cm_idx[v], count);
+                        store_coherent(&parent[v], count);
+                        order[count] = v;
+                        f_node[0] = v;
+                    }
+                    f_begin = count;
+                    f_count = 1;
+                    count += 1;
+                    cursor += r + 1;
+                    have = true;
+                    found = true;
+                } else {
+                    cursor += kBlock;
+                }
+                __syncthreads();
+            }
+            if (done) break;
+        }
+        if (f_count > (uint32_t)kNarrowFrontier) break;
+        if (!have) {
+            for (uint32_t i = tid; i < f_count; i += kBlock) f_node[i] = order[f_begin + i];
+            __syncthreads();
+        }
+        // stored entries of the frontier, and where each node's entries start among them
+        uint32_t run = 0;  // entries of the frontier nodes before this thread's first one
+        {
+            constexpr int PER = kNarrowFrontier / kBlock;
+            uint32_t d[PER], mine = 0;
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                const uint32_t i = tid * PER + q;
+                d[q] = 0;
+                if (i < f_count) {
+                    const uint32_t u = f_node[i];
+                    const int64_t a = rowptr[u], b = rowptr[u + 1];
+                    f_row[i] = a;
+                    // a degree beyond the cap is enough to know that the level is too wide
+                    d[q] = (b - a) > (int64_t)kNarrowEdges ? (uint32_t)kNarrowEdges + 1u : (uint32_t)(b - a);
+                }
+                mine += d[q];
+            }
+            uint32_t total = 0;
+            run = block_scan_u32(mine, &total, s_scan);
+            if (total > (uint32_t)kNarrowEdges) {
+                have = false;
+                break;  // too many entries for one workgroup: the grid-wide kernels take the level
+            }
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                const uint32_t i = tid * PER + q;
+                if (i < f_count) f_pre[i] = run;
+                run += d[q];
+            }
+            if (tid == 0) {
+                f_pre[f_count] = total;
+                s_cnt = 0;
+            }
+            __syncthreads();
+            // every stored entry offers its row's queue index to its column
+            for (uint32_t t = tid; t < total; t += kBlock) {
+                uint32_t lo = 0, hi = f_count;  // node i with f_pre[i] <= t < f_pre[i + 1]
+                while (hi - lo > 1) {
+                    const uint32_t mid = (lo + hi) >> 1;
+                    if (f_pre[mid] <= t) lo = mid;
+                    else hi = mid;
+                }
+                const uint32_t w = col[f_row[lo] + (int64_t)(t - f_pre[lo])];
+                const uint32_t old = atomicMin(&parent[w], f_begin + lo);
+                if (old == kNone) nextl[atomicAdd(&s_cnt, 1u)] = w;
+            }
+            __syncthreads();
+        }
+        ++levels;
+        const uint32_t m = s_cnt;
+        if (m == 0) {  // the component is complete
+            f_count = 0;
+            have = false;
+            __syncthreads();
+            continue;
+        }
+        // order the next level by (smallest queue index that offered, rank in (degree, id))
+        if (m <= (uint32_t)kBlock) {
+            uint64_t key = 0;
+            uint32_t w = 0;
+            if (tid < m) {
+                w = nextl[tid];
+                key = ((uint64_t)load_coherent(&parent[w]) << 32) | degrank[w];
+                keys[tid] = key;
+            }
+            __syncthreads();
+            if (tid < m) {
+                uint32_t rank = 0;
+                for (uint32_t j = 0; j < m; ++j) rank += keys[j] < key ? 1u : 0u;
+                vals[rank] = w;
+            }
+            __syncthreads();
+        } else {
+            uint32_t P = 512;
+            while (P < m) P <<= 1;
+            for (uint32_t i = tid; i < P; i += kBlock) {
+                uint64_t key = ~0ull;
+                uint32_t w = 0;
+                if (i < m) {
+                    w = nextl[i];
+                    key = ((uint64_t)load_coherent(&parent[w]) << 32) | degrank[w];
+                }
+                keys[i] = key;
+                vals[i] = w;
+            }
+            __syncthreads();
+            for (uint32_t k = 2; k <= P; k <<= 1)
+                for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+                    for (uint32_t t = tid; t < P / 2; t += kBlock) {
+                        const uint32_t a = (t / j) * 2 * j + (t % j), b = a + j;
+                        const bool up = (a & k) == 0;
+                        const uint64_t ka = keys[a], kb = keys[b];
+                        if ((ka > kb) == up) {
+                            keys[a] = kb;
+                            keys[b] = ka;
+                            const uint32_t va = vals[a];
+                            vals[a] = vals[b];
+                            vals[b] = va;
+                        }
+                    }
+                    __syncthreads();
+                }
+        }
+        for (uint32_t i = tid; i < m; i += kBlock) {
+            const uint32_t w = vals[i];
+            store_coherent(&cm_idx[w], count + i);
+            order[count + i] = w;
+            if (i < (uint32_t)kNarrowFrontier) f_node[i] = w;
+        }
+        f_begin = count;
+        f_count = m;
+        count += m;
+        have = m <= (uint32_t)kNarrowFrontier;
+        __syncthreads();
+    }
+    __threadfence();
+    if (tid == 0) {
+        st->count = count;
+        st->cursor = cursor;
+        st->f_begin = f_begin;
+        st->f_count = f_count;
+        st->done = done;
+        st->levels += levels;
+    }
 }
 
 // One wavefront per frontier node order[f_begin + i]: offers its queue index to every unvisited
@@ -262,12 +472,11 @@ int mixgcn_reorder_rcm(const mixgcn_graph* g, uint32_t* pos, void* stream)
     if (n == 0) return MIXGCN_OK;
     const Csr& m = g->fwd;
     DevMem mem;
-    uint64_t *keys, *alt, *offs;
-    uint32_t *bydeg, *degrank, *single, *cm_idx, *parent, *order, *next_list, *flags, *counters;
+    uint64_t *keys, *alt;
+    uint32_t *bydeg, *degrank, *single, *cm_idx, *parent, *order, *next_list, *counters;
     void* tmp;
     MIXGCN_TRY(mem.alloc(&keys, n));
     MIXGCN_TRY(mem.alloc(&alt, n));
-    MIXGCN_TRY(mem.alloc(&offs, n));
     MIXGCN_TRY(mem.alloc(&bydeg, n));
     MIXGCN_TRY(mem.alloc(&degrank, n));
     MIXGCN_TRY(mem.alloc(&single, n));
@@ -275,8 +484,7 @@ int mixgcn_reorder_rcm(const mixgcn_graph* g, uint32_t* pos, void* stream)
     MIXGCN_TRY(mem.alloc(&parent, n));
     MIXGCN_TRY(mem.alloc(&order, n));
     MIXGCN_TRY(mem.alloc(&next_list, n));
-    MIXGCN_TRY(mem.alloc(&flags, n));
-    MIXGCN_TRY(mem.alloc(&counters, 2));  // [0] next-level count, [1] next root position
+    MIXGCN_TRY(mem.alloc(&counters, 2));  // [0] next-level count
     const size_t tmp_bytes = sort_tmp_bytes(n) > scan_tmp_bytes(n) ? sort_tmp_bytes(n) : scan_tmp_bytes(n);
     {
         char* t;
@@ -292,46 +500,35 @@ int mixgcn_reorder_rcm(const mixgcn_graph* g, uint32_t* pos, void* stream)
     hipLaunchKernelGGL(rank_kernel, dim3(blocks_for(n)), dim3(kBlock), 0, s, sorted, m.rowptr, m.col,
                        n, bydeg, degrank, single, cm_idx, parent);
 
-    uint32_t count = 0;   // nodes placed so far
-    uint32_t cursor = 0;  // position in bydeg from which the next root is searched
-    while (count < n) {
-        // next root that has neighbors; every unvisited node before it is a single-node component
-        const uint32_t none = kNone;
-        MIXGCN_HIP_TRY(hipMemcpyAsync(counters + 1, &none, 4, hipMemcpyHostToDevice, s));
-        hipLaunchKernelGGL(next_root_kernel, dim3(1024), dim3(kBlock), 0, s, bydeg, cm_idx, single,
-                           cursor, n, counters + 1);
-        uint32_t root_at = kNone;
-        MIXGCN_TRY(read_u32(counters + 1, &root_at, s));
-        const uint32_t run_end = root_at == kNone ? n : root_at;
-        if (run_end > cursor) {
-            const uint32_t cnt = run_end - cursor;
-            hipLaunchKernelGGL(single_flags_kernel, dim3(blocks_for(cnt)), dim3(kBlock), 0, s, bydeg,
-                               cm_idx, cursor, cnt, flags);
-            uint64_t* total = keys;  // free at this point
-            MIXGCN_TRY(exclusive_scan_u32_to_u64(flags, offs, cnt, total, tmp, s));
-            hipLaunchKernelGGL(single_append_kernel, dim3(blocks_for(cnt)), dim3(kBlock), 0, s, bydeg,
-                               flags, offs, cursor, cnt, count, cm_idx, order);
-            uint64_t added = 0;
-            MIXGCN_HIP_TRY(hipMemcpyAsync(&added, total, 8, hipMemcpyDeviceToHost, s));
-            MIXGCN_HIP_TRY(hipStreamSynchronize(s));
-            count += (uint32_t)added;
-        }
-        if (root_at == kNone) break;
-        cursor = root_at + 1;
-
-        // breadth-first levels of the component of bydeg[root_at]
-        hipLaunchKernelGGL(start_component_kernel, dim3(1), dim3(1), 0, s, bydeg, root_at, count,
-                           cm_idx, order);
-        uint32_t f_begin = count, f_count = 1;
-        count += 1;
-        while (f_count > 0) {
+    // The resident workgroup walks narrow levels and finds roots until it meets a level too
+    // wide for it; the host then runs that one level with the grid-wide kernels and hands back.
+    RcmState* d_state;
+    MIXGCN_TRY(mem.alloc(&d_state, 1));
+    RcmState st = {};
+    MIXGCN_HIP_TRY(hipMemcpyAsync(d_state, &st, sizeof(st), hipMemcpyHostToDevice, s));
+    for (;;) {
+        hipLaunchKernelGGL(narrow_levels_kernel, dim3(1), dim3(kBlock), 0, s, m.rowptr, m.col, bydeg,
+                           degrank, single, cm_idx, parent, order, n, d_state);
+        MIXGCN_HIP_TRY(hipMemcpyAsync(&st, d_state, sizeof(st), hipMemcpyDeviceToHost, s));
+        MIXGCN_HIP_TRY(hipStreamSynchronize(s));
+        if (st.done) break;
+        if (st.f_count == 0 || st.count >= n + 1)
+            return fail(MIXGCN_EHIP, "reorder_rcm: the level walk stopped without a frontier");
+        // wide levels, until the frontier is narrow again or the component ends
+        uint32_t count = st.count, f_begin = st.f_begin, f_count = st.f_count;
+        bool first = true;  // the level the workgroup refused is run here whatever its node count
+        while (f_count > 0 && (first || f_count > (uint32_t)kNarrowFrontier)) {
+            first = false;
             MIXGCN_HIP_TRY(hipMemsetAsync(counters, 0, 4, s));
             hipLaunchKernelGGL(expand_kernel, dim3((unsigned)ceil_div(f_count, kBlock / kWave)),
                                dim3(kBlock), 0, s, m.rowptr, m.col, order, f_begin, f_count, cm_idx,
                                parent, next_list, counters);
             uint32_t mcount = 0;
             MIXGCN_TRY(read_u32(counters, &mcount, s));
-            if (mcount == 0) break;
+            if (mcount == 0) {
+                f_count = 0;
+                break;
+            }
             hipLaunchKernelGGL(level_keys_kernel, dim3(blocks_for(mcount)), dim3(kBlock), 0, s,
                                next_list, mcount, parent, degrank, keys);
             const uint64_t max_key = ((uint64_t)(count - 1) << 32) | (uint64_t)(n - 1);
@@ -344,7 +541,12 @@ int mixgcn_reorder_rcm(const mixgcn_graph* g, uint32_t* pos, void* stream)
             f_count = mcount;
             count += mcount;
         }
+        st.count = count;
+        st.f_begin = f_begin;
+        st.f_count = f_count;
+        MIXGCN_HIP_TRY(hipMemcpyAsync(d_state, &st, sizeof(st), hipMemcpyHostToDevice, s));
     }
+    if (st.count != n) return fail(MIXGCN_EHIP, "reorder_rcm: not every node was placed");
     hipLaunchKernelGGL(reverse_kernel, dim3(blocks_for(n)), dim3(kBlock), 0, s, order, n, pos);
     MIXGCN_HIP_TRY(hipGetLastError());
     MIXGCN_HIP_TRY(hipStreamSynchronize(s));  // the work arrays are freed on return

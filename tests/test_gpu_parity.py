@@ -422,11 +422,25 @@ def _reorder_cases():
     cases["c2@15"] = (s, d, n2, True, True)
     s, d = gg.ring_lattice_edges(2000, 6)
     cases["ring2000_k6"] = (s, d, 2000, True, True)
+    # levels of several hundred nodes (between the two in-workgroup sorts and the grid-wide path)
+    r, c = 300, 300
+    idx = rng.permutation(r * c).reshape(r, c)
+    cases["grid300x300_scrambled"] = (np.r_[idx[:, :-1].ravel(), idx[:-1, :].ravel()],
+                                      np.r_[idx[:, 1:].ravel(), idx[1:, :].ravel()], r * c, True, True)
+    # one node whose row alone exceeds what the resident workgroup takes on, with paths hanging
+    # off its leaves: narrow levels, one level handed to the grid-wide kernels, narrow levels again
+    hub, leaves = 0, np.arange(1, 6001)
+    tails = np.arange(6001, 6001 + 3 * 6000).reshape(6000, 3)
+    star_s = np.r_[np.full(6000, hub), leaves, tails[:, 0], tails[:, 1]]
+    star_d = np.r_[leaves, tails[:, 0], tails[:, 1], tails[:, 2]]
+    perm = rng.permutation(6001 + 18000)
+    cases["hub_with_tails"] = (perm[star_s], perm[star_d], 6001 + 18000, True, True)
     return cases
 
 
 @pytest.mark.parametrize("name", ["path300_scrambled", "grid24x40_scrambled", "many_small_components",
-                                  "no_self_loops", "directed_rmat13", "c1", "c2@15", "ring2000_k6"])
+                                  "no_self_loops", "directed_rmat13", "c1", "c2@15", "ring2000_k6",
+                                  "grid300x300_scrambled", "hub_with_tails"])
 def test_reorder_rcm_bit_exact_and_bandwidth(mg, name):
     src, dst, n, sym, loops = _reorder_cases()[name]
     src = np.asarray(src, dtype=np.uint32)
@@ -454,6 +468,31 @@ def test_reorder_rcm_bit_exact_and_bandwidth(mg, name):
     g2 = mg.build_csr(s2, d2, n, flags)
     assert g2.nnz == g.nnz and mg.bandwidth(g2) == b1
     g2.free()
+    g.free()
+
+
+def test_reorder_rcm_on_a_banded_graph_with_many_levels(mg):
+    """A 16-regular ring lattice of 2^20 nodes has 65 k breadth-first levels of 16 nodes: they
+    are walked on the device by one resident workgroup, without a host round trip per level.
+    Bit-exact against the serial oracle, and timed."""
+    import time
+
+    n, k = 1 << 20, 16
+    s0, d0 = gg.ring_lattice_edges(n, k)
+    perm = np.random.default_rng(3).permutation(n).astype(np.uint32)
+    src, dst = perm[s0], perm[d0]
+    say(f"reorder_rcm ring lattice n={n} k={k}")
+    g = _gpu_graph(mg, src, dst, n)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    pos = mg.reorder_rcm(g)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    say(f"reorder_rcm ring lattice: {dt * 1e3:.0f} ms")
+    want = oracle.rcm(oracle.build_csr(src, dst, n))
+    assert np.array_equal(pos.cpu().numpy().view(np.uint32), want)
+    assert mg.bandwidth(g, pos) <= 2 * k
+    assert dt < 1.0, f"{dt:.2f} s for 65 k levels"
     g.free()
 
 
