@@ -376,6 +376,7 @@ def bench_model(args, mg, dev, config, with_bf16x3=True):
                         f"N={n}, nnz(A_hat)={nnz}",
             "n_nodes": n, "nnz": nnz, "row_chunks": args.chunks, "seed": args.seed,
             "hip_graph": bool(args.hip_graph), "update_arith": args.update_arith,
+            "aggregate_whole_rows": bool(args.whole_rows),
         },
         "loss": loss, "generate_inputs_s": t_gen, "build_csr_normalize_ms": t_build * 1e3,
         "kernels": kinds, "roofline": aggregation_roofline(config, kinds, nnz, n, esz, args.chunks),
@@ -538,6 +539,9 @@ def main():
     ap.add_argument("--hip-graph", action="store_true",
                     help="record the step into a HIP graph and time its replays (one stream, no "
                          "per-kernel events): for small inputs, where launches dominate")
+    ap.add_argument("--whole-rows", action="store_true",
+                    help="measurement aid: aggregations without column slices, the gather a fused "
+                         "aggregate->update kernel would do (not the benchmark line)")
     ap.add_argument("--update-arith", default="fp32", choices=["fp32", "bf16x3"],
                     help="matrix-core arithmetic of the update products of fp32 features: fp32 MFMA "
                          "(the benchmark line) or three bf16 terms per operand, six bf16 MFMAs per "
@@ -556,6 +560,7 @@ def main():
     mg.load_library()
     torch.cuda.set_device(0)
     mg.set_update_arith(mg.ARITH_BF16X3 if args.update_arith == "bf16x3" else mg.ARITH_FP32)
+    mg.set_aggregate_whole_rows(args.whole_rows)
 
     def dev(a):
         return torch.from_numpy(np.ascontiguousarray(a)).cuda()

@@ -455,6 +455,15 @@ int mixgcn_permute_rows(int dtype, const void* X, int64_t ldx, void* Y, int64_t 
 int mixgcn_measure_peaks(double* read_gbs, double* copy_gbs, double* gather_l2_gbs,
                          double* gather_hbm_gbs, double* mfma_f32_tflops,
                          double* mfma_bf16_tflops, void* stream);
+/*
+ * Measurement aid, not part of the training path: with on != 0 every later aggregation of this
+ * process gathers whole rows (no column slices pinned to XCDs), which is what a kernel would have
+ * to do that keeps the aggregated tile on the compute unit for the update product (Sec. 3.2.2,
+ * the fine-grain pipeline in its tightest form).  Same results, other speed; timing it bounds
+ * such a fusion from below.  Process-wide and not thread safe; set it BEFORE mixgcn_normalize of
+ * the graphs it is used with (it changes the size of their aggregation scratch).
+ */
+int mixgcn_set_aggregate_whole_rows(int on);
 const char* mixgcn_strerror(int code);
 const char* mixgcn_last_error(void);
 int mixgcn_version(void);

@@ -12,6 +12,6 @@ from .binding import (  # noqa: F401
     backward_pipelined, bandwidth, build_csr, dropout_bitmap, forward_pipelined, pipeline_window,
     cu_subset_stream,
     layer_bwd, layer_fwd, lib_path, load_library, measure_peaks, normalize, permute_rows, pipeline_stages, relabel_edges,
-    relu_bitmap, reorder_rcm, set_update_arith, softmax_xent, update, version,
+    relu_bitmap, reorder_rcm, set_aggregate_whole_rows, set_update_arith, softmax_xent, update, version,
 )
 from .model import GCNDropoutStep, GCNStep, GINStep, SAGEStep  # noqa: F401

@@ -108,6 +108,8 @@ def load_library():
     lib.mixgcn_softmax_xent.argtypes = [ctypes.c_int, vp, i64, vp, i64, i32, vp, i64, vp, vp]
     lib.mixgcn_set_update_arith.argtypes = [ctypes.c_int]
     lib.mixgcn_set_update_arith.restype = ctypes.c_int
+    lib.mixgcn_set_aggregate_whole_rows.argtypes = [ctypes.c_int]
+    lib.mixgcn_set_aggregate_whole_rows.restype = ctypes.c_int
     lib.mixgcn_graph_info.argtypes = [vp, ctypes.POINTER(_GraphView)]
     lib.mixgcn_graph_free.argtypes = [vp]
     lib.mixgcn_pipeline_create.argtypes = [vp, vp, ctypes.POINTER(vp)]
@@ -500,6 +502,11 @@ def pipeline_window(n_nodes: int, n_chunks: int, bandwidth: int, chunk: int):
                                                  ctypes.byref(f), ctypes.byref(l)),
            "pipeline_window")
     return r0.value, r1.value, f.value, l.value
+
+
+def set_aggregate_whole_rows(on: bool) -> None:
+    """Measurement aid: aggregations without column slices (set before normalize)."""
+    _check(load_library().mixgcn_set_aggregate_whole_rows(int(bool(on))), "set_aggregate_whole_rows")
 
 
 def set_update_arith(mode: int) -> None:

@@ -518,6 +518,12 @@ int mixgcn_set_update_arith(int mode)
     return MIXGCN_OK;
 }
 
+int mixgcn_set_aggregate_whole_rows(int on)
+{
+    g_aggregate_whole_rows = on ? 1 : 0;
+    return MIXGCN_OK;
+}
+
 int mixgcn_softmax_xent(int dtype, const void* logits, int64_t ldl, const int32_t* labels,
                         int64_t n, int32_t n_classes, void* dlogits, int64_t ldd, double* loss,
                         void* stream)

@@ -45,6 +45,7 @@ constexpr uint32_t kEntryColMask = 0x3FFFFFFFu;
 // Widest pass of the aggregation kernel in columns (fp32 and bf16 alike), and the bytes of row
 // pieces one call can need on a graph with `nnz` stored entries, whatever its ranges.
 constexpr int kAggMaxPassCols = 256;
+extern int g_aggregate_whole_rows;  // measurement aid, see mixgcn_set_aggregate_whole_rows
 size_t agg_scratch_bound(int64_t nnz);
 size_t agg_scratch_need(int dtype, int32_t n_cols, int64_t e0, int64_t e1);
 

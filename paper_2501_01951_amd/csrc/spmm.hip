@@ -494,6 +494,16 @@ int launch_fixup(const Csr& m, void* Z, int64_t ldz, int c0, int width, int64_t 
 // of 128-byte lines; with a power-of-two pitch a slice's lines fall on few L2 channels.)
 constexpr int slice_lanes(int gf) { return gf < 8 ? gf : 8; }
 
+}  // namespace
+
+// Measurement aid (mixgcn_set_aggregate_whole_rows): passes are not cut into column slices, a
+// lane group gathers the whole width of the pass from every neighbor row.  That is the gather a
+// kernel would have to do that keeps the aggregated tile on the compute unit for the update
+// product (it needs every column of its rows), so timing it bounds such a fusion from below.
+int g_aggregate_whole_rows = 0;
+
+namespace {
+
 // One pass: column block, width class and span length.
 struct Pass { int32_t cb; int w, gf; int64_t span; };
 
@@ -505,7 +515,7 @@ inline void plan_pass(int vec, int32_t cb, int w, int64_t entries, Pass* p)
     p->w = w;
     p->gf = 4;  // lanes that span the whole pass: fix-up group and partial-slot stride
     while (p->gf * vec < w) p->gf *= 2;
-    const int lpr = slice_lanes(p->gf);
+    const int lpr = g_aggregate_whole_rows ? p->gf : slice_lanes(p->gf);
     p->span = span_entries(lpr, entries, (int)ceil_div(w, lpr * vec));
 }
 
@@ -559,9 +569,13 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const uint2* cv, const void* 
         const int w = p.w;
         const int64_t span = p.span;
 #define MIXGCN_AGG_PASS(GG)                                                                      \
-    MIXGCN_TRY((launch_main<slice_lanes(GG), GG, DT>(m, cv, (int64_t)g->n, H, ldh, Z, ldz, cb, w, r0, \
-                                                     r1, e0, e1, span, P, relu, mask, ldm, s,     \
-                                                     timer)));                                    \
+    if (g_aggregate_whole_rows)                                                                  \
+        MIXGCN_TRY((launch_main<GG, GG, DT>(m, cv, (int64_t)g->n, H, ldh, Z, ldz, cb, w, r0, r1, e0, \
+                                            e1, span, P, relu, mask, ldm, s, timer)));            \
+    else                                                                                         \
+        MIXGCN_TRY((launch_main<slice_lanes(GG), GG, DT>(m, cv, (int64_t)g->n, H, ldh, Z, ldz, cb, w, \
+                                                         r0, r1, e0, e1, span, P, relu, mask,     \
+                                                         ldm, s, timer)));                        \
     MIXGCN_TRY((launch_fixup<GG, DT>(m, Z, ldz, cb, w, e0, e1, span, P, relu, mask, ldm, s)))
         switch (p.gf) {
         case 4: MIXGCN_AGG_PASS(4); break;
@@ -733,7 +747,7 @@ size_t agg_scratch_bound(int64_t nnz)
         for (int w = 1; w <= kAggMaxPassCols; ++w) {
             Pass p;
             plan_pass(vec, 0, w, nnz, &p);
-            const int lpr = slice_lanes(p.gf);
+            const int lpr = g_aggregate_whole_rows ? p.gf : slice_lanes(p.gf);
             const int n_slices = (int)ceil_div(w, lpr * vec);
             const int64_t full = (int64_t)kBatchesPerSpan * (kWave / lpr);
             int64_t spans = ceil_div(nnz, full) + 1;  // a range need not start on a span boundary

@@ -205,6 +205,32 @@ def test_aggregate_column_slices_on_eight_streams_at_once(mg, reserve):
     g.free()
 
 
+def test_aggregate_whole_rows_mode_gives_the_same_result(mg):
+    """The measurement aid that gathers whole rows (no column slices): same sums, checked against
+    the oracle at several widths and storage types, and switched off again afterwards."""
+    src, dst, n = gg.config_graph("c2", scale_override=14)
+    og = oracle.transpose(oracle.normalize(oracle.build_csr(src, dst, n)))
+    mg.set_aggregate_whole_rows(True)
+    try:
+        g = _gpu_graph(mg, src, dst, n)  # normalised with the mode on: its scratch is sized for it
+        for f in (16, 100, 128, 256, 300):
+            say(f"aggregate, whole rows, f={f}")
+            ld = (f + 7) // 8 * 8
+            h = gg.normal(33, f, n, f, ld=ld)
+            z = torch.full((n, ld), 7.0, device="cuda")
+            mg.aggregate(g, dev(h), z, col_end=f)
+            assert_close(z.cpu().numpy()[:, :f], oracle.spmm(og, h[:, :f].astype(np.float64)), RTOL_F32,
+                         f"whole rows f={f}")
+        hb = dev(gg.normal(34, 1, n, 256)).to(torch.bfloat16)
+        zb = torch.zeros(n, 256, dtype=torch.bfloat16, device="cuda")
+        mg.aggregate(g, hb, zb, row_begin=100, row_end=n - 7)
+        ref = oracle.spmm(og, hb.float().cpu().numpy().astype(np.float64), q=oracle.Q_BF16)
+        assert_close(zb.float().cpu().numpy()[100:n - 7], ref[100:n - 7], RTOL_BF16, "whole rows bf16")
+        g.free()
+    finally:
+        mg.set_aggregate_whole_rows(False)
+
+
 def test_aggregate_more_streams_than_scratch_slots(mg):
     """A graph keeps 16 scratch buffers; a 17th and 18th stream take over the least recently
     used ones (after a device synchronisation) and still give the right result."""
