@@ -80,11 +80,11 @@ def model_dims(name):
             "c5": [100, 256, 256, 47]}[name]
 
 
-def make_inputs(name, scale, seed):
+def make_inputs(name, scale, seed, scramble=True):
     import graphgen as gg
 
     dims = model_dims(name)
-    src, dst, n = gg.config_graph(name, seed=seed, scale_override=scale)
+    src, dst, n = gg.config_graph(name, seed=seed, scale_override=scale, scramble=scramble)
     if name in ("c1", "c5"):
         x = gg.uniform(seed, 1, n, dims[0])
     else:
@@ -324,7 +324,7 @@ def bench_model(args, mg, dev, config, with_bf16x3=True):
     import torch
 
     t_gen = time.perf_counter()
-    src, dst, n, x, ws, y, dims = make_inputs(config, args.scale, args.seed)
+    src, dst, n, x, ws, y, dims = make_inputs(config, args.scale, args.seed, not args.unscrambled)
     t_gen = time.perf_counter() - t_gen
     s_d, d_d = dev(src.view(np.int32)), dev(dst.view(np.int32))
     torch.cuda.synchronize()
@@ -376,7 +376,7 @@ def bench_model(args, mg, dev, config, with_bf16x3=True):
                         f"N={n}, nnz(A_hat)={nnz}",
             "n_nodes": n, "nnz": nnz, "row_chunks": args.chunks, "seed": args.seed,
             "hip_graph": bool(args.hip_graph), "update_arith": args.update_arith,
-            "aggregate_whole_rows": bool(args.whole_rows),
+            "aggregate_whole_rows": bool(args.whole_rows), "rmat_ids_scrambled": not args.unscrambled,
         },
         "loss": loss, "generate_inputs_s": t_gen, "build_csr_normalize_ms": t_build * 1e3,
         "kernels": kinds, "roofline": aggregation_roofline(config, kinds, nnz, n, esz, args.chunks),
@@ -539,6 +539,9 @@ def main():
     ap.add_argument("--hip-graph", action="store_true",
                     help="record the step into a HIP graph and time its replays (one stream, no "
                          "per-kernel events): for small inputs, where launches dominate")
+    ap.add_argument("--unscrambled", action="store_true",
+                    help="secondary data point: keep the R-MAT generator's own node numbering "
+                         "(hubs at low ids) for configs 2 and 5 instead of the fixed scramble")
     ap.add_argument("--whole-rows", action="store_true",
                     help="measurement aid: aggregations without column slices, the gather a fused "
                          "aggregate->update kernel would do (not the benchmark line)")

@@ -132,7 +132,8 @@ def ring_lattice_edges(n: int, k: int):
     return i, ((i.astype(np.uint64) + off) % n).astype(np.uint32)
 
 
-def config_graph(name: str, seed: int = MASTER_SEED, scale_override: int | None = None):
+def config_graph(name: str, seed: int = MASTER_SEED, scale_override: int | None = None,
+                 scramble: bool = True):
     """Edge list + node count for a named benchmark configuration.
 
     c1: Erdos-Renyi N=4096, average degree 10.
@@ -141,6 +142,7 @@ def config_graph(name: str, seed: int = MASTER_SEED, scale_override: int | None 
     c4: N = 111,000,000, 1.6e9 directed edges with power-law (alpha = 2.1) out-degrees;
         scale_override = s gives the same recipe at N = 2^s with 14.4 N edges.
     c5: R-MAT scale 22 with ids >= 2,450,000 rejected, 25*N directed edges.
+    scramble = False keeps the R-MAT generator's own numbering (hubs at low ids) for c2, c3, c5.
     """
     if name == "c1":
         n = 4096
@@ -149,12 +151,12 @@ def config_graph(name: str, seed: int = MASTER_SEED, scale_override: int | None 
     if name == "c2":
         scale = scale_override or 20
         n = 1 << scale
-        s, d = rmat_edges(seed, scale, 16 * n)
+        s, d = rmat_edges(seed, scale, 16 * n, scramble=scramble)
         return s, d, n
     if name == "c3":
         scale = scale_override or 24
         n = 1 << scale
-        s, d = rmat_edges(seed, scale, 8 * n)
+        s, d = rmat_edges(seed, scale, 8 * n, scramble=scramble)
         return s, d, n
     if name == "c4":
         if scale_override:
@@ -170,6 +172,6 @@ def config_graph(name: str, seed: int = MASTER_SEED, scale_override: int | None 
             n = int((1 << scale) * (2_450_000 / (1 << 22)))
         else:
             scale, n = 22, 2_450_000
-        s, d = rmat_edges(seed, scale, 25 * n, n_limit=n)
+        s, d = rmat_edges(seed, scale, 25 * n, n_limit=n, scramble=scramble)
         return s, d, n
     raise ValueError(name)

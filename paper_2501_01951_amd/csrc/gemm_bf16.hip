@@ -232,24 +232,35 @@ struct FastStage {
 // ---- row-block kernel: C[n x MD] = (A (.) 1[R > 0])[n x KD] * Bop[KD x MD] ---------------------
 // Bop is given split, in the order of split_weights_kernel (bn = BN): j < n_col_tiles * BN,
 // kk < ldb (a multiple of BKB), zero outside the weights.
+// Occupancy decides these kernels: they are bound by memory traffic, and what hides a
+// workgroup's barrier and load waits is another workgroup on the same compute unit.  The wide
+// tile therefore keeps ONE set of operand tiles in LDS (two barriers per step) and one set of
+// staging registers, which fits three workgroups per compute unit (34 KB of LDS, 160 registers);
+// with double-buffered tiles and two register sets only two fit, and every shape of config 5 ran
+// 5-24 % slower.  The narrow tile is small enough for four workgroups with double buffering.
 template <class S, bool RELU, bool MASK>
-__global__ __launch_bounds__(kBlock) void rowblock_bf16_kernel(
+__global__ __launch_bounds__(kBlock)
+    __attribute__((amdgpu_waves_per_eu(S::BN >= 128 ? 3 : 4, S::BN >= 128 ? 3 : 4))) void rowblock_bf16_kernel(
     const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ Bh,
     const uint16_t* __restrict__ Bl, int ldb, uint16_t* __restrict__ C, int64_t ldc, int64_t n,
     int KD, int MD, const uint16_t* __restrict__ R, int64_t ldr, int n_col_tiles)
 {
-    // one buffer: the double-buffered operand tiles, and after the last step the output tile
+    // one buffer: the operand tiles (one set for the wide tile, two for the narrow one), and
+    // after the last step the output tile
+    constexpr bool kDouble = S::BN < 128;
     constexpr int kTileA = S::BM * LDT, kTileB = S::BN * LDT;
     constexpr int LDC = S::BN + 4;  // output tile rows: 66 or 18 banks, 8-byte aligned
-    static_assert(S::BM * LDC <= 2 * (kTileA + 2 * kTileB), "the output tile fits the operand buffers");
-    __shared__ __attribute__((aligned(16))) uint16_t smem[2 * (kTileA + 2 * kTileB)];
+    constexpr int kSets = kDouble ? 2 : 1;
+    constexpr int kOperands = kSets * (kTileA + 2 * kTileB);
+    constexpr int kSmem = S::BM * LDC > kOperands ? S::BM * LDC : kOperands;
+    __shared__ __attribute__((aligned(16))) uint16_t smem[kSmem];
     uint16_t *As[2], *Bhs[2], *Bls[2];
     As[0] = smem;
-    As[1] = smem + kTileA;
-    Bhs[0] = smem + 2 * kTileA;
-    Bhs[1] = smem + 2 * kTileA + kTileB;
-    Bls[0] = smem + 2 * kTileA + 2 * kTileB;
-    Bls[1] = smem + 2 * kTileA + 3 * kTileB;
+    As[1] = kDouble ? smem + kTileA : As[0];
+    Bhs[0] = smem + kSets * kTileA;
+    Bhs[1] = kDouble ? Bhs[0] + kTileB : Bhs[0];
+    Bls[0] = smem + kSets * kTileA + kSets * kTileB;
+    Bls[1] = kDouble ? Bls[0] + kTileB : Bls[0];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / S::WN, wn = wave % S::WN;
     const unsigned lid = xcd_local_index(blockIdx.x, gridDim.x);
@@ -327,14 +338,9 @@ __global__ __launch_bounds__(kBlock) void rowblock_bf16_kernel(
     // every row of the tile exists, whole reduction steps, 32-bit offsets inside a tile
     const bool fast = row0 + S::BM <= n && KD % BKB == 0 && lda < (1 << 22) && ldr < (1 << 22);
     if (fast) {
-        // Global loads run two steps ahead of their LDS writes, in two register sets: at eight or
-        // fewer steps per tile the kernel lives on the bytes it keeps in flight.  Loads beyond the
-        // last step repeat it (never stored), so that no load is conditional and the wait for one
-        // set can leave the other set's loads in flight.  Two steps per trip keep the LDS buffer
-        // and the register set of every access known at compile time.
-        FastStage<S, MASK> st0, st1;
+        // Loads beyond the last step repeat it (never stored), so that no load is conditional.
+        FastStage<S, MASK> st0;
         st0.init(tid, (uint32_t)lda * 2u, (uint32_t)ldr * 2u);
-        st1.init(tid, (uint32_t)lda * 2u, (uint32_t)ldr * 2u);
         const char* a0 = reinterpret_cast<const char*>(A + row0 * lda);
         const char* r0 = MASK ? reinterpret_cast<const char*>(R + row0 * ldr) : nullptr;
         const size_t tile0 = split_weight_index(col0, 0, S::BN, ldb / BKB);
@@ -345,32 +351,18 @@ __global__ __launch_bounds__(kBlock) void rowblock_bf16_kernel(
             const size_t o = sc * (BKB * 2), ob = sc * (S::BN * BKB * 2);
             st.load(a0 + o, r0 + o, bh0 + ob, bl0 + ob, (size_t)lda * 2, (size_t)ldr * 2);
         };
-        if constexpr (S::BN >= 128) {
+        if constexpr (!kDouble) {
+            // one set of tiles: the loads of the next step are in flight during the products
             load(st0, 0);
-            load(st1, 1);
-            st0.store(As[0], Bhs[0], Bls[0]);
-            load(st0, 2);
-            __syncthreads();
-            int i = 0;
-            for (; i + 2 < nk; i += 2) {
-                mma_step(As[0], Bhs[0], Bls[0]);
-                st1.store(As[1], Bhs[1], Bls[1]);
-                load(st1, i + 3);
-                __syncthreads();
-                mma_step(As[1], Bhs[1], Bls[1]);
+            for (int i = 0; i < nk; ++i) {
                 st0.store(As[0], Bhs[0], Bls[0]);
-                load(st0, i + 4);
+                load(st0, i + 1);
                 __syncthreads();
-            }
-            mma_step(As[0], Bhs[0], Bls[0]);
-            if (nk - i == 2) {
-                st1.store(As[1], Bhs[1], Bls[1]);
-                __syncthreads();
-                mma_step(As[1], Bhs[1], Bls[1]);
+                mma_step(As[0], Bhs[0], Bls[0]);
+                __syncthreads();  // before the next step's tiles overwrite these
             }
         } else {
-            // narrow outputs are bound by their memory traffic and run faster with the wavefronts
-            // that the second register set would cost: one step ahead, one set
+            // two sets of tiles, one barrier per step, loads one step ahead
             load(st0, 0);
             st0.store(As[0], Bhs[0], Bls[0]);
             __syncthreads();
@@ -397,14 +389,24 @@ __global__ __launch_bounds__(kBlock) void rowblock_bf16_kernel(
         }
     } else {
         issue_tiles(0);
-        store_tiles(As[0], Bhs[0], Bls[0]);
-        __syncthreads();
-        for (int i = 0; i < nk; ++i) {
-            const int cur = i & 1;
-            if (i + 1 < nk) issue_tiles((i + 1) * BKB);
-            mma_step(As[cur], Bhs[cur], Bls[cur]);
-            if (i + 1 < nk) store_tiles(As[cur ^ 1], Bhs[cur ^ 1], Bls[cur ^ 1]);
+        if constexpr (!kDouble) {
+            for (int i = 0; i < nk; ++i) {
+                store_tiles(As[0], Bhs[0], Bls[0]);
+                if (i + 1 < nk) issue_tiles((i + 1) * BKB);
+                __syncthreads();
+                mma_step(As[0], Bhs[0], Bls[0]);
+                __syncthreads();
+            }
+        } else {
+            store_tiles(As[0], Bhs[0], Bls[0]);
             __syncthreads();
+            for (int i = 0; i < nk; ++i) {
+                const int cur = i & 1;
+                if (i + 1 < nk) issue_tiles((i + 1) * BKB);
+                mma_step(As[cur], Bhs[cur], Bls[cur]);
+                if (i + 1 < nk) store_tiles(As[cur ^ 1], Bhs[cur ^ 1], Bls[cur ^ 1]);
+                __syncthreads();
+            }
         }
     }
 
