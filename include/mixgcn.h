@@ -159,14 +159,11 @@ int mixgcn_normalize_mode(mixgcn_graph* g, int mode, float eps, void* stream);
  *   A_hat^T (transpose = 1).
  * [col_begin, col_end) is the worker's feature slice [floor(d i/m), floor(d (i+1)/m));
  * [row_begin, row_end) is a pipeline chunk.  H and Z are indexed with absolute columns; entries
- * of Z outside the ranges are not touched, with one exception: the kernel writes whole 16-byte
- * groups, so when col_end is not a multiple of 4 (fp32) or 8 (bf16) the columns from col_end up
- * to the next such multiple are overwritten as well (with the sums of whatever H holds there);
- * they must exist in both matrices (ld at least that multiple), i.e. lie in the row padding or
- * belong to nobody else.  col_begin must be a multiple of 4 (fp32) or 8 (bf16).  A slice bound
- * floor(d i/m) of Algorithm 2 that is not such a multiple is therefore not accepted as a
- * col_begin: split at multiples of the group instead (Proposition 3.4 does not depend on where
- * the cuts fall).  H and Z must not overlap.
+ * of Z outside the ranges are not touched: the bounds need not be multiples of anything, so the
+ * slice bounds floor(d i/m) of Algorithm 2 can be passed as they are (the kernel works on
+ * 16-byte groups of a row and writes the elements of a group that lie outside the range one by
+ * one around it; H is read in whole groups, which always lie inside the row pitch).  H and Z
+ * must not overlap.
  *
  * Concurrency.  Rows that are cut by the kernel's work split are completed through a scratch
  * buffer that belongs to the graph and to the stream of the call: calls on one stream share it

@@ -346,13 +346,10 @@ static int aggregate_impl(const mixgcn_graph* g, int transpose, int dtype, const
         return fail(MIXGCN_EINVAL, "aggregate: row range");
     MIXGCN_TRY(check_matrix("aggregate: H", H, ldh, col_end, es));
     MIXGCN_TRY(check_matrix("aggregate: Z", Z, ldz, col_end, es));
-    if (col_begin % vec != 0) return fail(MIXGCN_EINVAL, "aggregate: col_begin not vector aligned");
+    // The kernels read and write whole 16-byte groups of a row; a row pitch is a whole number of
+    // groups (checked above), so the groups that hold [col_begin, col_end) lie inside the row, and
+    // the stores leave out the elements of the first and last group that are outside the range.
     const int64_t up = ((int64_t)col_end + vec - 1) / vec * vec;
-    if (col_end % vec != 0) {
-        // the last vector reaches into the row padding, which must exist in both matrices
-        if (up > ldh || up > ldz)
-            return fail(MIXGCN_EINVAL, "aggregate: col_end not vector aligned and no row padding");
-    }
     {
         const char* h0 = (const char*)H;
         const char* h1 = h0 + (size_t)g->n * ldh * es;

@@ -48,6 +48,10 @@ struct Feat<MIXGCN_F32> {
         *reinterpret_cast<float4*>(reinterpret_cast<float*>(base) + elem_off) =
             make_float4(a[0], a[1], a[2], a[3]);
     }
+    __device__ static inline void store_one(void* base, int64_t elem_off, float a)
+    {
+        reinterpret_cast<float*>(base)[elem_off] = a;
+    }
     __device__ static inline const Raw* ptr(const void* base, int64_t elem_off)
     {
         return reinterpret_cast<const Raw*>(reinterpret_cast<const float*>(base) + elem_off);
@@ -88,11 +92,32 @@ struct Feat<MIXGCN_BF16> {
         r.w = pack2(a[6], a[7]);
         *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(base) + elem_off) = r;
     }
+    __device__ static inline void store_one(void* base, int64_t elem_off, float a)
+    {
+        reinterpret_cast<uint16_t*>(base)[elem_off] = (uint16_t)pack2(a, 0.f);
+    }
     __device__ static inline const Raw* ptr(const void* base, int64_t elem_off)
     {
         return reinterpret_cast<const Raw*>(reinterpret_cast<const uint16_t*>(base) + elem_off);
     }
 };
+
+// Writes a lane's VEC columns [c, c + VEC) of one output row: the whole 16-byte group when it
+// lies inside the call's column range [c_lo, c_hi), else only the elements that do, one by one
+// (a range need not start or end on a group; what lies outside it is never written).
+template <int DT>
+__device__ inline void store_in_range(void* Z, int64_t row_off, int64_t c, const float* t, int c_lo,
+                                      int c_hi)
+{
+    using F = Feat<DT>;
+    if (c >= c_lo && c + F::VEC <= c_hi) {
+        F::store(Z, row_off + c, t);
+    } else {
+#pragma unroll
+        for (int i = 0; i < F::VEC; ++i)
+            if (c + i >= c_lo && c + i < c_hi) F::store_one(Z, row_off + c + i, t[i]);
+    }
+}
 
 // A value that is the same in every lane, moved to scalar registers.
 __device__ inline int uniform32(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -152,7 +177,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
     void* __restrict__ Z, int64_t ldz, int c0, int width, int64_t row_begin, int64_t row_end,
     int64_t e_begin, int64_t e_end, int64_t span_first, int64_t n_spans,
     float* __restrict__ partials, int n_slices, int relu, const uint32_t* __restrict__ mask,
-    int64_t ldm, int span_batches)
+    int64_t ldm, int span_batches, int c_lo, int c_hi)
 {
     using F = Feat<DT>;
     constexpr int VEC = F::VEC;
@@ -294,7 +319,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(
                                 for (int i = 0; i < VEC; ++i) t[i] = fmaxf(t[i], 0.f);
                             }
                             if (mask) apply_mask<VEC>(t, mask, ldm, r, coff);
-                            F::store(Z, r * ldz + coff, t);
+                            store_in_range<DT>(Z, r * ldz, coff, t, c_lo, c_hi);
                         }
                     }
                     head = false;
@@ -348,7 +373,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_fixup_kernel(
     const int64_t* __restrict__ rowptr, const uint32_t* __restrict__ grp_row,
     void* __restrict__ Z, int64_t ldz, int c0, int width, int64_t e_begin, int64_t e_end,
     int64_t span, int64_t span_first, int64_t n_spans, const float* __restrict__ partials,
-    int relu, const uint32_t* __restrict__ mask, int64_t ldm)
+    int relu, const uint32_t* __restrict__ mask, int64_t ldm, int c_lo, int c_hi)
 {
     using F = Feat<DT>;
     constexpr int VEC = F::VEC;
@@ -385,7 +410,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_fixup_kernel(
         for (int i = 0; i < VEC; ++i) acc[i] = fmaxf(acc[i], 0.f);
     }
     if (mask) apply_mask<VEC>(acc, mask, ldm, r, (int64_t)c0 + (int64_t)lg * VEC);
-    F::store(Z, r * ldz + (int64_t)c0 + (int64_t)lg * VEC, acc);
+    store_in_range<DT>(Z, r * ldz, (int64_t)c0 + (int64_t)lg * VEC, acc, c_lo, c_hi);
 }
 
 // Rows without stored entries get no visit from the main kernel: they are set here, to zero, or
@@ -436,7 +461,8 @@ template <int LPR, int GF, int DT>
 int launch_main(const Csr& m, const uint2* cv, int64_t n_nodes, const void* H, int64_t ldh,
                 void* Z, int64_t ldz, int c0, int width,
                 int64_t r0, int64_t r1, int64_t e0, int64_t e1, int64_t SPAN, float* partials,
-                int relu, const uint32_t* mask, int64_t ldm, hipStream_t s, Timer* timer)
+                int relu, const uint32_t* mask, int64_t ldm, int c_lo, int c_hi, hipStream_t s,
+                Timer* timer)
 {
     constexpr int PW = LPR * Feat<DT>::VEC;
     // timed by the width class of the whole pass
@@ -458,7 +484,7 @@ int launch_main(const Csr& m, const uint2* cv, int64_t n_nodes, const void* H, i
     hipLaunchKernelGGL((aggregate_kernel<LPR, GF, DT, EMPTY, O32>), dim3(grid), dim3(kBlock), 0, \
                        s, m.rowptr, cv, m.grp_row, H, ldh, Z, ldz, c0, width, r0, r1, e0, e1,  \
                        span_first, n_spans, partials, n_slices, relu, mask, ldm,                 \
-                       (int)(SPAN / (kWave / LPR)))
+                       (int)(SPAN / (kWave / LPR)), c_lo, c_hi)
     if (m.has_empty_rows) {
         if (off32) MIXGCN_AGG_LAUNCH(true, true);
         else MIXGCN_AGG_LAUNCH(true, false);
@@ -474,7 +500,7 @@ int launch_main(const Csr& m, const uint2* cv, int64_t n_nodes, const void* H, i
 template <int GF, int DT>
 int launch_fixup(const Csr& m, void* Z, int64_t ldz, int c0, int width, int64_t e0, int64_t e1,
                  int64_t span, const float* partials, int relu, const uint32_t* mask,
-                 int64_t ldm, hipStream_t s)
+                 int64_t ldm, int c_lo, int c_hi, hipStream_t s)
 {
     constexpr int GPB = kBlock / GF;
     const int64_t span_first = e0 / span;
@@ -483,7 +509,7 @@ int launch_fixup(const Csr& m, void* Z, int64_t ldz, int c0, int width, int64_t 
         const unsigned fgrid = (unsigned)ceil_div(n_spans - 1, GPB);
         hipLaunchKernelGGL((aggregate_fixup_kernel<GF, DT>), dim3(fgrid), dim3(kBlock), 0, s,
                            m.rowptr, m.grp_row, Z, ldz, c0, width, e0, e1, span, span_first,
-                           n_spans, partials, relu, mask, ldm);
+                           n_spans, partials, relu, mask, ldm, c_lo, c_hi);
     }
     return MIXGCN_OK;
 }
@@ -548,6 +574,10 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const uint2* cv, const void* 
 {
     constexpr int VEC = Feat<DT>::VEC;
     const int64_t e0 = m.h_rowptr[(size_t)r0], e1 = m.h_rowptr[(size_t)r1];
+    // the lanes work on whole 16-byte groups: the passes start at the group that holds the first
+    // column, and the stores leave out what lies outside [c_lo, c_hi)
+    const int32_t c_lo = c0, c_hi = c1;
+    c0 = c0 / VEC * VEC;
     // the row pieces of every pass must fit the scratch: checked before anything is launched
     const size_t need = agg_scratch_need(DT, c1 - c0, e0, e1);
     if (need > P_bytes)
@@ -559,7 +589,7 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const uint2* cv, const void* 
     const bool acc_only = (relu & kEpiAccumulate) && !(relu & kEpiRelu);
     if (m.has_empty_rows && !acc_only && r1 > r0)
         hipLaunchKernelGGL((empty_rows_kernel<DT>), dim3((unsigned)ceil_div(r1 - r0, kBlock)),
-                           dim3(kBlock), 0, s, m.rowptr, Z, ldz, c0, c1 - c0, r0, r1,
+                           dim3(kBlock), 0, s, m.rowptr, Z, ldz, c_lo, c_hi - c_lo, r0, r1,
                            (relu & kEpiAccumulate) ? 1 : 0);
     if (e1 <= e0) return MIXGCN_OK;
     for (int32_t cbk = c0; cbk < c1; cbk += kAggMaxPassCols) {
@@ -571,12 +601,12 @@ int launch_dt(const mixgcn_graph* g, const Csr& m, const uint2* cv, const void* 
 #define MIXGCN_AGG_PASS(GG)                                                                      \
     if (g_aggregate_whole_rows)                                                                  \
         MIXGCN_TRY((launch_main<GG, GG, DT>(m, cv, (int64_t)g->n, H, ldh, Z, ldz, cb, w, r0, r1, e0, \
-                                            e1, span, P, relu, mask, ldm, s, timer)));            \
+                                            e1, span, P, relu, mask, ldm, c_lo, c_hi, s, timer))); \
     else                                                                                         \
         MIXGCN_TRY((launch_main<slice_lanes(GG), GG, DT>(m, cv, (int64_t)g->n, H, ldh, Z, ldz, cb, w, \
                                                          r0, r1, e0, e1, span, P, relu, mask,     \
-                                                         ldm, s, timer)));                        \
-    MIXGCN_TRY((launch_fixup<GG, DT>(m, Z, ldz, cb, w, e0, e1, span, P, relu, mask, ldm, s)))
+                                                         ldm, c_lo, c_hi, s, timer)));            \
+    MIXGCN_TRY((launch_fixup<GG, DT>(m, Z, ldz, cb, w, e0, e1, span, P, relu, mask, ldm, c_lo, c_hi, s)))
         switch (p.gf) {
         case 4: MIXGCN_AGG_PASS(4); break;
         case 8: MIXGCN_AGG_PASS(8); break;

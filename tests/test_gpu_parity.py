@@ -96,8 +96,8 @@ def test_build_csr_host_input_and_errors(mg):
     mg.normalize(g)
     with pytest.raises(mg.MixGCNError):  # H and Z overlap
         mg.aggregate(g, h, h)
-    with pytest.raises(mg.MixGCNError):  # column range not vector aligned
-        mg.aggregate(g, h, torch.empty_like(h), col_begin=2, col_end=8)
+    with pytest.raises(mg.MixGCNError):  # column range beyond the row
+        mg.aggregate(g, h, torch.empty_like(h), col_begin=2, col_end=17)
     with pytest.raises(mg.MixGCNError):  # row range outside the graph
         mg.aggregate(g, h, torch.empty_like(h), row_end=n + 1)
     g.free()
@@ -131,8 +131,7 @@ def test_aggregate_full_width(mg, rmat15, f, ld):
     ref = oracle.spmm(og, h[:, :f].astype(np.float64))
     z = z.cpu().numpy()
     assert_close(z[:, :f], ref, RTOL_F32, f"Z f={f}")
-    up = (f + 3) // 4 * 4
-    assert np.all(z[:, up:] == 7.0)  # columns beyond the vector-rounded slice stay untouched
+    assert np.all(z[:, f:] == 7.0)  # nothing beyond the column range is written
 
 
 def test_aggregate_slices_and_row_ranges(mg, rmat15):
@@ -164,6 +163,53 @@ def test_aggregate_slices_and_row_ranges(mg, rmat15):
 
 
 # S-SpMM (Sec. 3.2.1, Eq. 4): masked aggregation with the mask in bitmap form
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d,m", [(100, 8), (47, 5), (256, 7), (300, 3)])
+def test_aggregate_exact_slice_bounds_of_algorithm_2(mg, rmat15, d, m, dtype):
+    """The aggregation worker's slice [floor(d i / m), floor(d (i + 1) / m)) of Algorithm 2 with
+    bounds that are multiples of nothing (d = 100, m = 8: 12, 25, 37, ...), each slice on a stream
+    of its own, into one output: every slice writes exactly its columns (neighbors that share a
+    16-byte group do not disturb each other), together they give the full product, and a slice
+    alone leaves every other column as it was."""
+    og, g = rmat15
+    bf16 = dtype == "bf16"
+    ld = (d + 7) // 8 * 8 + 8
+    h = gg.normal(35, d, og.n, d, ld=ld)
+    if bf16:
+        h = bf16_round(h)
+    hd = dev(h).to(torch.bfloat16) if bf16 else dev(h)
+    ref = oracle.spmm(og, h[:, :d].astype(np.float64), q=oracle.Q_BF16 if bf16 else oracle.Q_NONE)
+    rtol = RTOL_BF16 if bf16 else RTOL_F32
+    bounds = [d * i // m for i in range(m + 1)]
+    say(f"exact slice bounds d={d} m={m} {dtype}: {bounds}")
+    z = torch.full((og.n, ld), 9.0, device="cuda", dtype=hd.dtype)
+    streams = [torch.cuda.Stream() for _ in range(m)]
+    torch.cuda.synchronize()
+    for i, st in enumerate(streams):
+        mg.aggregate(g, hd, z, col_begin=bounds[i], col_end=bounds[i + 1], stream=st)
+    torch.cuda.synchronize()
+    zz = z.float().cpu().numpy()
+    assert_close(zz[:, :d], ref, rtol, "all slices")
+    assert np.all(zz[:, d:] == 9.0)
+    i = m // 2
+    z = torch.full((og.n, ld), 9.0, device="cuda", dtype=hd.dtype)
+    mg.aggregate(g, hd, z, col_begin=bounds[i], col_end=bounds[i + 1], row_begin=17, row_end=og.n - 3,
+                 transpose=True)
+    zz = z.float().cpu().numpy()
+    assert_close(zz[17:og.n - 3, bounds[i]:bounds[i + 1]], ref[17:og.n - 3, bounds[i]:bounds[i + 1]], rtol,
+                 "one slice, row range, transposed")
+    zz[17:og.n - 3, bounds[i]:bounds[i + 1]] = 9.0
+    assert np.all(zz == 9.0)
+    # the masked and the accumulating forms keep to the range as well
+    z = torch.full((og.n, ld), 2.0, device="cuda", dtype=hd.dtype)
+    mg.aggregate(g, hd, z, col_begin=bounds[i], col_end=bounds[i + 1], accumulate=True)
+    zz = z.float().cpu().numpy()
+    acc_ref = ref[:, bounds[i]:bounds[i + 1]] + 2.0
+    assert_close(zz[:, bounds[i]:bounds[i + 1]], acc_ref, rtol, "accumulating slice")
+    zz[:, bounds[i]:bounds[i + 1]] = 2.0
+    assert np.all(zz == 2.0)
+
+
 @pytest.mark.parametrize("reserve", [True, False])
 def test_aggregate_column_slices_on_eight_streams_at_once(mg, reserve):
     """The m = 8 column slices of Algorithm 2's aggregation phase, each on a stream of its own

@@ -65,13 +65,13 @@ def test_random_aggregations(mg, seed):
         oracle.transpose(og)
         bf = bool(rng.integers(0, 3) == 0)
         vec = 8 if bf else 4
-        f = int(rng.choice([4, 8, 12, 16, 40, 64, 100, 128, 200, 256, 264, 520, 1040]))
-        if bf: f = (f + 7) // 8 * 8
-        ld = f + vec * int(rng.integers(0, 3))
+        f = int(rng.choice([4, 7, 8, 12, 16, 33, 40, 64, 100, 127, 128, 200, 256, 257, 264, 520, 1040]))
+        ld = (f + vec - 1) // vec * vec + vec * int(rng.integers(0, 3))
         tr = bool(rng.integers(0, 2))
         relu, acc = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
-        c0 = vec * int(rng.integers(0, f // vec)) if rng.integers(0, 2) else 0
-        c1 = f if rng.integers(0, 2) else min(f, c0 + vec * int(rng.integers(1, f // vec + 1)))
+        # column bounds that are multiples of nothing (slice bounds floor(d i / m) of Algorithm 2)
+        c0 = int(rng.integers(0, f)) if rng.integers(0, 2) else 0
+        c1 = f if rng.integers(0, 2) else int(rng.integers(c0 + 1, f + 1))
         r0 = int(rng.integers(0, n)) if rng.integers(0, 2) else 0
         r1 = n if rng.integers(0, 2) else int(rng.integers(r0, n + 1))
         use_mask = bool(rng.integers(0, 3) == 0) and not (relu or acc)
