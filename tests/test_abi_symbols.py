@@ -99,6 +99,29 @@ def test_aggregation_scratch_bound_covers_every_call(nnz):
     assert lib.mixgcn_aggregate_scratch_bytes(-1) == 0
 
 
+def test_aggregation_scratch_bound_with_whole_row_gathers():
+    """The measurement aid that gathers whole rows uses shorter spans (one entry per gather
+    instruction at 256 fp32 columns), so a graph normalised with it on gets a larger scratch:
+    the bound follows the mode, and still covers every call."""
+    import paper_2501_01951_amd as m
+
+    lib = m.load_library()
+    nnz = 5_000_000
+    plain = lib.mixgcn_aggregate_scratch_bytes(nnz)
+    assert lib.mixgcn_set_aggregate_whole_rows(1) == 0
+    try:
+        bound = lib.mixgcn_aggregate_scratch_bytes(nnz)
+        assert bound > plain
+        for dtype in (m.F32, m.BF16):
+            for w in (1, 16, 47, 100, 128, 256, 300):
+                for e0, e1 in ((0, nnz), (12345, 12345 + 70_000), (nnz - 300, nnz), (1000, 1001)):
+                    need = lib.mixgcn_aggregate_scratch_need(dtype, w, e0, e1)
+                    assert 0 <= need <= bound, (dtype, w, e0, e1, need, bound)
+    finally:
+        assert lib.mixgcn_set_aggregate_whole_rows(0) == 0
+    assert lib.mixgcn_aggregate_scratch_bytes(nnz) == plain
+
+
 # ---- host arithmetic of the cross-layer pipeline (Sec. 3.2.2) -------------------------------
 
 def _windows(m, n, s, b):
