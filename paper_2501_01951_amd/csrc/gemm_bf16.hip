@@ -207,7 +207,11 @@ struct FastStage {
             bl[p] = *reinterpret_cast<const uint4*>(bl0 + p * 64 * kPitchB + boff);
         }
     }
-    __device__ inline void store(uint16_t* as, uint16_t* bhs, uint16_t* bls) const
+    // TAIL: the last step of a reduction depth that is not a whole number of steps; `km` clears
+    // the elements past the depth (what the row holds there is not part of the operand)
+    template <bool TAIL = false>
+    __device__ inline void store(uint16_t* as, uint16_t* bhs, uint16_t* bls,
+                                 const uint4& km = uint4()) const
     {
 #pragma unroll
         for (int p = 0; p < A_PASSES; ++p) {
@@ -217,6 +221,12 @@ struct FastStage {
                 v.y = keep_positive(v.y, r[p].y);
                 v.z = keep_positive(v.z, r[p].z);
                 v.w = keep_positive(v.w, r[p].w);
+            }
+            if (TAIL) {
+                v.x &= km.x;
+                v.y &= km.y;
+                v.z &= km.z;
+                v.w &= km.w;
             }
             lds_store16(as + lpos + p * 64 * LDT, v);
         }
@@ -335,9 +345,27 @@ __global__ __launch_bounds__(kBlock)
     };
 
     const int nk = (KD + BKB - 1) / BKB;
-    // every row of the tile exists, whole reduction steps, 32-bit offsets inside a tile
-    const bool fast = row0 + S::BM <= n && KD % BKB == 0 && lda < (1 << 22) && ldr < (1 << 22);
+    // every row of the tile exists, 32-bit offsets inside a tile, and the reduction depth is a
+    // whole number of steps or the rows are long enough to read the last step whole (what lies
+    // past the depth is cleared on the way to LDS)
+    const bool ragged = KD % BKB != 0;
+    const bool fast = row0 + S::BM <= n && lda < (1 << 22) && ldr < (1 << 22) &&
+                      (!ragged || ((int64_t)nk * BKB <= lda && (!MASK || (int64_t)nk * BKB <= ldr)));
     if (fast) {
+        uint4 km;
+        {
+            const int left = KD - (nk - 1) * BKB - pk;  // elements of this thread's piece inside
+            const auto word = [&](int w) {
+                return (left > 2 * w ? 0x0000FFFFu : 0u) | (left > 2 * w + 1 ? 0xFFFF0000u : 0u);
+            };
+            km = make_uint4(word(0), word(1), word(2), word(3));
+        }
+        // writes the staged step to LDS; the last step of a ragged depth goes through the mask
+        auto put = [&](const FastStage<S, MASK>& st, int step, uint16_t* as, uint16_t* bhs,
+                       uint16_t* bls) {
+            if (ragged && step == nk - 1) st.template store<true>(as, bhs, bls, km);
+            else st.template store<false>(as, bhs, bls);
+        };
         // Loads beyond the last step repeat it (never stored), so that no load is conditional.
         FastStage<S, MASK> st0;
         st0.init(tid, (uint32_t)lda * 2u, (uint32_t)ldr * 2u);
@@ -355,7 +383,7 @@ __global__ __launch_bounds__(kBlock)
             // one set of tiles: the loads of the next step are in flight during the products
             load(st0, 0);
             for (int i = 0; i < nk; ++i) {
-                st0.store(As[0], Bhs[0], Bls[0]);
+                put(st0, i, As[0], Bhs[0], Bls[0]);
                 load(st0, i + 1);
                 __syncthreads();
                 mma_step(As[0], Bhs[0], Bls[0]);
@@ -364,23 +392,23 @@ __global__ __launch_bounds__(kBlock)
         } else {
             // two sets of tiles, one barrier per step, loads one step ahead
             load(st0, 0);
-            st0.store(As[0], Bhs[0], Bls[0]);
+            put(st0, 0, As[0], Bhs[0], Bls[0]);
             __syncthreads();
             int i = 0;
             for (; i + 2 < nk; i += 2) {
                 load(st0, i + 1);
                 mma_step(As[0], Bhs[0], Bls[0]);
-                st0.store(As[1], Bhs[1], Bls[1]);
+                put(st0, i + 1, As[1], Bhs[1], Bls[1]);
                 __syncthreads();
                 load(st0, i + 2);
                 mma_step(As[1], Bhs[1], Bls[1]);
-                st0.store(As[0], Bhs[0], Bls[0]);
+                put(st0, i + 2, As[0], Bhs[0], Bls[0]);
                 __syncthreads();
             }
             if (nk - i == 2) {
                 load(st0, i + 1);
                 mma_step(As[0], Bhs[0], Bls[0]);
-                st0.store(As[1], Bhs[1], Bls[1]);
+                put(st0, i + 1, As[1], Bhs[1], Bls[1]);
                 __syncthreads();
                 mma_step(As[1], Bhs[1], Bls[1]);
             } else {
