@@ -294,6 +294,27 @@ def bench_single_layer(args, mg, dev, config):
     dt = (time.perf_counter() - t0) / args.steps
     kinds = read_kinds(pipe)
     pipe.timing(False)
+    # The same layer with the fine-grain pipeline of Sec. 3.2.2 (aggregation of row chunk k on one
+    # stream while the update of chunk k - 1 runs on the other), after and outside the timed
+    # region above: reported beside the result.
+    pipelined = None
+    if args.chunks == 1 and not args.no_pipelined:
+        nc = 16
+
+        def step_chunked():
+            mg.layer_fwd(g, hd, wd, zd, outd, pipe, relu=relu, n_chunks=nc)
+            mg.layer_bwd(g, zd, outd, wd, gd, dwd, dhd, pipe, relu=relu, n_chunks=nc)
+
+        step_chunked()
+        torch.cuda.synchronize()
+        reps = max(1, min(5, args.steps))
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            step_chunked()
+        torch.cuda.synchronize()
+        dtc = (time.perf_counter() - t0) / reps
+        pipelined = {"row_chunks": nc, "steps": reps, "ms_per_step": dtc * 1e3, "value": nnz * k / dtc,
+                     "speedup_over_unpipelined": dt / dtc}
     out = {
         "metric": "GCN layer fwd+bwd edges*feat/s", "value": nnz * k / dt, "unit": "edges*feat/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
@@ -310,6 +331,8 @@ def bench_single_layer(args, mg, dev, config):
                  MFMA_F32_TFLOPS}
             for kk in ("update_fwd", "update_dgrad", "update_wgrad") if kk in kinds},
     }
+    if pipelined:
+        out["with_row_chunk_pipeline"] = pipelined
     pipe.free()
     g.free()
     del hd, zd, outd, gd, dhd, dwd, wd
@@ -532,6 +555,8 @@ def main():
     ap.add_argument("--no-secondary", action="store_true",
                     help="default run without the secondary configurations")
     ap.add_argument("--no-event-timing", action="store_true")
+    ap.add_argument("--no-pipelined", action="store_true",
+                    help="single-layer configurations: skip the extra run with 16 row chunks on two streams")
     ap.add_argument("--no-peaks", action="store_true", help="skip the measured-peaks block")
     ap.add_argument("--model", default="gcn", choices=["gcn", "sage", "gin"],
                     help="gcn: the benchmark line; sage / gin: the two other architectures of the "
