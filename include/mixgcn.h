@@ -161,9 +161,9 @@ int mixgcn_normalize_mode(mixgcn_graph* g, int mode, float eps, void* stream);
  * [row_begin, row_end) is a pipeline chunk.  H and Z are indexed with absolute columns; entries
  * of Z outside the ranges are not touched: the bounds need not be multiples of anything, so the
  * slice bounds floor(d i/m) of Algorithm 2 can be passed as they are (the kernel works on
- * 16-byte groups of a row and writes the elements of a group that lie outside the range one by
- * one around it; H is read in whole groups, which always lie inside the row pitch).  H and Z
- * must not overlap.
+ * 16-byte groups of a row; of the first and the last group of a range it writes only the
+ * elements inside the range, one by one; H is read in whole groups, which always lie inside the
+ * row pitch).  H and Z must not overlap.
  *
  * Concurrency.  Rows that are cut by the kernel's work split are completed through a scratch
  * buffer that belongs to the graph and to the stream of the call: calls on one stream share it
