@@ -105,3 +105,35 @@ def test_static_scratch_rejects_what_does_not_fit():
     torch.cuda.synchronize()
     assert torch.equal(z, z_ref)
     g.free()
+
+
+def test_static_scratch_degenerate_calls():
+    """Empty ranges are no-ops, a one-node graph and an edgeless graph give A_hat = I, and bad
+    arguments are refused like mixgcn_aggregate refuses them."""
+    import paper_2501_01951_amd as mg
+
+    mg.load_library()
+    src, dst, n = gg.config_graph("c2", scale_override=10)
+    g = _graph(mg, src, dst, n)
+    h = torch.randn(n, 24, device="cuda")
+    z = torch.full((n, 24), 4.0, device="cuda")
+    mg.aggregate_static(g, h, z, row_begin=7, row_end=7)
+    mg.aggregate_static(g, h, z, col_begin=5, col_end=5)
+    torch.cuda.synchronize()
+    assert bool((z == 4.0).all())
+    with pytest.raises(mg.MixGCNError):
+        mg.aggregate_static(g, h, h)  # H and Z overlap
+    with pytest.raises(mg.MixGCNError):
+        mg.aggregate_static(g, h, z, row_end=n + 1)
+    g.free()
+    for n1, s1, d1 in ((1, np.zeros(0, np.uint32), np.zeros(0, np.uint32)),
+                       (9, np.zeros(0, np.uint32), np.zeros(0, np.uint32))):
+        g1 = _graph(mg, s1, d1, n1)
+        x = torch.randn(n1, 7, device="cuda")
+        xp = torch.zeros(n1, 8, device="cuda")
+        xp[:, :7] = x
+        out = torch.zeros(n1, 8, device="cuda")
+        mg.aggregate_static(g1, xp[:, :7], out[:, :7])
+        torch.cuda.synchronize()
+        assert torch.equal(out[:, :7], x) and bool((out[:, 7] == 0).all())
+        g1.free()
