@@ -221,3 +221,55 @@ def test_bench_refuses_more_than_one_gpu():
                        capture_output=True, text=True, timeout=60)
     assert r.returncode != 0
     assert "one GPU" in r.stderr
+
+
+# ---- host logic around the library -------------------------------------------------------------
+
+def test_row_pitch_rule_of_the_step_helper():
+    """Feature buffers of the step helper: rows longer than a 128-byte line get a pitch of an odd
+    number of lines (spreads a column slice over the L2 channels), shorter rows a power-of-two
+    pitch (a gathered row never straddles two lines); every pitch is a whole number of 16-byte
+    groups, as the ABI asks."""
+    import torch
+    from paper_2501_01951_amd.model import padded_rows
+
+    for dtype, es in ((torch.float32, 4), (torch.bfloat16, 2)):
+        for f in (1, 3, 4, 8, 16, 17, 31, 32, 47, 64, 65, 100, 128, 172, 256, 300, 1024):
+            t = padded_rows(5, f, dtype, "cpu")
+            assert t.shape == (5, f) and t.stride(1) == 1
+            pitch = t.stride(0) * es
+            assert pitch % 16 == 0 and pitch >= f * es
+            if f * es <= 128:
+                assert pitch & (pitch - 1) == 0 and pitch < 2 * max(16, f * es)
+            else:
+                lines = pitch // 128
+                assert pitch % 128 == 0 and lines % 2 == 1 and lines <= (f * es + 127) // 128 + 1
+
+
+def test_roofline_block_of_the_benchmark_line():
+    """bench.py's roofline block: achieved = algorithmic bytes / launch time, frac against the
+    published 8 TB/s, the counter traffic labelled with its source file (or null), per launch."""
+    import sys
+
+    sys.path.insert(0, ROOT)
+    import bench
+
+    kinds = {"agg_g64": {"total_ms": 28.0, "launches": 10, "avg_ms": 2.8},
+             "agg_g4": {"total_ms": 3.7, "launches": 10, "avg_ms": 0.37},
+             "update_fwd": {"total_ms": 7.0, "launches": 10, "avg_ms": 0.7}}
+    nnz, n = 32_450_196, 1 << 20
+    r = bench.aggregation_roofline("c2", kinds, nnz, n, 4)
+    algo = 8.0 * nnz + 2.0 * n * 256 * 4 + 8.0 * n
+    assert r["bound"] == "hbm" and r["peak"] == 8000.0 and r["unit"] == "GB/s"
+    assert abs(r["algorithmic_bytes_per_launch"] - algo) < 1 and abs(r["achieved"] - algo / 2.8e-3 / 1e9) < 1e-6
+    assert abs(r["frac"] - r["achieved"] / 8000.0) < 1e-12
+    assert r["traffic"] and "profiles/c2_aggregate_pmc.txt" in r["traffic_source"]
+    assert abs(r["counter_traffic_frac"] - r["traffic"] / 2.8e-3 / 1e9 / 8000.0) < 1e-12
+    assert r["no_reuse_bytes_per_launch"] == nnz * (8.0 + 1024) + n * 1024
+    # a configuration without a committed counter summary reports null, never a guess
+    r1 = bench.aggregation_roofline("c1", kinds, nnz, n, 4)
+    assert r1["traffic"] is None and r1["traffic_source"] is None and "counter_traffic_frac" not in r1
+    for cfg, width in bench.TRAFFIC_FILES:
+        assert os.path.exists(os.path.join(ROOT, "profiles", bench.TRAFFIC_FILES[(cfg, width)]))
+        t, src = bench.measured_traffic(cfg, width)
+        assert t and t > 0 and src
