@@ -10,8 +10,9 @@ synthetic inputs that are resident in HBM before each timed region, and prints O
              spreads them over 32 GPUs; one layer at its real shape does).  If it cannot run
              (not enough device memory on this machine), config 3 and then config 2 take its
              place and the line says so.
-  secondary  config 2 (3-layer GCN 128-256-256-16, R-MAT scale 20, fp32), one epoch, and
-             config 5 (3-layer GCN 100-256-256-47, N = 2.45e6, bf16 storage), one epoch.
+  secondary  config 2 (3-layer GCN 128-256-256-16, R-MAT scale 20, fp32), one epoch,
+             config 5 (3-layer GCN 100-256-256-47, N = 2.45e6, bf16 storage), one epoch, and
+             config 3 (one layer 128 -> 1024 on a 128-column slice, R-MAT scale 24, fp32).
 
 `value` is whole-job throughput in edges*feat/s: sum over layers of nnz(A_hat) * d^(l), divided
 by the step time.  `roofline` describes the dominant kernel (the aggregation gather): its
@@ -531,7 +532,7 @@ def baseline_for(args, config):
     if config == "c4":
         return cpu_baseline_layer("c4", args.cpu_scale or 21, args.seed, 128, 128, False)
     if config == "c3":
-        return cpu_baseline_layer("c3", args.cpu_scale or 20, args.seed, 128, 1024, True)
+        return cpu_baseline_layer("c3", args.cpu_scale or 18, args.seed, 128, 1024, True)
     if config == "c5":
         return cpu_baseline_model("c5", args.cpu_scale or 18, args.seed)
     if config == "c2":
@@ -630,11 +631,15 @@ def main():
             "fallback after: " + "; ".join(fallbacks))
         if not args.no_secondary:
             out["secondary"] = {}
-            for config in ("c2", "c5"):
+            for config in ("c2", "c5", "c3"):
                 if config == used:
                     continue
                 try:
-                    out["secondary"][config] = bench_model(args, mg, dev, config, with_bf16x3=(config == "c2"))
+                    if config == "c3":
+                        out["secondary"][config] = bench_single_layer(args, mg, dev, config)
+                    else:
+                        out["secondary"][config] = bench_model(args, mg, dev, config,
+                                                               with_bf16x3=(config == "c2"))
                 except (mg.MixGCNError, torch.OutOfMemoryError, MemoryError) as e:
                     out["secondary"][config] = {"error": f"{type(e).__name__}: {str(e)[:200]}"}
     # what this device sustains on a plain copy and on register-only MFMA chains (outside the
@@ -647,7 +652,7 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = baseline_for(args, used)
         if not single and not args.no_secondary:
-            for config in ("c2", "c5"):
+            for config in ("c2", "c5", "c3"):
                 blk = out.get("secondary", {}).get(config)
                 if blk and "error" not in blk:
                     blk["cpu_baseline"] = baseline_for(args, config)
