@@ -434,7 +434,7 @@ def test_apply_bitmap(mg, dtype):
     assert np.array_equal(got[:, :c], np.where(keep, x[:, :c], 0.0).astype(np.float32))
 
 
-@pytest.mark.parametrize("name", ["c1", "c2@16"])
+@pytest.mark.parametrize("name", ["c1", "c2@16", "c2"])
 def test_gcn_with_dropout_masks_end_to_end(mg, name):
     """Forward use of the S-SpMM in a whole step (Eq. 4 on every aggregation), against the oracle."""
     src, dst, n, dims, x, y = _sage_case(name)
