@@ -58,9 +58,8 @@ def measured_traffic(config, width):
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split()[1]), (
-                    f"profiles/{name}: 2.0 x FETCH_SIZE + WRITE_SIZE from two rocprofv3 --pmc runs "
-                    f"of this workload (committed summary, not re-measured in this run)")
+                return float(line.split()[1]), (f"profiles/{name} (committed rocprofv3 --pmc summary of "
+                                                f"this workload; not re-measured in this run)")
     except OSError:
         pass
     return None, None
@@ -128,9 +127,9 @@ def cpu_baseline_model(name, scale, seed, single_thread_scale=None):
     work = sum(g.nnz * d for d in dims[:-1])
     out = {
         "value": work / med, "unit": "edges*feat/s", "cores": oracle.num_threads(), "kind": "oracle",
-        "cpu_model": cpu_model(), "median_s": med, "runs_s": ts,
-        "sample": f"{name}'s generator and model at scale {scale} (N={n}, nnz={g.nnz}), one "
-                  f"fwd+bwd step, median of 3 after a warm-up",
+        "cpu_model": cpu_model(), "median_s": med,
+        "sample": f"{name} recipe at scale {scale} (N={n}, nnz={g.nnz}), one fwd+bwd step, "
+                  f"median of 3 after a warm-up",
     }
     if single_thread_scale:
         g1, n1, dims1, step1 = prepare(single_thread_scale)
@@ -142,9 +141,8 @@ def cpu_baseline_model(name, scale, seed, single_thread_scale=None):
             oracle.set_num_threads(threads)
         out["single_thread"] = {
             "value": sum(g1.nnz * d for d in dims1[:-1]) / med1, "unit": "edges*feat/s", "cores": 1,
-            "median_s": med1, "runs_s": ts1,
-            "sample": f"{name}'s generator and model at scale {single_thread_scale} (N={n1}, "
-                      f"nnz={g1.nnz}), one thread"}
+            "median_s": med1,
+            "sample": f"{name} recipe at scale {single_thread_scale} (N={n1}, nnz={g1.nnz}), one thread"}
     return out
 
 
@@ -177,9 +175,9 @@ def cpu_baseline_layer(name, scale, seed, k, m, relu):
     med, ts = timed_median(step)
     return {
         "value": g.nnz * k / med, "unit": "edges*feat/s", "cores": oracle.num_threads(),
-        "kind": "oracle", "cpu_model": cpu_model(), "median_s": med, "runs_s": ts,
-        "sample": f"{name}'s graph generator at scale {scale} (N={n}, nnz={g.nnz}), one layer "
-                  f"{k}->{m} fwd+bwd, median of 3 after a warm-up",
+        "kind": "oracle", "cpu_model": cpu_model(), "median_s": med,
+        "sample": f"{name} graph recipe at scale {scale} (N={n}, nnz={g.nnz}), one layer {k}->{m} "
+                  f"fwd+bwd, median of 3 after a warm-up",
     }
 
 
@@ -190,6 +188,11 @@ def read_kinds(pipe):
         if cnt:
             kinds[nm] = {"total_ms": ms, "launches": cnt, "avg_ms": ms / cnt}
     return kinds
+
+
+def kernels_compact(kinds):
+    """{kind: [average ms per launch, launches]} for the printed line."""
+    return {k: [v["avg_ms"], v["launches"]] for k, v in kinds.items()}
 
 
 def aggregation_roofline(config, kinds, nnz, n, esz, chunks=1):
@@ -210,8 +213,6 @@ def aggregation_roofline(config, kinds, nnz, n, esz, chunks=1):
     out = {
         "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": source,
-        "what_achieved_counts": "algorithmic bytes (each feature row read once) per launch / "
-                                "average launch duration",
         "kernel": f"aggregate_kernel<8, {gsz}, {1 if esz == 2 else 0}, ...> "
                   f"({f} {'bf16' if esz == 2 else 'fp32'} columns)",
         "avg_launch_ms": agg[dom]["avg_ms"], "launches": agg[dom]["launches"],
@@ -324,7 +325,7 @@ def bench_single_layer(args, mg, dev, config):
         "config": {"workload": f"{what}, N={n}, nnz(A_hat)={nnz}", "n_nodes": n, "nnz": nnz,
                    "row_chunks": args.chunks, "seed": args.seed, "update_arith": args.update_arith},
         "generate_edges_s": t_gen, "build_csr_normalize_ms": t_build * 1e3,
-        "kernels": kinds,
+        "kernels_avg_ms_launches": kernels_compact(kinds),
         "roofline": aggregation_roofline(config, kinds, nnz, n, 4, args.chunks),
         "update_products": {
             kk: {"tflops": 2.0 * n * k * m / (kinds[kk]["avg_ms"] * 1e-3) / 1e12,
@@ -403,7 +404,8 @@ def bench_model(args, mg, dev, config, with_bf16x3=True):
             "aggregate_whole_rows": bool(args.whole_rows), "rmat_ids_scrambled": not args.unscrambled,
         },
         "loss": loss, "generate_inputs_s": t_gen, "build_csr_normalize_ms": t_build * 1e3,
-        "kernels": kinds, "roofline": aggregation_roofline(config, kinds, nnz, n, esz, args.chunks),
+        "kernels_avg_ms_launches": kernels_compact(kinds),
+        "roofline": aggregation_roofline(config, kinds, nnz, n, esz, args.chunks),
     }
     upd = sum(v["total_ms"] for k, v in kinds.items() if k.startswith("update")) / args.steps
     if kinds:
@@ -520,6 +522,44 @@ def bench_variant(args, mg, dev):
     print(json.dumps(out))
 
 
+def rounded(obj, digits=6):
+    """The record with every float rounded to `digits` significant digits (keeps the line short)."""
+    if isinstance(obj, float):
+        return float(f"{obj:.{digits}g}")
+    if isinstance(obj, dict):
+        return {k: rounded(v, digits) for k, v in obj.items()}
+    if isinstance(obj, (list, tuple)):
+        return [rounded(v, digits) for v in obj]
+    return obj
+
+
+def summary_of(block):
+    """The figures of a secondary block that the headline's `config` carries as well."""
+    r = block.get("roofline") or {}
+    out = {"ms_per_step": block.get("ms_per_step"), "value": block.get("value"),
+           "roofline_frac": r.get("frac"), "roofline_achieved_GBps": r.get("achieved"),
+           "counter_traffic_frac": r.get("counter_traffic_frac")}
+    if "cpu_baseline" in block:
+        out["cpu_baseline_value"] = block["cpu_baseline"].get("value")
+    return out
+
+
+def trimmed(block):
+    """A secondary block without the fields that repeat the headline's (metric, unit, step
+    counts, peaks): what is left is what differs per configuration."""
+    drop = {"metric", "unit", "n_gpus", "steps", "warmup", "higher_is_better", "scaling", "vs_baseline",
+            "data", "generate_edges_s", "generate_inputs_s", "build_csr_normalize_ms"}
+    out = {k: v for k, v in block.items() if k not in drop}
+    out["config"] = {"workload": block["config"]["workload"]}
+    if out.get("roofline"):
+        keep = ("bound", "achieved", "frac", "traffic", "traffic_source", "counter_traffic_frac", "kernel",
+                "avg_launch_ms", "launches", "algorithmic_bytes_per_launch")
+        out["roofline"] = {k: v for k, v in out["roofline"].items() if k in keep}
+        if out["roofline"].get("traffic_source"):
+            out["roofline"]["traffic_source"] = out["roofline"]["traffic_source"].split(" ")[0]
+    return out
+
+
 def run_config(args, mg, dev, config):
     if config in ("c3", "c4"):
         return bench_single_layer(args, mg, dev, config)
@@ -626,8 +666,8 @@ def main():
         sys.exit("bench.py: no configuration could run: " + "; ".join(fallbacks))
     if not single:
         out["config"]["headline_choice"] = (
-            "the largest benchmark configuration that one GPU holds (config 4, one layer at its "
-            "real shape); configs 2 and 5 follow as secondary blocks" if used == "c4" else
+            "largest configuration one GPU holds (config 4, one layer at its real shape); "
+            "configs 2, 5 and 3 follow as secondary blocks" if used == "c4" else
             "fallback after: " + "; ".join(fallbacks))
         if not args.no_secondary:
             out["secondary"] = {}
@@ -656,7 +696,18 @@ def main():
                 blk = out.get("secondary", {}).get(config)
                 if blk and "error" not in blk:
                     blk["cpu_baseline"] = baseline_for(args, config)
-    print(json.dumps(out))
+    try:  # the untrimmed record, for whoever wants every field (best effort, never fatal)
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "bench_full.json"), "w") as fh:
+            json.dump(out, fh)
+    except OSError:
+        pass
+    if "secondary" in out:
+        # the same figures once more inside `config`, for readers that keep only the standard keys
+        out["config"]["secondary_configs"] = {k: summary_of(v) for k, v in out["secondary"].items()
+                                              if "error" not in v}
+        out["secondary"] = {k: (v if "error" in v else trimmed(v)) for k, v in out["secondary"].items()}
+    print(json.dumps(rounded(out), separators=(",", ":")))
 
 
 if __name__ == "__main__":
